@@ -1,0 +1,363 @@
+"""CPU oracle for the single-GPU hot path of a Tutel-style MoE layer.  TEST INFRASTRUCTURE ONLY.
+
+Nothing in the product path may import this file: only tests/, __graft_entry__.smoke() and bench.py's cpu_baseline
+leg use it.  It shares no code with the HIP library and never receives a value computed by it.
+
+What it computes (arXiv 2206.03382):
+  * Sec. 2.1 (background, Fig. 2): gating function -> dispatch -> expert feed-forward layer -> combine.
+  * Sec. 2.1, Eq. 1: expert capacity  C = k * f * T / E  (rounded up here; the paper states no rounding).
+  * Sec. 2.1 "MoE Frameworks": the routing logic is GShard's, kept unchanged: deterministic, order-based
+    truncation at capacity.
+  * Appendix B (the dense-vs-sparse figure and the text around it): encode/decode are, by definition, contractions with a
+    one-hot [T, E, C] mask; the sparse form only skips the multiplications by zero.  The *dense* form is the
+    definition and is what `encode_dense` / `decode_dense` write out.  `encode_sparse` / `decode_sparse` are the
+    same sums with the zero terms skipped (used where the [T, E, C] mask would not fit in memory).
+
+Precision: every floating-point step is fp64, with one exception that the method fixes: the gate logits are
+rounded once to fp32, because top-k selection (an integer decision) is taken on fp32 logits with ties going to
+the lower expert index.  Softmax, gate weights, FFN and combine are fp64 on the fp32 logits / the given inputs.
+
+Readings where the paper is silent (each listed again in the design notes):
+  R1  C = ceil(k*f*T/E) evaluated left to right in double.
+  R2  gate = linear layer (x @ Wg + bias) -> softmax over all E experts; top-k chosen on the fp32 logits.
+  R3  ties -> lower expert index; -0.0 == +0.0.
+  R4  arrival order at an expert = (choice rank j ascending, token t ascending); `loc` is the 0-based arrival
+      position counted over ALL arrivals (so a dropped choice has loc >= C); kept <=> loc < C.
+  R5  gate weight of choice j = p[t, idx[t,j]]; with normalize=1 it is divided by the sum over all k choices
+      (kept or dropped alike).
+  R6  encode copies rows unscaled; only decode applies the gate weight.  Unfilled slots are zero.
+  R7  activations: ReLU; GeLU = 0.5 x (1 + erf(x / sqrt 2)); SiLU = x / (1 + exp(-x)).
+  R8  a token whose choices were all dropped gets an all-zero output row.
+
+Pins (tests/test_oracle_*.py): Eq. 1 closed forms; the Fig. 2 worked shape; a hand-worked routing example;
+exhaustive/brute-force sequential-arrival simulation; invariants; tie cases; special cases that reduce to
+torch's linear/softmax/topk/activation routines; dense == sparse.  No function here is "parity unpinned".
+"""
+from __future__ import annotations
+
+import math
+from typing import Dict, Optional, Sequence
+
+import numpy as np
+from scipy.special import erf as _erf
+
+ACT_RELU, ACT_GELU, ACT_SILU = 0, 1, 2
+
+
+# ---------------------------------------------------------------------------------------------------------------
+# Eq. 1 (Sec. 2.1): expert capacity
+# ---------------------------------------------------------------------------------------------------------------
+
+def capacity(T: int, E: int, k: int, f: float) -> int:
+    """C = ceil(k * f * T / E), evaluated left to right in double (reading R1)."""
+    return int(math.ceil(float(k) * float(f) * float(T) / float(E)))
+
+
+# ---------------------------------------------------------------------------------------------------------------
+# Gating function (Sec. 2.1; reading R2/R3)
+# ---------------------------------------------------------------------------------------------------------------
+
+def gate_logits(x: np.ndarray, Wg: np.ndarray, bias: Optional[np.ndarray] = None, rows_per_pass: int = 8192) -> np.ndarray:
+    """logits[t,e] = sum_m x[t,m] Wg[m,e] + bias[e], summed in fp64 and rounded once to fp32.
+
+    Token rows are independent, so they are processed `rows_per_pass` at a time only to bound memory.
+    """
+    T = x.shape[0]
+    Wd = np.asarray(Wg, dtype=np.float64)
+    out = np.empty((T, Wd.shape[1]), dtype=np.float32)
+    bd = None if bias is None else np.asarray(bias, dtype=np.float64)
+    for s in range(0, T, rows_per_pass):
+        acc = np.asarray(x[s:s + rows_per_pass], dtype=np.float64) @ Wd
+        if bd is not None:
+            acc = acc + bd[None, :]
+        out[s:s + rows_per_pass] = acc.astype(np.float32)
+    return out
+
+
+def softmax_rows(logits: np.ndarray) -> np.ndarray:
+    """p[t,:] = softmax over all E experts of the fp32 logits, in fp64 (max-subtracted)."""
+    z = np.asarray(logits, dtype=np.float32).astype(np.float64)
+    z = z - z.max(axis=1, keepdims=True)
+    e = np.exp(z)
+    return e / e.sum(axis=1, keepdims=True)
+
+
+def topk_experts(logits: np.ndarray, k: int) -> np.ndarray:
+    """idx[t,j] = the j-th largest fp32 logit of token t; equal logits -> lower expert index first (R3).
+
+    k rounds of argmax with the already chosen experts masked out; numpy's argmax returns the first maximum.
+    """
+    work = np.array(logits, dtype=np.float32, copy=True)
+    T, E = work.shape
+    assert 1 <= k <= E
+    assert np.isfinite(work).all(), "routing is undefined for non-finite logits"
+    rows = np.arange(T)
+    idx = np.empty((T, k), dtype=np.int32)
+    for j in range(k):
+        idx[:, j] = np.argmax(work, axis=1)
+        work[rows, idx[:, j]] = -np.inf
+    return idx
+
+
+def gate_weights(p: np.ndarray, idx: np.ndarray, normalize: int) -> np.ndarray:
+    """w[t,j] = p[t, idx[t,j]], optionally divided by the sum over the token's k choices (R5). fp64."""
+    T = idx.shape[0]
+    w = p[np.arange(T)[:, None], idx]
+    if normalize:
+        w = w / w.sum(axis=1, keepdims=True)
+    return w
+
+
+# ---------------------------------------------------------------------------------------------------------------
+# Slot assignment (GShard logic kept by the paper, Sec. 2.1; reading R4)
+# ---------------------------------------------------------------------------------------------------------------
+
+def slot_locations(idx: np.ndarray, E: int):
+    """loc[t,j] and un-truncated counts[e].
+
+    For each rank j: one-hot mask_j[t,e]; positions = inclusive cumsum over t minus 1; later ranks are offset by
+    all arrivals of earlier ranks at that expert.
+    """
+    T, k = idx.shape
+    rows = np.arange(T)
+    loc = np.empty((T, k), dtype=np.int64)
+    counts = np.zeros(E, dtype=np.int64)
+    for j in range(k):
+        mask = np.zeros((T, E), dtype=np.int64)
+        mask[rows, idx[:, j]] = 1
+        pos = np.cumsum(mask, axis=0) - 1 + counts[None, :]
+        loc[:, j] = (pos * mask).sum(axis=1)
+        counts = counts + mask.sum(axis=0)
+    return loc.astype(np.int32), counts.astype(np.int32)
+
+
+def route(logits: np.ndarray, k: int, C: int, normalize: int) -> Dict[str, np.ndarray]:
+    """Gate decisions from fp32 logits: idx, loc, kept, counts, gate_w (fp64), p (fp64)."""
+    logits = np.asarray(logits, dtype=np.float32)
+    E = logits.shape[1]
+    idx = topk_experts(logits, k)
+    loc, counts = slot_locations(idx, E)
+    p = softmax_rows(logits)
+    w = gate_weights(p, idx, normalize)
+    return dict(idx=idx, loc=loc, kept=(loc < C), counts=counts, gate_w=w, p=p)
+
+
+def slot_source(idx: np.ndarray, loc: np.ndarray, E: int, C: int) -> np.ndarray:
+    """Inverse map slot_src[e,c] = token occupying slot (e,c), or -1 for an unfilled slot."""
+    T, k = idx.shape
+    src = np.full((E, C), -1, dtype=np.int32)
+    for j in range(k):
+        t = np.nonzero(loc[:, j] < C)[0]
+        src[idx[t, j], loc[t, j]] = t
+    return src
+
+
+# ---------------------------------------------------------------------------------------------------------------
+# Dense (definition) encode / decode: Appendix B, dense implementation
+# ---------------------------------------------------------------------------------------------------------------
+
+def dense_masks(idx: np.ndarray, loc: np.ndarray, gate_w: np.ndarray, E: int, C: int):
+    """dispatch_mask[t,e,c] in {0,1} and combine_w[t,e,c] = gate weight at the same positions."""
+    T, k = idx.shape
+    D = np.zeros((T, E, C), dtype=np.float64)
+    W = np.zeros((T, E, C), dtype=np.float64)
+    for j in range(k):
+        t = np.nonzero(loc[:, j] < C)[0]
+        D[t, idx[t, j], loc[t, j]] += 1.0
+        W[t, idx[t, j], loc[t, j]] += gate_w[t, j]
+    return D, W
+
+
+def encode_dense(D: np.ndarray, x: np.ndarray) -> np.ndarray:
+    """Z[e,c,m] = sum_t dispatch_mask[t,e,c] x[t,m]   (einsum 'tec,tm->ecm' written as one matmul)."""
+    T, E, C = D.shape
+    return (D.reshape(T, E * C).T @ np.asarray(x, dtype=np.float64)).reshape(E, C, -1)
+
+
+def decode_dense(W: np.ndarray, Y: np.ndarray) -> np.ndarray:
+    """out[t,m] = sum_{e,c} combine_w[t,e,c] Y[e,c,m]   (einsum 'tec,ecm->tm' written as one matmul)."""
+    T, E, C = W.shape
+    return W.reshape(T, E * C) @ np.asarray(Y, dtype=np.float64).reshape(E * C, -1)
+
+
+# ---------------------------------------------------------------------------------------------------------------
+# Zero-skipping encode / decode: Appendix B, sparse implementation (same sums, zero terms skipped)
+# ---------------------------------------------------------------------------------------------------------------
+
+def encode_sparse(x: np.ndarray, idx: np.ndarray, loc: np.ndarray, E: int, C: int, dtype=np.float64) -> np.ndarray:
+    T, k = idx.shape
+    Z = np.zeros((E, C, x.shape[1]), dtype=dtype)
+    for j in range(k):
+        t = np.nonzero(loc[:, j] < C)[0]
+        Z[idx[t, j], loc[t, j]] = x[t]
+    return Z
+
+
+def decode_sparse(Y: np.ndarray, idx: np.ndarray, loc: np.ndarray, gate_w: np.ndarray, C: int) -> np.ndarray:
+    T, k = idx.shape
+    out = np.zeros((T, Y.shape[2]), dtype=np.float64)
+    for j in range(k):
+        t = np.nonzero(loc[:, j] < C)[0]
+        out[t] += gate_w[t, j][:, None] * Y[idx[t, j], loc[t, j]].astype(np.float64)
+    return out
+
+
+# ---------------------------------------------------------------------------------------------------------------
+# Expert feed-forward layer (Sec. 2.1: "a feed-forward network layer (fflayer)"; reading R7)
+# ---------------------------------------------------------------------------------------------------------------
+
+def activation(h: np.ndarray, act: int) -> np.ndarray:
+    if act == ACT_RELU:
+        return np.maximum(h, 0.0)
+    if act == ACT_GELU:
+        return 0.5 * h * (1.0 + _erf(h / math.sqrt(2.0)))
+    if act == ACT_SILU:
+        return h / (1.0 + np.exp(-h))
+    raise ValueError(f"unknown activation {act}")
+
+
+def ffn_rows(z: np.ndarray, W1e, b1e, W2e, b2e, act: int) -> np.ndarray:
+    """One expert on a [rows, M] slab: act(z W1 + b1) W2 + b2 in fp64."""
+    h = np.asarray(z, dtype=np.float64) @ np.asarray(W1e, dtype=np.float64)
+    if b1e is not None:
+        h = h + np.asarray(b1e, dtype=np.float64)[None, :]
+    h = activation(h, act)
+    y = h @ np.asarray(W2e, dtype=np.float64)
+    if b2e is not None:
+        y = y + np.asarray(b2e, dtype=np.float64)[None, :]
+    return y
+
+
+def expert_ffn(Z: np.ndarray, W1, b1, W2, b2, act: int, rows: Optional[Sequence[int]] = None) -> np.ndarray:
+    """Y[e] = FFN_e(Z[e]) for every expert, one expert at a time.
+
+    `rows[e]`, if given, limits the work to the first rows[e] slots of expert e (the filled ones); the remaining
+    rows of Y are left zero and are never read by decode because their combine weight is zero.
+    """
+    E, C, M = Z.shape
+    Y = np.zeros((E, C, W2.shape[2]), dtype=np.float64)
+    for e in range(E):
+        r = C if rows is None else int(min(rows[e], C))
+        if r > 0:
+            Y[e, :r] = ffn_rows(Z[e, :r], W1[e], None if b1 is None else b1[e], W2[e], None if b2 is None else b2[e], act)
+    return Y
+
+
+# ---------------------------------------------------------------------------------------------------------------
+# Whole layer
+# ---------------------------------------------------------------------------------------------------------------
+
+def moe_layer(x, Wg, gate_bias, W1, b1, W2, b2, k: int, f: float, normalize: int, act: int,
+              tier: str = "sparse", logits: Optional[np.ndarray] = None) -> Dict[str, np.ndarray]:
+    """gate -> encode -> expert FFN -> decode on one device (Sec. 2.1 with both all-to-alls the identity).
+
+    tier = "dense": the literal one-hot-mask contractions (needs a [T,E,C] mask: small inputs only).
+    tier = "sparse": the same sums with zero terms skipped; the FFN visits filled slots only.
+    """
+    T = x.shape[0]
+    E = W1.shape[0]
+    C = capacity(T, E, k, f)
+    if logits is None:
+        logits = gate_logits(x, Wg, gate_bias)
+    r = route(logits, k, C, normalize)
+    if tier == "dense":
+        D, W = dense_masks(r["idx"], r["loc"], r["gate_w"], E, C)
+        Z = encode_dense(D, x)
+        Y = expert_ffn(Z, W1, b1, W2, b2, act)
+        out = decode_dense(W, Y)
+    elif tier == "sparse":
+        Z = encode_sparse(x, r["idx"], r["loc"], E, C)
+        Y = expert_ffn(Z, W1, b1, W2, b2, act, rows=r["counts"])
+        out = decode_sparse(Y, r["idx"], r["loc"], r["gate_w"], C)
+    else:
+        raise ValueError(tier)
+    r.update(C=C, logits=logits, Z=Z, Y=Y, out=out)
+    return r
+
+
+def token_outputs_direct(tokens: Sequence[int], x, idx, loc, gate_w, C: int, W1, b1, W2, b2, act: int) -> np.ndarray:
+    """out[t,:] = sum over kept choices j of gate_w[t,j] * FFN_{idx[t,j]}(x[t,:]), with no [E,C,M] buffers.
+
+    Used for sampled rows at sizes where the buffered oracle would not fit, and as a cross-check of it.
+    """
+    tokens = np.asarray(tokens, dtype=np.int64)
+    out = np.zeros((len(tokens), W2.shape[2]), dtype=np.float64)
+    k = idx.shape[1]
+    for j in range(k):
+        sel = np.nonzero(loc[tokens, j] < C)[0]
+        if sel.size == 0:
+            continue
+        experts = idx[tokens[sel], j]
+        for e in np.unique(experts):
+            s = sel[experts == e]
+            y = ffn_rows(x[tokens[s]], W1[e], None if b1 is None else b1[e], W2[e], None if b2 is None else b2[e], act)
+            out[s] += gate_w[tokens[s], j][:, None] * y
+    return out
+
+
+# ---------------------------------------------------------------------------------------------------------------
+# Brute force, independent of everything above except `activation` (tiny inputs only)
+# ---------------------------------------------------------------------------------------------------------------
+
+def brute_force_route(logits: np.ndarray, k: int, C: int):
+    """Sequential arrival simulation with plain Python loops: for each rank, for each token, take the next slot."""
+    T, E = logits.shape
+    choice = [[-1] * k for _ in range(T)]
+    for t in range(T):
+        taken = set()
+        for j in range(k):
+            best = None
+            for e in range(E):
+                if e in taken:
+                    continue
+                if best is None or float(np.float32(logits[t, e])) > float(np.float32(logits[t, best])):
+                    best = e
+            taken.add(best)
+            choice[t][j] = best
+    arrivals = [0] * E
+    loc = [[-1] * k for _ in range(T)]
+    for j in range(k):
+        for t in range(T):
+            e = choice[t][j]
+            loc[t][j] = arrivals[e]
+            arrivals[e] += 1
+    idx = np.array(choice, dtype=np.int32)
+    loc = np.array(loc, dtype=np.int32)
+    return idx, loc, loc < C, np.array(arrivals, dtype=np.int32)
+
+
+def brute_force_layer(x, Wg, gate_bias, W1, b1, W2, b2, k, f, normalize, act) -> np.ndarray:
+    """Per token, per kept choice: run the chosen expert on the token's row and add it, scaled by its gate weight."""
+    T, M = x.shape
+    E = W1.shape[0]
+    C = capacity(T, E, k, f)
+    logits = np.zeros((T, E), dtype=np.float32)
+    for t in range(T):
+        for e in range(E):
+            s = 0.0
+            for m in range(M):
+                s += float(x[t, m]) * float(Wg[m, e])
+            if gate_bias is not None:
+                s += float(gate_bias[e])
+            logits[t, e] = np.float32(s)
+    idx, loc, kept, _ = brute_force_route(logits, k, C)
+    out = np.zeros((T, W2.shape[2]), dtype=np.float64)
+    for t in range(T):
+        z = [float(v) for v in logits[t]]
+        mx = max(z)
+        ex = [math.exp(v - mx) for v in z]
+        den = sum(ex)
+        p = [v / den for v in ex]
+        wsum = sum(p[idx[t, j]] for j in range(k))
+        for j in range(k):
+            if not kept[t, j]:
+                continue
+            e = int(idx[t, j])
+            w = p[e] / wsum if normalize else p[e]
+            h = np.array([sum(float(x[t, m]) * float(W1[e, m, n]) for m in range(M)) + (0.0 if b1 is None else float(b1[e, n]))
+                          for n in range(W1.shape[2])])
+            h = activation(h, act)
+            y = np.array([sum(h[n] * float(W2[e, n, m]) for n in range(W2.shape[1])) + (0.0 if b2 is None else float(b2[e, m]))
+                          for m in range(W2.shape[2])])
+            out[t] += w * y
+    return out

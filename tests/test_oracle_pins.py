@@ -1,0 +1,347 @@
+"""Pins of the CPU oracle against things other than itself (CPU only).
+
+Each check takes the oracle module as an argument so that `test_planted_mistakes_are_caught` can run the same
+checks on copies of the oracle with one deliberate mistake each and see them fail.
+"""
+import itertools
+import math
+import os
+import types
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import moe_oracle as ORACLE
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+GOLDEN = os.path.join(ROOT, "tests", "golden")
+
+
+def _rng(seed):
+    return np.random.default_rng(seed)
+
+
+def _tiny_layer_inputs(seed, T, M, H, E, bias=True):
+    r = _rng(seed)
+    x = r.standard_normal((T, M)).astype(np.float32)
+    Wg = (r.standard_normal((M, E)) / math.sqrt(M)).astype(np.float32)
+    gb = r.standard_normal(E).astype(np.float32) * 0.1 if bias else None
+    W1 = (r.standard_normal((E, M, H)) / math.sqrt(M)).astype(np.float32)
+    W2 = (r.standard_normal((E, H, M)) / math.sqrt(H)).astype(np.float32)
+    b1 = r.standard_normal((E, H)).astype(np.float32) * 0.1 if bias else None
+    b2 = r.standard_normal((E, M)).astype(np.float32) * 0.1 if bias else None
+    return x, Wg, gb, W1, b1, W2, b2
+
+
+def _torch_act(h, act):
+    if act == ORACLE.ACT_RELU:
+        return torch.relu(h)
+    if act == ORACLE.ACT_GELU:
+        return torch.nn.functional.gelu(h, approximate="none")
+    return torch.nn.functional.silu(h)
+
+
+# ----------------------------------------------------------------------------------------------------------------
+# individual pins (o = oracle module under test)
+# ----------------------------------------------------------------------------------------------------------------
+
+def pin_capacity_golden(o):
+    for line in open(os.path.join(GOLDEN, "capacity_eq1.txt")):
+        line = line.split("#")[0].strip()
+        if not line:
+            continue
+        T, E, k, f, C = line.split()
+        assert o.capacity(int(T), int(E), int(k), float(f)) == int(C), line
+
+
+def _read_worked_example():
+    blocks, name = {}, None
+    for line in open(os.path.join(GOLDEN, "routing_worked_example.txt")):
+        line = line.split("#")[0].rstrip()
+        if not line.strip():
+            continue
+        if line.strip().isalpha():
+            name = line.strip()
+            blocks[name] = []
+        else:
+            blocks[name].append([float(v) for v in line.split()])
+    return {k: np.array(v) for k, v in blocks.items()}
+
+
+def pin_worked_routing_example(o):
+    g = _read_worked_example()
+    logits = g["logits"].astype(np.float32)
+    T, E = logits.shape
+    C = o.capacity(T, E, 2, 1.0)
+    assert C == 4
+    r = o.route(logits, 2, C, 1)
+    assert np.array_equal(r["idx"], g["idx"].astype(np.int32))
+    assert np.array_equal(r["loc"], g["loc"].astype(np.int32))
+    assert np.array_equal(r["kept"], g["kept"].astype(bool))
+    assert np.array_equal(r["counts"], g["counts"].astype(np.int32).ravel())
+    # gate weights of token 0: softmax(3,1,2) -> p0, p2 renormalised over the two choices
+    e = np.exp(np.array([3.0, 1.0, 2.0]) - 3.0)
+    p = e / e.sum()
+    np.testing.assert_allclose(r["gate_w"][0], [p[0] / (p[0] + p[2]), p[2] / (p[0] + p[2])], rtol=1e-14)
+
+
+def pin_fig2_even_top1(o):
+    """Fig. 2: 2 samples x 6 tokens, 3 experts, evenly dispatched top-1, f = 1 -> C = 4, every slot filled once."""
+    T, E, M = 12, 3, 5
+    C = o.capacity(T, E, 1, 1.0)
+    assert C == 4
+    pref = np.array([0, 1, 2, 2, 0, 1, 1, 2, 0, 0, 1, 2])     # four tokens per expert
+    logits = np.full((T, E), -1.0, dtype=np.float32)
+    logits[np.arange(T), pref] = 1.0
+    r = o.route(logits, 1, C, 0)
+    assert r["kept"].all() and np.array_equal(r["counts"], [4, 4, 4])
+    x = _rng(1).standard_normal((T, M)).astype(np.float32)
+    D, W = o.dense_masks(r["idx"], r["loc"], r["gate_w"], E, C)
+    assert D.sum() == 12 and (D.sum(axis=0) == 1).all() and (D.sum(axis=(1, 2)) == 1).all()
+    Z = o.encode_dense(D, x).reshape(E * C, M)
+    src = o.slot_source(r["idx"], r["loc"], E, C).ravel()
+    assert sorted(src.tolist()) == list(range(T))          # Z is a row permutation of x
+    assert np.array_equal(Z, x[src].astype(np.float64))
+    # expert e holds its tokens in token order
+    for e in range(E):
+        assert np.array_equal(src.reshape(E, C)[e], np.nonzero(pref == e)[0])
+
+
+def pin_exhaustive_top1_locations(o):
+    """All E^T top-1 routings for small T, E: cumsum-based locations == sequential arrival simulation."""
+    for T, E in ((4, 2), (5, 3), (6, 3)):
+        for C in (1, 2, T):
+            for assign in itertools.product(range(E), repeat=T):
+                idx = np.array(assign, dtype=np.int32)[:, None]
+                loc, counts = o.slot_locations(idx, E)
+                seen = [0] * E
+                for t, e in enumerate(assign):
+                    assert loc[t, 0] == seen[e]
+                    seen[e] += 1
+                assert counts.tolist() == seen
+
+
+def pin_random_topk_vs_bruteforce(o):
+    for seed, (T, E, k) in enumerate([(17, 4, 2), (33, 8, 3), (64, 5, 5), (40, 8, 1), (29, 6, 4)]):
+        r = _rng(100 + seed)
+        logits = (np.round(r.standard_normal((T, E)) * 2) / 2).astype(np.float32)   # coarse grid -> many exact ties
+        for f in (0.5, 1.0, 2.0):
+            C = o.capacity(T, E, k, f)
+            got = o.route(logits, k, C, 1)
+            idx, loc, kept, counts = o.brute_force_route(logits, k, C)
+            assert np.array_equal(got["idx"], idx)
+            assert np.array_equal(got["loc"], loc)
+            assert np.array_equal(got["kept"], kept)
+            assert np.array_equal(got["counts"], counts)
+
+
+def pin_invariants(o):
+    T, E, k = 600, 16, 3
+    logits = (np.round(_rng(7).standard_normal((T, E)) * 4) / 4).astype(np.float32)
+    logits[:, 0] += 1.0                                   # skew so that expert 0 overflows
+    C = o.capacity(T, E, k, 1.0)
+    r = o.route(logits, k, C, 1)
+    idx, loc, kept, counts = r["idx"], r["loc"], r["kept"], r["counts"]
+    assert all(len(set(row)) == k for row in idx.tolist())                     # k distinct experts per token
+    assert counts.sum() == T * k and counts.max() > C                          # something is dropped
+    for e in range(E):
+        sel = idx == e
+        assert sel.sum() == counts[e]
+        assert sorted(loc[sel].tolist()) == list(range(counts[e]))            # arrival positions are a bijection
+        assert (kept & sel).sum() == min(counts[e], C)
+        assert sorted(loc[sel & kept].tolist()) == list(range(min(counts[e], C)))
+        for j in range(k - 1):                                                 # rank j entirely before rank j+1
+            a, b = loc[sel[:, j], j], loc[sel[:, j + 1], j + 1]
+            if a.size and b.size:
+                assert a.max() < b.min()
+        for j in range(k):                                                     # token order within a rank
+            assert (np.diff(loc[sel[:, j], j]) > 0).all()
+    # selected logits are the k largest, in non-increasing order
+    srt = -np.sort(-logits, axis=1)[:, :k]
+    assert np.array_equal(logits[np.arange(T)[:, None], idx], srt)
+    np.testing.assert_allclose(r["gate_w"].sum(axis=1), 1.0, rtol=1e-13)
+    # minimum no-drop capacity (Sec. 4.1, dynamic capacity factor = 0) is max_e counts
+    r2 = o.route(logits, k, int(counts.max()), 1)
+    assert r2["kept"].all()
+    r3 = o.route(logits, k, int(counts.max()) - 1, 1)
+    assert (~r3["kept"]).sum() == (counts == counts.max()).sum()
+
+
+def pin_ties_lower_index(o):
+    T, E = 9, 6
+    eq = np.zeros((T, E), dtype=np.float32)
+    assert np.array_equal(o.topk_experts(eq, 4), np.tile(np.arange(4, dtype=np.int32), (T, 1)))
+    dup = np.array([[1.0, 5.0, 5.0, 0.0, 5.0, -2.0]], dtype=np.float32)
+    assert o.topk_experts(dup, 4).tolist() == [[1, 2, 4, 0]]
+    z = np.array([[-0.0, 0.0, -1.0]], dtype=np.float32)
+    assert o.topk_experts(z, 2).tolist() == [[0, 1]]
+    z = np.array([[0.0, -0.0, -1.0]], dtype=np.float32)
+    assert o.topk_experts(z, 2).tolist() == [[0, 1]]
+
+
+def pin_gate_against_torch(o):
+    x, Wg, gb, *_ = _tiny_layer_inputs(3, 50, 24, 8, 7)
+    ref = (torch.from_numpy(x).double() @ torch.from_numpy(Wg).double() + torch.from_numpy(gb).double()).float().numpy()
+    got = o.gate_logits(x, Wg, gb, rows_per_pass=16)
+    assert got.dtype == np.float32
+    np.testing.assert_allclose(got, ref, rtol=0, atol=1e-6)
+    assert (got != ref).mean() < 0.05                    # identical up to the odd last-bit rounding of the fp64 sum
+    p = o.softmax_rows(got)
+    np.testing.assert_allclose(p, torch.softmax(torch.from_numpy(got).double(), dim=1).numpy(), rtol=1e-13)
+    k = 3
+    tv, ti = torch.topk(torch.from_numpy(got), k, dim=1, largest=True, sorted=True)   # tie-free random logits
+    assert np.array_equal(o.topk_experts(got, k), ti.numpy().astype(np.int32))
+    w = o.gate_weights(p, ti.numpy(), 1)
+    tw = torch.gather(torch.from_numpy(p), 1, ti)
+    np.testing.assert_allclose(w, (tw / tw.sum(1, keepdim=True)).numpy(), rtol=1e-13)
+    w0 = o.gate_weights(p, ti.numpy(), 0)
+    np.testing.assert_allclose(w0, tw.numpy(), rtol=1e-15)
+
+
+def pin_activations_and_ffn_against_torch(o):
+    h = np.linspace(-6, 6, 241)
+    for act in (o.ACT_RELU, o.ACT_GELU, o.ACT_SILU):
+        np.testing.assert_allclose(o.activation(h, act), _torch_act(torch.from_numpy(h), act).numpy(), rtol=1e-12, atol=1e-15)
+    # E = 1, k = 1, C >= T: the layer is 1.0 * a dense two-layer MLP
+    for act in (o.ACT_RELU, o.ACT_GELU, o.ACT_SILU):
+        x, Wg, gb, W1, b1, W2, b2 = _tiny_layer_inputs(5 + act, 21, 12, 20, 1)
+        r = o.moe_layer(x, Wg, gb, W1, b1, W2, b2, k=1, f=1.0, normalize=0, act=act, tier="dense")
+        tx = torch.from_numpy(x).double()
+        ref = torch.nn.functional.linear(
+            _torch_act(torch.nn.functional.linear(tx, torch.from_numpy(W1[0]).double().T, torch.from_numpy(b1[0]).double()), act),
+            torch.from_numpy(W2[0]).double().T, torch.from_numpy(b2[0]).double())
+        np.testing.assert_allclose(r["out"], ref.numpy(), rtol=1e-12, atol=1e-13)
+        np.testing.assert_allclose(r["gate_w"], 1.0, rtol=1e-15)
+
+
+def pin_no_drop_equals_weighted_sum_of_experts(o):
+    """C >= T (f >= E/k): nothing is dropped, so out[t] = sum_j w[t,j] FFN_{idx[t,j]}(x[t]) -- evaluated with torch."""
+    T, M, H, E, k = 37, 16, 24, 4, 2
+    x, Wg, gb, W1, b1, W2, b2 = _tiny_layer_inputs(11, T, M, H, E)
+    for tier in ("dense", "sparse"):
+        r = o.moe_layer(x, Wg, gb, W1, b1, W2, b2, k=k, f=float(E) / k, normalize=1, act=o.ACT_GELU, tier=tier)
+        assert r["C"] == T and r["kept"].all()
+        tl = torch.from_numpy(r["logits"]).double()
+        tp = torch.softmax(tl, dim=1)
+        tv, ti = torch.topk(tl, k, dim=1)
+        tw = torch.gather(tp, 1, ti)
+        tw = tw / tw.sum(1, keepdim=True)
+        tx = torch.from_numpy(x).double()
+        ref = torch.zeros(T, M, dtype=torch.float64)
+        for e in range(E):
+            y = _torch_act(tx @ torch.from_numpy(W1[e]).double() + torch.from_numpy(b1[e]).double(), o.ACT_GELU)
+            y = y @ torch.from_numpy(W2[e]).double() + torch.from_numpy(b2[e]).double()
+            for j in range(k):
+                m = (ti[:, j] == e).double()[:, None]
+                ref += m * tw[:, j:j + 1] * y
+        np.testing.assert_allclose(r["out"], ref.numpy(), rtol=1e-11, atol=1e-12)
+
+
+def pin_identity_experts_masked_scaling(o):
+    """W1 = W2 = I, ReLU, x >= 0: decode(encode(x)) scales each row by the sum of its kept gate weights."""
+    T, M, E, k = 40, 8, 4, 2
+    r_ = _rng(13)
+    x = np.abs(r_.standard_normal((T, M))).astype(np.float32)
+    Wg = r_.standard_normal((M, E)).astype(np.float32)
+    W = np.tile(np.eye(M, dtype=np.float32), (E, 1, 1))
+    for tier in ("dense", "sparse"):
+        r = o.moe_layer(x, Wg, None, W, None, W, None, k=k, f=0.5, normalize=1, act=o.ACT_RELU, tier=tier)
+        assert (~r["kept"]).any() and (~r["kept"]).all(axis=1).any()       # some tokens lose everything
+        scale = (r["gate_w"] * r["kept"]).sum(axis=1)
+        np.testing.assert_allclose(r["out"], scale[:, None] * x.astype(np.float64), rtol=1e-13, atol=0)
+        dead = (~r["kept"]).all(axis=1)
+        assert (r["out"][dead] == 0.0).all() and not np.signbit(r["out"][dead]).any()
+
+
+def pin_dense_equals_sparse_and_direct(o):
+    T, M, H, E, k = 48, 12, 20, 6, 3
+    x, Wg, gb, W1, b1, W2, b2 = _tiny_layer_inputs(17, T, M, H, E)
+    for f in (0.5, 1.0, 1.5):
+        d = o.moe_layer(x, Wg, gb, W1, b1, W2, b2, k=k, f=f, normalize=1, act=o.ACT_SILU, tier="dense")
+        s = o.moe_layer(x, Wg, gb, W1, b1, W2, b2, k=k, f=f, normalize=1, act=o.ACT_SILU, tier="sparse")
+        assert np.array_equal(d["Z"], s["Z"])                        # at most one non-zero term per slot: exact
+        np.testing.assert_allclose(d["out"], s["out"], rtol=1e-12, atol=1e-13)
+        filled = o.slot_source(d["idx"], d["loc"], E, d["C"]) >= 0
+        np.testing.assert_allclose(d["Y"][filled], s["Y"][filled], rtol=1e-12, atol=1e-13)
+        direct = o.token_outputs_direct(np.arange(T), x, d["idx"], d["loc"], d["gate_w"], d["C"], W1, b1, W2, b2, o.ACT_SILU)
+        np.testing.assert_allclose(direct, d["out"], rtol=1e-12, atol=1e-13)
+
+
+def pin_bruteforce_layer(o):
+    T, M, H, E = 10, 5, 7, 3
+    for k, f, norm, act in ((1, 1.0, 0, o.ACT_RELU), (2, 0.75, 1, o.ACT_GELU), (3, 0.5, 1, o.ACT_SILU), (2, 1.0, 0, o.ACT_GELU)):
+        x, Wg, gb, W1, b1, W2, b2 = _tiny_layer_inputs(23 + k, T, M, H, E)
+        ref = o.brute_force_layer(x, Wg, gb, W1, b1, W2, b2, k, f, norm, act)
+        for tier in ("dense", "sparse"):
+            r = o.moe_layer(x, Wg, gb, W1, b1, W2, b2, k=k, f=f, normalize=norm, act=act, tier=tier)
+            np.testing.assert_allclose(r["out"], ref, rtol=1e-11, atol=1e-12)
+
+
+PINS = [pin_capacity_golden, pin_worked_routing_example, pin_fig2_even_top1, pin_exhaustive_top1_locations,
+        pin_random_topk_vs_bruteforce, pin_invariants, pin_ties_lower_index, pin_gate_against_torch,
+        pin_activations_and_ffn_against_torch, pin_no_drop_equals_weighted_sum_of_experts,
+        pin_identity_experts_masked_scaling, pin_dense_equals_sparse_and_direct, pin_bruteforce_layer]
+
+
+@pytest.mark.parametrize("pin", PINS, ids=lambda p: p.__name__)
+def test_pin(pin):
+    pin(ORACLE)
+
+
+# ----------------------------------------------------------------------------------------------------------------
+# planted mistakes: each edit of the oracle's source must make at least one pin fail
+# ----------------------------------------------------------------------------------------------------------------
+
+MISTAKES = {
+    "capacity_floor": ("int(math.ceil(float(k)", "int(math.floor(float(k)"),
+    "capacity_drops_k": ("math.ceil(float(k) * float(f)", "math.ceil(float(f)"),
+    "ties_to_higher_index": ("idx[:, j] = np.argmax(work, axis=1)", "idx[:, j] = E - 1 - np.argmax(work[:, ::-1], axis=1)"),
+    "topk_picks_smallest": ("idx[:, j] = np.argmax(work, axis=1)", "idx[:, j] = np.argmin(np.where(np.isinf(work), np.inf, work), axis=1)"),
+    "chosen_expert_not_masked": ("work[rows, idx[:, j]] = -np.inf", "work[rows, idx[:, j]] -= 1.0"),
+    "loc_one_based": ("pos = np.cumsum(mask, axis=0) - 1 + counts[None, :]", "pos = np.cumsum(mask, axis=0) + counts[None, :]"),
+    "later_ranks_not_offset": ("pos = np.cumsum(mask, axis=0) - 1 + counts[None, :]", "pos = np.cumsum(mask, axis=0) - 1"),
+    "kept_off_by_one": ("kept=(loc < C)", "kept=(loc <= C)"),
+    "normalize_ignored": ("    if normalize:\n        w = w / w.sum(axis=1, keepdims=True)", "    if False:\n        pass"),
+    "softmax_no_denominator": ("return e / e.sum(axis=1, keepdims=True)", "return e"),
+    "gate_bias_dropped": ("acc = acc + bd[None, :]", "acc = acc"),
+    "gate_weight_transposed": ("@ Wd\n", "@ Wd[:, ::-1]\n"),
+    "encode_scaled_by_gate": ("D[t, idx[t, j], loc[t, j]] += 1.0", "D[t, idx[t, j], loc[t, j]] += gate_w[t, j]"),
+    "decode_unweighted": ("W[t, idx[t, j], loc[t, j]] += gate_w[t, j]", "W[t, idx[t, j], loc[t, j]] += 1.0"),
+    "sparse_decode_unweighted": ("out[t] += gate_w[t, j][:, None] * Y[", "out[t] += Y["),
+    "sparse_encode_keeps_dropped": ("        t = np.nonzero(loc[:, j] < C)[0]\n        Z[idx[t, j], loc[t, j]] = x[t]",
+                                    "        t = np.nonzero(loc[:, j] < C + 1)[0]\n        Z[idx[t, j], np.minimum(loc[t, j], C - 1)] = x[t]"),
+    "gelu_tanh_form": ("0.5 * h * (1.0 + _erf(h / math.sqrt(2.0)))",
+                       "0.5 * h * (1.0 + np.tanh(math.sqrt(2.0 / math.pi) * (h + 0.044715 * h ** 3)))"),
+    "silu_sign": ("h / (1.0 + np.exp(-h))", "h / (1.0 + np.exp(h))"),
+    "ffn_activation_dropped": ("    h = activation(h, act)\n    y = h @", "    y = h @"),
+    "ffn_activation_before_b1": ("    h = np.asarray(z, dtype=np.float64) @ np.asarray(W1e, dtype=np.float64)\n",
+                                 "    h = activation(np.asarray(z, dtype=np.float64) @ np.asarray(W1e, dtype=np.float64), act)\n"
+                                 "    act = -1\n"),
+    "ffn_w2_transposed_block": ("y = h @ np.asarray(W2e, dtype=np.float64)", "y = h @ np.asarray(W2e, dtype=np.float64)[::-1]"),
+    "ffn_b2_dropped": ("        y = y + np.asarray(b2e, dtype=np.float64)[None, :]", "        pass"),
+    "direct_ignores_drops": ("sel = np.nonzero(loc[tokens, j] < C)[0]", "sel = np.nonzero(loc[tokens, j] >= 0)[0]"),
+}
+
+
+def _mutated_oracle(old, new):
+    path = os.path.join(ROOT, "oracle", "moe_oracle.py")
+    src = open(path).read()
+    assert src.count(old) >= 1, f"mutation anchor not found: {old!r}"
+    mod = types.ModuleType("moe_oracle_mutant")
+    mod.__file__ = path
+    exec(compile(src.replace(old, new, 1), path, "exec"), mod.__dict__)
+    return mod
+
+
+@pytest.mark.parametrize("name", sorted(MISTAKES))
+def test_planted_mistakes_are_caught(name):
+    old, new = MISTAKES[name]
+    mutant = _mutated_oracle(old, new)
+    failed = []
+    for pin in PINS:
+        try:
+            pin(mutant)
+        except Exception:            # any failure of a pin counts (assertion, shape or index error)
+            failed.append(pin.__name__)
+    assert failed, f"planted mistake '{name}' passed every pin"
