@@ -1,0 +1,133 @@
+/*
+ * moe_mi355x.h -- C ABI of the single-GPU hot path of a Tutel-style Mixture-of-Experts layer on AMD MI355X (gfx950).
+ *
+ * Path (arXiv 2206.03382, Sec. 2.1 and Fig. 2): gating function -> encode (dispatch) -> expert feed-forward layer ->
+ * decode (combine).  On one GPU both all-to-alls of the paper are the identity, so the dispatch buffer
+ * [E, C, M] goes straight to the local experts.
+ *
+ * Symbols follow the paper: T tokens per step, M model (channel) dim -- the paper's D --, H expert hidden dim,
+ * E experts, top-k routing, capacity factor f, C = expert capacity (Eq. 1).
+ *
+ * Conventions that hold for every entry point unless it says otherwise
+ *   - Every tensor pointer is a DEVICE pointer owned by the caller, row-major, contiguous, 16-byte aligned.
+ *   - The library never allocates or frees device memory; scratch comes from a caller-provided workspace.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All work is enqueued
+ *     asynchronously on it; no call synchronises with the host.  Outputs are fully overwritten.
+ *   - dtype selects the storage type of x / weights / Z / Y / out: MOE_F32 or MOE_BF16 (raw 16-bit patterns).
+ *     Accumulation is always at least fp32.  M and H must be multiples of 8 elements, else MOE_UNSUPPORTED.
+ *   - Return value: MOE_OK or an error code; on a validation error (codes 1-3) nothing has been launched;
+ *     MOE_HIP_ERROR reports a failed launch or event call.
+ *     Arguments are validated on the host (sizes >= 1, 1 <= k <= E, non-null required pointers, alignment).
+ *   - Inputs are assumed finite; routing of NaN/Inf logits is undefined (but never out of bounds).
+ *   - Calls that share a workspace or output buffers must be ordered by the caller (same stream or events).
+ */
+#ifndef MOE_MI355X_H
+#define MOE_MI355X_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum { MOE_OK = 0, MOE_INVALID_ARG = 1, MOE_UNSUPPORTED = 2, MOE_WORKSPACE_TOO_SMALL = 3, MOE_HIP_ERROR = 4 };
+enum { MOE_F32 = 0, MOE_BF16 = 1 };
+enum { MOE_ACT_RELU = 0, MOE_ACT_GELU = 1, MOE_ACT_SILU = 2 };
+
+/* Number of events moe_layer_forward records when `stage_events` is given:
+ * [0] start, [1] after gate logits, [2] after top-k + slot assignment, [3] after encode,
+ * [4] after the first expert GEMM (+activation), [5] after the second expert GEMM, [6] after decode. */
+#define MOE_NUM_STAGE_EVENTS 7
+
+/* Human-readable name of a status code (static storage, never NULL). */
+const char* moe_status_string(int status);
+
+/* Expert capacity, Sec. 2.1 Eq. 1:  C = k * f * T / E, rounded up (the paper states no rounding), evaluated
+ * left to right in double.  Host-only, pure.  Returns -1 if T < 1, E < 1, k < 1, k > E or f <= 0. */
+int64_t moe_capacity(int64_t T, int64_t E, int k, double f);
+
+/* Bytes of workspace moe_gate_topk needs (per-block per-expert arrival counters). 0 on invalid arguments. */
+size_t moe_gate_workspace_bytes(int64_t T, int64_t E, int k);
+
+/* Bytes of workspace moe_layer_forward needs: gate intermediates, the dispatch buffer [E,C,M], the hidden
+ * activations [E,C,H] and the expert output [E,C,M].  0 on invalid arguments. */
+size_t moe_layer_workspace_bytes(int64_t T, int64_t M, int64_t H, int64_t E, int k, int64_t C, int dtype);
+
+/* Gating function, linear part (Sec. 2.1):  logits[t,e] = sum_m x[t,m] * Wg[m,e] + gate_bias[e].
+ *   x [T,M] and Wg [M,E] in `dtype`; gate_bias [E] fp32 or NULL; logits [T,E] fp32 (output).
+ * The sum is accumulated in fp64 and rounded once to fp32, so the result does not depend on summation order
+ * (up to the last bit of the fp64 sum) and the routing decisions taken on it are reproducible. */
+int moe_gate_logits(const void* x, const void* Wg, const float* gate_bias, int dtype,
+                    int64_t T, int64_t M, int64_t E, float* logits, void* stream);
+
+/* Gating function, decision part (Sec. 2.1; Sec. 4.1 "dynamic top-ANY gating": any 1 <= k <= E per call) and
+ * capacity-limited slot assignment with the GShard logic the paper keeps (Sec. 2.1 "MoE Frameworks"; the
+ * location scan of Appendix B).
+ *   logits   [T,E] fp32 (input).
+ *   idx      [T,k] int32: expert of the j-th largest logit; equal logits -> lower expert index.
+ *   gate_w   [T,k] fp32: softmax over all E experts, taken at idx; if normalize != 0 divided by the sum over
+ *            the token's k choices (dropped ones included).
+ *   loc      [T,k] int32: 0-based arrival position at expert idx[t,j]; arrivals are ordered by (j, t):
+ *            all first choices in token order, then all second choices, ...  A choice is kept iff loc < C.
+ *   counts   [E] int32: arrivals per expert before truncation (max over e = minimum capacity that drops nothing,
+ *            Sec. 4.1 "dynamic capacity factor").
+ *   slot_src [E,C] int32 or NULL: token occupying slot (e,c), -1 if the slot is unfilled.
+ *   ws / ws_bytes: workspace of at least moe_gate_workspace_bytes(T,E,k), 16-byte aligned.
+ * Limits: E <= 512 and k*E <= 16384, else MOE_UNSUPPORTED.  Integer outputs are deterministic (no
+ * order-dependent atomics). */
+int moe_gate_topk(const float* logits, int64_t T, int64_t E, int k, int64_t C, int normalize,
+                  int32_t* idx, float* gate_w, int32_t* loc, int32_t* counts, int32_t* slot_src,
+                  void* ws, size_t ws_bytes, void* stream);
+
+/* Fast encode (Sec. 4.2 "Fast Encode and Decode", Appendix B):  Z[e,c,:] = x[t,:] for the kept choice (t,j) with
+ * idx[t,j] = e and loc[t,j] = c; unfilled slots are set to zero.  Rows are copied unscaled (bit-exact).
+ *   x [T,M], Z [E,C,M] in `dtype`; idx, loc [T,k] from moe_gate_topk.
+ *   slot_src [E,C] from moe_gate_topk, or NULL: with it the kernel is a single write-coalesced gather; without
+ *   it Z is zero-filled and the rows are scattered from idx/loc. */
+int moe_encode(const void* x, int dtype, const int32_t* idx, const int32_t* loc, const int32_t* slot_src,
+               int64_t T, int64_t M, int64_t E, int k, int64_t C, void* Z, void* stream);
+
+/* Local experts' feed-forward layer (Sec. 2.1; the per-expert [C,M] slab layout of Sec. 4.2 "Flexible All-to-All"):
+ *   Y[e] = act(Z[e] * W1[e] + b1[e]) * W2[e] + b2[e]     for every expert e.
+ *   Z [E,C,M], W1 [E,M,H], W2 [E,H,M], Y [E,C,M], hidden [E,C,H] (scratch) in `dtype`; b1 [E,H], b2 [E,M] in
+ *   `dtype` or NULL.  bf16: products accumulate in fp32 on the matrix cores, the hidden activations are rounded to
+ *   bf16 once after the activation and Y once at the end.  fp32: plain fp32 FMA accumulation.
+ *   counts [E] int32 or NULL: if given, only the first min(counts[e], C) rows of each expert are computed and the
+ *   remaining rows of Y and hidden are left untouched (decode never reads them); if NULL all C rows are computed.
+ *   act: ReLU, GeLU (exact erf form) or SiLU. */
+int moe_expert_ffn(const void* Z, const void* W1, const void* b1, const void* W2, const void* b2,
+                   int act, int dtype, const int32_t* counts,
+                   int64_t E, int64_t C, int64_t M, int64_t H, void* hidden, void* Y, void* stream);
+
+/* Fast decode (Sec. 4.2, Appendix B):  out[t,:] = sum over kept choices j (ascending) of
+ * gate_w[t,j] * Y[idx[t,j], loc[t,j], :], accumulated in fp32 and rounded once to `dtype`.
+ * A token whose choices were all dropped gets an all-zero row.  Y [E,C,M], out [T,M] in `dtype`. */
+int moe_decode(const void* Y, int dtype, const int32_t* idx, const int32_t* loc, const float* gate_w,
+               int64_t T, int64_t M, int64_t E, int k, int64_t C, void* out, void* stream);
+
+/* The whole path on one stream: gate logits -> top-k + slots -> encode -> expert FFN (filled rows only) -> decode,
+ * with C = moe_capacity(T,E,k,f).
+ *   Inputs as in the entry points above.  out [T,M] (output, required).
+ *   Optional outputs (each may be NULL): idx, loc [T,k] int32; gate_w [T,k] fp32; counts [E] int32; logits [T,E] fp32.
+ *   ws / ws_bytes: at least moe_layer_workspace_bytes(T,M,H,E,k,C,dtype), 256-byte aligned.
+ *   stage_events: NULL, or MOE_NUM_STAGE_EVENTS hipEvent_t handles recorded on `stream` at the stage boundaries
+ *   listed above (for per-stage timing; the events belong to the caller). */
+int moe_layer_forward(const void* x, const void* Wg, const float* gate_bias,
+                      const void* W1, const void* b1, const void* W2, const void* b2,
+                      int64_t T, int64_t M, int64_t H, int64_t E, int k, double f, int normalize, int act, int dtype,
+                      void* out, int32_t* idx, int32_t* loc, float* gate_w, int32_t* counts, float* logits,
+                      void* ws, size_t ws_bytes, void* stream, void* const* stage_events);
+
+/* Thin wrappers over HIP events so that a caller without HIP headers can time on the library's stream.
+ * moe_event_create stores a new hipEvent_t in *event; moe_event_elapsed_ms needs both events completed. */
+int moe_event_create(void** event);
+int moe_event_destroy(void* event);
+int moe_event_record(void* event, void* stream);
+int moe_event_synchronize(void* event);
+int moe_event_elapsed_ms(void* start, void* stop, float* ms);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOE_MI355X_H */

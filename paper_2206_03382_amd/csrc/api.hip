@@ -1,0 +1,216 @@
+// C ABI of the MoE hot-path library: argument validation, workspace layout, stage sequencing.
+#include <cmath>
+
+#include "common.h"
+
+namespace moe {
+hipError_t launch_grouped_gemm_generic(const void* A, const void* B, const void* bias, int act, int dtype,
+                                       const int32_t* counts, int64_t E, int64_t C, int64_t K, int64_t N, void* out,
+                                       hipStream_t s);
+hipError_t launch_grouped_gemm_mfma(const void* A, const void* B, const void* bias, int act, const int32_t* counts,
+                                    int64_t E, int64_t C, int64_t K, int64_t N, void* out, hipStream_t s);
+bool grouped_gemm_mfma_supports(int64_t E, int64_t C, int64_t K, int64_t N);
+
+hipError_t launch_grouped_gemm(const void* A, const void* B, const void* bias, int act, int dtype, const int32_t* counts,
+                               int64_t E, int64_t C, int64_t K, int64_t N, void* out, hipStream_t s) {
+  if (dtype == MOE_BF16 && grouped_gemm_mfma_supports(E, C, K, N))
+    return launch_grouped_gemm_mfma(A, B, bias, act, counts, E, C, K, N, out, s);
+  return launch_grouped_gemm_generic(A, B, bias, act, dtype, counts, E, C, K, N, out, s);
+}
+
+namespace {
+
+inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+inline bool dtype_ok(int d) { return d == MOE_F32 || d == MOE_BF16; }
+inline bool act_ok(int a) { return a == MOE_ACT_RELU || a == MOE_ACT_GELU || a == MOE_ACT_SILU; }
+inline size_t esize(int d) { return d == MOE_F32 ? 4 : 2; }
+constexpr int64_t kMaxDim = (int64_t)1 << 30;
+
+inline int gate_shape_status(int64_t T, int64_t E, int k) {
+  if (T < 1 || E < 1 || k < 1 || k > E || T > kMaxDim) return MOE_INVALID_ARG;
+  if (E > 512 || (int64_t)k * E > 16384) return MOE_UNSUPPORTED;
+  return MOE_OK;
+}
+
+inline int row_shape_status(int64_t M) {
+  if (M < 1 || M > kMaxDim) return MOE_INVALID_ARG;
+  if (M % 8 != 0) return MOE_UNSUPPORTED;
+  return MOE_OK;
+}
+
+struct LayerWorkspace {
+  size_t logits, idx, loc, gate_w, counts, slot_src, gate_ws, Z, hidden, Y, total;
+};
+
+LayerWorkspace layer_layout(int64_t T, int64_t M, int64_t H, int64_t E, int k, int64_t C, int dtype) {
+  LayerWorkspace w;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { const size_t at = off; off = align_up(off + bytes, 256); return at; };
+  w.logits = take((size_t)T * E * 4);
+  w.idx = take((size_t)T * k * 4);
+  w.loc = take((size_t)T * k * 4);
+  w.gate_w = take((size_t)T * k * 4);
+  w.counts = take((size_t)E * 4);
+  w.slot_src = take((size_t)E * C * 4);
+  w.gate_ws = take(moe_gate_workspace_bytes(T, E, k));
+  w.Z = take((size_t)E * C * M * esize(dtype));
+  w.hidden = take((size_t)E * C * H * esize(dtype));
+  w.Y = take((size_t)E * C * M * esize(dtype));
+  w.total = off;
+  return w;
+}
+
+}  // namespace
+}  // namespace moe
+
+using namespace moe;
+
+extern "C" {
+
+const char* moe_status_string(int status) {
+  switch (status) {
+    case MOE_OK: return "ok";
+    case MOE_INVALID_ARG: return "invalid argument";
+    case MOE_UNSUPPORTED: return "unsupported shape, dtype or alignment";
+    case MOE_WORKSPACE_TOO_SMALL: return "workspace too small";
+    case MOE_HIP_ERROR: return "HIP runtime error";
+    default: return "unknown status";
+  }
+}
+
+int64_t moe_capacity(int64_t T, int64_t E, int k, double f) {
+  if (T < 1 || E < 1 || k < 1 || k > E || !(f > 0.0)) return -1;
+  return (int64_t)std::ceil((double)k * f * (double)T / (double)E);
+}
+
+size_t moe_gate_workspace_bytes(int64_t T, int64_t E, int k) {
+  if (gate_shape_status(T, E, k) != MOE_OK) return 0;
+  return (size_t)k * (size_t)ceil_div(T, kGateTokensPerBlock) * (size_t)E * sizeof(int32_t);
+}
+
+size_t moe_layer_workspace_bytes(int64_t T, int64_t M, int64_t H, int64_t E, int k, int64_t C, int dtype) {
+  if (gate_shape_status(T, E, k) != MOE_OK || row_shape_status(M) != MOE_OK || row_shape_status(H) != MOE_OK || C < 1 ||
+      C > kMaxDim || !dtype_ok(dtype))
+    return 0;
+  return layer_layout(T, M, H, E, k, C, dtype).total;
+}
+
+int moe_gate_logits(const void* x, const void* Wg, const float* gate_bias, int dtype, int64_t T, int64_t M, int64_t E,
+                    float* logits, void* stream) {
+  if (!x || !Wg || !logits || !dtype_ok(dtype) || T < 1 || E < 1 || T > kMaxDim || E > kMaxDim) return MOE_INVALID_ARG;
+  if (int st = row_shape_status(M)) return st;
+  if (!aligned(x, 16) || !aligned(Wg, 2) || !aligned(logits, 4)) return MOE_UNSUPPORTED;
+  return launch_gate_logits(x, Wg, gate_bias, dtype, T, M, E, logits, (hipStream_t)stream) == hipSuccess ? MOE_OK : MOE_HIP_ERROR;
+}
+
+int moe_gate_topk(const float* logits, int64_t T, int64_t E, int k, int64_t C, int normalize, int32_t* idx, float* gate_w,
+                  int32_t* loc, int32_t* counts, int32_t* slot_src, void* ws, size_t ws_bytes, void* stream) {
+  if (!logits || !idx || !gate_w || !loc || !counts || !ws || C < 1 || C > kMaxDim) return MOE_INVALID_ARG;
+  if (int st = gate_shape_status(T, E, k)) return st;
+  if (!aligned(ws, 16)) return MOE_UNSUPPORTED;
+  if (ws_bytes < moe_gate_workspace_bytes(T, E, k)) return MOE_WORKSPACE_TOO_SMALL;
+  return launch_gate_topk(logits, T, E, k, C, normalize, idx, gate_w, loc, counts, slot_src, (int32_t*)ws,
+                          (hipStream_t)stream) == hipSuccess ? MOE_OK : MOE_HIP_ERROR;
+}
+
+int moe_encode(const void* x, int dtype, const int32_t* idx, const int32_t* loc, const int32_t* slot_src, int64_t T,
+               int64_t M, int64_t E, int k, int64_t C, void* Z, void* stream) {
+  if (!x || !idx || !loc || !Z || !dtype_ok(dtype) || T < 1 || E < 1 || k < 1 || k > E || C < 1 || T > kMaxDim ||
+      E > kMaxDim || C > kMaxDim)
+    return MOE_INVALID_ARG;
+  if (int st = row_shape_status(M)) return st;
+  if (!aligned(x, 16) || !aligned(Z, 16)) return MOE_UNSUPPORTED;
+  return launch_encode(x, dtype, idx, loc, slot_src, T, M, E, k, C, Z, (hipStream_t)stream) == hipSuccess ? MOE_OK : MOE_HIP_ERROR;
+}
+
+int moe_expert_ffn(const void* Z, const void* W1, const void* b1, const void* W2, const void* b2, int act, int dtype,
+                   const int32_t* counts, int64_t E, int64_t C, int64_t M, int64_t H, void* hidden, void* Y, void* stream) {
+  if (!Z || !W1 || !W2 || !hidden || !Y || !dtype_ok(dtype) || !act_ok(act) || E < 1 || C < 1 || E > 65535 || C > kMaxDim)
+    return MOE_INVALID_ARG;
+  if (int st = row_shape_status(M)) return st;
+  if (int st = row_shape_status(H)) return st;
+  if (!aligned(Z, 16) || !aligned(W1, 16) || !aligned(W2, 16) || !aligned(hidden, 16) || !aligned(Y, 16)) return MOE_UNSUPPORTED;
+  hipStream_t s = (hipStream_t)stream;
+  if (launch_grouped_gemm(Z, W1, b1, act, dtype, counts, E, C, M, H, hidden, s) != hipSuccess) return MOE_HIP_ERROR;
+  if (launch_grouped_gemm(hidden, W2, b2, -1, dtype, counts, E, C, H, M, Y, s) != hipSuccess) return MOE_HIP_ERROR;
+  return MOE_OK;
+}
+
+int moe_decode(const void* Y, int dtype, const int32_t* idx, const int32_t* loc, const float* gate_w, int64_t T, int64_t M,
+               int64_t E, int k, int64_t C, void* out, void* stream) {
+  if (!Y || !idx || !loc || !gate_w || !out || !dtype_ok(dtype) || T < 1 || E < 1 || k < 1 || k > E || C < 1 ||
+      T > kMaxDim || E > kMaxDim || C > kMaxDim)
+    return MOE_INVALID_ARG;
+  if (int st = row_shape_status(M)) return st;
+  if (!aligned(Y, 16) || !aligned(out, 16)) return MOE_UNSUPPORTED;
+  return launch_decode(Y, dtype, idx, loc, gate_w, T, M, E, k, C, out, (hipStream_t)stream) == hipSuccess ? MOE_OK : MOE_HIP_ERROR;
+}
+
+int moe_layer_forward(const void* x, const void* Wg, const float* gate_bias, const void* W1, const void* b1, const void* W2,
+                      const void* b2, int64_t T, int64_t M, int64_t H, int64_t E, int k, double f, int normalize, int act,
+                      int dtype, void* out, int32_t* idx, int32_t* loc, float* gate_w, int32_t* counts, float* logits,
+                      void* ws, size_t ws_bytes, void* stream, void* const* stage_events) {
+  if (!x || !Wg || !W1 || !W2 || !out || !ws || !dtype_ok(dtype) || !act_ok(act) || !(f > 0.0)) return MOE_INVALID_ARG;
+  if (int st = gate_shape_status(T, E, k)) return st;
+  if (int st = row_shape_status(M)) return st;
+  if (int st = row_shape_status(H)) return st;
+  const int64_t C = moe_capacity(T, E, k, f);
+  if (C < 1 || C > kMaxDim) return MOE_INVALID_ARG;
+  if (!aligned(x, 16) || !aligned(W1, 16) || !aligned(W2, 16) || !aligned(out, 16) || !aligned(ws, 256)) return MOE_UNSUPPORTED;
+  const LayerWorkspace w = layer_layout(T, M, H, E, k, C, dtype);
+  if (ws_bytes < w.total) return MOE_WORKSPACE_TOO_SMALL;
+  if (stage_events)
+    for (int i = 0; i < MOE_NUM_STAGE_EVENTS; ++i)
+      if (!stage_events[i]) return MOE_INVALID_ARG;
+
+  char* base = (char*)ws;
+  float* d_logits = logits ? logits : (float*)(base + w.logits);
+  int32_t* d_idx = idx ? idx : (int32_t*)(base + w.idx);
+  int32_t* d_loc = loc ? loc : (int32_t*)(base + w.loc);
+  float* d_gw = gate_w ? gate_w : (float*)(base + w.gate_w);
+  int32_t* d_counts = counts ? counts : (int32_t*)(base + w.counts);
+  int32_t* d_src = (int32_t*)(base + w.slot_src);
+  int32_t* d_gws = (int32_t*)(base + w.gate_ws);
+  void* d_Z = base + w.Z;
+  void* d_hidden = base + w.hidden;
+  void* d_Y = base + w.Y;
+  hipStream_t s = (hipStream_t)stream;
+  int stage = 0;
+  auto mark = [&]() -> bool { return !stage_events || hipEventRecord((hipEvent_t)stage_events[stage++], s) == hipSuccess; };
+
+  if (!mark()) return MOE_HIP_ERROR;
+  if (launch_gate_logits(x, Wg, gate_bias, dtype, T, M, E, d_logits, s) != hipSuccess || !mark()) return MOE_HIP_ERROR;
+  if (launch_gate_topk(d_logits, T, E, k, C, normalize, d_idx, d_gw, d_loc, d_counts, d_src, d_gws, s) != hipSuccess || !mark())
+    return MOE_HIP_ERROR;
+  if (launch_encode(x, dtype, d_idx, d_loc, d_src, T, M, E, k, C, d_Z, s) != hipSuccess || !mark()) return MOE_HIP_ERROR;
+  if (launch_grouped_gemm(d_Z, W1, b1, act, dtype, d_counts, E, C, M, H, d_hidden, s) != hipSuccess || !mark()) return MOE_HIP_ERROR;
+  if (launch_grouped_gemm(d_hidden, W2, b2, -1, dtype, d_counts, E, C, H, M, d_Y, s) != hipSuccess || !mark()) return MOE_HIP_ERROR;
+  if (launch_decode(d_Y, dtype, d_idx, d_loc, d_gw, T, M, E, k, C, out, s) != hipSuccess || !mark()) return MOE_HIP_ERROR;
+  return MOE_OK;
+}
+
+int moe_event_create(void** event) {
+  if (!event) return MOE_INVALID_ARG;
+  hipEvent_t ev;
+  if (hipEventCreate(&ev) != hipSuccess) return MOE_HIP_ERROR;
+  *event = (void*)ev;
+  return MOE_OK;
+}
+int moe_event_destroy(void* event) {
+  if (!event) return MOE_INVALID_ARG;
+  return hipEventDestroy((hipEvent_t)event) == hipSuccess ? MOE_OK : MOE_HIP_ERROR;
+}
+int moe_event_record(void* event, void* stream) {
+  if (!event) return MOE_INVALID_ARG;
+  return hipEventRecord((hipEvent_t)event, (hipStream_t)stream) == hipSuccess ? MOE_OK : MOE_HIP_ERROR;
+}
+int moe_event_synchronize(void* event) {
+  if (!event) return MOE_INVALID_ARG;
+  return hipEventSynchronize((hipEvent_t)event) == hipSuccess ? MOE_OK : MOE_HIP_ERROR;
+}
+int moe_event_elapsed_ms(void* start, void* stop, float* ms) {
+  if (!start || !stop || !ms) return MOE_INVALID_ARG;
+  return hipEventElapsedTime(ms, (hipEvent_t)start, (hipEvent_t)stop) == hipSuccess ? MOE_OK : MOE_HIP_ERROR;
+}
+
+}  // extern "C"

@@ -1,0 +1,56 @@
+// Shared device helpers and internal launcher declarations of the MoE hot-path library (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/moe_mi355x.h"
+
+namespace moe {
+
+constexpr int kWave = 64;            // CDNA wavefront width
+constexpr int kGateTokensPerBlock = 256;   // tokens whose arrivals one gate block counts and ranks
+
+__device__ __forceinline__ float bf16_bits_to_f32(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+
+// round-to-nearest-even fp32 -> bf16 bit pattern (NaN stays NaN)
+__device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+template <typename T> __device__ __forceinline__ float load_as_f32(const T* p);
+template <> __device__ __forceinline__ float load_as_f32<float>(const float* p) { return *p; }
+template <> __device__ __forceinline__ float load_as_f32<uint16_t>(const uint16_t* p) { return bf16_bits_to_f32(*p); }
+
+template <typename T> __device__ __forceinline__ void store_from_f32(T* p, float v);
+template <> __device__ __forceinline__ void store_from_f32<float>(float* p, float v) { *p = v; }
+template <> __device__ __forceinline__ void store_from_f32<uint16_t>(uint16_t* p, float v) { *p = f32_to_bf16_bits(v); }
+
+__device__ __forceinline__ float apply_act(float v, int act) {
+  if (act == MOE_ACT_RELU) return v > 0.f ? v : 0.f;
+  if (act == MOE_ACT_GELU) return 0.5f * v * (1.0f + erff(v * 0.70710678118654752440f));
+  return v / (1.0f + __expf(-v));
+}
+
+static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+static inline size_t align_up(size_t a, size_t b) { return (a + b - 1) / b * b; }
+
+// ---- launchers (defined in gate.hip / dispatch.hip / ffn.hip); arguments are already validated ----------------
+hipError_t launch_gate_logits(const void* x, const void* Wg, const float* bias, int dtype, int64_t T, int64_t M,
+                              int64_t E, float* logits, hipStream_t s);
+hipError_t launch_gate_topk(const float* logits, int64_t T, int64_t E, int k, int64_t C, int normalize, int32_t* idx,
+                            float* gate_w, int32_t* loc, int32_t* counts, int32_t* slot_src, int32_t* block_counts,
+                            hipStream_t s);
+hipError_t launch_encode(const void* x, int dtype, const int32_t* idx, const int32_t* loc, const int32_t* slot_src,
+                         int64_t T, int64_t M, int64_t E, int k, int64_t C, void* Z, hipStream_t s);
+hipError_t launch_decode(const void* Y, int dtype, const int32_t* idx, const int32_t* loc, const float* gate_w,
+                         int64_t T, int64_t M, int64_t E, int k, int64_t C, void* out, hipStream_t s);
+// One grouped GEMM: out[e] = epilogue(A[e] (rows_e x K) * B[e] (K x N) + bias[e]); A [E,C,K], B [E,K,N], out [E,C,N].
+// act < 0 means no activation.
+hipError_t launch_grouped_gemm(const void* A, const void* B, const void* bias, int act, int dtype, const int32_t* counts,
+                               int64_t E, int64_t C, int64_t K, int64_t N, void* out, hipStream_t s);
+
+}  // namespace moe

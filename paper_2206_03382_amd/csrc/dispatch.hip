@@ -1,0 +1,155 @@
+// Fast encode / decode (arXiv 2206.03382 Sec. 4.2 and Appendix B): the sparse O(T*k*M) form of the one-hot-mask
+// dispatch and combine contractions.  Pure data movement, bound by HBM: every lane moves 16-byte pieces, a wave
+// moves whole rows, rows of one wave are adjacent in the destination so stores are fully coalesced.
+#include "common.h"
+
+namespace moe {
+
+// --- encode, gather form: one pass over the [E*C] slots; slot_src says which token row (or none) lands there -----
+template <int ROWS>
+__global__ __launch_bounds__(256) void encode_gather_kernel(const uint4* __restrict__ x, const int32_t* __restrict__ slot_src,
+                                                            int64_t nrows, int64_t T, int cpr, uint4* __restrict__ Z) {
+  const int lane = threadIdx.x & 63;
+  const int64_t wave = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * 4 + (threadIdx.x >> 6)));
+  const int64_t nwaves = (int64_t)gridDim.x * 4;
+  for (int64_t r0 = wave * ROWS; r0 < nrows; r0 += nwaves * ROWS) {
+    int src[ROWS];
+#pragma unroll
+    for (int i = 0; i < ROWS; ++i) src[i] = (r0 + i < nrows) ? slot_src[r0 + i] : -2;
+    for (int c = lane; c < cpr; c += 64) {
+      uint4 v[ROWS];
+#pragma unroll
+      for (int i = 0; i < ROWS; ++i) v[i] = (src[i] >= 0 && src[i] < T) ? x[(int64_t)src[i] * cpr + c] : make_uint4(0, 0, 0, 0);
+#pragma unroll
+      for (int i = 0; i < ROWS; ++i)
+        if (src[i] != -2) Z[(r0 + i) * cpr + c] = v[i];
+    }
+  }
+}
+
+// --- encode, scatter form (no slot_src): zero-fill, then every token row goes to its kept slots ------------------
+__global__ __launch_bounds__(256) void zero_fill_kernel(uint4* __restrict__ p, int64_t n16) {
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (int64_t)gridDim.x * 256) p[i] = make_uint4(0, 0, 0, 0);
+}
+
+__global__ __launch_bounds__(256) void encode_scatter_kernel(const uint4* __restrict__ x, const int32_t* __restrict__ idx,
+                                                             const int32_t* __restrict__ loc, int64_t T, int E, int k,
+                                                             int64_t C, int cpr, uint4* __restrict__ Z) {
+  const int lane = threadIdx.x & 63;
+  const int64_t wave = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * 4 + (threadIdx.x >> 6)));
+  const int64_t nwaves = (int64_t)gridDim.x * 4;
+  for (int64_t t = wave; t < T; t += nwaves) {
+    for (int j = 0; j < k; ++j) {
+      const int e = idx[t * k + j], l = loc[t * k + j];
+      if (l < 0 || l >= C || (unsigned)e >= (unsigned)E) continue;   // dropped (or invalid) choice
+      const int64_t row = (int64_t)e * C + l;
+      for (int c = lane; c < cpr; c += 64) Z[row * cpr + c] = x[t * cpr + c];
+    }
+  }
+}
+
+hipError_t launch_encode(const void* x, int dtype, const int32_t* idx, const int32_t* loc, const int32_t* slot_src,
+                         int64_t T, int64_t M, int64_t E, int k, int64_t C, void* Z, hipStream_t s) {
+  const int es = (dtype == MOE_F32) ? 4 : 2;
+  const int cpr = (int)(M * es / 16);
+  const int64_t nrows = E * C;
+  if (slot_src) {
+    constexpr int ROWS = 4;
+    const int64_t blocks = ceil_div(nrows, 4 * ROWS);
+    const unsigned grid = (unsigned)(blocks < 8192 ? blocks : 8192);
+    encode_gather_kernel<ROWS><<<dim3(grid), dim3(256), 0, s>>>((const uint4*)x, slot_src, nrows, T, cpr, (uint4*)Z);
+    return hipGetLastError();
+  }
+  const int64_t n16 = nrows * cpr;
+  const int64_t zb = ceil_div(n16, 256 * 8);
+  zero_fill_kernel<<<dim3((unsigned)(zb < 16384 ? (zb > 0 ? zb : 1) : 16384)), dim3(256), 0, s>>>((uint4*)Z, n16);
+  hipError_t err = hipGetLastError();
+  if (err != hipSuccess) return err;
+  const int64_t sb = ceil_div(T, 4);
+  encode_scatter_kernel<<<dim3((unsigned)(sb < 8192 ? sb : 8192)), dim3(256), 0, s>>>((const uint4*)x, idx, loc, T, (int)E, k, C, cpr, (uint4*)Z);
+  return hipGetLastError();
+}
+
+// --- decode: out[t,:] = sum_j kept gate_w[t,j] * Y[idx[t,j], loc[t,j], :], fp32 accumulation in rank order -------
+template <typename ET> struct Pack16;
+template <> struct Pack16<float> {
+  static constexpr int N = 4;
+  static __device__ __forceinline__ void unpack(const uint4& v, float (&f)[4]) {
+    f[0] = __uint_as_float(v.x); f[1] = __uint_as_float(v.y); f[2] = __uint_as_float(v.z); f[3] = __uint_as_float(v.w);
+  }
+  static __device__ __forceinline__ uint4 pack(const float (&f)[4]) {
+    return make_uint4(__float_as_uint(f[0]), __float_as_uint(f[1]), __float_as_uint(f[2]), __float_as_uint(f[3]));
+  }
+};
+template <> struct Pack16<uint16_t> {
+  static constexpr int N = 8;
+  static __device__ __forceinline__ void unpack(const uint4& v, float (&f)[8]) {
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      f[2 * i] = __uint_as_float(w[i] << 16);
+      f[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+    }
+  }
+  static __device__ __forceinline__ uint4 pack(const float (&f)[8]) {
+    uint32_t w[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) w[i] = (uint32_t)f32_to_bf16_bits(f[2 * i]) | ((uint32_t)f32_to_bf16_bits(f[2 * i + 1]) << 16);
+    return make_uint4(w[0], w[1], w[2], w[3]);
+  }
+};
+
+template <typename ET>
+__global__ __launch_bounds__(256) void decode_kernel(const uint4* __restrict__ Y, const int32_t* __restrict__ idx,
+                                                     const int32_t* __restrict__ loc, const float* __restrict__ gate_w,
+                                                     int64_t T, int E, int k, int64_t C, int cpr, uint4* __restrict__ out) {
+  constexpr int N = Pack16<ET>::N;
+  const int lane = threadIdx.x & 63;
+  const int64_t wave = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * 4 + (threadIdx.x >> 6)));
+  const int64_t nwaves = (int64_t)gridDim.x * 4;
+  for (int64_t t = wave; t < T; t += nwaves) {
+    for (int c = lane; c < cpr; c += 64) {
+      float acc[N];
+#pragma unroll
+      for (int i = 0; i < N; ++i) acc[i] = 0.f;
+      for (int j0 = 0; j0 < k; j0 += 4) {
+        uint4 v[4];
+        float w[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int j = j0 + u;
+          w[u] = 0.f;
+          v[u] = make_uint4(0, 0, 0, 0);
+          if (j < k) {
+            const int l = loc[t * k + j], e = idx[t * k + j];
+            if (l >= 0 && l < C && (unsigned)e < (unsigned)E) {           // kept choice
+              w[u] = gate_w[t * k + j];
+              v[u] = Y[((int64_t)e * C + l) * cpr + c];
+            }
+          }
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          float f[N];
+          Pack16<ET>::unpack(v[u], f);
+#pragma unroll
+          for (int i = 0; i < N; ++i) acc[i] = fmaf(w[u], f[i], acc[i]);
+        }
+      }
+      out[t * cpr + c] = Pack16<ET>::pack(acc);
+    }
+  }
+}
+
+hipError_t launch_decode(const void* Y, int dtype, const int32_t* idx, const int32_t* loc, const float* gate_w,
+                         int64_t T, int64_t M, int64_t E, int k, int64_t C, void* out, hipStream_t s) {
+  const int es = (dtype == MOE_F32) ? 4 : 2;
+  const int cpr = (int)(M * es / 16);
+  const int64_t blocks = ceil_div(T, 4);
+  const dim3 grid((unsigned)(blocks < 16384 ? blocks : 16384)), block(256);
+  if (dtype == MOE_F32) decode_kernel<float><<<grid, block, 0, s>>>((const uint4*)Y, idx, loc, gate_w, T, (int)E, k, C, cpr, (uint4*)out);
+  else decode_kernel<uint16_t><<<grid, block, 0, s>>>((const uint4*)Y, idx, loc, gate_w, T, (int)E, k, C, cpr, (uint4*)out);
+  return hipGetLastError();
+}
+
+}  // namespace moe

@@ -1,0 +1,221 @@
+"""Thin ctypes binding of libmoe_mi355x.so: argument marshalling only.
+
+Every step of the path (gate, slot assignment, encode, expert FFN, decode) runs in the library's HIP kernels;
+PyTorch is used for device memory and the current stream.  There is no CPU fallback: if the library has not
+been built, or no GPU is present, calls raise.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Dict, Optional, Sequence
+
+import torch
+
+OK, INVALID_ARG, UNSUPPORTED, WORKSPACE_TOO_SMALL, HIP_ERROR = range(5)
+F32, BF16 = 0, 1
+ACT_RELU, ACT_GELU, ACT_SILU = 0, 1, 2
+NUM_STAGE_EVENTS = 7
+STAGE_NAMES = ("gate_logits", "gate_topk", "encode", "ffn_gemm1", "ffn_gemm2", "decode")
+
+LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libmoe_mi355x.so")
+
+_c = ctypes
+_vp, _i64, _i32, _sz, _dbl = _c.c_void_p, _c.c_int64, _c.c_int, _c.c_size_t, _c.c_double
+
+# name -> (restype, argtypes); mirrors include/moe_mi355x.h
+SIGNATURES = {
+    "moe_status_string": (_c.c_char_p, [_i32]),
+    "moe_capacity": (_i64, [_i64, _i64, _i32, _dbl]),
+    "moe_gate_workspace_bytes": (_sz, [_i64, _i64, _i32]),
+    "moe_layer_workspace_bytes": (_sz, [_i64, _i64, _i64, _i64, _i32, _i64, _i32]),
+    "moe_gate_logits": (_i32, [_vp, _vp, _vp, _i32, _i64, _i64, _i64, _vp, _vp]),
+    "moe_gate_topk": (_i32, [_vp, _i64, _i64, _i32, _i64, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "moe_encode": (_i32, [_vp, _i32, _vp, _vp, _vp, _i64, _i64, _i64, _i32, _i64, _vp, _vp]),
+    "moe_expert_ffn": (_i32, [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _i64, _i64, _i64, _i64, _vp, _vp, _vp]),
+    "moe_decode": (_i32, [_vp, _i32, _vp, _vp, _vp, _i64, _i64, _i64, _i32, _i64, _vp, _vp]),
+    "moe_layer_forward": (_i32, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _i64, _i32, _dbl, _i32, _i32, _i32,
+                                 _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp, _c.POINTER(_vp)]),
+    "moe_event_create": (_i32, [_c.POINTER(_vp)]),
+    "moe_event_destroy": (_i32, [_vp]),
+    "moe_event_record": (_i32, [_vp, _vp]),
+    "moe_event_synchronize": (_i32, [_vp]),
+    "moe_event_elapsed_ms": (_i32, [_vp, _vp, _c.POINTER(_c.c_float)]),
+}
+
+_lib = None
+
+
+class MoEError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {lib().moe_status_string(status).decode()} (status {status})")
+
+
+def lib() -> ctypes.CDLL:
+    """Loads the HIP library on first use; fails loudly if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2206_03382_amd.build` "
+                               "(there is no fallback path)")
+        handle = ctypes.CDLL(LIB_PATH)
+        for name, (res, args) in SIGNATURES.items():
+            fn = getattr(handle, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = handle
+    return _lib
+
+
+def _check(status: int, where: str) -> None:
+    if status != OK:
+        raise MoEError(status, where)
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError(f"unsupported storage dtype {t.dtype}")
+
+
+def _p(t: Optional[torch.Tensor]):
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("tensors must be contiguous device tensors")
+    return t.data_ptr()
+
+
+def _stream():
+    return torch.cuda.current_stream().cuda_stream
+
+
+def capacity(T: int, E: int, k: int, f: float) -> int:
+    return int(lib().moe_capacity(T, E, k, float(f)))
+
+
+def gate_workspace_bytes(T: int, E: int, k: int) -> int:
+    return int(lib().moe_gate_workspace_bytes(T, E, k))
+
+
+def layer_workspace_bytes(T: int, M: int, H: int, E: int, k: int, C: int, dtype: int) -> int:
+    return int(lib().moe_layer_workspace_bytes(T, M, H, E, k, C, dtype))
+
+
+def gate_logits(x: torch.Tensor, Wg: torch.Tensor, gate_bias: Optional[torch.Tensor] = None) -> torch.Tensor:
+    T, M = x.shape
+    E = Wg.shape[1]
+    logits = torch.empty((T, E), dtype=torch.float32, device=x.device)
+    _check(lib().moe_gate_logits(_p(x), _p(Wg), _p(gate_bias), _dtype_code(x), T, M, E, _p(logits), _stream()), "moe_gate_logits")
+    return logits
+
+
+def gate_topk(logits: torch.Tensor, k: int, C: int, normalize: int, want_slot_src: bool = True) -> Dict[str, torch.Tensor]:
+    T, E = logits.shape
+    dev = logits.device
+    idx = torch.empty((T, k), dtype=torch.int32, device=dev)
+    loc = torch.empty((T, k), dtype=torch.int32, device=dev)
+    gate_w = torch.empty((T, k), dtype=torch.float32, device=dev)
+    counts = torch.empty((E,), dtype=torch.int32, device=dev)
+    slot_src = torch.empty((E, C), dtype=torch.int32, device=dev) if want_slot_src else None
+    nbytes = gate_workspace_bytes(T, E, k)
+    ws = torch.empty((max(nbytes, 16),), dtype=torch.uint8, device=dev)
+    _check(lib().moe_gate_topk(_p(logits), T, E, k, C, int(normalize), _p(idx), _p(gate_w), _p(loc), _p(counts), _p(slot_src),
+                               _p(ws), ws.numel(), _stream()), "moe_gate_topk")
+    return dict(idx=idx, loc=loc, gate_w=gate_w, counts=counts, slot_src=slot_src)
+
+
+def encode(x: torch.Tensor, idx: torch.Tensor, loc: torch.Tensor, slot_src: Optional[torch.Tensor], E: int, C: int) -> torch.Tensor:
+    T, M = x.shape
+    k = idx.shape[1]
+    Z = torch.empty((E, C, M), dtype=x.dtype, device=x.device)
+    _check(lib().moe_encode(_p(x), _dtype_code(x), _p(idx), _p(loc), _p(slot_src), T, M, E, k, C, _p(Z), _stream()), "moe_encode")
+    return Z
+
+
+def expert_ffn(Z: torch.Tensor, W1: torch.Tensor, b1: Optional[torch.Tensor], W2: torch.Tensor, b2: Optional[torch.Tensor],
+               act: int, counts: Optional[torch.Tensor] = None, Y: Optional[torch.Tensor] = None,
+               hidden: Optional[torch.Tensor] = None) -> torch.Tensor:
+    E, C, M = Z.shape
+    H = W1.shape[2]
+    if Y is None:
+        Y = torch.empty((E, C, M), dtype=Z.dtype, device=Z.device)
+    if hidden is None:
+        hidden = torch.empty((E, C, H), dtype=Z.dtype, device=Z.device)
+    _check(lib().moe_expert_ffn(_p(Z), _p(W1), _p(b1), _p(W2), _p(b2), act, _dtype_code(Z), _p(counts), E, C, M, H,
+                                _p(hidden), _p(Y), _stream()), "moe_expert_ffn")
+    return Y
+
+
+def decode(Y: torch.Tensor, idx: torch.Tensor, loc: torch.Tensor, gate_w: torch.Tensor) -> torch.Tensor:
+    E, C, M = Y.shape
+    T, k = idx.shape
+    out = torch.empty((T, M), dtype=Y.dtype, device=Y.device)
+    _check(lib().moe_decode(_p(Y), _dtype_code(Y), _p(idx), _p(loc), _p(gate_w), T, M, E, k, C, _p(out), _stream()), "moe_decode")
+    return out
+
+
+class StageEvents:
+    """MOE_NUM_STAGE_EVENTS HIP events, recorded by moe_layer_forward on its stream at the stage boundaries."""
+
+    def __init__(self):
+        self.handles = (_vp * NUM_STAGE_EVENTS)()
+        for i in range(NUM_STAGE_EVENTS):
+            ev = _vp()
+            _check(lib().moe_event_create(ctypes.byref(ev)), "moe_event_create")
+            self.handles[i] = ev
+
+    def stage_ms(self) -> Sequence[float]:
+        _check(lib().moe_event_synchronize(self.handles[NUM_STAGE_EVENTS - 1]), "moe_event_synchronize")
+        out = []
+        for i in range(NUM_STAGE_EVENTS - 1):
+            ms = ctypes.c_float()
+            _check(lib().moe_event_elapsed_ms(self.handles[i], self.handles[i + 1], ctypes.byref(ms)), "moe_event_elapsed_ms")
+            out.append(ms.value)
+        return out
+
+    def close(self):
+        for h in self.handles:
+            if h:
+                lib().moe_event_destroy(h)
+        self.handles = (_vp * NUM_STAGE_EVENTS)()
+
+
+class MoELayer:
+    """Holds the layer's parameters, output and workspace so that `forward` allocates nothing."""
+
+    def __init__(self, Wg, gate_bias, W1, b1, W2, b2, T: int, k: int, f: float, normalize: int, act: int,
+                 keep_routing: bool = False):
+        self.Wg, self.gate_bias, self.W1, self.b1, self.W2, self.b2 = Wg, gate_bias, W1, b1, W2, b2
+        self.E, self.M, self.H = W1.shape
+        self.T, self.k, self.f, self.normalize, self.act = T, k, float(f), int(normalize), int(act)
+        self.dtype = _dtype_code(W1)
+        self.C = capacity(T, self.E, k, f)
+        if self.C < 1:
+            raise MoEError(INVALID_ARG, "moe_capacity")
+        nbytes = layer_workspace_bytes(T, self.M, self.H, self.E, k, self.C, self.dtype)
+        if nbytes == 0:
+            raise MoEError(UNSUPPORTED, "moe_layer_workspace_bytes")
+        dev = W1.device
+        self.ws = torch.empty((nbytes,), dtype=torch.uint8, device=dev)
+        self.out = torch.empty((T, self.M), dtype=W1.dtype, device=dev)
+        self.routing = None
+        if keep_routing:
+            self.routing = dict(idx=torch.empty((T, k), dtype=torch.int32, device=dev),
+                                loc=torch.empty((T, k), dtype=torch.int32, device=dev),
+                                gate_w=torch.empty((T, k), dtype=torch.float32, device=dev),
+                                counts=torch.empty((self.E,), dtype=torch.int32, device=dev),
+                                logits=torch.empty((T, self.E), dtype=torch.float32, device=dev))
+
+    def forward(self, x: torch.Tensor, events: Optional[StageEvents] = None) -> torch.Tensor:
+        if tuple(x.shape) != (self.T, self.M) or _dtype_code(x) != self.dtype:
+            raise ValueError(f"x must be [{self.T}, {self.M}] in the layer's storage dtype")
+        r = self.routing or {}
+        ev = events.handles if events is not None else None
+        _check(lib().moe_layer_forward(_p(x), _p(self.Wg), _p(self.gate_bias), _p(self.W1), _p(self.b1), _p(self.W2), _p(self.b2),
+                                       self.T, self.M, self.H, self.E, self.k, self.f, self.normalize, self.act, self.dtype,
+                                       _p(self.out), _p(r.get("idx")), _p(r.get("loc")), _p(r.get("gate_w")), _p(r.get("counts")),
+                                       _p(r.get("logits")), _p(self.ws), self.ws.numel(), _stream(), ev), "moe_layer_forward")
+        return self.out

@@ -1,0 +1,81 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every declared symbol, and its pure
+host functions (capacity, workspace sizes, argument validation) behave as the header says."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "moe_mi355x.h")
+
+
+@pytest.fixture(scope="module")
+def moe():
+    from paper_2206_03382_amd import moe as m
+    if not os.path.exists(m.LIB_PATH):
+        from paper_2206_03382_amd.build import build_library
+        build_library(verbose=False)
+    m.lib()
+    return m
+
+
+def declared_functions():
+    text = re.sub(r"/\*.*?\*/", "", open(HEADER).read(), flags=re.S)
+    return sorted(set(re.findall(r"\b(moe_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported_and_bound(moe):
+    names = declared_functions()
+    assert {"moe_gate_topk", "moe_encode", "moe_expert_ffn", "moe_decode", "moe_layer_forward"} <= set(names)
+    handle = ctypes.CDLL(moe.LIB_PATH)
+    for n in names:
+        assert hasattr(handle, n), f"{n} is declared in the header but not exported"
+    assert sorted(moe.SIGNATURES) == names
+
+
+def test_capacity_follows_eq1(moe, golden_dir):
+    for line in open(os.path.join(golden_dir, "capacity_eq1.txt")):
+        line = line.split("#")[0].strip()
+        if line:
+            T, E, k, f, C = line.split()
+            assert moe.capacity(int(T), int(E), int(k), float(f)) == int(C), line
+    for bad in ((0, 4, 1, 1.0), (8, 0, 1, 1.0), (8, 4, 0, 1.0), (8, 4, 5, 1.0), (8, 4, 1, 0.0), (8, 4, 1, -1.0)):
+        assert moe.capacity(*bad) == -1
+
+
+def test_workspace_sizes(moe):
+    assert moe.gate_workspace_bytes(1000, 8, 2) == 2 * 4 * 8 * 4            # k * ceil(T/256) * E * sizeof(int32)
+    assert moe.gate_workspace_bytes(1000, 8, 9) == 0                       # k > E
+    T, M, H, E, k, C = 16384, 2048, 2048, 8, 2, 5120
+    need = moe.layer_workspace_bytes(T, M, H, E, k, C, moe.BF16)
+    payload = T * E * 4 + 3 * T * k * 4 + E * 4 + E * C * 4 + moe.gate_workspace_bytes(T, E, k) + 2 * E * C * M * 2 + E * C * H * 2
+    assert payload <= need <= payload + 10 * 256
+    assert moe.layer_workspace_bytes(T, M + 4, H, E, k, C, moe.BF16) == 0   # M not a multiple of 8
+    assert moe.layer_workspace_bytes(T, M, H, E, k, C, 7) == 0              # unknown dtype
+
+
+def test_argument_validation_never_launches(moe):
+    L = moe.lib()
+    assert L.moe_status_string(moe.OK) == b"ok" and b"workspace" in L.moe_status_string(moe.WORKSPACE_TOO_SMALL)
+    fake = 4096                                                               # non-null, 16-byte aligned, never dereferenced
+    assert L.moe_gate_topk(None, 8, 4, 1, 2, 0, fake, fake, fake, fake, None, fake, 1 << 20, None) == moe.INVALID_ARG
+    assert L.moe_gate_topk(fake, 8, 4, 5, 2, 0, fake, fake, fake, fake, None, fake, 1 << 20, None) == moe.INVALID_ARG   # k > E
+    assert L.moe_gate_topk(fake, 8, 1024, 1, 2, 0, fake, fake, fake, fake, None, fake, 1 << 20, None) == moe.UNSUPPORTED
+    assert L.moe_gate_topk(fake, 8, 4, 1, 2, 0, fake, fake, fake, fake, None, fake, 1, None) == moe.WORKSPACE_TOO_SMALL
+    assert L.moe_gate_logits(fake, fake, None, moe.BF16, 8, 12, 4, fake, None) == moe.UNSUPPORTED                      # M % 8
+    assert L.moe_encode(fake, 9, fake, fake, None, 8, 16, 4, 1, 2, fake, None) == moe.INVALID_ARG                      # dtype
+    assert L.moe_encode(fake + 2, moe.BF16, fake, fake, None, 8, 16, 4, 1, 2, fake, None) == moe.UNSUPPORTED           # alignment
+    assert L.moe_expert_ffn(fake, fake, None, fake, None, 5, moe.BF16, None, 4, 2, 16, 16, fake, fake, None) == moe.INVALID_ARG
+    assert L.moe_decode(fake, moe.F32, fake, fake, None, 8, 16, 4, 1, 2, fake, None) == moe.INVALID_ARG               # gate_w null
+    assert L.moe_layer_forward(fake, fake, None, fake, None, fake, None, 8, 16, 16, 4, 1, 0.0, 0, 0, moe.F32, fake,
+                               None, None, None, None, None, fake, 1 << 30, None, None) == moe.INVALID_ARG            # f <= 0
+    assert L.moe_layer_forward(fake, fake, None, fake, None, fake, None, 8, 16, 16, 4, 1, 1.0, 0, 0, moe.F32, fake,
+                               None, None, None, None, None, fake, 16, None, None) == moe.WORKSPACE_TOO_SMALL
+
+
+def test_missing_library_fails_loudly(moe, monkeypatch):
+    monkeypatch.setattr(moe, "_lib", None)
+    monkeypatch.setattr(moe, "LIB_PATH", "/nonexistent/libmoe_mi355x.so")
+    with pytest.raises(RuntimeError, match="no fallback"):
+        moe.lib()

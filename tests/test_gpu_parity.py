@@ -1,0 +1,293 @@
+"""Parity of the HIP path (through the C ABI) with the CPU oracle on the same seeded inputs.  Needs an MI355X.
+
+Bars: routing integers (idx, loc, kept, counts, slot_src) bit-exact; encode bit-exact; floating-point outputs within
+max-abs-error <= 1e-5 * max|ref| (fp32 storage) or 2e-2 * max|ref| (bf16 storage) of the fp64 oracle.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import moe_oracle as O
+from paper_2206_03382_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+TOL = {synth.DT_F32: 1e-5, synth.DT_BF16: 2e-2}
+RMS_TOL = {synth.DT_F32: 3e-6, synth.DT_BF16: 6e-3}      # tighter, catches small systematic errors
+
+
+@pytest.fixture(scope="module")
+def moe():
+    assert torch.cuda.is_available(), "these tests need a GPU"
+    from paper_2206_03382_amd import moe as m
+    m.lib()                                   # fails loudly if the HIP library is not built
+    return m
+
+
+def dev(a, dtype):
+    """numpy fp32 values -> device tensor in the storage dtype (bf16 values are already representable: exact)."""
+    if a is None:
+        return None
+    if dtype == synth.DT_BF16:
+        bits = synth.bf16_bits(a)
+        return torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+
+
+def host(t):
+    return t.float().cpu().numpy() if t.dtype == torch.bfloat16 else t.cpu().numpy()
+
+
+def assert_close(got, ref, dtype, what):
+    ref = np.asarray(ref, dtype=np.float64)
+    got = np.asarray(got, dtype=np.float64)
+    assert np.isfinite(got).all(), f"{what}: non-finite values"
+    scale = np.abs(ref).max()
+    err = np.abs(got - ref).max()
+    assert err <= TOL[dtype] * scale, f"{what}: max abs err {err:.3e} > {TOL[dtype]:.0e} * max|ref| ({scale:.3e})"
+    rms = np.sqrt(np.mean((got - ref) ** 2)) / max(np.sqrt(np.mean(ref ** 2)), 1e-300)
+    assert rms <= RMS_TOL[dtype], f"{what}: relative rms err {rms:.3e} > {RMS_TOL[dtype]:.0e}"
+
+
+def assert_routing_equal(got, ref, C, what=""):
+    idx, loc = got["idx"].cpu().numpy(), got["loc"].cpu().numpy()
+    assert np.array_equal(idx, ref["idx"]), f"{what} idx differs at {np.argwhere(idx != ref['idx'])[:5]}"
+    assert np.array_equal(loc, ref["loc"]), f"{what} loc differs at {np.argwhere(loc != ref['loc'])[:5]}"
+    assert np.array_equal(loc < C, ref["kept"])
+    assert np.array_equal(got["counts"].cpu().numpy(), ref["counts"])
+    np.testing.assert_allclose(got["gate_w"].cpu().numpy(), ref["gate_w"], rtol=1e-5, atol=1e-9)
+
+
+# ----------------------------------------------------------------------------------------------------------------
+# moe_gate_topk from identical fp32 logits
+# ----------------------------------------------------------------------------------------------------------------
+GATE_CASES = [
+    # T, E, k, f, normalize, quantum
+    (1, 1, 1, 1.0, 0, 0.0), (5, 1, 1, 1.0, 1, 0.0), (7, 2, 2, 1.0, 1, 0.0), (300, 4, 1, 1.0, 0, 0.0),
+    (1000, 5, 3, 1.0, 1, 0.5), (1024, 8, 2, 1.25, 1, 0.0), (777, 12, 12, 0.5, 1, 0.25), (2049, 32, 1, 1.25, 0, 0.0),
+    (4096, 64, 2, 1.0, 1, 0.125), (1500, 100, 5, 2.0, 1, 0.0), (3000, 128, 8, 2.0, 1, 0.0), (600, 200, 3, 1.0, 0, 0.5),
+    (513, 512, 32, 1.0, 1, 0.0), (256, 16, 4, 8.0, 1, 0.0), (257, 16, 16, 0.1, 1, 1.0),
+]
+
+
+@pytest.mark.parametrize("T,E,k,f,normalize,quantum", GATE_CASES)
+def test_gate_topk(moe, T, E, k, f, normalize, quantum):
+    logits = synth.make_logits(T, E, seed=T + E + k, quantum=quantum)
+    if quantum == 0.0 and E >= 4:
+        logits[:, 1] += 0.75                  # an overloaded expert, so that capacity truncation happens
+    C = O.capacity(T, E, k, f)
+    assert moe.capacity(T, E, k, f) == C
+    ref = O.route(logits, k, C, normalize)
+    got = moe.gate_topk(torch.from_numpy(logits).cuda(), k, C, normalize)
+    assert_routing_equal(got, ref, C, f"T={T} E={E} k={k}")
+    assert np.array_equal(got["slot_src"].cpu().numpy(), O.slot_source(ref["idx"], ref["loc"], E, C))
+    # all-equal logits: experts 0..k-1 in order, for every token
+    flat = moe.gate_topk(torch.zeros((T, E), device="cuda"), k, C, normalize)
+    assert np.array_equal(flat["idx"].cpu().numpy(), np.tile(np.arange(k, dtype=np.int32), (T, 1)))
+
+
+def test_gate_topk_is_deterministic(moe):
+    logits = torch.from_numpy(synth.make_logits(5000, 64, seed=3, quantum=0.25)).cuda()
+    a = moe.gate_topk(logits, 4, 300, 1)
+    for _ in range(3):
+        b = moe.gate_topk(logits, 4, 300, 1)
+        for key in ("idx", "loc", "counts", "slot_src", "gate_w"):
+            assert torch.equal(a[key], b[key])
+
+
+# ----------------------------------------------------------------------------------------------------------------
+# moe_gate_logits
+# ----------------------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype", [synth.DT_F32, synth.DT_BF16])
+@pytest.mark.parametrize("T,M,E,bias", [(1, 8, 1, False), (70, 40, 4, True), (1000, 256, 8, False), (333, 776, 17, True),
+                                        (2048, 1024, 128, True), (130, 64, 130, False), (65, 2048, 300, True)])
+def test_gate_logits(moe, dtype, T, M, E, bias):
+    cfg = synth.CONFIGS[1].scaled(T=T, M=M, H=8, E=E, dtype=dtype, cfg_id=40 + dtype)
+    inp = synth.make_inputs(cfg, seed=T)
+    gb = (np.linspace(-1, 1, E).astype(np.float32)) if bias else None
+    ref = O.gate_logits(inp["x"], inp["Wg"], gb)
+    got = moe.gate_logits(dev(inp["x"], dtype), dev(inp["Wg"], dtype), None if gb is None else torch.from_numpy(gb).cuda())
+    got = got.cpu().numpy()
+    # fp64 accumulation on both sides, one rounding to fp32: equal except where the fp64 sums straddle a rounding
+    # boundary (last bit, rare)
+    ulp = np.spacing(np.abs(ref).astype(np.float32))
+    assert (np.abs(got - ref) <= ulp).all()
+    assert (got != ref).mean() <= 1e-4
+
+
+# ----------------------------------------------------------------------------------------------------------------
+# moe_encode / moe_decode
+# ----------------------------------------------------------------------------------------------------------------
+DISPATCH_CASES = [(1, 8, 1, 1, 1.0), (50, 24, 3, 2, 0.7), (1000, 256, 8, 2, 1.25), (777, 776, 5, 3, 0.5), (2049, 1536, 32, 1, 1.25),
+                  (1500, 4096, 16, 8, 2.0), (64, 8200, 4, 2, 1.0)]
+
+
+@pytest.mark.parametrize("dtype", [synth.DT_F32, synth.DT_BF16])
+@pytest.mark.parametrize("T,M,E,k,f", DISPATCH_CASES)
+def test_encode_decode(moe, dtype, T, M, E, k, f):
+    cfg = synth.CONFIGS[1].scaled(T=T, M=M, H=8, E=E, k=k, f=f, dtype=dtype, cfg_id=42)
+    x = synth.make_inputs(cfg, seed=M)["x"]
+    logits = synth.make_logits(T, E, seed=T, quantum=0.25)
+    C = O.capacity(T, E, k, f)
+    r = O.route(logits, k, C, 1)
+    g = moe.gate_topk(torch.from_numpy(logits).cuda(), k, C, 1)
+    xd = dev(x, dtype)
+    Zref = O.encode_sparse(x, r["idx"], r["loc"], E, C, dtype=np.float32)
+    for slot_src in (g["slot_src"], None):                       # gather form, scatter form
+        Z = moe.encode(xd, g["idx"], g["loc"], slot_src, E, C)
+        assert np.array_equal(host(Z).view(np.uint32), Zref.view(np.uint32)), "encode must be a bit-exact copy / +0 fill"
+    Y = synth.make_inputs(cfg.scaled(T=E * C, cfg_id=43), seed=7)["x"].reshape(E, C, M)     # stands in for expert outputs
+    ref = O.decode_sparse(Y, r["idx"], r["loc"], r["gate_w"], C)
+    out = host(moe.decode(dev(Y, dtype), g["idx"], g["loc"], g["gate_w"]))
+    assert_close(out, ref, dtype, "decode")
+    dead = (~r["kept"]).all(axis=1)
+    assert (out[dead].view(np.uint32) == 0).all(), "all-dropped tokens must be exact +0 rows"
+
+
+# ----------------------------------------------------------------------------------------------------------------
+# moe_expert_ffn
+# ----------------------------------------------------------------------------------------------------------------
+FFN_CASES = [
+    # dtype, E, C, M, H, act, bias, use_counts
+    (synth.DT_F32, 1, 1, 8, 8, O.ACT_RELU, False, False),
+    (synth.DT_F32, 3, 70, 40, 72, O.ACT_GELU, True, True),
+    (synth.DT_F32, 4, 256, 256, 512, O.ACT_RELU, False, False),
+    (synth.DT_F32, 2, 130, 264, 136, O.ACT_SILU, True, True),
+    (synth.DT_BF16, 2, 100, 72, 40, O.ACT_GELU, True, True),            # generic (non-MFMA) bf16 shapes
+    (synth.DT_BF16, 3, 300, 256, 256, O.ACT_RELU, False, False),        # MFMA path, ragged last row tile
+    (synth.DT_BF16, 2, 513, 512, 768, O.ACT_GELU, True, True),
+    (synth.DT_BF16, 5, 1000, 768, 1024, O.ACT_SILU, True, True),
+    (synth.DT_BF16, 1, 256, 1024, 256, O.ACT_GELU, False, False),
+    (synth.DT_BF16, 9, 37, 256, 512, O.ACT_SILU, False, True),
+]
+
+
+@pytest.mark.parametrize("dtype,E,C,M,H,act,bias,use_counts", FFN_CASES)
+def test_expert_ffn(moe, dtype, E, C, M, H, act, bias, use_counts):
+    cfg = synth.CONFIGS[1].scaled(T=E * C, M=M, H=H, E=E, dtype=dtype, cfg_id=44)
+    inp = synth.make_inputs(cfg, seed=C, bias_std=0.5 if bias else 0.0)
+    Z = inp["x"].reshape(E, C, M)
+    counts = None
+    if use_counts:
+        counts = np.random.default_rng(C).integers(0, C + 40, size=E).astype(np.int32)   # some empty, some beyond C
+        counts[0] = C // 2
+        if E > 1:
+            counts[1] = 0
+    ref = O.expert_ffn(Z, inp["W1"], inp["b1"], inp["W2"], inp["b2"], act, rows=counts)
+    Yd = torch.full((E, C, M), float("nan"), device="cuda").to(torch.bfloat16 if dtype == synth.DT_BF16 else torch.float32)
+    moe.expert_ffn(dev(Z, dtype), dev(inp["W1"], dtype), dev(inp["b1"], dtype), dev(inp["W2"], dtype), dev(inp["b2"], dtype), act,
+                   None if counts is None else torch.from_numpy(counts).cuda(), Y=Yd)
+    got = host(Yd)
+    if counts is None:
+        assert_close(got, ref, dtype, "ffn")
+    else:
+        rows = np.minimum(counts, C)
+        mask = np.arange(C)[None, :] < rows[:, None]
+        assert_close(got[mask], ref[mask], dtype, "ffn (filled rows)")
+        assert np.isnan(got[~mask]).all(), "rows past counts[e] must be left untouched"
+
+
+# ----------------------------------------------------------------------------------------------------------------
+# moe_layer_forward: reduced versions of the five workloads (several tiles + ragged tails), full element-wise check
+# ----------------------------------------------------------------------------------------------------------------
+def run_layer(moe, cfg, inp):
+    d = cfg.dtype
+    layer = moe.MoELayer(dev(inp["Wg"], d), None if inp["gate_bias"] is None else torch.from_numpy(inp["gate_bias"]).cuda(),
+                         dev(inp["W1"], d), dev(inp["b1"], d), dev(inp["W2"], d), dev(inp["b2"], d),
+                         T=cfg.T, k=cfg.k, f=cfg.f, normalize=cfg.normalize, act=cfg.act, keep_routing=True)
+    out = layer.forward(dev(inp["x"], d))
+    torch.cuda.synchronize()
+    return layer, out
+
+
+def check_logits(got, ref):
+    ulp = np.spacing(np.abs(ref).astype(np.float32))
+    assert (np.abs(got - ref) <= ulp).all() and (got != ref).mean() <= 1e-4
+
+
+SMALL_LAYERS = [
+    synth.CONFIGS[0].scaled(T=300, M=40, H=72, E=3),
+    synth.CONFIGS[0],
+    synth.CONFIGS[1].scaled(T=1500, M=256, H=512, E=8),
+    synth.CONFIGS[1].scaled(T=2000, M=264, H=520, E=8),                   # shapes that take the generic bf16 GEMM
+    synth.CONFIGS[2].scaled(T=1960, M=768, H=1024, E=32),
+    synth.CONFIGS[3].scaled(T=4096, M=256, H=512, E=64),
+    synth.CONFIGS[4].scaled(T=4096, M=512, H=256, E=128),
+]
+
+
+@pytest.mark.parametrize("cfg", SMALL_LAYERS, ids=lambda c: f"{c.name}-T{c.T}-M{c.M}-H{c.H}-E{c.E}")
+@pytest.mark.parametrize("bias", [False, True])
+def test_layer_small(moe, cfg, bias):
+    inp = synth.make_inputs(cfg, seed=0, bias_std=0.25 if bias else 0.0)
+    tier = "dense" if cfg.T * cfg.E * O.capacity(cfg.T, cfg.E, cfg.k, cfg.f) <= 2 ** 28 else "sparse"
+    ref = O.moe_layer(inp["x"], inp["Wg"], inp["gate_bias"], inp["W1"], inp["b1"], inp["W2"], inp["b2"],
+                      cfg.k, cfg.f, cfg.normalize, cfg.act, tier=tier)
+    layer, out = run_layer(moe, cfg, inp)
+    assert layer.C == ref["C"]
+    check_logits(layer.routing["logits"].cpu().numpy(), ref["logits"])
+    assert_routing_equal(layer.routing, ref, ref["C"], cfg.name)
+    got = host(out)
+    assert_close(got, ref["out"], cfg.dtype, f"layer output ({cfg.name})")
+    dead = (~ref["kept"]).all(axis=1)
+    assert (got[dead].view(np.uint32) == 0).all()
+
+
+# ----------------------------------------------------------------------------------------------------------------
+# moe_layer_forward at the full benchmark sizes, in the launch configuration bench.py times
+# ----------------------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("cfg", synth.CONFIGS[1:4], ids=lambda c: c.name)
+def test_layer_full_size(moe, cfg):
+    print(f"[full-size] {cfg.name}: generating inputs", flush=True)
+    inp = synth.make_inputs(cfg, seed=0)
+    print("[full-size] oracle", flush=True)
+    ref = O.moe_layer(inp["x"], inp["Wg"], inp["gate_bias"], inp["W1"], inp["b1"], inp["W2"], inp["b2"],
+                      cfg.k, cfg.f, cfg.normalize, cfg.act, tier="sparse")
+    print("[full-size] HIP path", flush=True)
+    layer, out = run_layer(moe, cfg, inp)
+    check_logits(layer.routing["logits"].cpu().numpy(), ref["logits"])
+    assert_routing_equal(layer.routing, ref, ref["C"], cfg.name)
+    assert_close(host(out), ref["out"], cfg.dtype, f"layer output ({cfg.name})")
+
+
+def test_layer_full_size_finegrained_sampled(moe):
+    """T=131072, E=128, top-8: routing is checked in full; encode, FFN rows and outputs on samples the oracle
+    evaluates one by one (the buffered fp64 oracle would need > 100 GB)."""
+    cfg = synth.CONFIGS[4]
+    print("[finegrained] generating inputs", flush=True)
+    inp = synth.make_inputs(cfg, seed=0)
+    C = O.capacity(cfg.T, cfg.E, cfg.k, cfg.f)
+    print("[finegrained] oracle routing", flush=True)
+    logits = O.gate_logits(inp["x"], inp["Wg"], inp["gate_bias"])
+    ref = O.route(logits, cfg.k, C, cfg.normalize)
+    print("[finegrained] HIP path", flush=True)
+    d = cfg.dtype
+    xd, W1d, W2d = dev(inp["x"], d), dev(inp["W1"], d), dev(inp["W2"], d)
+    layer = moe.MoELayer(dev(inp["Wg"], d), None, W1d, None, W2d, None, T=cfg.T, k=cfg.k, f=cfg.f,
+                         normalize=cfg.normalize, act=cfg.act, keep_routing=True)
+    out = layer.forward(xd)
+    torch.cuda.synchronize()
+    check_logits(layer.routing["logits"].cpu().numpy(), logits)
+    assert_routing_equal(layer.routing, ref, C, cfg.name)
+    rng = np.random.default_rng(0)
+    tokens = np.sort(rng.choice(cfg.T, size=160, replace=False))
+    print("[finegrained] oracle outputs for sampled tokens", flush=True)
+    want = O.token_outputs_direct(tokens, inp["x"], ref["idx"], ref["loc"], ref["gate_w"], C, inp["W1"], None, inp["W2"], None, cfg.act)
+    got = host(out[torch.from_numpy(tokens).cuda()])
+    assert_close(got, want, d, "sampled layer outputs")
+    # stage entry points on the same routing: sampled slots of the dispatch buffer and of the expert output
+    g = layer.routing
+    src = O.slot_source(ref["idx"], ref["loc"], cfg.E, C)
+    slot_src = torch.from_numpy(src).cuda()
+    Z = moe.encode(xd, g["idx"], g["loc"], slot_src, cfg.E, C)
+    se, sc = rng.integers(0, cfg.E, size=4096), rng.integers(0, C, size=4096)
+    zs = host(Z[torch.from_numpy(se).cuda(), torch.from_numpy(sc).cuda()])
+    want_z = np.where((src[se, sc] >= 0)[:, None], inp["x"][np.maximum(src[se, sc], 0)], np.float32(0))
+    assert np.array_equal(zs.view(np.uint32), want_z.view(np.uint32))
+    Y = moe.expert_ffn(Z, W1d, None, W2d, None, cfg.act, g["counts"])
+    filled = np.argwhere(src >= 0)
+    pick = filled[rng.choice(len(filled), size=96, replace=False)]
+    for e in np.unique(pick[:, 0]):
+        cs = pick[pick[:, 0] == e, 1]
+        want_y = O.ffn_rows(inp["x"][src[e, cs]], inp["W1"][e], None, inp["W2"][e], None, cfg.act)
+        assert_close(host(Y[int(e)][torch.from_numpy(cs).cuda()]), want_y, d, f"sampled FFN rows of expert {e}")
