@@ -1,0 +1,137 @@
+#!/usr/bin/env python3
+"""Benchmark of the MoE-layer hot path on one MI355X: `python bench.py [--gpus 1] [--steps K] [--warmup W]`.
+
+One step = one pass of the whole path (gate logits -> top-k + slots -> encode -> expert FFN -> decode) over one batch
+of seeded synthetic input that is already resident in HBM.  Prints one JSON line:
+  value      layer forward tokens/s (T / mean step time)
+  roofline   the dominant kernel (grouped bf16 MFMA GEMM of the expert FFN): algorithmic FLOP per launch divided by
+             its mean launch time, measured with HIP events recorded on the library's stream inside the timed loop
+  stages     per-stage mean milliseconds and, for encode/decode, algorithmic HBM GB/s
+  cpu_baseline  the CPU oracle timed on this machine's host cores on the same workload
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+FP32_VECTOR_PEAK_TFLOPS = 157.3
+# HBM bytes per grouped-GEMM launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (see profiles/), keyed by
+# workload name; None where no counter run has been recorded.
+MEASURED_GEMM_TRAFFIC_BYTES = {}
+
+
+def to_device(a, dtype_code):
+    import torch
+    from paper_2206_03382_amd import synth
+    if a is None:
+        return None
+    if dtype_code == synth.DT_BF16:
+        return torch.from_numpy(synth.bf16_bits(a).view(np.int16)).cuda().view(torch.bfloat16)
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", type=int, default=1, help="index into the five workloads (default 1: T=16384, M=H=2048, E=8, top-2)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures the single-GPU hot path only: run it with --gpus 1 "
+              "(this build has no cross-GPU all-to-all; see DESIGN.md, 'How it would shard').", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2206_03382_amd import moe, synth
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        return 2
+    moe.lib()
+    cfg = synth.CONFIGS[args.config]
+    inp = synth.make_inputs(cfg, seed=0)
+    d = cfg.dtype
+    x = to_device(inp["x"], d)
+    gate_bias = None if inp["gate_bias"] is None else torch.from_numpy(inp["gate_bias"]).cuda()
+    layer = moe.MoELayer(to_device(inp["Wg"], d), gate_bias, to_device(inp["W1"], d), to_device(inp["b1"], d),
+                         to_device(inp["W2"], d), to_device(inp["b2"], d), T=cfg.T, k=cfg.k, f=cfg.f,
+                         normalize=cfg.normalize, act=cfg.act, keep_routing=True)
+    events = [moe.StageEvents() for _ in range(args.steps)]
+
+    for _ in range(args.warmup):
+        layer.forward(x)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        layer.forward(x, events[i])
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+
+    ms_per_step = elapsed * 1e3 / args.steps
+    stage_ms = np.mean(np.array([e.stage_ms() for e in events]), axis=0)
+    for e in events:
+        e.close()
+    counts = layer.routing["counts"].cpu().numpy().astype(np.int64)
+    C, T, M, H, E, k = layer.C, cfg.T, cfg.M, cfg.H, cfg.E, cfg.k
+    es = 4 if d == synth.DT_F32 else 2
+    R = int(np.minimum(counts, C).sum())                         # filled slots = kept (token, choice) pairs
+    flop_per_gemm = 2.0 * R * M * H                              # GEMM1 [R,M]x[M,H] and GEMM2 [R,H]x[H,M]: same count
+    gemm_ms = float(stage_ms[3] + stage_ms[4]) / 2.0
+    bf16 = d == synth.DT_BF16
+    peak = MFMA_BF16_PEAK_TFLOPS if bf16 else FP32_VECTOR_PEAK_TFLOPS
+    achieved = flop_per_gemm / (gemm_ms * 1e-3) / 1e12
+    enc_bytes = (R + E * C) * M * es + 8 * T * k                 # read each kept row once, write every slot
+    dec_bytes = (R + T) * M * es + 12 * T * k                    # read each kept expert-output row once, write [T,M]
+    stages = {name: round(float(ms), 5) for name, ms in zip(moe.STAGE_NAMES, stage_ms)}
+    stages["encode_GBps"] = round(enc_bytes / (stage_ms[2] * 1e-3) / 1e9, 1)
+    stages["decode_GBps"] = round(dec_bytes / (stage_ms[5] * 1e-3) / 1e9, 1)
+    stages["encode_frac_hbm"] = round(stages["encode_GBps"] / HBM_PEAK_GBS, 4)
+    stages["decode_frac_hbm"] = round(stages["decode_GBps"] / HBM_PEAK_GBS, 4)
+    stages["ffn_TFLOPs_filled_rows"] = round(2 * flop_per_gemm / ((stage_ms[3] + stage_ms[4]) * 1e-3) / 1e12, 1)
+
+    result = {
+        "metric": "MoE layer fwd tokens/s on 1 MI355X",
+        "value": round(T / (ms_per_step * 1e-3), 1),
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: T={T} M={M} H={H} E={E} top-{k} f={cfg.f} C={C} act={('relu', 'gelu', 'silu')[cfg.act]}",
+                   "filled_slots": R, "slots": E * C},
+        "roofline": {"bound": "mfma" if bf16 else "alu", "kernel": "grouped_gemm_mfma_kernel" if bf16 else "gemm_generic_kernel",
+                     "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
+                     "flop_per_launch": flop_per_gemm, "avg_launch_ms": round(gemm_ms, 5),
+                     "traffic": MEASURED_GEMM_TRAFFIC_BYTES.get(cfg.name)},
+        "stages": stages,
+    }
+
+    if not args.no_cpu_baseline:
+        from oracle import moe_oracle as O
+        from threadpoolctl import threadpool_info
+        blas = [p["num_threads"] for p in threadpool_info() if p.get("user_api") == "blas"]
+        threads = max(blas) if blas else (os.cpu_count() or 1)     # the oracle's time is in numpy's BLAS matmuls
+        c0 = time.perf_counter()
+        O.moe_layer(inp["x"], inp["Wg"], inp["gate_bias"], inp["W1"], inp["b1"], inp["W2"], inp["b2"],
+                    cfg.k, cfg.f, cfg.normalize, cfg.act, tier="sparse")
+        cpu_s = time.perf_counter() - c0
+        result["cpu_baseline"] = {"value": round(T / cpu_s, 1), "unit": "tokens/s", "cores": int(threads),
+                                  "kind": "oracle", "sample": f"the full workload once (all {T} tokens, fp64 numpy, zero-skipping tier), {cpu_s:.1f} s"}
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
