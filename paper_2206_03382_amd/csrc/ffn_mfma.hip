@@ -9,10 +9,10 @@
 // ring (2 x 64 KB) filled by direct global->LDS loads (16 bytes per lane, no staging registers).
 //
 // LDS layouts (both written by the direct loads, which place lane l's 16 bytes at base + 16 l):
-//   A tile  [256 rows][8 chunks of 8 k]:   chunk g of row r is stored at chunk position g ^ (r % 8), so the 8 lanes
-//           that share an LDS cycle of a ds_read_b128 (8 consecutive rows, same g) hit 8 different bank groups.
-//   B tile  [64 k][32 chunks of 8 n]:      chunk c of row k is stored at position c ^ (2 (k % 4)); the 16-lane
-//           block of a ds_read_b64_tr_b16 (4 k rows x 32 bytes) then covers all banks once.
+//   A tile  [256 rows][8 chunks of 8 k]:   chunk g of row r is stored at chunk position g ^ ((r / 2) % 8), so the 16 lanes
+//           that share an LDS cycle of a ds_read_b128 (16 consecutive rows, same g) cover all 64 banks once.
+//   B tile  [64 k][32 chunks of 8 n]:      chunk c of row k is stored at position c ^ (4 (k % 4)); the two 16-lane
+//           blocks of a ds_read_b64_tr_b16 that share a cycle (4 k rows x 32 bytes each) then cover all banks once.
 // B is K x N with N contiguous, but the matrix cores want k-contiguous operands: ds_read_b64_tr_b16 transposes
 // 4 k x 16 n sub-blocks on the way out of LDS (source lane s of a 16-lane block supplies row k0 + s/4,
 // columns n0 + 4 (s%4) .. +3; result lane l holds column n0 + l, rows k0 .. k0+3).
@@ -44,14 +44,6 @@ __device__ __forceinline__ void global_to_lds_16(const char* src, uint32_t lds_a
   asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(lds_addr) : "memory", "m0");
 }
 
-__device__ __forceinline__ void load_tile_async(const char* const (&a_src)[4], const char* const (&b_src)[4],
-                                                uint32_t stage_addr, int wave) {
-#pragma unroll
-  for (int q = 0; q < 4; ++q) global_to_lds_16(a_src[q], stage_addr + (q * 8 + wave) * 1024);
-#pragma unroll
-  for (int q = 0; q < 4; ++q) global_to_lds_16(b_src[q], stage_addr + kATileBytes + (q * 8 + wave) * 1024);
-}
-
 // Branch-free activations for the bf16 epilogue.  erf by the 5-term rational/exponential form of Abramowitz & Stegun
 // 7.1.26 (absolute error < 1.5e-7, far below bf16 resolution).
 __device__ __forceinline__ float fast_erf(float x) {
@@ -73,6 +65,136 @@ template <int ACT> __device__ __forceinline__ float epilogue_act(float v) {
 }
 
 }  // namespace
+
+#define PHASE_BARRIER()                        \
+  do {                                         \
+    __builtin_amdgcn_sched_barrier(0);         \
+    asm volatile("s_barrier" ::: "memory");    \
+    __builtin_amdgcn_sched_barrier(0);         \
+  } while (0)
+
+// ---- main loop -------------------------------------------------------------------------------------------------
+// Two groups of four waves (one wave of each group per SIMD) run one phase apart.  A K-step of 64 is two halves; each
+// half is a MEM phase (LDS -> fragment registers) followed by a COMPUTE phase (16 MFMAs); every phase ends with a
+// workgroup barrier, so between two barriers one wave per SIMD feeds the matrix core while the other moves data.
+// Global phase numbering (g0 = group 0, g1 = group 1), K-step kt:
+//   4kt   : g0 MEM(kt, 1st half)      g1 COMPUTE(kt-1, 2nd half)
+//   4kt+1 : g0 COMPUTE(kt, 1st half)  g1 MEM(kt, 1st half)
+//   4kt+2 : g0 MEM(kt, 2nd half)      g1 COMPUTE(kt, 1st half)
+//   4kt+3 : g0 COMPUTE(kt, 2nd half)  g1 MEM(kt, 2nd half)
+// Issuing a direct-to-LDS load blocks the issuing wave while the address unit is busy, so the 8 loads a wave
+// contributes to K-step kt+1 are spread 3/3/2 over phases 4kt, 4kt+1, 4kt+2, between LDS reads or MFMAs.  They are
+// waited for (s_waitcnt vmcnt(0)) before the barrier that ends phase 4kt+3; the stage they fill was last read in
+// phase 4kt-1.
+template <bool FULL>
+__device__ __forceinline__ void tile_main_loop(char* smem, const char* const (&a_src)[4], const char* const (&b_src)[4],
+                                               int64_t a_step, int64_t b_step, const int (&a_off)[4],
+                                               const int (&b_off)[2], int a_swz, int kg, int ni, int grp, int wave,
+                                               int K, f32x16 (&acc)[4][2]) {
+  bf16x8 af[2][4], bfr[2][2];
+  const uint32_t smem_addr = (uint32_t)(uintptr_t)LDS_PTR(char, smem);
+  const int KT = K / BK;
+
+  auto load_frags = [&](const char* stage, int s, bf16x8 (&a)[4], bf16x8 (&b)[2]) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      if (FULL || i < ni) a[i] = *LDS_PTR(bf16x8, stage + a_off[i] + (((2 * s + kg) ^ a_swz) << 4));
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(short4v, stage + b_off[j] + (16 * s) * 512));
+      const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(short4v, stage + b_off[j] + (16 * s + 4) * 512));
+      b[j] = __builtin_bit_cast(bf16x8, (short8v)__builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+    }
+  };
+  // MFMAs of sub-tile rows [i0, i0+2)
+  auto mma2 = [&](int i0, const bf16x8 (&a)[4], const bf16x8 (&b)[2]) {
+#pragma unroll
+    for (int i = i0; i < i0 + 2; ++i)
+      if (FULL || i < ni) {
+#pragma unroll
+        for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[j], a[i], acc[i][j], 0, 0, 0);
+      }
+  };
+  // load number idx (0..7: A0 B0 A1 B1 A2 B2 A3 B3) of K-step `tile`; does nothing past the last K-step
+  auto dma = [&](int idx, int tile) {
+    if (tile >= KT) return;
+    const int q = idx >> 1;
+    const uint32_t dst = smem_addr + (tile & 1) * kStageBytes + (q * 8 + wave) * 1024;
+    if (idx & 1) global_to_lds_16(b_src[q] + tile * b_step, dst + kATileBytes);
+    else global_to_lds_16(a_src[q] + tile * a_step, dst);
+  };
+#define PIN() __builtin_amdgcn_sched_barrier(0)
+
+#pragma unroll
+  for (int idx = 0; idx < 8; ++idx) dma(idx, 0);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  PHASE_BARRIER();
+
+  if (grp == 0) {
+    for (int kt = 0; kt < KT; ++kt) {
+      const char* cur = smem + (kt & 1) * kStageBytes;
+      // phase 4kt: MEM, first half
+      load_frags(cur, 0, af[0], bfr[0]);
+      PIN(); dma(0, kt + 1); PIN();
+      load_frags(cur, 1, af[1], bfr[1]);
+      PIN(); dma(1, kt + 1); dma(2, kt + 1);
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+      PHASE_BARRIER();
+      // phase 4kt+1: COMPUTE, first half
+      mma2(0, af[0], bfr[0]); PIN(); dma(3, kt + 1); PIN();
+      mma2(2, af[0], bfr[0]); PIN(); dma(4, kt + 1); PIN();
+      mma2(0, af[1], bfr[1]); PIN(); dma(5, kt + 1); PIN();
+      mma2(2, af[1], bfr[1]);
+      PHASE_BARRIER();
+      // phase 4kt+2: MEM, second half
+      load_frags(cur, 2, af[0], bfr[0]);
+      PIN(); dma(6, kt + 1); PIN();
+      load_frags(cur, 3, af[1], bfr[1]);
+      PIN(); dma(7, kt + 1);
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+      PHASE_BARRIER();
+      // phase 4kt+3: COMPUTE, second half
+      mma2(0, af[0], bfr[0]);
+      mma2(2, af[0], bfr[0]);
+      mma2(0, af[1], bfr[1]);
+      mma2(2, af[1], bfr[1]);
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      PHASE_BARRIER();
+    }
+    PHASE_BARRIER();
+  } else {
+    dma(0, 1); dma(1, 1); dma(2, 1);                                // phase 0: group 1 has nothing to compute yet
+    PHASE_BARRIER();
+    for (int kt = 0; kt < KT; ++kt) {
+      const char* cur = smem + (kt & 1) * kStageBytes;
+      // phase 4kt+1: MEM, first half
+      load_frags(cur, 0, af[0], bfr[0]);
+      PIN(); dma(3, kt + 1); PIN();
+      load_frags(cur, 1, af[1], bfr[1]);
+      PIN(); dma(4, kt + 1); dma(5, kt + 1);
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+      PHASE_BARRIER();
+      // phase 4kt+2: COMPUTE, first half
+      mma2(0, af[0], bfr[0]); PIN(); dma(6, kt + 1); PIN();
+      mma2(2, af[0], bfr[0]); PIN(); dma(7, kt + 1); PIN();
+      mma2(0, af[1], bfr[1]);
+      mma2(2, af[1], bfr[1]);
+      PHASE_BARRIER();
+      // phase 4kt+3: MEM, second half
+      load_frags(cur, 2, af[0], bfr[0]);
+      load_frags(cur, 3, af[1], bfr[1]);
+      asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+      PHASE_BARRIER();
+      // phase 4(kt+1): COMPUTE, second half; first loads of K-step kt+2 (its stage was last read in phase 4kt+3)
+      mma2(0, af[0], bfr[0]); PIN(); dma(0, kt + 2); PIN();
+      mma2(2, af[0], bfr[0]); PIN(); dma(1, kt + 2); PIN();
+      mma2(0, af[1], bfr[1]); PIN(); dma(2, kt + 2); PIN();
+      mma2(2, af[1], bfr[1]);
+      PHASE_BARRIER();
+    }
+  }
+#undef PIN
+}
 
 template <int ACT>
 __global__ __launch_bounds__(kThreads) void grouped_gemm_mfma_kernel(const uint16_t* __restrict__ A,
@@ -101,35 +223,41 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_mfma_kernel(const uint1
   const int wm = wave >> 2, wn = wave & 3;
 
   // ---- global sources of this lane's direct-to-LDS loads ---------------------------------------------------------
+  // A: 1 KB block q*8+wave of the tile = rows 8(q*8+wave) .. +7, lane l writes row +l/8, chunk position l%8.
+  // B: 1 KB block q*8+wave = k-rows 2(q*8+wave), +1, lane l writes k-row +l/32, chunk position l%32.
   const char* Ae = (const char*)(A + (int64_t)e * C * K);
   const char* Be = (const char*)(B + (int64_t)e * K * N);
   const char* a_src[4];
   const char* b_src[4];
 #pragma unroll
   for (int q = 0; q < 4; ++q) {
-    const int r = q * 64 + wave * 8 + (lane >> 3);                  // tile row written by this lane
+    const int r = q * 64 + wave * 8 + (lane >> 3);
     int64_t row = m0 + r;
     row = row < C ? row : C - 1;                                    // rows past the slab are clamped (never stored)
-    const int g = (lane & 7) ^ (lane >> 3);                         // global chunk that lands at position lane % 8
+    const int g = (lane & 7) ^ ((r >> 1) & 7);                      // global chunk that lands at position lane % 8
     a_src[q] = Ae + (row * K + g * 8) * 2;
-    const int kr = q * 16 + wave * 2 + (lane >> 5);                 // tile k-row written by this lane
-    const int c = (lane & 31) ^ (2 * (kr & 3));
+    const int kr = q * 16 + wave * 2 + (lane >> 5);
+    const int c = (lane & 31) ^ (4 * (kr & 3));
     b_src[q] = Be + ((int64_t)kr * N + n0 + c * 8) * 2;
   }
   const int64_t a_step = (int64_t)BK * 2, b_step = (int64_t)BK * N * 2;
 
   // ---- LDS read offsets of this lane's MFMA fragments ------------------------------------------------------------
-  int a_off[4];                                                     // + ((2 s + kg) ^ (lane & 7)) * 16
+  const int kg = lane >> 5;
+  const int a_swz = ((lane & 31) >> 1) & 7;                         // ((row >> 1) & 7): tile-row offsets are multiples of 32
+  int a_off[4];                                                     // + ((2 s + kg) ^ a_swz) * 16
 #pragma unroll
   for (int i = 0; i < 4; ++i) a_off[i] = (wm * 128 + i * 32 + (lane & 31)) * 128;
-  const int kg = lane >> 5;
   int b_off[2];                                                     // + (16 s + 4 rd) * 512
 #pragma unroll
   for (int j = 0; j < 2; ++j) {
     const int c = wn * 8 + j * 4 + ((lane >> 4) & 1) * 2 + ((lane & 3) >> 1);
-    const int swz = 2 * ((lane >> 2) & 3);
+    const int swz = 4 * ((lane >> 2) & 3);                          // 4 (k & 3), k & 3 = (lane % 16) / 4
     b_off[j] = kATileBytes + (kg * 8 + ((lane & 15) >> 2)) * 512 + ((c ^ swz) << 4) + ((lane & 1) << 3);
   }
+  // 32-row sub-tiles of this wave that hold real rows (the last row tile of an expert is usually ragged)
+  const int64_t wave_rows = rows - m0 - wm * 128;
+  const int ni = wave_rows >= 128 ? 4 : (wave_rows <= 0 ? 0 : (int)((wave_rows + 31) >> 5));
 
   f32x16 acc[4][2];
 #pragma unroll
@@ -139,40 +267,8 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_mfma_kernel(const uint1
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  const int KT = K / BK;
-  const uint32_t smem_addr = (uint32_t)(uintptr_t)LDS_PTR(char, smem);
-  load_tile_async(a_src, b_src, smem_addr, wave);
-  __builtin_amdgcn_s_waitcnt(0x0F70);                               // vmcnt(0)
-  __syncthreads();
-
-  for (int kt = 0; kt < KT; ++kt) {
-    char* cur = smem + (kt & 1) * kStageBytes;
-    if (kt + 1 < KT) {
-#pragma unroll
-      for (int q = 0; q < 4; ++q) { a_src[q] += a_step; b_src[q] += b_step; }
-      load_tile_async(a_src, b_src, smem_addr + ((kt + 1) & 1) * kStageBytes, wave);
-    }
-#pragma unroll
-    for (int s = 0; s < 4; ++s) {
-      bf16x8 af[4], bfr[2];
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-        af[i] = *LDS_PTR(bf16x8, cur + a_off[i] + (((2 * s + kg) ^ (lane & 7)) << 4));
-#pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(short4v, cur + b_off[j] + (16 * s) * 512));
-        const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(short4v, cur + b_off[j] + (16 * s + 4) * 512));
-        const short8v both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-        bfr[j] = __builtin_bit_cast(bf16x8, both);
-      }
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
-    }
-    __builtin_amdgcn_s_waitcnt(0x0F70);                             // next stage has landed (this wave's part)
-    __syncthreads();                                                // ... and everyone is done reading `cur`
-  }
+  if (ni == 4) tile_main_loop<true>(smem, a_src, b_src, a_step, b_step, a_off, b_off, a_swz, kg, ni, wm, wave, K, acc);
+  else tile_main_loop<false>(smem, a_src, b_src, a_step, b_step, a_off, b_off, a_swz, kg, ni, wm, wave, K, acc);
 
   // ---- epilogue: bias, activation, bf16, 8-byte stores (4 consecutive columns per lane and register group) -------
   uint16_t* oute = out + (int64_t)e * C * N;
