@@ -4,9 +4,13 @@
 //   out[e] = epilogue(A[e] (rows_e x K) * B[e] (K x N) + bias[e]),  A [E,C,K], B [E,K,N], out [E,C,N], all bf16,
 //   fp32 accumulation, rows_e = min(counts[e], C) (or C).  Requires K % 64 == 0 and N % 256 == 0.
 //
-// Tiling: one 512-thread block (8 waves, 2 per SIMD) owns a 256 x 256 output tile; waves form a 2 x 4 grid, each
-// owning 128 x 64 as 4 x 2 tiles of v_mfma_f32_32x32x16_bf16.  K advances in steps of 64 through a two-stage LDS
-// ring (2 x 64 KB) filled by direct global->LDS loads (16 bytes per lane, no staging registers).
+// Tiling: one 256-thread block (4 waves, one per SIMD) owns a 256 x 256 output tile; waves form a 2 x 2 grid, each
+// owning 128 x 128 as 4 x 4 tiles of v_mfma_f32_32x32x16_bf16 (256 accumulator registers per lane).  Large wave tiles
+// keep LDS->register traffic, the scarce resource on this chip, at 2 x 128 x 2 bytes per k per wave.  K advances in
+// steps of 64 through a two-stage LDS ring (2 x 64 KB) filled by direct global->LDS loads (16 bytes per lane, no
+// staging registers).  Within a wave every MFMA is followed by at most one LDS read or one direct load, so the
+// data movement of the next sub-step hides in the shadow of the current sub-step's MFMAs; one workgroup barrier per
+// K-step hands the LDS stages over.
 //
 // LDS layouts (both written by the direct loads, which place lane l's 16 bytes at base + 16 l):
 //   A tile  [256 rows][8 chunks of 8 k]:   chunk g of row r is stored at chunk position g ^ ((r / 2) % 8), so the 16 lanes
@@ -19,6 +23,8 @@
 //
 // The two MFMA operands are passed swapped (B fragment first), so that a lane's accumulator registers hold four
 // consecutive output columns of one row: D'[n][m] with m = lane % 32, n = 8 (v/4) + 4 (lane/32) + v % 4.
+#include <type_traits>
+
 #include "common.h"
 
 namespace moe {
@@ -31,17 +37,19 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 namespace {
 
 constexpr int BM = 256, BN = 256, BK = 64;
-constexpr int kThreads = 512;
+constexpr int kThreads = 256;
 constexpr int kStageBytes = 65536;          // A tile 32 KB + B tile 32 KB
 constexpr int kATileBytes = 32768;
+constexpr int kLoadsPerWave = 16;           // 64 KB per K-step / (4 waves x 1 KB per wave-load)
 
 #define LDS_PTR(T, p) ((__attribute__((address_space(3))) T*)(p))
+#define PIN() __builtin_amdgcn_sched_barrier(0)
 
-// Direct global->LDS load of 16 bytes per lane: lane l's data lands at lds_addr + 16 l.  Written as inline assembly so
-// that the compiler does not serialise the prefetch against the LDS reads of the other stage; completion is tracked
-// by hand (s_waitcnt vmcnt(0) + barrier before a stage is read).
-__device__ __forceinline__ void global_to_lds_16(const char* src, uint32_t lds_addr) {
-  asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(lds_addr) : "memory", "m0");
+// Direct global->LDS load of 16 bytes per lane from base + voff: lane l's data lands at lds_addr + 16 l.  Written as
+// inline assembly so that the compiler does not serialise the prefetch against the LDS reads of the other stage;
+// completion is tracked by hand (s_waitcnt vmcnt + barrier before a stage is read).
+__device__ __forceinline__ void global_to_lds_16(const char* base, uint32_t voff, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(voff), "s"(base), "s"(lds_addr) : "memory");
 }
 
 // Branch-free activations for the bf16 epilogue.  erf by the 5-term rational/exponential form of Abramowitz & Stegun
@@ -64,136 +72,114 @@ template <int ACT> __device__ __forceinline__ float epilogue_act(float v) {
   return v;
 }
 
+struct Frags {
+  bf16x8 a[4], b[4];
+};
+
 }  // namespace
 
-#define PHASE_BARRIER()                        \
-  do {                                         \
-    __builtin_amdgcn_sched_barrier(0);         \
-    asm volatile("s_barrier" ::: "memory");    \
-    __builtin_amdgcn_sched_barrier(0);         \
-  } while (0)
-
 // ---- main loop -------------------------------------------------------------------------------------------------
-// Two groups of four waves (one wave of each group per SIMD) run one phase apart.  A K-step of 64 is two halves; each
-// half is a MEM phase (LDS -> fragment registers) followed by a COMPUTE phase (16 MFMAs); every phase ends with a
-// workgroup barrier, so between two barriers one wave per SIMD feeds the matrix core while the other moves data.
-// Global phase numbering (g0 = group 0, g1 = group 1), K-step kt:
-//   4kt   : g0 MEM(kt, 1st half)      g1 COMPUTE(kt-1, 2nd half)
-//   4kt+1 : g0 COMPUTE(kt, 1st half)  g1 MEM(kt, 1st half)
-//   4kt+2 : g0 MEM(kt, 2nd half)      g1 COMPUTE(kt, 1st half)
-//   4kt+3 : g0 COMPUTE(kt, 2nd half)  g1 MEM(kt, 2nd half)
-// Issuing a direct-to-LDS load blocks the issuing wave while the address unit is busy, so the 8 loads a wave
-// contributes to K-step kt+1 are spread 3/3/2 over phases 4kt, 4kt+1, 4kt+2, between LDS reads or MFMAs.  They are
-// waited for (s_waitcnt vmcnt(0)) before the barrier that ends phase 4kt+3; the stage they fill was last read in
-// phase 4kt-1.
+// K-step kt (64 wide) is four sub-steps of 16 MFMAs.  While sub-step s computes from one fragment buffer, the 12 LDS
+// reads of sub-step s+1 fill the other.  The direct loads of K-step kt+2 go into the stage K-step kt is read from, so
+// they may start only after the barrier that follows the last read of that stage (issued during sub-step 2): 8 of a
+// wave's 16 loads are issued in sub-step 3 of K-step kt, the other 8 in sub-step 0 of K-step kt+1, and they are
+// waited for before the barrier of K-step kt+1, two sub-steps later.
 template <bool FULL>
-__device__ __forceinline__ void tile_main_loop(char* smem, const char* const (&a_src)[4], const char* const (&b_src)[4],
-                                               int64_t a_step, int64_t b_step, const int (&a_off)[4],
-                                               const int (&b_off)[2], int a_swz, int kg, int ni, int grp, int wave,
-                                               int K, f32x16 (&acc)[4][2]) {
-  bf16x8 af[2][4], bfr[2][2];
+__device__ __forceinline__ void tile_main_loop(char* smem, const char* a_base, const char* b_base,
+                                               const uint32_t (&a_voff)[8], const uint32_t (&b_voff)[8], int64_t a_step,
+                                               int64_t b_step, const int (&a_off)[4], const int (&b_off)[4], int a_swz,
+                                               int kg, int ni, int wave, int K, f32x16 (&acc)[4][4]) {
+  Frags f[2];
   const uint32_t smem_addr = (uint32_t)(uintptr_t)LDS_PTR(char, smem);
   const int KT = K / BK;
 
-  auto load_frags = [&](const char* stage, int s, bf16x8 (&a)[4], bf16x8 (&b)[2]) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-      if (FULL || i < ni) a[i] = *LDS_PTR(bf16x8, stage + a_off[i] + (((2 * s + kg) ^ a_swz) << 4));
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(short4v, stage + b_off[j] + (16 * s) * 512));
-      const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(short4v, stage + b_off[j] + (16 * s + 4) * 512));
-      b[j] = __builtin_bit_cast(bf16x8, (short8v)__builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
-    }
-  };
-  // MFMAs of sub-tile rows [i0, i0+2)
-  auto mma2 = [&](int i0, const bf16x8 (&a)[4], const bf16x8 (&b)[2]) {
-#pragma unroll
-    for (int i = i0; i < i0 + 2; ++i)
-      if (FULL || i < ni) {
-#pragma unroll
-        for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[j], a[i], acc[i][j], 0, 0, 0);
+  // read number r (0..11) of sub-step s from `stage` into fragment buffer `d`: 0-3 A rows, 4-11 B column halves
+  auto read = [&](const char* stage, int s, int r, Frags& d, short4v (&lo)[4]) {
+    if (r < 4) {
+      if (FULL || r < ni) d.a[r] = *LDS_PTR(bf16x8, stage + a_off[r] + (((2 * s + kg) ^ a_swz) << 4));
+    } else {
+      const int j = (r - 4) >> 1;
+      if (((r - 4) & 1) == 0) {
+        lo[j] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(short4v, stage + b_off[j] + (16 * s) * 512));
+      } else {
+        const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(short4v, stage + b_off[j] + (16 * s + 4) * 512));
+        d.b[j] = __builtin_bit_cast(bf16x8, (short8v)__builtin_shufflevector(lo[j], hi, 0, 1, 2, 3, 4, 5, 6, 7));
       }
+    }
   };
-  // load number idx (0..7: A0 B0 A1 B1 A2 B2 A3 B3) of K-step `tile`; does nothing past the last K-step
+  // direct load number idx (0..15: A0..A7, B0..B7) of K-step `tile` (the caller guarantees tile < KT)
   auto dma = [&](int idx, int tile) {
-    if (tile >= KT) return;
-    const int q = idx >> 1;
-    const uint32_t dst = smem_addr + (tile & 1) * kStageBytes + (q * 8 + wave) * 1024;
-    if (idx & 1) global_to_lds_16(b_src[q] + tile * b_step, dst + kATileBytes);
-    else global_to_lds_16(a_src[q] + tile * a_step, dst);
+    const int q = idx & 7;
+    const uint32_t dst = smem_addr + (tile & 1) * kStageBytes + (q * 4 + wave) * 1024;
+    if (idx < 8) global_to_lds_16(a_base + tile * a_step, a_voff[q], dst);
+    else global_to_lds_16(b_base + tile * b_step, b_voff[q], dst + kATileBytes);
   };
-#define PIN() __builtin_amdgcn_sched_barrier(0)
+  auto mfma = [&](int m, const Frags& c) {
+    const int i = m >> 2, j = m & 3;
+    if (FULL || i < ni) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(c.b[j], c.a[i], acc[i][j], 0, 0, 0);
+  };
+  // one sub-step: 16 MFMAs from `c`, interleaved with the 12 reads of (stage, s_next) into `n` (if READS) and with the
+  // direct loads dma_first .. dma_first+7 of K-step dma_tile (if DMA); both switches are compile-time so that the
+  // steady-state loop body is branch-free
+  auto substep = [&](auto reads_tag, auto dma_tag, const Frags& c, Frags& n, const char* stage, int s_next, int dma_first,
+                     int dma_tile) {
+    constexpr bool READS = decltype(reads_tag)::value, DMA = decltype(dma_tag)::value;
+    short4v lo[4];
+#pragma unroll
+    for (int m = 0; m < 16; ++m) {
+      mfma(m, c);
+      PIN();
+      if (READS && m < 12) read(stage, s_next, m, n, lo);
+      if (DMA && (m & 1) == 1) dma(dma_first + (m >> 1), dma_tile);
+      PIN();
+    }
+  };
+  using T_ = std::true_type;
+  using F_ = std::false_type;
+  // one K-step; DMA0: second half of the loads of K-step kt+1 (sub-step 0), DMA3: first half of K-step kt+2
+  // (sub-step 3), NEXT: a K-step kt+1 exists
+  auto kstep = [&](auto dma0_tag, auto dma3_tag, auto next_tag, int kt) {
+    const char* cur = smem + (kt & 1) * kStageBytes;
+    const char* nxt = smem + ((kt + 1) & 1) * kStageBytes;
+    substep(T_{}, dma0_tag, f[0], f[1], cur, 1, 8, kt + 1);
+    substep(T_{}, F_{}, f[1], f[0], cur, 2, 0, 0);
+    substep(T_{}, F_{}, f[0], f[1], cur, 3, 0, 0);
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");      // K-step kt+1 has landed; reads of `cur` are done
+    PIN();
+    asm volatile("s_barrier" ::: "memory");
+    PIN();
+    substep(next_tag, dma3_tag, f[1], f[0], nxt, 0, 0, kt + 2);
+  };
 
 #pragma unroll
-  for (int idx = 0; idx < 8; ++idx) dma(idx, 0);
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  PHASE_BARRIER();
-
-  if (grp == 0) {
-    for (int kt = 0; kt < KT; ++kt) {
-      const char* cur = smem + (kt & 1) * kStageBytes;
-      // phase 4kt: MEM, first half
-      load_frags(cur, 0, af[0], bfr[0]);
-      PIN(); dma(0, kt + 1); PIN();
-      load_frags(cur, 1, af[1], bfr[1]);
-      PIN(); dma(1, kt + 1); dma(2, kt + 1);
-      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-      PHASE_BARRIER();
-      // phase 4kt+1: COMPUTE, first half
-      mma2(0, af[0], bfr[0]); PIN(); dma(3, kt + 1); PIN();
-      mma2(2, af[0], bfr[0]); PIN(); dma(4, kt + 1); PIN();
-      mma2(0, af[1], bfr[1]); PIN(); dma(5, kt + 1); PIN();
-      mma2(2, af[1], bfr[1]);
-      PHASE_BARRIER();
-      // phase 4kt+2: MEM, second half
-      load_frags(cur, 2, af[0], bfr[0]);
-      PIN(); dma(6, kt + 1); PIN();
-      load_frags(cur, 3, af[1], bfr[1]);
-      PIN(); dma(7, kt + 1);
-      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-      PHASE_BARRIER();
-      // phase 4kt+3: COMPUTE, second half
-      mma2(0, af[0], bfr[0]);
-      mma2(2, af[0], bfr[0]);
-      mma2(0, af[1], bfr[1]);
-      mma2(2, af[1], bfr[1]);
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-      PHASE_BARRIER();
-    }
-    PHASE_BARRIER();
+  for (int idx = 0; idx < kLoadsPerWave; ++idx) dma(idx, 0);
+  if (KT > 1) {
+#pragma unroll
+    for (int idx = 0; idx < kLoadsPerWave; ++idx) dma(idx, 1);
+    asm volatile("s_waitcnt vmcnt(16)" ::: "memory");               // loads return in order: K-step 0 has landed
   } else {
-    dma(0, 1); dma(1, 1); dma(2, 1);                                // phase 0: group 1 has nothing to compute yet
-    PHASE_BARRIER();
-    for (int kt = 0; kt < KT; ++kt) {
-      const char* cur = smem + (kt & 1) * kStageBytes;
-      // phase 4kt+1: MEM, first half
-      load_frags(cur, 0, af[0], bfr[0]);
-      PIN(); dma(3, kt + 1); PIN();
-      load_frags(cur, 1, af[1], bfr[1]);
-      PIN(); dma(4, kt + 1); dma(5, kt + 1);
-      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-      PHASE_BARRIER();
-      // phase 4kt+2: COMPUTE, first half
-      mma2(0, af[0], bfr[0]); PIN(); dma(6, kt + 1); PIN();
-      mma2(2, af[0], bfr[0]); PIN(); dma(7, kt + 1); PIN();
-      mma2(0, af[1], bfr[1]);
-      mma2(2, af[1], bfr[1]);
-      PHASE_BARRIER();
-      // phase 4kt+3: MEM, second half
-      load_frags(cur, 2, af[0], bfr[0]);
-      load_frags(cur, 3, af[1], bfr[1]);
-      asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
-      PHASE_BARRIER();
-      // phase 4(kt+1): COMPUTE, second half; first loads of K-step kt+2 (its stage was last read in phase 4kt+3)
-      mma2(0, af[0], bfr[0]); PIN(); dma(0, kt + 2); PIN();
-      mma2(2, af[0], bfr[0]); PIN(); dma(1, kt + 2); PIN();
-      mma2(0, af[1], bfr[1]); PIN(); dma(2, kt + 2); PIN();
-      mma2(2, af[1], bfr[1]);
-      PHASE_BARRIER();
-    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   }
-#undef PIN
+  PIN();
+  asm volatile("s_barrier" ::: "memory");
+  PIN();
+  {
+    short4v lo[4];
+#pragma unroll
+    for (int r = 0; r < 12; ++r) read(smem, 0, r, f[0], lo);
+  }
+
+  if (KT >= 3) {
+    kstep(F_{}, T_{}, T_{}, 0);                                      // K-step 1 was loaded whole in the prologue
+    for (int kt = 1; kt < KT - 2; ++kt) kstep(T_{}, T_{}, T_{}, kt);
+    kstep(T_{}, F_{}, T_{}, KT - 2);                                 // no K-step KT to load
+    kstep(F_{}, F_{}, F_{}, KT - 1);
+  } else if (KT == 2) {
+    kstep(F_{}, F_{}, T_{}, 0);
+    kstep(F_{}, F_{}, F_{}, 1);
+  } else {
+    kstep(F_{}, F_{}, F_{}, 0);
+  }
 }
 
 template <int ACT>
@@ -220,25 +206,24 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_mfma_kernel(const uint1
 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int wm = wave >> 2, wn = wave & 3;
+  const int wm = wave >> 1, wn = wave & 1;
 
-  // ---- global sources of this lane's direct-to-LDS loads ---------------------------------------------------------
-  // A: 1 KB block q*8+wave of the tile = rows 8(q*8+wave) .. +7, lane l writes row +l/8, chunk position l%8.
-  // B: 1 KB block q*8+wave = k-rows 2(q*8+wave), +1, lane l writes k-row +l/32, chunk position l%32.
-  const char* Ae = (const char*)(A + (int64_t)e * C * K);
-  const char* Be = (const char*)(B + (int64_t)e * K * N);
-  const char* a_src[4];
-  const char* b_src[4];
+  // ---- global sources of this lane's direct-to-LDS loads (32-bit offsets from per-expert scalar bases) -------------
+  // A: 1 KB block q*4+wave of the tile = rows 8(q*4+wave) .. +7, lane l writes row +l/8, chunk position l%8.
+  // B: 1 KB block q*4+wave = k-rows 2(q*4+wave), +1, lane l writes k-row +l/32, chunk position l%32.
+  const char* a_base = (const char*)(A + (int64_t)e * C * K);
+  const char* b_base = (const char*)(B + (int64_t)e * K * N);
+  uint32_t a_voff[8], b_voff[8];
 #pragma unroll
-  for (int q = 0; q < 4; ++q) {
-    const int r = q * 64 + wave * 8 + (lane >> 3);
+  for (int q = 0; q < 8; ++q) {
+    const int r = (q * 4 + wave) * 8 + (lane >> 3);
     int64_t row = m0 + r;
     row = row < C ? row : C - 1;                                    // rows past the slab are clamped (never stored)
     const int g = (lane & 7) ^ ((r >> 1) & 7);                      // global chunk that lands at position lane % 8
-    a_src[q] = Ae + (row * K + g * 8) * 2;
-    const int kr = q * 16 + wave * 2 + (lane >> 5);
+    a_voff[q] = (uint32_t)((row * K + g * 8) * 2);
+    const int kr = (q * 4 + wave) * 2 + (lane >> 5);
     const int c = (lane & 31) ^ (4 * (kr & 3));
-    b_src[q] = Be + ((int64_t)kr * N + n0 + c * 8) * 2;
+    b_voff[q] = (uint32_t)(((int64_t)kr * N + n0 + c * 8) * 2);
   }
   const int64_t a_step = (int64_t)BK * 2, b_step = (int64_t)BK * N * 2;
 
@@ -248,10 +233,10 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_mfma_kernel(const uint1
   int a_off[4];                                                     // + ((2 s + kg) ^ a_swz) * 16
 #pragma unroll
   for (int i = 0; i < 4; ++i) a_off[i] = (wm * 128 + i * 32 + (lane & 31)) * 128;
-  int b_off[2];                                                     // + (16 s + 4 rd) * 512
+  int b_off[4];                                                     // + (16 s + 4 rd) * 512
 #pragma unroll
-  for (int j = 0; j < 2; ++j) {
-    const int c = wn * 8 + j * 4 + ((lane >> 4) & 1) * 2 + ((lane & 3) >> 1);
+  for (int j = 0; j < 4; ++j) {
+    const int c = wn * 16 + j * 4 + ((lane >> 4) & 1) * 2 + ((lane & 3) >> 1);
     const int swz = 4 * ((lane >> 2) & 3);                          // 4 (k & 3), k & 3 = (lane % 16) / 4
     b_off[j] = kATileBytes + (kg * 8 + ((lane & 15) >> 2)) * 512 + ((c ^ swz) << 4) + ((lane & 1) << 3);
   }
@@ -259,16 +244,16 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_mfma_kernel(const uint1
   const int64_t wave_rows = rows - m0 - wm * 128;
   const int ni = wave_rows >= 128 ? 4 : (wave_rows <= 0 ? 0 : (int)((wave_rows + 31) >> 5));
 
-  f32x16 acc[4][2];
+  f32x16 acc[4][4];
 #pragma unroll
   for (int i = 0; i < 4; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < 4; ++j)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  if (ni == 4) tile_main_loop<true>(smem, a_src, b_src, a_step, b_step, a_off, b_off, a_swz, kg, ni, wm, wave, K, acc);
-  else tile_main_loop<false>(smem, a_src, b_src, a_step, b_step, a_off, b_off, a_swz, kg, ni, wm, wave, K, acc);
+  if (ni == 4) tile_main_loop<true>(smem, a_base, b_base, a_voff, b_voff, a_step, b_step, a_off, b_off, a_swz, kg, ni, wave, K, acc);
+  else tile_main_loop<false>(smem, a_base, b_base, a_voff, b_voff, a_step, b_step, a_off, b_off, a_swz, kg, ni, wave, K, acc);
 
   // ---- epilogue: bias, activation, bf16, 8-byte stores (4 consecutive columns per lane and register group) -------
   uint16_t* oute = out + (int64_t)e * C * N;
@@ -277,10 +262,10 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_mfma_kernel(const uint1
     const int64_t row = m0 + wm * 128 + i * 32 + (lane & 31);
     if (row >= rows) continue;
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
+    for (int j = 0; j < 4; ++j) {
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
-        const int col = n0 + wn * 64 + j * 32 + 8 * g + 4 * kg;
+        const int col = n0 + wn * 128 + j * 32 + 8 * g + 4 * kg;
         float v[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) v[u] = acc[i][j][4 * g + u];
@@ -292,8 +277,8 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_mfma_kernel(const uint1
 #pragma unroll
         for (int u = 0; u < 4; ++u) v[u] = epilogue_act<ACT>(v[u]);
         uint2 pk;
-        pk.x = (uint32_t)f32_to_bf16_bits(v[0]) | ((uint32_t)f32_to_bf16_bits(v[1]) << 16);
-        pk.y = (uint32_t)f32_to_bf16_bits(v[2]) | ((uint32_t)f32_to_bf16_bits(v[3]) << 16);
+        pk.x = pack_bf16x2(v[0], v[1]);
+        pk.y = pack_bf16x2(v[2], v[3]);
         *reinterpret_cast<uint2*>(oute + row * N + col) = pk;
       }
     }
@@ -303,7 +288,8 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_mfma_kernel(const uint1
 bool grouped_gemm_mfma_supports(int64_t E, int64_t C, int64_t K, int64_t N) {
   if (K % BK != 0 || N % BN != 0) return false;
   const int64_t tiles = E * ceil_div(C, BM) * (N / BN);
-  return tiles < ((int64_t)1 << 30) && C * K < ((int64_t)1 << 40);
+  // 32-bit byte offsets inside one expert's A slab and B matrix
+  return tiles < ((int64_t)1 << 30) && C * K * 2 < ((int64_t)1 << 32) && K * N * 2 < ((int64_t)1 << 32);
 }
 
 hipError_t launch_grouped_gemm_mfma(const void* A, const void* B, const void* bias, int act, const int32_t* counts,

@@ -20,63 +20,97 @@ typedef __attribute__((ext_vector_type(4))) double f64x4;
 // A lane keeps 8 consecutive x values (k = kq*8 .. kq*8+7 of a 32-wide chunk); MFMA step s uses k = kq*8+s for
 // both operands, so the chunk's 32 k-values are covered exactly once.
 // ---------------------------------------------------------------------------------------------------------------
-template <typename XT> __device__ __forceinline__ void load8_as_f32(const XT* p, float (&v)[8]);
-template <> __device__ __forceinline__ void load8_as_f32<float>(const float* p, float (&v)[8]) {
-  const float4 a = *reinterpret_cast<const float4*>(p), b = *reinterpret_cast<const float4*>(p + 4);
-  v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
-}
-template <> __device__ __forceinline__ void load8_as_f32<uint16_t>(const uint16_t* p, float (&v)[8]) {
-  const uint4 a = *reinterpret_cast<const uint4*>(p);
-  const uint32_t w[4] = {a.x, a.y, a.z, a.w};
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    v[2 * i] = __uint_as_float(w[i] << 16);
-    v[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+// Eight consecutive x values of one lane, kept raw while in flight and widened when used.
+template <typename XT> struct Raw8;
+template <> struct Raw8<float> {
+  float4 a, b;
+  __device__ __forceinline__ void load(const float* p) { a = *reinterpret_cast<const float4*>(p); b = *reinterpret_cast<const float4*>(p + 4); }
+  __device__ __forceinline__ void zero() { a = make_float4(0.f, 0.f, 0.f, 0.f); b = a; }
+  __device__ __forceinline__ void widen(float (&v)[8]) const {
+    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
   }
-}
+};
+template <> struct Raw8<uint16_t> {
+  uint4 a;
+  __device__ __forceinline__ void load(const uint16_t* p) { a = *reinterpret_cast<const uint4*>(p); }
+  __device__ __forceinline__ void zero() { a = make_uint4(0, 0, 0, 0); }
+  __device__ __forceinline__ void widen(float (&v)[8]) const {
+    const uint32_t w[4] = {a.x, a.y, a.z, a.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      v[2 * i] = __uint_as_float(w[i] << 16);
+      v[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+    }
+  }
+};
 
 template <typename XT, int NT>
 __global__ __launch_bounds__(256) void gate_logits_kernel(const XT* __restrict__ x, const XT* __restrict__ Wg,
                                                           const float* __restrict__ bias, int64_t T, int M, int E,
                                                           int e_base, float* __restrict__ logits) {
-  constexpr int BK = 32, EN = NT * 16;
+  // Wg is staged through LDS as fp64 in chunks of BK rows (32 KB whatever NT is).  x goes straight from global memory
+  // to registers; with one wave per SIMD nothing else hides its latency, so each lane keeps PF passes (PF * 32 k) of
+  // its row in flight in a register ring.
+  constexpr int EN = NT * 16, BK = 4096 / EN, PF = 8;
+  static_assert((PF * 32) % BK == 0, "LDS chunks must tile the register ring");
   __shared__ double wlds[BK][EN];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int m = lane & 15, kq = lane >> 4;
   const int64_t t0 = ((int64_t)blockIdx.x * 4 + wave) * 16;
   const int64_t trow = (t0 + m < T) ? (t0 + m) : (T - 1);
-  const XT* xrow = x + trow * (int64_t)M;
+  const XT* xrow = x + trow * (int64_t)M + kq * 8;
   f64x4 acc[NT];
 #pragma unroll
   for (int nt = 0; nt < NT; ++nt) acc[nt] = f64x4{0.0, 0.0, 0.0, 0.0};
 
-  float xv[8], xn[8];
+  // this thread's 16 elements of a Wg chunk, fetched one chunk ahead so that their latency hides behind the MFMAs
+  constexpr int WPT = BK * EN / 256;
+  XT wraw[WPT];
+  auto wg_fetch = [&](int kchunk) {
 #pragma unroll
-  for (int i = 0; i < 8; ++i) xv[i] = 0.f;
-  if (kq * 8 < M) load8_as_f32<XT>(xrow + kq * 8, xv);
-
-  for (int k0 = 0; k0 < M; k0 += BK) {
-    __syncthreads();                                   // the previous chunk of Wg has been consumed
-    for (int i = threadIdx.x; i < BK * EN; i += 256) {
-      const int r = i / EN, c = i % EN, kk = k0 + r, e = e_base + c;
-      wlds[r][c] = (kk < M && e < E) ? (double)load_as_f32<XT>(Wg + (int64_t)kk * E + e) : 0.0;
+    for (int i = 0; i < WPT; ++i) {
+      const int id = threadIdx.x + i * 256, kk = kchunk + id / EN, e = e_base + id % EN;
+      wraw[i] = (kk < M && e < E) ? Wg[(int64_t)kk * E + e] : XT(0);
     }
-    const int kn = k0 + BK + kq * 8;                   // prefetch this lane's x values of the next chunk
+  };
+  wg_fetch(0);
+
+  Raw8<XT> ring[PF];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) xn[i] = 0.f;
-    if (kn < M) load8_as_f32<XT>(xrow + kn, xn);
-    __syncthreads();
+  for (int j = 0; j < PF; ++j) {
+    if (j * 32 + kq * 8 < M) ring[j].load(xrow + j * 32); else ring[j].zero();
+  }
+
+  for (int kbase = 0; kbase < M; kbase += PF * 32) {
 #pragma unroll
-    for (int s = 0; s < 8; ++s) {
-      const double a = (double)xv[s];
+    for (int j = 0; j < PF; ++j) {
+      const int k0 = kbase + j * 32;                   // this pass covers k0 .. k0+31 (uniform across the block)
+      if (k0 >= M) break;
+      if ((j * 32) % BK == 0) {                        // refill the LDS chunk of Wg that starts here
+        __syncthreads();
 #pragma unroll
-      for (int nt = 0; nt < NT; ++nt) {
-        const double b = wlds[kq * 8 + s][nt * 16 + m];
-        acc[nt] = __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, acc[nt], 0, 0, 0);
+        for (int i = 0; i < WPT; ++i) {
+          const int id = threadIdx.x + i * 256;
+          wlds[id / EN][id % EN] = (double)load_as_f32<XT>(&wraw[i]);
+        }
+        __syncthreads();
+        wg_fetch(k0 + BK);
+      }
+      float xv[8];
+      ring[j].widen(xv);
+      const int kn = k0 + PF * 32 + kq * 8;            // refill the ring slot with the pass PF ahead
+      if (kn < M) ring[j].load(xrow + k0 + PF * 32); else ring[j].zero();
+      const int r0 = (j * 32) % BK + kq * 8;
+#pragma unroll
+      for (int s = 0; s < 8; ++s) {
+        const double a = (double)xv[s];
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+          const double b = wlds[r0 + s][nt * 16 + m];
+          acc[nt] = __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, acc[nt], 0, 0, 0);
+        }
       }
     }
-#pragma unroll
-    for (int i = 0; i < 8; ++i) xv[i] = xn[i];
   }
 #pragma unroll
   for (int nt = 0; nt < NT; ++nt) {
