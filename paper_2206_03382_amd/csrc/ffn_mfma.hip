@@ -88,7 +88,7 @@ template <bool FULL>
 __device__ __forceinline__ void tile_main_loop(char* smem, const char* a_base, const char* b_base,
                                                const uint32_t (&a_voff)[8], const uint32_t (&b_voff)[8], int64_t a_step,
                                                int64_t b_step, const int (&a_off)[4], const int (&b_off)[4], int a_swz,
-                                               int kg, int ni, int wave, int K, f32x16 (&acc)[4][4]) {
+                                               int kg, int ni, int a_mask, int wave, int K, f32x16 (&acc)[4][4]) {
   Frags f[2];
   const uint32_t smem_addr = (uint32_t)(uintptr_t)LDS_PTR(char, smem);
   const int KT = K / BK;
@@ -97,7 +97,7 @@ __device__ __forceinline__ void tile_main_loop(char* smem, const char* a_base, c
   auto read = [&](const char* stage, int s, int r, Frags& d, short4v (&lo)[4]) {
     if (r < 4) {
       if (FULL || r < ni) d.a[r] = *LDS_PTR(bf16x8, stage + a_off[r] + (((2 * s + kg) ^ a_swz) << 4));
-    } else {
+    } else if (FULL || ni > 0) {
       const int j = (r - 4) >> 1;
       if (((r - 4) & 1) == 0) {
         lo[j] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(short4v, stage + b_off[j] + (16 * s) * 512));
@@ -111,8 +111,9 @@ __device__ __forceinline__ void tile_main_loop(char* smem, const char* a_base, c
   auto dma = [&](int idx, int tile) {
     const int q = idx & 7;
     const uint32_t dst = smem_addr + (tile & 1) * kStageBytes + (q * 4 + wave) * 1024;
-    if (idx < 8) global_to_lds_16(a_base + tile * a_step, a_voff[q], dst);
-    else global_to_lds_16(b_base + tile * b_step, b_voff[q], dst + kATileBytes);
+    if (idx < 8) {
+      if (FULL || ((a_mask >> q) & 1)) global_to_lds_16(a_base + tile * a_step, a_voff[q], dst);   // skip rows past the slab's fill
+    } else global_to_lds_16(b_base + tile * b_step, b_voff[q], dst + kATileBytes);
   };
   auto mfma = [&](int m, const Frags& c) {
     const int i = m >> 2, j = m & 3;
@@ -156,7 +157,8 @@ __device__ __forceinline__ void tile_main_loop(char* smem, const char* a_base, c
   if (KT > 1) {
 #pragma unroll
     for (int idx = 0; idx < kLoadsPerWave; ++idx) dma(idx, 1);
-    asm volatile("s_waitcnt vmcnt(16)" ::: "memory");               // loads return in order: K-step 0 has landed
+    if (FULL) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");     // loads return in order: K-step 0 has landed
+    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");           // ragged tiles issue fewer loads: wait for all
   } else {
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   }
@@ -214,8 +216,10 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_mfma_kernel(const uint1
   const char* a_base = (const char*)(A + (int64_t)e * C * K);
   const char* b_base = (const char*)(B + (int64_t)e * K * N);
   uint32_t a_voff[8], b_voff[8];
+  int a_mask = 0;                                                   // bit q: A block q of this wave holds at least one real row
 #pragma unroll
   for (int q = 0; q < 8; ++q) {
+    if (m0 + (q * 4 + wave) * 8 < rows) a_mask |= 1 << q;
     const int r = (q * 4 + wave) * 8 + (lane >> 3);
     int64_t row = m0 + r;
     row = row < C ? row : C - 1;                                    // rows past the slab are clamped (never stored)
@@ -252,8 +256,8 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_mfma_kernel(const uint1
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  if (ni == 4) tile_main_loop<true>(smem, a_base, b_base, a_voff, b_voff, a_step, b_step, a_off, b_off, a_swz, kg, ni, wave, K, acc);
-  else tile_main_loop<false>(smem, a_base, b_base, a_voff, b_voff, a_step, b_step, a_off, b_off, a_swz, kg, ni, wave, K, acc);
+  if (ni == 4) tile_main_loop<true>(smem, a_base, b_base, a_voff, b_voff, a_step, b_step, a_off, b_off, a_swz, kg, ni, a_mask, wave, K, acc);
+  else tile_main_loop<false>(smem, a_base, b_base, a_voff, b_voff, a_step, b_step, a_off, b_off, a_swz, kg, ni, a_mask, wave, K, acc);
 
   // ---- epilogue: bias, activation, bf16, 8-byte stores (4 consecutive columns per lane and register group) -------
   uint16_t* oute = out + (int64_t)e * C * N;
