@@ -27,7 +27,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 FP32_VECTOR_PEAK_TFLOPS = 157.3
 # HBM bytes per grouped-GEMM launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (see profiles/), keyed by
 # workload name; None where no counter run has been recorded.
-MEASURED_GEMM_TRAFFIC_BYTES = {}
+MEASURED_GEMM_TRAFFIC_BYTES = {"mid_bf16": 635_624_000}     # profiles/bench_mid_bf16_hbm_traffic.txt
 
 
 def to_device(a, dtype_code):
@@ -47,6 +47,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", type=int, default=1, help="index into the five workloads (default 1: T=16384, M=H=2048, E=8, top-2)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run plain 256 MiB device copies first, so that a rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE run of "
+                         "this command can be scaled by what the same counter reads for a copy of known size")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures the single-GPU hot path only: run it with --gpus 1 "
@@ -69,6 +72,13 @@ def main() -> int:
                          to_device(inp["W2"], d), to_device(inp["b2"], d), T=cfg.T, k=cfg.k, f=cfg.f,
                          normalize=cfg.normalize, act=cfg.act, keep_routing=True)
     events = [moe.StageEvents() for _ in range(args.steps)]
+    if args.copy_calibration:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").random_(0, 255)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         layer.forward(x)
