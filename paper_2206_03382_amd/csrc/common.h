@@ -9,7 +9,7 @@
 namespace moe {
 
 constexpr int kWave = 64;            // CDNA wavefront width
-constexpr int kGateTokensPerBlock = 256;   // tokens whose arrivals one gate block counts and ranks
+constexpr int kGateTokensPerBlock = 64;    // tokens whose arrivals one gate block counts and ranks (one wave in assign)
 
 __device__ __forceinline__ float bf16_bits_to_f32(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
 

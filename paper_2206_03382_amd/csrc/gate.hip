@@ -160,9 +160,11 @@ __global__ __launch_bounds__(256) void gate_topk_kernel(const float* __restrict_
   __syncthreads();
   const int groups = 256 / G, g = threadIdx.x / G, gl = threadIdx.x % G;
   const float NEG_INF = -__builtin_inff();
-  for (int it = 0; it < G; ++it) {
-    const int64_t t = (int64_t)blockIdx.x * kGateTokensPerBlock + it * groups + g;
-    const bool valid = t < T;
+  const int passes = (kGateTokensPerBlock + groups - 1) / groups;
+  for (int it = 0; it < passes; ++it) {
+    const int tb = it * groups + g;                    // token of this block handled by this lane group in this pass
+    const int64_t t = (int64_t)blockIdx.x * kGateTokensPerBlock + tb;
+    const bool valid = tb < kGateTokensPerBlock && t < T;
     float v[V];
 #pragma unroll
     for (int vi = 0; vi < V; ++vi) {
@@ -254,26 +256,33 @@ __global__ __launch_bounds__(256) void gate_scan_kernel(int32_t* __restrict__ bl
   }
 }
 
-// One thread per token of the block: position among the block's earlier tokens with the same (rank, expert).
-__global__ __launch_bounds__(256) void gate_assign_kernel(const int32_t* __restrict__ idx,
-                                                          const int32_t* __restrict__ block_off, int64_t T, int E, int k,
-                                                          int64_t C, int NB, int32_t* __restrict__ loc,
-                                                          int32_t* __restrict__ slot_src) {
-  __shared__ int se[kGateTokensPerBlock];
-  const int tid = threadIdx.x;
-  const int64_t t = (int64_t)blockIdx.x * kGateTokensPerBlock + tid;
+// One wave per block of 64 tokens, one lane per token: position among the block's earlier tokens with the same
+// (rank, expert), found by grouping the lanes by expert with ballots (one round per distinct expert in the wave).
+__global__ __launch_bounds__(kGateTokensPerBlock) void gate_assign_kernel(const int32_t* __restrict__ idx,
+                                                                          const int32_t* __restrict__ block_off, int64_t T,
+                                                                          int E, int k, int64_t C, int NB,
+                                                                          int32_t* __restrict__ loc,
+                                                                          int32_t* __restrict__ slot_src) {
+  const int lane = threadIdx.x;
+  const int64_t t = (int64_t)blockIdx.x * kGateTokensPerBlock + lane;
+  const bool valid = t < T;
+  const unsigned long long below = (1ull << lane) - 1ull;
   for (int j = 0; j < k; ++j) {
-    const int e = (t < T) ? idx[t * k + j] : -1;
-    se[tid] = e;
-    __syncthreads();
+    const int e = valid ? idx[t * k + j] : -1;
+    unsigned long long remaining = __ballot(valid);
     int r = 0;
-    for (int i = 0; i < tid; ++i) r += (se[i] == e) ? 1 : 0;
-    if (t < T) {
+    while (remaining) {
+      const int leader = __ffsll((long long)remaining) - 1;
+      const int e0 = __shfl(e, leader);
+      const unsigned long long same = __ballot(valid && e == e0);
+      if (e == e0) r = __popcll(same & below);
+      remaining &= ~same;
+    }
+    if (valid) {
       const int l = block_off[((int64_t)j * NB + blockIdx.x) * E + e] + r;
       loc[t * k + j] = l;
       if (slot_src && l < C) slot_src[(int64_t)e * C + l] = (int32_t)t;
     }
-    __syncthreads();
   }
 }
 
@@ -295,7 +304,7 @@ hipError_t launch_gate_topk(const float* logits, int64_t T, int64_t E, int k, in
   gate_scan_kernel<<<dim3((unsigned)E), block, 0, s>>>(block_counts, k * NB, (int)E, C, counts, slot_src);
   err = hipGetLastError();
   if (err != hipSuccess) return err;
-  gate_assign_kernel<<<grid, block, 0, s>>>(idx, block_counts, T, (int)E, k, C, NB, loc, slot_src);
+  gate_assign_kernel<<<grid, dim3(kGateTokensPerBlock), 0, s>>>(idx, block_counts, T, (int)E, k, C, NB, loc, slot_src);
   return hipGetLastError();
 }
 

@@ -45,7 +45,7 @@ def test_capacity_follows_eq1(moe, golden_dir):
 
 
 def test_workspace_sizes(moe):
-    assert moe.gate_workspace_bytes(1000, 8, 2) == 2 * 4 * 8 * 4            # k * ceil(T/256) * E * sizeof(int32)
+    assert moe.gate_workspace_bytes(1000, 8, 2) == 2 * 16 * 8 * 4           # k * ceil(T/64) * E * sizeof(int32)
     assert moe.gate_workspace_bytes(1000, 8, 9) == 0                       # k > E
     T, M, H, E, k, C = 16384, 2048, 2048, 8, 2, 5120
     need = moe.layer_workspace_bytes(T, M, H, E, k, C, moe.BF16)
