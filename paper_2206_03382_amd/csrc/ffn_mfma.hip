@@ -84,11 +84,12 @@ struct Frags {
 // they may start only after the barrier that follows the last read of that stage (issued during sub-step 2): 8 of a
 // wave's 16 loads are issued in sub-step 3 of K-step kt, the other 8 in sub-step 0 of K-step kt+1, and they are
 // waited for before the barrier of K-step kt+1, two sub-steps later.
-template <bool FULL>
+template <int NI>
 __device__ __forceinline__ void tile_main_loop(char* smem, const char* a_base, const char* b_base,
                                                const uint32_t (&a_voff)[8], const uint32_t (&b_voff)[8], int64_t a_step,
                                                int64_t b_step, const int (&a_off)[4], const int (&b_off)[4], int a_swz,
-                                               int kg, int ni, int a_mask, int wave, int K, f32x16 (&acc)[4][4]) {
+                                               int kg, int a_mask, int wave, int K, f32x16 (&acc)[4][4]) {
+  constexpr bool FULL = NI == 4;
   Frags f[2];
   const uint32_t smem_addr = (uint32_t)(uintptr_t)LDS_PTR(char, smem);
   const int KT = K / BK;
@@ -96,8 +97,8 @@ __device__ __forceinline__ void tile_main_loop(char* smem, const char* a_base, c
   // read number r (0..11) of sub-step s from `stage` into fragment buffer `d`: 0-3 A rows, 4-11 B column halves
   auto read = [&](const char* stage, int s, int r, Frags& d, short4v (&lo)[4]) {
     if (r < 4) {
-      if (FULL || r < ni) d.a[r] = *LDS_PTR(bf16x8, stage + a_off[r] + (((2 * s + kg) ^ a_swz) << 4));
-    } else if (FULL || ni > 0) {
+      if (r < NI) d.a[r] = *LDS_PTR(bf16x8, stage + a_off[r] + (((2 * s + kg) ^ a_swz) << 4));
+    } else if (NI > 0) {
       const int j = (r - 4) >> 1;
       if (((r - 4) & 1) == 0) {
         lo[j] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(short4v, stage + b_off[j] + (16 * s) * 512));
@@ -117,7 +118,7 @@ __device__ __forceinline__ void tile_main_loop(char* smem, const char* a_base, c
   };
   auto mfma = [&](int m, const Frags& c) {
     const int i = m >> 2, j = m & 3;
-    if (FULL || i < ni) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(c.b[j], c.a[i], acc[i][j], 0, 0, 0);
+    if (i < NI) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(c.b[j], c.a[i], acc[i][j], 0, 0, 0);
   };
   // one sub-step: 16 MFMAs from `c`, interleaved with the 12 reads of (stage, s_next) into `n` (if READS) and with the
   // direct loads dma_first .. dma_first+7 of K-step dma_tile (if DMA); both switches are compile-time so that the
@@ -256,8 +257,17 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_mfma_kernel(const uint1
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  if (ni == 4) tile_main_loop<true>(smem, a_base, b_base, a_voff, b_voff, a_step, b_step, a_off, b_off, a_swz, kg, ni, a_mask, wave, K, acc);
-  else tile_main_loop<false>(smem, a_base, b_base, a_voff, b_voff, a_step, b_step, a_off, b_off, a_swz, kg, ni, a_mask, wave, K, acc);
+  // the number of live sub-tiles is a template argument, so that the loop body of a ragged tile is as branch-free as a
+  // full one's (a wave with no rows still loads its share of B and joins the barriers)
+#define MOE_TILE_LOOP(NI) tile_main_loop<NI>(smem, a_base, b_base, a_voff, b_voff, a_step, b_step, a_off, b_off, a_swz, kg, a_mask, wave, K, acc)
+  switch (ni) {
+    case 4: MOE_TILE_LOOP(4); break;
+    case 3: MOE_TILE_LOOP(3); break;
+    case 2: MOE_TILE_LOOP(2); break;
+    case 1: MOE_TILE_LOOP(1); break;
+    default: MOE_TILE_LOOP(0); break;
+  }
+#undef MOE_TILE_LOOP
 
   // ---- epilogue: bias, activation, bf16, 8-byte stores (4 consecutive columns per lane and register group) -------
   uint16_t* oute = out + (int64_t)e * C * N;
