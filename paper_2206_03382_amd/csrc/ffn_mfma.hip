@@ -22,7 +22,8 @@
 // columns n0 + 4 (s%4) .. +3; result lane l holds column n0 + l, rows k0 .. k0+3).
 //
 // The two MFMA operands are passed swapped (B fragment first), so that a lane's accumulator registers hold four
-// consecutive output columns of one row: D'[n][m] with m = lane % 32, n = 8 (v/4) + 4 (lane/32) + v % 4.
+// consecutive output columns of one row: D'[n][m] with m = lane % 32, n = 8 (v/4) + 4 (lane/32) + v % 4.  The
+// epilogue packs them to 8 bytes, transposes the wave's 128 x 128 tile through LDS and stores whole 256-byte row pieces.
 #include <type_traits>
 
 #include "common.h"
@@ -33,6 +34,8 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) short short4v;
 typedef __attribute__((ext_vector_type(8))) short short8v;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
 namespace {
 
@@ -269,33 +272,46 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_mfma_kernel(const uint1
   }
 #undef MOE_TILE_LOOP
 
-  // ---- epilogue: bias, activation, bf16, 8-byte stores (4 consecutive columns per lane and register group) -------
-  uint16_t* oute = out + (int64_t)e * C * N;
+  // ---- epilogue: bias, activation, bf16; transposed through LDS so that global stores are 16 bytes per lane and a
+  // wave's store covers 4 rows x 256 contiguous bytes.  After the last barrier of the main loop no wave reads the
+  // stages and no direct load is in flight, so wave w may use the 32 KB at smem + 32 KB * w as its own
+  // [128 rows][16 chunks of 8 columns]; chunk c of row r sits at position c ^ (r % 16), which makes both the 8-byte
+  // writes (32 rows per instruction) and the 16-byte row-contiguous reads conflict-free.
+  char* wtile = smem + wave * 32768;
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    const int64_t row = m0 + wm * 128 + i * 32 + (lane & 31);
-    if (row >= rows) continue;
+    if (i >= ni) break;
+    const int r = i * 32 + (lane & 31);
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
-        const int col = n0 + wn * 128 + j * 32 + 8 * g + 4 * kg;
         float v[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) v[u] = acc[i][j][4 * g + u];
         if (bias) {
+          const int col = n0 + wn * 128 + j * 32 + 8 * g + 4 * kg;
           const uint2 bb = *reinterpret_cast<const uint2*>(bias + (int64_t)e * N + col);
           v[0] += __uint_as_float(bb.x << 16); v[1] += __uint_as_float(bb.x & 0xffff0000u);
           v[2] += __uint_as_float(bb.y << 16); v[3] += __uint_as_float(bb.y & 0xffff0000u);
         }
 #pragma unroll
         for (int u = 0; u < 4; ++u) v[u] = epilogue_act<ACT>(v[u]);
-        uint2 pk;
+        u32x2 pk;
         pk.x = pack_bf16x2(v[0], v[1]);
         pk.y = pack_bf16x2(v[2], v[3]);
-        *reinterpret_cast<uint2*>(oute + row * N + col) = pk;
+        *LDS_PTR(u32x2, wtile + r * 256 + (((4 * j + g) ^ (r & 15)) << 4) + 8 * kg) = pk;
       }
     }
+  }
+  uint16_t* oute = out + ((int64_t)e * C + m0 + wm * 128) * N + n0 + wn * 128;
+  const int64_t live = rows - m0 - wm * 128;                        // rows of this wave's tile that exist
+#pragma unroll 8
+  for (int it = 0; it < 32; ++it) {
+    if (it * 4 >= ni * 32) break;
+    const int r = it * 4 + (lane >> 4);
+    const u32x4 q = *LDS_PTR(u32x4, wtile + r * 256 + ((lane & 15) << 4));
+    if (r < live) *reinterpret_cast<u32x4*>(oute + (int64_t)r * N + (((lane & 15) ^ (r & 15)) << 3)) = q;
   }
 }
 
