@@ -91,7 +91,8 @@ template <int NI>
 __device__ __forceinline__ void tile_main_loop(char* smem, const char* a_base, const char* b_base,
                                                const uint32_t (&a_voff)[8], const uint32_t (&b_voff)[8], int64_t a_step,
                                                int64_t b_step, const int (&a_off)[4], const int (&b_off)[4], int a_swz,
-                                               int kg, int a_mask, int wave, int K, f32x16 (&acc)[4][4]) {
+                                               int kg, int a_mask, int wave, int K, const uint16_t* bias_w,
+                                               f32x16 (&acc)[4][4]) {
   constexpr bool FULL = NI == 4;
   Frags f[2];
   const uint32_t smem_addr = (uint32_t)(uintptr_t)LDS_PTR(char, smem);
@@ -161,6 +162,27 @@ __device__ __forceinline__ void tile_main_loop(char* smem, const char* a_base, c
   if (KT > 1) {
 #pragma unroll
     for (int idx = 0; idx < kLoadsPerWave; ++idx) dma(idx, 1);
+  }
+  // while the first stages are in flight: the accumulators start from the bias (register 4 g + u of tile (i, j) is
+  // column 32 j + 8 g + 4 kg + u of the wave's 128), or from zero
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      float b0 = 0.f, b1 = 0.f, b2 = 0.f, b3 = 0.f;
+      if (bias_w) {
+        const u32x2 bb = *reinterpret_cast<const u32x2*>(bias_w + j * 32 + 8 * g + 4 * kg);
+        b0 = __uint_as_float(bb.x << 16); b1 = __uint_as_float(bb.x & 0xffff0000u);
+        b2 = __uint_as_float(bb.y << 16); b3 = __uint_as_float(bb.y & 0xffff0000u);
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        if (i < NI) { acc[i][j][4 * g] = b0; acc[i][j][4 * g + 1] = b1; acc[i][j][4 * g + 2] = b2; acc[i][j][4 * g + 3] = b3; }
+      }
+    }
+  }
+  PIN();
+  if (KT > 1) {
     if (FULL) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");     // loads return in order: K-step 0 has landed
     else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");           // ragged tiles issue fewer loads: wait for all
   } else {
@@ -174,6 +196,7 @@ __device__ __forceinline__ void tile_main_loop(char* smem, const char* a_base, c
 #pragma unroll
     for (int r = 0; r < 12; ++r) read(smem, 0, r, f[0], lo);
   }
+  PIN();
 
   if (KT >= 3) {
     kstep(F_{}, T_{}, T_{}, 0);                                      // K-step 1 was loaded whole in the prologue
@@ -253,16 +276,11 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_mfma_kernel(const uint1
   const int ni = wave_rows >= 128 ? 4 : (wave_rows <= 0 ? 0 : (int)((wave_rows + 31) >> 5));
 
   f32x16 acc[4][4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+  const uint16_t* bias_w = bias ? bias + (int64_t)e * N + n0 + wn * 128 : nullptr;
 
   // the number of live sub-tiles is a template argument, so that the loop body of a ragged tile is as branch-free as a
   // full one's (a wave with no rows still loads its share of B and joins the barriers)
-#define MOE_TILE_LOOP(NI) tile_main_loop<NI>(smem, a_base, b_base, a_voff, b_voff, a_step, b_step, a_off, b_off, a_swz, kg, a_mask, wave, K, acc)
+#define MOE_TILE_LOOP(NI) tile_main_loop<NI>(smem, a_base, b_base, a_voff, b_voff, a_step, b_step, a_off, b_off, a_swz, kg, a_mask, wave, K, bias_w, acc)
   switch (ni) {
     case 4: MOE_TILE_LOOP(4); break;
     case 3: MOE_TILE_LOOP(3); break;
@@ -272,7 +290,7 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_mfma_kernel(const uint1
   }
 #undef MOE_TILE_LOOP
 
-  // ---- epilogue: bias, activation, bf16; transposed through LDS so that global stores are 16 bytes per lane and a
+  // ---- epilogue: activation, bf16; transposed through LDS so that global stores are 16 bytes per lane and a
   // wave's store covers 4 rows x 256 contiguous bytes.  After the last barrier of the main loop no wave reads the
   // stages and no direct load is in flight, so wave w may use the 32 KB at smem + 32 KB * w as its own
   // [128 rows][16 chunks of 8 columns]; chunk c of row r sits at position c ^ (r % 16), which makes both the 8-byte
@@ -289,12 +307,6 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_mfma_kernel(const uint1
         float v[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) v[u] = acc[i][j][4 * g + u];
-        if (bias) {
-          const int col = n0 + wn * 128 + j * 32 + 8 * g + 4 * kg;
-          const uint2 bb = *reinterpret_cast<const uint2*>(bias + (int64_t)e * N + col);
-          v[0] += __uint_as_float(bb.x << 16); v[1] += __uint_as_float(bb.x & 0xffff0000u);
-          v[2] += __uint_as_float(bb.y << 16); v[3] += __uint_as_float(bb.y & 0xffff0000u);
-        }
 #pragma unroll
         for (int u = 0; u < 4; ++u) v[u] = epilogue_act<ACT>(v[u]);
         u32x2 pk;
