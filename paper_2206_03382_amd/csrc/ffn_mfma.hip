@@ -55,22 +55,26 @@ __device__ __forceinline__ void global_to_lds_16(const char* base, uint32_t voff
   asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(voff), "s"(base), "s"(lds_addr) : "memory");
 }
 
-// Branch-free activations for the bf16 epilogue.  erf by the 5-term rational/exponential form of Abramowitz & Stegun
-// 7.1.26 (absolute error < 1.5e-7, far below bf16 resolution).
-__device__ __forceinline__ float fast_erf(float x) {
-  const float ax = fabsf(x);
-  const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, ax, 1.0f));
-  float p = fmaf(1.061405429f, t, -1.453152027f);
-  p = fmaf(p, t, 1.421413741f);
-  p = fmaf(p, t, -0.284496736f);
-  p = fmaf(p, t, 0.254829592f);
-  const float r = 1.0f - p * t * __expf(-ax * ax);
-  return copysignf(r, x);
+// Branch-free activations for the bf16 epilogue.  gelu(v) = v Phi(v) with Phi(-y) = erfc(y / sqrt 2) / 2 for y = |v|:
+// e = 2^-P(y) with a degree-5 polynomial P fitted to -log2 erfc(y / sqrt 2) (fit_gelu_poly.py beside this file derives
+// the coefficients; |gelu error| < 6e-7 everywhere, three orders below bf16 resolution), then Phi = 1 - e/2 for
+// v >= 0 and e/2 for v < 0.  One exponential, no division.
+constexpr float kGeluC1 = 1.151000500e+00f, kGeluC2 = 4.595958591e-01f, kGeluC3 = 5.214662850e-02f,
+                kGeluC4 = -7.198722102e-03f, kGeluC5 = 4.881033092e-04f;
+__device__ __forceinline__ float fast_gelu(float v) {
+  const float y = fabsf(v);
+  float p = fmaf(kGeluC5, y, kGeluC4);
+  p = fmaf(p, y, kGeluC3);
+  p = fmaf(p, y, kGeluC2);
+  p = fmaf(p, y, kGeluC1);
+  const float e = __builtin_amdgcn_exp2f(-(p * y));
+  const float d = copysignf(fmaf(-0.5f, e, 0.5f), v);              // Phi(v) - 1/2
+  return v * (0.5f + d);
 }
 
 template <int ACT> __device__ __forceinline__ float epilogue_act(float v) {
   if (ACT == MOE_ACT_RELU) return fmaxf(v, 0.f);
-  if (ACT == MOE_ACT_GELU) return 0.5f * v * (1.0f + fast_erf(v * 0.70710678118654752440f));
+  if (ACT == MOE_ACT_GELU) return fast_gelu(v);
   if (ACT == MOE_ACT_SILU) return v * __builtin_amdgcn_rcpf(1.0f + __expf(-v));
   return v;
 }
