@@ -11,6 +11,9 @@
 
 namespace moe {
 
+#ifndef GATE_TW
+#define GATE_TW 4
+#endif
 typedef __attribute__((ext_vector_type(4))) double f64x4;
 
 // ---------------------------------------------------------------------------------------------------------------
@@ -26,6 +29,12 @@ template <> struct Raw8<float> {
   float4 a, b;
   __device__ __forceinline__ void load(const float* p) { a = *reinterpret_cast<const float4*>(p); b = *reinterpret_cast<const float4*>(p + 4); }
   __device__ __forceinline__ void zero() { a = make_float4(0.f, 0.f, 0.f, 0.f); b = a; }
+  __device__ __forceinline__ void keep_if(uint32_t m) {            // m = all ones keeps the values, 0 makes them +0
+    a.x = __uint_as_float(__float_as_uint(a.x) & m); a.y = __uint_as_float(__float_as_uint(a.y) & m);
+    a.z = __uint_as_float(__float_as_uint(a.z) & m); a.w = __uint_as_float(__float_as_uint(a.w) & m);
+    b.x = __uint_as_float(__float_as_uint(b.x) & m); b.y = __uint_as_float(__float_as_uint(b.y) & m);
+    b.z = __uint_as_float(__float_as_uint(b.z) & m); b.w = __uint_as_float(__float_as_uint(b.w) & m);
+  }
   __device__ __forceinline__ void widen(float (&v)[8]) const {
     v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
   }
@@ -34,6 +43,7 @@ template <> struct Raw8<uint16_t> {
   uint4 a;
   __device__ __forceinline__ void load(const uint16_t* p) { a = *reinterpret_cast<const uint4*>(p); }
   __device__ __forceinline__ void zero() { a = make_uint4(0, 0, 0, 0); }
+  __device__ __forceinline__ void keep_if(uint32_t m) { a.x &= m; a.y &= m; a.z &= m; a.w &= m; }
   __device__ __forceinline__ void widen(float (&v)[8]) const {
     const uint32_t w[4] = {a.x, a.y, a.z, a.w};
 #pragma unroll
@@ -44,97 +54,193 @@ template <> struct Raw8<uint16_t> {
   }
 };
 
-template <typename XT, int NT>
+template <typename XT, int NT, int KS, int TW, bool VECW>
 __global__ __launch_bounds__(256) void gate_logits_kernel(const XT* __restrict__ x, const XT* __restrict__ Wg,
-                                                          const float* __restrict__ bias, int64_t T, int M, int E,
+                                                          const float* __restrict__ bias, int64_t T, int M, int Mq, int E,
                                                           int e_base, float* __restrict__ logits) {
-  // Wg is staged through LDS as fp64 in chunks of BK rows (32 KB whatever NT is).  x goes straight from global memory
-  // to registers; with one wave per SIMD nothing else hides its latency, so each lane keeps PF passes (PF * 32 k) of
-  // its row in flight in a register ring.
-  constexpr int EN = NT * 16, BK = 4096 / EN, PF = 8;
-  static_assert((PF * 32) % BK == 0, "LDS chunks must tile the register ring");
-  __shared__ double wlds[BK][EN];
+  // The block's four waves are 4/KS token groups times KS splits of the reduction; a wave owns TW tiles of 16 tokens.
+  // Split ks owns k in [ks*Mq, (ks+1)*Mq) (Mq a multiple of BKW); the partial sums are added in split order at the
+  // end.  Narrow gates (few experts) have one accumulator tile per 16 tokens, a serial chain of dependent MFMAs: TW
+  // token tiles per wave and several waves per SIMD give the matrix pipe independent chains to interleave, and the
+  // TW tiles share every Wg operand read.
+  // Wg is staged through LDS as fp64, BKW rows per split at a time (32 KB in all whatever NT is).  x goes straight
+  // from global memory to registers through a ring of PF passes (PF * 32 k) per lane and token tile.
+  constexpr int EN = NT * 16, ENP = EN + 1, BKW = 4096 / (KS * EN), PF = 8 / TW, TG = 4 / KS;
+  static_assert(BKW % 32 == 0 && ((PF * 32) % BKW == 0 || BKW % (PF * 32) == 0), "LDS chunks must hold whole passes");
+  // rows are padded by one double: the 64-byte pieces that the staging threads write and the 4 rows x 16 columns that
+  // an MFMA operand read gathers then both spread evenly over the LDS banks
+  __shared__ double wlds[KS * BKW * ENP];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int ks = wave % KS, tg = wave / KS;
   const int m = lane & 15, kq = lane >> 4;
-  const int64_t t0 = ((int64_t)blockIdx.x * 4 + wave) * 16;
-  const int64_t trow = (t0 + m < T) ? (t0 + m) : (T - 1);
-  const XT* xrow = x + trow * (int64_t)M + kq * 8;
-  f64x4 acc[NT];
+  const int64_t t0 = ((int64_t)blockIdx.x * TG + tg) * (16 * TW);
+  const int kfirst = ks * Mq;                                       // first k of this wave's split
+  const XT* xrow[TW];
 #pragma unroll
-  for (int nt = 0; nt < NT; ++nt) acc[nt] = f64x4{0.0, 0.0, 0.0, 0.0};
+  for (int w = 0; w < TW; ++w) {
+    const int64_t t = t0 + w * 16 + m;
+    xrow[w] = x + (t < T ? t : T - 1) * (int64_t)M + kfirst + kq * 8;
+  }
+  f64x4 acc[TW][NT];
+#pragma unroll
+  for (int w = 0; w < TW; ++w)
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) acc[w][nt] = f64x4{0.0, 0.0, 0.0, 0.0};
 
-  // this thread's 16 elements of a Wg chunk, fetched one chunk ahead so that their latency hides behind the MFMAs
-  constexpr int WPT = BK * EN / 256;
-  XT wraw[WPT];
-  auto wg_fetch = [&](int kchunk) {
+  // this thread's part of a Wg chunk (rows kl .. kl+BKW-1 of every split), fetched one chunk ahead so that its latency
+  // hides behind the MFMAs.  VECW (E a multiple of the 16-byte vector, Wg 16-byte aligned): 16-byte pieces of a row;
+  // otherwise single elements.
+  constexpr int VEC = VECW ? 16 / (int)sizeof(XT) : 1;
+  constexpr int WPT = KS * BKW * EN / (256 * VEC);
+  constexpr int WORDS = VECW ? 4 : 1;                  // raw 32-bit words of one piece
+  static_assert(WPT >= 1, "every thread stages at least one piece");
+  uint32_t wraw[WPT][WORDS];
+  // branch-free (dead pieces re-read the start of Wg and are masked to zero): a load inside a divergent branch would be
+  // waited for on the spot, together with every x load in flight
+  auto wg_fetch = [&](int kl) {
 #pragma unroll
     for (int i = 0; i < WPT; ++i) {
-      const int id = threadIdx.x + i * 256, kk = kchunk + id / EN, e = e_base + id % EN;
-      wraw[i] = (kk < M && e < E) ? Wg[(int64_t)kk * E + e] : XT(0);
+      const int id = (threadIdx.x + i * 256) * VEC, q = id / (BKW * EN), r = (id / EN) % BKW, e = e_base + id % EN;
+      const int kk = q * Mq + kl + r;
+      const bool live = kl + r < Mq && kk < M && e < E;
+      const XT* src = Wg + (live ? (int64_t)kk * E + e : 0);
+      const uint32_t keep = live ? 0xffffffffu : 0u;
+      if (VECW) {
+        const uint4 v = *reinterpret_cast<const uint4*>(src);
+        wraw[i][0] = v.x & keep; wraw[i][WORDS > 1 ? 1 : 0] = v.y & keep; wraw[i][WORDS > 2 ? 2 : 0] = v.z & keep;
+        wraw[i][WORDS > 3 ? 3 : 0] = v.w & keep;
+      } else if (sizeof(XT) == 2) {
+        wraw[i][0] = (uint32_t)*reinterpret_cast<const uint16_t*>(src) & keep;
+      } else {
+        wraw[i][0] = *reinterpret_cast<const uint32_t*>(src) & keep;
+      }
+    }
+  };
+  auto wg_stage = [&]() {
+#pragma unroll
+    for (int i = 0; i < WPT; ++i) {
+      const int id = (threadIdx.x + i * 256) * VEC;
+      double* dst = wlds + (id / EN) * ENP + id % EN;
+      if (sizeof(XT) == 2) {                           // bf16: even element in the low half of a word
+        if (VECW) {
+#pragma unroll
+          for (int u = 0; u < 4; ++u) {
+            dst[2 * u] = (double)__uint_as_float(wraw[i][u % WORDS] << 16);
+            dst[2 * u + 1] = (double)__uint_as_float(wraw[i][u % WORDS] & 0xffff0000u);
+          }
+        } else dst[0] = (double)__uint_as_float(wraw[i][0] << 16);
+      } else {
+#pragma unroll
+        for (int u = 0; u < VEC; ++u) dst[u] = (double)__uint_as_float(wraw[i][u % WORDS]);
+      }
     }
   };
   wg_fetch(0);
 
-  Raw8<XT> ring[PF];
+  Raw8<XT> ring[TW][PF];
 #pragma unroll
-  for (int j = 0; j < PF; ++j) {
-    if (j * 32 + kq * 8 < M) ring[j].load(xrow + j * 32); else ring[j].zero();
-  }
+  for (int j = 0; j < PF; ++j)
+#pragma unroll
+    for (int w = 0; w < TW; ++w) {
+      const bool live = j * 32 + kq * 8 < Mq && kfirst + j * 32 + kq * 8 < M;
+      ring[w][j].load(xrow[w] + (live ? j * 32 : -(kfirst + kq * 8)));       // dead lanes re-read the row's start
+      ring[w][j].keep_if(live ? 0xffffffffu : 0u);
+    }
 
-  for (int kbase = 0; kbase < M; kbase += PF * 32) {
+  const double* wmine = wlds + ks * BKW * ENP;
+  for (int kbase = 0; kbase < Mq; kbase += PF * 32) {
 #pragma unroll
     for (int j = 0; j < PF; ++j) {
-      const int k0 = kbase + j * 32;                   // this pass covers k0 .. k0+31 (uniform across the block)
-      if (k0 >= M) break;
-      if ((j * 32) % BK == 0) {                        // refill the LDS chunk of Wg that starts here
+      const int kl = kbase + j * 32;                   // this pass covers kl .. kl+31 of the split (uniform across the block)
+      if (kl >= Mq) break;
+      if (kl % BKW == 0) {                             // refill the LDS chunk of Wg that starts here
         __syncthreads();
-#pragma unroll
-        for (int i = 0; i < WPT; ++i) {
-          const int id = threadIdx.x + i * 256;
-          wlds[id / EN][id % EN] = (double)load_as_f32<XT>(&wraw[i]);
-        }
+        wg_stage();
         __syncthreads();
-        wg_fetch(k0 + BK);
+        wg_fetch(kl + BKW);
       }
-      float xv[8];
-      ring[j].widen(xv);
-      const int kn = k0 + PF * 32 + kq * 8;            // refill the ring slot with the pass PF ahead
-      if (kn < M) ring[j].load(xrow + k0 + PF * 32); else ring[j].zero();
-      const int r0 = (j * 32) % BK + kq * 8;
+      float xv[TW][8];
+      const int kn = kl + PF * 32 + kq * 8;            // refill the ring slot with the pass PF ahead
+#pragma unroll
+      for (int w = 0; w < TW; ++w) {
+        ring[w][j].widen(xv[w]);
+        // branch-free (dead lanes re-read the row's start), so that the compiler can count the loads in flight and
+        // the wait for the next Wg chunk does not drain this prefetch
+        const bool live = kn < Mq && kfirst + kn < M;
+        ring[w][j].load(xrow[w] + (live ? kl + PF * 32 : -(kfirst + kq * 8)));
+        ring[w][j].keep_if(live ? 0xffffffffu : 0u);
+      }
+      const int r0 = kl % BKW + kq * 8;
 #pragma unroll
       for (int s = 0; s < 8; ++s) {
-        const double a = (double)xv[s];
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
-          const double b = wlds[r0 + s][nt * 16 + m];
-          acc[nt] = __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, acc[nt], 0, 0, 0);
+          const double b = wmine[(r0 + s) * ENP + nt * 16 + m];
+#pragma unroll
+          for (int w = 0; w < TW; ++w) acc[w][nt] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)xv[w][s], b, acc[w][nt], 0, 0, 0);
         }
       }
     }
   }
+  if (KS > 1) {                                        // partial sums of splits 1 .. KS-1 go through LDS to split 0
+    double* red = wlds;                                // [KS-1][TG][TW][NT][64 lanes][4]
+    static_assert((KS - 1) * TG * TW * NT * 256 <= KS * BKW * ENP, "the partial sums must fit into the staging buffer");
+    __syncthreads();
+    if (ks > 0) {
 #pragma unroll
-  for (int nt = 0; nt < NT; ++nt) {
-    const int e = e_base + nt * 16 + m;
-    if (e >= E) continue;
-    const double be = bias ? (double)bias[e] : 0.0;
+      for (int w = 0; w < TW; ++w)
 #pragma unroll
-    for (int v = 0; v < 4; ++v) {
-      const int64_t t = t0 + 4 * v + kq;
-      if (t < T) logits[t * E + e] = (float)(acc[nt][v] + be);
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+          for (int v = 0; v < 4; ++v) red[(((((ks - 1) * TG + tg) * TW + w) * NT + nt) * 64 + lane) * 4 + v] = acc[w][nt][v];
     }
+    __syncthreads();
+    if (ks > 0) return;
+#pragma unroll
+    for (int q = 1; q < KS; ++q)
+#pragma unroll
+      for (int w = 0; w < TW; ++w)
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+          for (int v = 0; v < 4; ++v) acc[w][nt][v] += red[(((((q - 1) * TG + tg) * TW + w) * NT + nt) * 64 + lane) * 4 + v];
   }
+#pragma unroll
+  for (int w = 0; w < TW; ++w)
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+      const int e = e_base + nt * 16 + m;
+      if (e >= E) continue;
+      const double be = bias ? (double)bias[e] : 0.0;
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const int64_t t = t0 + w * 16 + 4 * v + kq;
+        if (t < T) logits[t * E + e] = (float)(acc[w][nt][v] + be);
+      }
+    }
+}
+
+template <typename XT, int NT, int KS, int TW>
+static void launch_gate_logits_one(const XT* x, const XT* Wg, const float* bias, int64_t T, int64_t M, int64_t E,
+                                   int64_t e_base, float* logits, hipStream_t s) {
+  constexpr int BKW = 4096 / (KS * NT * 16);
+  const int Mq = (int)(ceil_div(ceil_div(M, KS), BKW) * BKW);       // k per split, a whole number of LDS chunks
+  const dim3 grid((unsigned)ceil_div(T, 16 * TW * (4 / KS))), block(256);
+  constexpr int VEC = 16 / (int)sizeof(XT);
+  const bool vecw = E % VEC == 0 && e_base % VEC == 0 && ((uintptr_t)Wg & 15) == 0;
+  if (vecw) gate_logits_kernel<XT, NT, KS, TW, true><<<grid, block, 0, s>>>(x, Wg, bias, T, (int)M, Mq, (int)E, (int)e_base, logits);
+  else gate_logits_kernel<XT, NT, KS, TW, false><<<grid, block, 0, s>>>(x, Wg, bias, T, (int)M, Mq, (int)E, (int)e_base, logits);
 }
 
 template <typename XT>
 static hipError_t launch_gate_logits_t(const XT* x, const XT* Wg, const float* bias, int64_t T, int64_t M, int64_t E,
                                        float* logits, hipStream_t s) {
-  const dim3 grid((unsigned)ceil_div(T, 64)), block(256);
   for (int64_t e_base = 0; e_base < E; e_base += 128) {
     const int64_t rem = E - e_base;
-    if (rem <= 16) gate_logits_kernel<XT, 1><<<grid, block, 0, s>>>(x, Wg, bias, T, (int)M, (int)E, (int)e_base, logits);
-    else if (rem <= 32) gate_logits_kernel<XT, 2><<<grid, block, 0, s>>>(x, Wg, bias, T, (int)M, (int)E, (int)e_base, logits);
-    else if (rem <= 64) gate_logits_kernel<XT, 4><<<grid, block, 0, s>>>(x, Wg, bias, T, (int)M, (int)E, (int)e_base, logits);
-    else gate_logits_kernel<XT, 8><<<grid, block, 0, s>>>(x, Wg, bias, T, (int)M, (int)E, (int)e_base, logits);
+    if (rem <= 16) launch_gate_logits_one<XT, 1, 4, GATE_TW>(x, Wg, bias, T, M, E, e_base, logits, s);
+    else if (rem <= 32) launch_gate_logits_one<XT, 2, 4, 1>(x, Wg, bias, T, M, E, e_base, logits, s);
+    else if (rem <= 64) launch_gate_logits_one<XT, 4, 2, 1>(x, Wg, bias, T, M, E, e_base, logits, s);
+    else launch_gate_logits_one<XT, 8, 1, 1>(x, Wg, bias, T, M, E, e_base, logits, s);
   }
   return hipGetLastError();
 }
