@@ -11,9 +11,8 @@
 
 namespace moe {
 
-#ifndef GATE_TW
-#define GATE_TW 4
-#endif
+// token tiles (of 16) per wave for gates of at most 16 experts: 4 measured best on MI355X (2: +5 %, 1: +10 % time)
+constexpr int kNarrowGateTilesPerWave = 4;
 typedef __attribute__((ext_vector_type(4))) double f64x4;
 
 // ---------------------------------------------------------------------------------------------------------------
@@ -237,7 +236,7 @@ static hipError_t launch_gate_logits_t(const XT* x, const XT* Wg, const float* b
                                        float* logits, hipStream_t s) {
   for (int64_t e_base = 0; e_base < E; e_base += 128) {
     const int64_t rem = E - e_base;
-    if (rem <= 16) launch_gate_logits_one<XT, 1, 4, GATE_TW>(x, Wg, bias, T, M, E, e_base, logits, s);
+    if (rem <= 16) launch_gate_logits_one<XT, 1, 4, kNarrowGateTilesPerWave>(x, Wg, bias, T, M, E, e_base, logits, s);
     else if (rem <= 32) launch_gate_logits_one<XT, 2, 4, 1>(x, Wg, bias, T, M, E, e_base, logits, s);
     else if (rem <= 64) launch_gate_logits_one<XT, 4, 2, 1>(x, Wg, bias, T, M, E, e_base, logits, s);
     else launch_gate_logits_one<XT, 8, 1, 1>(x, Wg, bias, T, M, E, e_base, logits, s);
