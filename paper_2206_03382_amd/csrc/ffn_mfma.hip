@@ -224,13 +224,22 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_mfma_kernel(const uint1
                                                                      uint16_t* __restrict__ out) {
   __shared__ __attribute__((aligned(1024))) char smem[2 * kStageBytes];
 
-  // ---- which tile: spread consecutive logical tiles over one XCD (blocks are dealt round-robin to the 8 XCDs) ----
+  // ---- which tile -------------------------------------------------------------------------------------------------
+  // Logical tiles are numbered expert by expert, inside an expert by blocks of 8 tile columns, inside a block row by
+  // row: 32 consecutive numbers are 4 row tiles x 8 column tiles that share A rows and B columns.  Such groups of 32
+  // are dealt round-robin to the 8 XCDs (hardware deals blocks round-robin, so block b runs on XCD b % 8, whose 32 CUs
+  // then hold one group at a time in their own L2); dealing by group rather than by contiguous range keeps the XCDs
+  // evenly loaded when experts differ widely in row count.
   const int total = E * MT * NT;
   const int b = blockIdx.x;
-  const int per = total / 8, rem = total % 8, xcd = b % 8, within = b / 8;
-  const int pid = xcd * per + (xcd < rem ? xcd : rem) + within;
-  const int e = pid / (MT * NT);
-  const int mt = (pid / NT) % MT, nt = pid % NT;
+  const int xcd = b % 8, within = b / 8;
+  const int pid = ((within / 32) * 8 + xcd) * 32 + within % 32;
+  if (pid >= total) return;
+  const int e = pid / (MT * NT), q = pid % (MT * NT);
+  const int full = (NT / 8) * MT * 8;                               // tiles of this expert that lie in full 8-column blocks
+  int mt, nt;
+  if (q < full) { mt = (q % (MT * 8)) / 8; nt = (q / (MT * 8)) * 8 + q % 8; }
+  else { const int w = NT % 8, r = q - full; mt = r / w; nt = (NT / 8) * 8 + r % w; }
   int64_t rows = C;
   if (counts) { const int64_t c = counts[e]; rows = c < C ? (c > 0 ? c : 0) : C; }
   const int64_t m0 = (int64_t)mt * BM;
@@ -341,7 +350,7 @@ bool grouped_gemm_mfma_supports(int64_t E, int64_t C, int64_t K, int64_t N) {
 hipError_t launch_grouped_gemm_mfma(const void* A, const void* B, const void* bias, int act, const int32_t* counts,
                                     int64_t E, int64_t C, int64_t K, int64_t N, void* out, hipStream_t s) {
   const int MT = (int)ceil_div(C, BM), NT = (int)(N / BN);
-  const dim3 grid((unsigned)(E * MT * NT)), block(kThreads);
+  const dim3 grid((unsigned)(ceil_div(E * MT * NT, 256) * 256)), block(kThreads);   // whole groups of 32 tiles on 8 XCDs
 #define MOE_LAUNCH_GEMM(ACT)                                                                                          \
   grouped_gemm_mfma_kernel<ACT><<<grid, block, 0, s>>>((const uint16_t*)A, (const uint16_t*)B, (const uint16_t*)bias, \
                                                        counts, (int)E, C, (int)K, (int)N, MT, NT, (uint16_t*)out)
