@@ -133,12 +133,14 @@ def main() -> int:
         from threadpoolctl import threadpool_info
         blas = [p["num_threads"] for p in threadpool_info() if p.get("user_api") == "blas"]
         threads = max(blas) if blas else (os.cpu_count() or 1)     # the oracle's time is in numpy's BLAS matmuls
-        c0 = time.perf_counter()
-        O.moe_layer(inp["x"], inp["Wg"], inp["gate_bias"], inp["W1"], inp["b1"], inp["W2"], inp["b2"],
-                    cfg.k, cfg.f, cfg.normalize, cfg.act, tier="sparse")
+        reps, c0 = 0, time.perf_counter()
+        while reps == 0 or time.perf_counter() - c0 < 10.0:          # about 10 s of oracle work, whole passes only
+            O.moe_layer(inp["x"], inp["Wg"], inp["gate_bias"], inp["W1"], inp["b1"], inp["W2"], inp["b2"],
+                        cfg.k, cfg.f, cfg.normalize, cfg.act, tier="sparse")
+            reps += 1
         cpu_s = time.perf_counter() - c0
-        result["cpu_baseline"] = {"value": round(T / cpu_s, 1), "unit": "tokens/s", "cores": int(threads),
-                                  "kind": "oracle", "sample": f"the full workload once (all {T} tokens, fp64 numpy, zero-skipping tier), {cpu_s:.1f} s"}
+        result["cpu_baseline"] = {"value": round(T * reps / cpu_s, 1), "unit": "tokens/s", "cores": int(threads),
+                                  "kind": "oracle", "sample": f"the full workload {reps} times (all {T} tokens each, fp64 numpy, zero-skipping tier), {cpu_s:.1f} s"}
     print(json.dumps(result))
     return 0
 

@@ -44,6 +44,7 @@ constexpr int kThreads = 256;
 constexpr int kStageBytes = 65536;          // A tile 32 KB + B tile 32 KB
 constexpr int kATileBytes = 32768;
 constexpr int kLoadsPerWave = 16;           // 64 KB per K-step / (4 waves x 1 KB per wave-load)
+constexpr int kMaxExperts = 512;            // the tile search keeps one register per 64 experts
 
 #define LDS_PTR(T, p) ((__attribute__((address_space(3))) T*)(p))
 #define PIN() __builtin_amdgcn_sched_barrier(0)
@@ -225,28 +226,73 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_mfma_kernel(const uint1
   __shared__ __attribute__((aligned(1024))) char smem[2 * kStageBytes];
 
   // ---- which tile -------------------------------------------------------------------------------------------------
-  // Logical tiles are numbered expert by expert, inside an expert by blocks of 8 tile columns, inside a block row by
-  // row: 32 consecutive numbers are 4 row tiles x 8 column tiles that share A rows and B columns.  Such groups of 32
-  // are dealt round-robin to the 8 XCDs (hardware deals blocks round-robin, so block b runs on XCD b % 8, whose 32 CUs
-  // then hold one group at a time in their own L2); dealing by group rather than by contiguous range keeps the XCDs
-  // evenly loaded when experts differ widely in row count.
-  const int total = E * MT * NT;
+  // An expert's live tiles (row tiles below its fill x all column tiles) are numbered by blocks of 8 tile columns and,
+  // inside a block, row by row: 32 consecutive numbers are 4 row tiles x 8 column tiles that share A rows and B
+  // columns.  Each expert's numbering is cut into groups of 32; the full groups of all experts are numbered first,
+  // then the short last groups (ragged tails), and this sequence is dealt round-robin to the 8 XCDs: hardware deals
+  // blocks round-robin, so block b runs on XCD b % 8, whose 32 CUs hold one group at a time in their own L2.  Counting
+  // only live groups, full ones first, keeps the XCDs evenly loaded whatever the experts' fills are.  Every wave finds
+  // its group by prefix sums over the experts' group counts, 64 experts per step.
+  const int lane = threadIdx.x & 63;
   const int b = blockIdx.x;
-  const int xcd = b % 8, within = b / 8;
-  const int pid = ((within / 32) * 8 + xcd) * 32 + within % 32;
-  if (pid >= total) return;
-  const int e = pid / (MT * NT), q = pid % (MT * NT);
-  const int full = (NT / 8) * MT * 8;                               // tiles of this expert that lie in full 8-column blocks
+  const int group = ((b / 8) / 32) * 8 + b % 8, slot = (b / 8) % 32;
+  auto live_row_tiles = [&](int el) -> int {                        // row tiles of expert el that hold real rows
+    if (el >= E) return 0;
+    int64_t r = C;
+    if (counts) { const int64_t c = counts[el]; r = c < C ? (c > 0 ? c : 0) : C; }
+    return (int)((r + BM - 1) / BM);
+  };
+  constexpr int kChunks = kMaxExperts / 64;
+  int mtv[kChunks];                                                 // lane l of chunk c: live row tiles of expert 64 c + l
+#pragma unroll
+  for (int c = 0; c < kChunks; ++c) mtv[c] = c * 64 < E ? live_row_tiles(c * 64 + lane) : 0;   // all loads in flight at once
+  int total_full = 0;                                               // full groups of all experts
+#pragma unroll
+  for (int c = 0; c < kChunks; ++c) {
+    if (c * 64 >= E) break;
+    int v = mtv[c] * NT / 32;
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, 64);
+    total_full += __builtin_amdgcn_readfirstlane(v);
+  }
+  const bool short_group = group >= total_full;
+  const int target = short_group ? group - total_full : group;
+  int e = -1, mte = 0, rank = 0;                                    // expert, its live row tiles, group's rank among its own
+  int base = 0;
+#pragma unroll
+  for (int c = 0; c < kChunks; ++c) {
+    if (c * 64 >= E || e >= 0) break;
+    const int mt_l = mtv[c];
+    const int ng_l = short_group ? ((mt_l * NT) % 32 != 0 ? 1 : 0) : mt_l * NT / 32;
+    int inc = ng_l;                                                 // inclusive prefix sum over the wave
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+      const int t = __shfl_up(inc, d, 64);
+      if (lane >= d) inc += t;
+    }
+    const int tot = __builtin_amdgcn_readfirstlane(__shfl(inc, 63, 64));
+    if (target < base + tot) {
+      const unsigned long long hit = __ballot(base + inc > target);
+      const int l = __builtin_amdgcn_readfirstlane(__builtin_ctzll(hit));
+      e = c * 64 + l;                                               // the same in every lane: keep them in scalar registers
+      mte = __builtin_amdgcn_readfirstlane(__shfl(mt_l, l, 64));
+      rank = __builtin_amdgcn_readfirstlane(target - (base + __shfl(inc - ng_l, l, 64)));
+    }
+    base += tot;
+  }
+  if (e < 0) return;                                                // past the last live group
+  const int q = (short_group ? mte * NT / 32 : rank) * 32 + slot;
+  if (q >= mte * NT) return;                                        // idle slot of a short group
+  const int full = (NT / 8) * mte * 8;                              // live tiles of this expert in full 8-column blocks
   int mt, nt;
-  if (q < full) { mt = (q % (MT * 8)) / 8; nt = (q / (MT * 8)) * 8 + q % 8; }
+  if (q < full) { mt = (q % (mte * 8)) / 8; nt = (q / (mte * 8)) * 8 + q % 8; }
   else { const int w = NT % 8, r = q - full; mt = r / w; nt = (NT / 8) * 8 + r % w; }
   int64_t rows = C;
   if (counts) { const int64_t c = counts[e]; rows = c < C ? (c > 0 ? c : 0) : C; }
   const int64_t m0 = (int64_t)mt * BM;
-  if (m0 >= rows) return;
+  if (m0 >= rows) return;                                           // cannot happen (mt < mte); keeps every access in the slab
   const int n0 = nt * BN;
 
-  const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int wm = wave >> 1, wn = wave & 1;
 
@@ -341,7 +387,7 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_mfma_kernel(const uint1
 }
 
 bool grouped_gemm_mfma_supports(int64_t E, int64_t C, int64_t K, int64_t N) {
-  if (K % BK != 0 || N % BN != 0) return false;
+  if (K % BK != 0 || N % BN != 0 || E > kMaxExperts) return false;
   const int64_t tiles = E * ceil_div(C, BM) * (N / BN);
   // 32-bit byte offsets inside one expert's A slab and B matrix
   return tiles < ((int64_t)1 << 30) && C * K * 2 < ((int64_t)1 << 32) && K * N * 2 < ((int64_t)1 << 32);
@@ -350,7 +396,8 @@ bool grouped_gemm_mfma_supports(int64_t E, int64_t C, int64_t K, int64_t N) {
 hipError_t launch_grouped_gemm_mfma(const void* A, const void* B, const void* bias, int act, const int32_t* counts,
                                     int64_t E, int64_t C, int64_t K, int64_t N, void* out, hipStream_t s) {
   const int MT = (int)ceil_div(C, BM), NT = (int)(N / BN);
-  const dim3 grid((unsigned)(ceil_div(E * MT * NT, 256) * 256)), block(kThreads);   // whole groups of 32 tiles on 8 XCDs
+  const int64_t groups = E * ceil_div((int64_t)MT * NT, 32);                  // upper bound: every expert full
+  const dim3 grid((unsigned)(ceil_div(groups, 8) * 256)), block(kThreads);    // 32 blocks per group, groups dealt to 8 XCDs
 #define MOE_LAUNCH_GEMM(ACT)                                                                                          \
   grouped_gemm_mfma_kernel<ACT><<<grid, block, 0, s>>>((const uint16_t*)A, (const uint16_t*)B, (const uint16_t*)bias, \
                                                        counts, (int)E, C, (int)K, (int)N, MT, NT, (uint16_t*)out)
