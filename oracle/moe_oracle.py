@@ -28,6 +28,10 @@ Readings where the paper is silent (each listed again in the design notes):
   R6  encode copies rows unscaled; only decode applies the gate weight.  Unfilled slots are zero.
   R7  activations: ReLU; GeLU = 0.5 x (1 + erf(x / sqrt 2)); SiLU = x / (1 + exp(-x)).
   R8  a token whose choices were all dropped gets an all-zero output row.
+  R9  dynamic capacity (Sec. 4.1 "Dynamic Capacity Factor", capacity_setting x): x > 0 is the factor f itself;
+      x = 0 means the smallest capacity that drops nothing, which is the arrival count of the fullest expert
+      (Eq. 1 with the smallest such factor gives exactly that integer); x < 0 the same but never above the
+      capacity that factor -x gives.
 
 Pins (tests/test_oracle_*.py): Eq. 1 closed forms; the Fig. 2 worked shape; a hand-worked routing example;
 exhaustive/brute-force sequential-arrival simulation; invariants; tie cases; special cases that reduce to
@@ -51,6 +55,17 @@ ACT_RELU, ACT_GELU, ACT_SILU = 0, 1, 2
 def capacity(T: int, E: int, k: int, f: float) -> int:
     """C = ceil(k * f * T / E), evaluated left to right in double (reading R1)."""
     return int(math.ceil(float(k) * float(f) * float(T) / float(E)))
+
+
+def dynamic_capacity(counts: np.ndarray, T: int, E: int, k: int, capacity_setting: float) -> int:
+    """Capacity under the dynamic capacity factor of Sec. 4.1 (reading R9); `counts` are the un-truncated arrivals."""
+    x = float(capacity_setting)
+    if x > 0:
+        return capacity(T, E, k, x)
+    needed = int(np.max(np.asarray(counts)))          # the fullest expert decides: nothing is dropped iff C >= this
+    if x == 0:
+        return needed
+    return min(needed, capacity(T, E, k, -x))
 
 
 # ---------------------------------------------------------------------------------------------------------------
@@ -248,17 +263,23 @@ def expert_ffn(Z: np.ndarray, W1, b1, W2, b2, act: int, rows: Optional[Sequence[
 # ---------------------------------------------------------------------------------------------------------------
 
 def moe_layer(x, Wg, gate_bias, W1, b1, W2, b2, k: int, f: float, normalize: int, act: int,
-              tier: str = "sparse", logits: Optional[np.ndarray] = None) -> Dict[str, np.ndarray]:
+              tier: str = "sparse", logits: Optional[np.ndarray] = None,
+              capacity_setting: Optional[float] = None) -> Dict[str, np.ndarray]:
     """gate -> encode -> expert FFN -> decode on one device (Sec. 2.1 with both all-to-alls the identity).
+
+    With `capacity_setting` given, the capacity follows Sec. 4.1's dynamic capacity factor instead of `f`.
 
     tier = "dense": the literal one-hot-mask contractions (needs a [T,E,C] mask: small inputs only).
     tier = "sparse": the same sums with zero terms skipped; the FFN visits filled slots only.
     """
     T = x.shape[0]
     E = W1.shape[0]
-    C = capacity(T, E, k, f)
     if logits is None:
         logits = gate_logits(x, Wg, gate_bias)
+    if capacity_setting is None:
+        C = capacity(T, E, k, f)
+    else:                                             # arrivals do not depend on the capacity: count first, then choose C
+        C = dynamic_capacity(route(logits, k, 1, normalize)["counts"], T, E, k, capacity_setting)
     r = route(logits, k, C, normalize)
     if tier == "dense":
         D, W = dense_masks(r["idx"], r["loc"], r["gate_w"], E, C)

@@ -278,7 +278,40 @@ def pin_bruteforce_layer(o):
             np.testing.assert_allclose(r["out"], ref, rtol=1e-11, atol=1e-12)
 
 
-PINS = [pin_capacity_golden, pin_worked_routing_example, pin_fig2_even_top1, pin_exhaustive_top1_locations,
+def pin_dynamic_capacity(o):
+    """Sec. 4.1, dynamic capacity factor: x > 0 is Eq. 1 with f = x; x = 0 is the smallest capacity that drops no
+    token (so one less must drop one); x < 0 is the same, capped by the capacity of factor -x."""
+    # the hand-worked example: arrivals per expert are 6, 2, 4 (T = 6, E = 3, top-2)
+    assert o.dynamic_capacity(np.array([6, 2, 4]), 6, 3, 2, 0) == 6
+    assert o.dynamic_capacity(np.array([6, 2, 4]), 6, 3, 2, -1.0) == 4       # capped by ceil(2 * 1.0 * 6 / 3)
+    assert o.dynamic_capacity(np.array([6, 2, 4]), 6, 3, 2, -2.0) == 6       # cap 8 is above what is needed
+    assert o.dynamic_capacity(np.array([6, 2, 4]), 6, 3, 2, 1.25) == 5       # positive: Eq. 1 as it stands
+    r_ = _rng(29)
+    for T, E, k in ((37, 5, 2), (64, 8, 3), (20, 4, 1)):
+        logits = r_.standard_normal((T, E)).astype(np.float32) + np.linspace(0, 1.5, E, dtype=np.float32)[None, :]
+        counts = o.route(logits, k, 1, 1)["counts"]
+        C0 = o.dynamic_capacity(counts, T, E, k, 0)
+        assert o.route(logits, k, C0, 1)["kept"].all()                       # nothing dropped ...
+        assert not o.route(logits, k, C0 - 1, 1)["kept"].all()               # ... and no smaller capacity does that
+        for x in (0.5, 1.0, 4.0):
+            assert o.dynamic_capacity(counts, T, E, k, x) == o.capacity(T, E, k, x)
+            Cn = o.dynamic_capacity(counts, T, E, k, -x)
+            assert Cn == min(C0, o.capacity(T, E, k, x)) and Cn <= o.capacity(T, E, k, x)
+            # the kept set under -x is the kept set of the static factor x
+            assert np.array_equal(o.route(logits, k, Cn, 1)["kept"], o.route(logits, k, o.capacity(T, E, k, x), 1)["kept"])
+    # through the layer: setting 0 reproduces a static factor that is large enough, and drops nothing
+    x, Wg, gb, W1, b1, W2, b2 = _tiny_layer_inputs(31, 30, 6, 9, 4)
+    d = o.moe_layer(x, Wg, gb, W1, b1, W2, b2, k=2, f=1.0, normalize=1, act=o.ACT_GELU, tier="dense", capacity_setting=0)
+    s_ = o.moe_layer(x, Wg, gb, W1, b1, W2, b2, k=2, f=float(4), normalize=1, act=o.ACT_GELU, tier="dense")
+    assert d["kept"].all() and d["C"] == int(d["counts"].max()) and d["C"] <= s_["C"]
+    np.testing.assert_allclose(d["out"], s_["out"], rtol=1e-12, atol=1e-13)
+    capped = o.moe_layer(x, Wg, gb, W1, b1, W2, b2, k=2, f=1.0, normalize=1, act=o.ACT_GELU, tier="dense", capacity_setting=-0.5)
+    static = o.moe_layer(x, Wg, gb, W1, b1, W2, b2, k=2, f=0.5, normalize=1, act=o.ACT_GELU, tier="dense")
+    assert not capped["kept"].all()
+    np.testing.assert_allclose(capped["out"], static["out"], rtol=1e-12, atol=1e-13)
+
+
+PINS = [pin_dynamic_capacity, pin_capacity_golden, pin_worked_routing_example, pin_fig2_even_top1, pin_exhaustive_top1_locations,
         pin_random_topk_vs_bruteforce, pin_invariants, pin_ties_lower_index, pin_gate_against_torch,
         pin_activations_and_ffn_against_torch, pin_no_drop_equals_weighted_sum_of_experts,
         pin_identity_experts_masked_scaling, pin_dense_equals_sparse_and_direct, pin_bruteforce_layer]
@@ -294,6 +327,11 @@ def test_pin(pin):
 # ----------------------------------------------------------------------------------------------------------------
 
 MISTAKES = {
+    "dynamic_capacity_least_full_expert": ("needed = int(np.max(np.asarray(counts)))", "needed = int(np.min(np.asarray(counts)))"),
+    "dynamic_capacity_mean_fill": ("needed = int(np.max(np.asarray(counts)))", "needed = int(math.ceil(np.mean(np.asarray(counts))))"),
+    "dynamic_capacity_bound_ignored": ("    return min(needed, capacity(T, E, k, -x))", "    return needed"),
+    "dynamic_capacity_bound_as_floor": ("    return min(needed, capacity(T, E, k, -x))", "    return max(needed, capacity(T, E, k, -x))"),
+    "dynamic_capacity_zero_uses_static": ("    if x == 0:\n        return needed", "    if x == 0:\n        return capacity(T, E, k, 1.0)"),
     "capacity_floor": ("int(math.ceil(float(k)", "int(math.floor(float(k)"),
     "capacity_drops_k": ("math.ceil(float(k) * float(f)", "math.ceil(float(f)"),
     "ties_to_higher_index": ("idx[:, j] = np.argmax(work, axis=1)", "idx[:, j] = E - 1 - np.argmax(work[:, ::-1], axis=1)"),
