@@ -80,6 +80,22 @@ int moe_gate_topk(const float* logits, int64_t T, int64_t E, int k, int64_t C, i
                   int32_t* idx, float* gate_w, int32_t* loc, int32_t* counts, int32_t* slot_src,
                   void* ws, size_t ws_bytes, void* stream);
 
+/* Dynamic capacity factor (Sec. 4.1 "Dynamic Capacity Factor"), for capacity_setting <= 0 (a positive setting is the
+ * factor f itself: use moe_capacity).  0: the smallest capacity that drops no token, i.e. the arrivals of the fullest
+ * expert; negative: the same, but never above the capacity that factor -capacity_setting gives by Eq. 1.
+ *   counts [E] int32 (device): un-truncated arrivals from moe_gate_topk (which may be called with slot_src = NULL and
+ *          any valid C: idx, gate_w, loc and counts do not depend on C).
+ *   C_out  [2] int64 (device, output): C_out[0] = capacity to use, C_out[1] = needed capacity max_e counts[e].
+ * The caller reads C_out back (one synchronisation), sizes the [E,C,M] buffers, builds slot_src with
+ * moe_slot_sources and continues with moe_encode / moe_expert_ffn / moe_decode. */
+int moe_dynamic_capacity(const int32_t* counts, int64_t T, int64_t E, int k, double capacity_setting, int64_t* C_out,
+                         void* stream);
+
+/* slot_src [E,C] (output) for a capacity chosen after routing (Sec. 4.1): token occupying slot (e,c), -1 if unfilled,
+ * from idx, loc [T,k] of moe_gate_topk; a choice is kept iff loc < C.  E*C must be below 2^31. */
+int moe_slot_sources(const int32_t* idx, const int32_t* loc, int64_t T, int64_t E, int k, int64_t C, int32_t* slot_src,
+                     void* stream);
+
 /* Fast encode (Sec. 4.2 "Fast Encode and Decode", Appendix B):  Z[e,c,:] = x[t,:] for the kept choice (t,j) with
  * idx[t,j] = e and loc[t,j] = c; unfilled slots are set to zero.  Rows are copied unscaled (bit-exact).
  *   x [T,M], Z [E,C,M] in `dtype`; idx, loc [T,k] from moe_gate_topk.

@@ -113,6 +113,25 @@ int moe_gate_topk(const float* logits, int64_t T, int64_t E, int k, int64_t C, i
                           (hipStream_t)stream) == hipSuccess ? MOE_OK : MOE_HIP_ERROR;
 }
 
+int moe_dynamic_capacity(const int32_t* counts, int64_t T, int64_t E, int k, double capacity_setting, int64_t* C_out,
+                         void* stream) {
+  if (!counts || !C_out || !(capacity_setting <= 0.0)) return MOE_INVALID_ARG;    // positive settings: moe_capacity
+  if (int st = gate_shape_status(T, E, k)) return st;
+  int64_t bound = 0;
+  if (capacity_setting < 0.0) {
+    bound = moe_capacity(T, E, k, -capacity_setting);
+    if (bound < 1 || bound > kMaxDim) return MOE_INVALID_ARG;
+  }
+  return launch_dynamic_capacity(counts, E, bound, C_out, (hipStream_t)stream) == hipSuccess ? MOE_OK : MOE_HIP_ERROR;
+}
+
+int moe_slot_sources(const int32_t* idx, const int32_t* loc, int64_t T, int64_t E, int k, int64_t C, int32_t* slot_src,
+                     void* stream) {
+  if (!idx || !loc || !slot_src || C < 1 || C > kMaxDim || E * C > kMaxDim) return MOE_INVALID_ARG;
+  if (int st = gate_shape_status(T, E, k)) return st;
+  return launch_slot_sources(idx, loc, T, E, k, C, slot_src, (hipStream_t)stream) == hipSuccess ? MOE_OK : MOE_HIP_ERROR;
+}
+
 int moe_encode(const void* x, int dtype, const int32_t* idx, const int32_t* loc, const int32_t* slot_src, int64_t T,
                int64_t M, int64_t E, int k, int64_t C, void* Z, void* stream) {
   if (!x || !idx || !loc || !Z || !dtype_ok(dtype) || T < 1 || E < 1 || k < 1 || k > E || C < 1 || T > kMaxDim ||

@@ -413,4 +413,57 @@ hipError_t launch_gate_topk(const float* logits, int64_t T, int64_t E, int k, in
   return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------------------------------------------
+// Dynamic capacity factor (Sec. 4.1): out[0] = capacity to use, out[1] = needed capacity = max_e counts[e].
+// bound > 0: capacity that the factor's upper bound gives (setting < 0); bound = 0: no upper bound (setting = 0).
+// ---------------------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void dynamic_capacity_kernel(const int32_t* __restrict__ counts, int E, int64_t bound,
+                                                               int64_t* __restrict__ out) {
+  __shared__ int part[4];
+  int m = 0;
+  for (int e = threadIdx.x; e < E; e += 256) m = max(m, counts[e]);
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) m = max(m, __shfl_xor(m, d, 64));
+  if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = m;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const int64_t needed = max(max(part[0], part[1]), max(part[2], part[3]));
+    out[0] = (bound > 0 && needed > bound) ? bound : needed;
+    out[1] = needed;
+  }
+}
+
+hipError_t launch_dynamic_capacity(const int32_t* counts, int64_t E, int64_t bound, int64_t* out, hipStream_t s) {
+  dynamic_capacity_kernel<<<dim3(1), dim3(256), 0, s>>>(counts, (int)E, bound, out);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------------------------
+// slot_src[e,c] for a capacity chosen after the arrivals were counted: -1 everywhere, then every kept choice writes
+// its token (loc is unique per expert, so no two writes meet).
+// ---------------------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void fill_i32_kernel(int32_t* __restrict__ p, int64_t n, int32_t v) {
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) p[i] = v;
+}
+
+__global__ __launch_bounds__(256) void slot_sources_kernel(const int32_t* __restrict__ idx, const int32_t* __restrict__ loc,
+                                                           int64_t pairs, int k, int E, int64_t C,
+                                                           int32_t* __restrict__ slot_src) {
+  for (int64_t p = (int64_t)blockIdx.x * 256 + threadIdx.x; p < pairs; p += (int64_t)gridDim.x * 256) {
+    const int e = idx[p], l = loc[p];
+    if (l >= 0 && l < C && (unsigned)e < (unsigned)E) slot_src[(int64_t)e * C + l] = (int32_t)(p / k);
+  }
+}
+
+hipError_t launch_slot_sources(const int32_t* idx, const int32_t* loc, int64_t T, int64_t E, int k, int64_t C,
+                               int32_t* slot_src, hipStream_t s) {
+  const int64_t n = E * C, fb = ceil_div(n, 256 * 4);
+  fill_i32_kernel<<<dim3((unsigned)(fb < 8192 ? fb : 8192)), dim3(256), 0, s>>>(slot_src, n, -1);
+  hipError_t err = hipGetLastError();
+  if (err != hipSuccess) return err;
+  const int64_t pairs = T * k, sb = ceil_div(pairs, 256);
+  slot_sources_kernel<<<dim3((unsigned)(sb < 8192 ? sb : 8192)), dim3(256), 0, s>>>(idx, loc, pairs, k, (int)E, C, slot_src);
+  return hipGetLastError();
+}
+
 }  // namespace moe

@@ -8,7 +8,7 @@ from __future__ import annotations
 
 import ctypes
 import os
-from typing import Dict, Optional, Sequence
+from typing import Tuple, Dict, Optional, Sequence
 
 import torch
 
@@ -31,6 +31,8 @@ SIGNATURES = {
     "moe_layer_workspace_bytes": (_sz, [_i64, _i64, _i64, _i64, _i32, _i64, _i32]),
     "moe_gate_logits": (_i32, [_vp, _vp, _vp, _i32, _i64, _i64, _i64, _vp, _vp]),
     "moe_gate_topk": (_i32, [_vp, _i64, _i64, _i32, _i64, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "moe_dynamic_capacity": (_i32, [_vp, _i64, _i64, _i32, _dbl, _vp, _vp]),
+    "moe_slot_sources": (_i32, [_vp, _vp, _i64, _i64, _i32, _i64, _vp, _vp]),
     "moe_encode": (_i32, [_vp, _i32, _vp, _vp, _vp, _i64, _i64, _i64, _i32, _i64, _vp, _vp]),
     "moe_expert_ffn": (_i32, [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _i64, _i64, _i64, _i64, _vp, _vp, _vp]),
     "moe_decode": (_i32, [_vp, _i32, _vp, _vp, _vp, _i64, _i64, _i64, _i32, _i64, _vp, _vp]),
@@ -125,6 +127,43 @@ def gate_topk(logits: torch.Tensor, k: int, C: int, normalize: int, want_slot_sr
     _check(lib().moe_gate_topk(_p(logits), T, E, k, C, int(normalize), _p(idx), _p(gate_w), _p(loc), _p(counts), _p(slot_src),
                                _p(ws), ws.numel(), _stream()), "moe_gate_topk")
     return dict(idx=idx, loc=loc, gate_w=gate_w, counts=counts, slot_src=slot_src)
+
+
+def dynamic_capacity(counts: torch.Tensor, T: int, k: int, capacity_setting: float) -> Tuple[int, int]:
+    """(capacity to use, needed capacity) for capacity_setting <= 0; reads two integers back from the device."""
+    E = counts.shape[0]
+    out = torch.empty((2,), dtype=torch.int64, device=counts.device)
+    _check(lib().moe_dynamic_capacity(_p(counts), T, E, k, float(capacity_setting), _p(out), _stream()), "moe_dynamic_capacity")
+    C, needed = out.cpu().tolist()
+    return int(C), int(needed)
+
+
+def slot_sources(idx: torch.Tensor, loc: torch.Tensor, E: int, C: int) -> torch.Tensor:
+    T, k = idx.shape
+    slot_src = torch.empty((E, C), dtype=torch.int32, device=idx.device)
+    _check(lib().moe_slot_sources(_p(idx), _p(loc), T, E, k, C, _p(slot_src), _stream()), "moe_slot_sources")
+    return slot_src
+
+
+def layer_forward_dynamic(x, Wg, gate_bias, W1, b1, W2, b2, k: int, capacity_setting: float, normalize: int,
+                          act: int) -> Dict[str, torch.Tensor]:
+    """The layer with the dynamic capacity factor: route, choose the capacity from the arrivals (one read-back), then
+    dispatch, experts and combine at that capacity.  A positive setting is the static factor."""
+    T, E = x.shape[0], W1.shape[0]
+    logits = gate_logits(x, Wg, gate_bias)
+    if capacity_setting > 0:
+        C = capacity(T, E, k, capacity_setting)
+        r = gate_topk(logits, k, C, normalize)
+        needed = None
+    else:
+        r = gate_topk(logits, k, 1, normalize, want_slot_src=False)      # arrivals do not depend on the capacity
+        C, needed = dynamic_capacity(r["counts"], T, k, capacity_setting)
+        r["slot_src"] = slot_sources(r["idx"], r["loc"], E, C)
+    Z = encode(x, r["idx"], r["loc"], r["slot_src"], E, C)
+    Y = expert_ffn(Z, W1, b1, W2, b2, act, counts=r["counts"])
+    out = decode(Y, r["idx"], r["loc"], r["gate_w"])
+    r.update(C=C, needed_capacity=needed, logits=logits, Z=Z, out=out)
+    return r
 
 
 def encode(x: torch.Tensor, idx: torch.Tensor, loc: torch.Tensor, slot_src: Optional[torch.Tensor], E: int, C: int) -> torch.Tensor:

@@ -68,6 +68,11 @@ def test_argument_validation_never_launches(moe):
     assert L.moe_encode(fake + 2, moe.BF16, fake, fake, None, 8, 16, 4, 1, 2, fake, None) == moe.UNSUPPORTED           # alignment
     assert L.moe_expert_ffn(fake, fake, None, fake, None, 5, moe.BF16, None, 4, 2, 16, 16, fake, fake, None) == moe.INVALID_ARG
     assert L.moe_decode(fake, moe.F32, fake, fake, None, 8, 16, 4, 1, 2, fake, None) == moe.INVALID_ARG               # gate_w null
+    assert L.moe_dynamic_capacity(fake, 8, 4, 1, 1.25, fake, None) == moe.INVALID_ARG      # positive setting: moe_capacity
+    assert L.moe_dynamic_capacity(None, 8, 4, 1, 0.0, fake, None) == moe.INVALID_ARG
+    assert L.moe_dynamic_capacity(fake, 8, 4, 5, -1.0, fake, None) == moe.INVALID_ARG      # k > E
+    assert L.moe_slot_sources(fake, fake, 8, 4, 1, 0, fake, None) == moe.INVALID_ARG       # C < 1
+    assert L.moe_slot_sources(fake, None, 8, 4, 1, 2, fake, None) == moe.INVALID_ARG
     assert L.moe_layer_forward(fake, fake, None, fake, None, fake, None, 8, 16, 16, 4, 1, 0.0, 0, 0, moe.F32, fake,
                                None, None, None, None, None, fake, 1 << 30, None, None) == moe.INVALID_ARG            # f <= 0
     assert L.moe_layer_forward(fake, fake, None, fake, None, fake, None, 8, 16, 16, 4, 1, 1.0, 0, 0, moe.F32, fake,

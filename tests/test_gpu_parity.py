@@ -234,6 +234,37 @@ def test_layer_small(moe, cfg, bias):
 
 
 # ----------------------------------------------------------------------------------------------------------------
+# dynamic capacity factor (capacity_setting 0, negative, positive): capacity chosen on the device from the arrivals
+# ----------------------------------------------------------------------------------------------------------------
+DYNAMIC_LAYERS = [
+    synth.CONFIGS[0].scaled(T=300, M=40, H=72, E=3),
+    synth.CONFIGS[1].scaled(T=1500, M=256, H=512, E=8),
+    synth.CONFIGS[3].scaled(T=4096, M=256, H=512, E=64),                  # Zipf-skewed gate: far from balanced arrivals
+]
+
+
+@pytest.mark.parametrize("cfg", DYNAMIC_LAYERS, ids=lambda c: f"{c.name}-T{c.T}-E{c.E}")
+@pytest.mark.parametrize("setting", [0.0, -0.5, -1.0, -64.0, 1.25])
+def test_layer_dynamic_capacity(moe, cfg, setting):
+    inp = synth.make_inputs(cfg, seed=3, bias_std=0.25)
+    ref = O.moe_layer(inp["x"], inp["Wg"], inp["gate_bias"], inp["W1"], inp["b1"], inp["W2"], inp["b2"],
+                      cfg.k, cfg.f, cfg.normalize, cfg.act, tier="sparse", capacity_setting=setting)
+    d = cfg.dtype
+    gb = None if inp["gate_bias"] is None else torch.from_numpy(inp["gate_bias"]).cuda()
+    got = moe.layer_forward_dynamic(dev(inp["x"], d), dev(inp["Wg"], d), gb, dev(inp["W1"], d), dev(inp["b1"], d),
+                                    dev(inp["W2"], d), dev(inp["b2"], d), cfg.k, setting, cfg.normalize, cfg.act)
+    torch.cuda.synchronize()
+    assert got["C"] == ref["C"]
+    if setting <= 0:
+        assert got["needed_capacity"] == int(ref["counts"].max())
+    if setting == 0:
+        assert ref["kept"].all()
+    assert_routing_equal(got, ref, ref["C"], cfg.name)
+    assert np.array_equal(got["slot_src"].cpu().numpy(), O.slot_source(ref["idx"], ref["loc"], cfg.E, ref["C"]))
+    assert_close(host(got["out"]), ref["out"], cfg.dtype, f"dynamic-capacity layer output ({cfg.name}, setting {setting})")
+
+
+# ----------------------------------------------------------------------------------------------------------------
 # moe_layer_forward at the full benchmark sizes, in the launch configuration bench.py times
 # ----------------------------------------------------------------------------------------------------------------
 @pytest.mark.parametrize("cfg", synth.CONFIGS[1:4], ids=lambda c: c.name)
