@@ -8,6 +8,8 @@ of seeded synthetic input that is already resident in HBM.  Prints one JSON line
              its mean launch time, measured with HIP events recorded on the library's stream inside the timed loop
   stages     per-stage mean milliseconds and, for encode/decode, algorithmic HBM GB/s
   cpu_baseline  the CPU oracle timed on this machine's host cores on the same workload
+  fused_dispatch  the same step through moe_layer_forward_fused (the first expert GEMM gathers its rows from the tokens,
+             no dispatch buffer), timed in a second loop of the same length; information only, `value` is the plain path
 """
 from __future__ import annotations
 
@@ -91,6 +93,16 @@ def main() -> int:
 
     ms_per_step = elapsed * 1e3 / args.steps
     stage_ms = np.mean(np.array([e.stage_ms() for e in events]), axis=0)
+
+    for _ in range(args.warmup):
+        layer.forward(x, fuse_dispatch=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        layer.forward(x, events[i], fuse_dispatch=True)
+    torch.cuda.synchronize()
+    fused_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    fused_stage_ms = np.mean(np.array([e.stage_ms() for e in events]), axis=0)
     for e in events:
         e.close()
     counts = layer.routing["counts"].cpu().numpy().astype(np.int64)
@@ -126,6 +138,8 @@ def main() -> int:
                      "flop_per_launch": flop_per_gemm, "avg_launch_ms": round(gemm_ms, 5),
                      "traffic": MEASURED_GEMM_TRAFFIC_BYTES.get(cfg.name)},
         "stages": stages,
+        "fused_dispatch": {"ms_per_step": round(fused_ms, 5), "value": round(T / (fused_ms * 1e-3), 1), "unit": "tokens/s",
+                           "stages": {name: round(float(ms), 5) for name, ms in zip(moe.STAGE_NAMES, fused_stage_ms)}},
     }
 
     if not args.no_cpu_baseline:

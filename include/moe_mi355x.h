@@ -116,6 +116,17 @@ int moe_expert_ffn(const void* Z, const void* W1, const void* b1, const void* W2
                    int act, int dtype, const int32_t* counts,
                    int64_t E, int64_t C, int64_t M, int64_t H, void* hidden, void* Y, void* stream);
 
+/* moe_encode followed by moe_expert_ffn without materialising the dispatch buffer (not in the paper, whose [E,C,M]
+ * buffer exists to feed the all-to-all; on one GPU the first expert GEMM can fetch its rows straight from the tokens):
+ * row c of expert e's operand is x[slot_src[e,c], :], read by the GEMM's own global->LDS loads.
+ *   x [T,M]; slot_src [E,C] from moe_gate_topk or moe_slot_sources; everything else as moe_expert_ffn.
+ *   Rows of Y and hidden past min(counts[e], C) (or, with counts = NULL, rows of unfilled slots) hold unspecified
+ *   values; decode never reads them.
+ * bf16 only, M % 64 == 0 and H % 256 == 0 and T*M*2 < 2^32, else MOE_UNSUPPORTED (use the two calls instead). */
+int moe_expert_ffn_gather(const void* x, const int32_t* slot_src, int64_t T, const void* W1, const void* b1, const void* W2,
+                          const void* b2, int act, int dtype, const int32_t* counts, int64_t E, int64_t C, int64_t M,
+                          int64_t H, void* hidden, void* Y, void* stream);
+
 /* Fast decode (Sec. 4.2, Appendix B):  out[t,:] = sum over kept choices j (ascending) of
  * gate_w[t,j] * Y[idx[t,j], loc[t,j], :], accumulated in fp32 and rounded once to `dtype`.
  * A token whose choices were all dropped gets an all-zero row.  Y [E,C,M], out [T,M] in `dtype`. */
@@ -134,6 +145,15 @@ int moe_layer_forward(const void* x, const void* Wg, const float* gate_bias,
                       int64_t T, int64_t M, int64_t H, int64_t E, int k, double f, int normalize, int act, int dtype,
                       void* out, int32_t* idx, int32_t* loc, float* gate_w, int32_t* counts, float* logits,
                       void* ws, size_t ws_bytes, void* stream, void* const* stage_events);
+
+/* moe_layer_forward with the dispatch fused into the first expert GEMM (moe_expert_ffn_gather) where that kernel
+ * supports the shape and dtype, identical to moe_layer_forward otherwise.  Same arguments, same outputs; the encode
+ * stage's events [2] and [3] are then recorded back to back. */
+int moe_layer_forward_fused(const void* x, const void* Wg, const float* gate_bias, const void* W1, const void* b1,
+                            const void* W2, const void* b2, int64_t T, int64_t M, int64_t H, int64_t E, int k, double f,
+                            int normalize, int act, int dtype, void* out, int32_t* idx, int32_t* loc, float* gate_w,
+                            int32_t* counts, float* logits, void* ws, size_t ws_bytes, void* stream,
+                            void* const* stage_events);
 
 /* Thin wrappers over HIP events so that a caller without HIP headers can time on the library's stream.
  * moe_event_create stores a new hipEvent_t in *event; moe_event_elapsed_ms needs both events completed. */

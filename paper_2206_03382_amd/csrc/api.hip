@@ -8,8 +8,9 @@ hipError_t launch_grouped_gemm_generic(const void* A, const void* B, const void*
                                        const int32_t* counts, int64_t E, int64_t C, int64_t K, int64_t N, void* out,
                                        hipStream_t s);
 hipError_t launch_grouped_gemm_mfma(const void* A, const void* B, const void* bias, int act, const int32_t* counts,
-                                    int64_t E, int64_t C, int64_t K, int64_t N, void* out, hipStream_t s);
-bool grouped_gemm_mfma_supports(int64_t E, int64_t C, int64_t K, int64_t N);
+                                    int64_t E, int64_t C, int64_t K, int64_t N, void* out, hipStream_t s,
+                                    const int32_t* gather = nullptr, int64_t gather_rows = 0);
+bool grouped_gemm_mfma_supports(int64_t E, int64_t C, int64_t K, int64_t N, int64_t gather_rows = 0);
 
 hipError_t launch_grouped_gemm(const void* A, const void* B, const void* bias, int act, int dtype, const int32_t* counts,
                                int64_t E, int64_t C, int64_t K, int64_t N, void* out, hipStream_t s) {
@@ -155,6 +156,22 @@ int moe_expert_ffn(const void* Z, const void* W1, const void* b1, const void* W2
   return MOE_OK;
 }
 
+int moe_expert_ffn_gather(const void* x, const int32_t* slot_src, int64_t T, const void* W1, const void* b1, const void* W2,
+                          const void* b2, int act, int dtype, const int32_t* counts, int64_t E, int64_t C, int64_t M, int64_t H,
+                          void* hidden, void* Y, void* stream) {
+  if (!x || !slot_src || !W1 || !W2 || !hidden || !Y || !dtype_ok(dtype) || !act_ok(act) || T < 1 || T > kMaxDim || E < 1 ||
+      C < 1 || E > 65535 || C > kMaxDim)
+    return MOE_INVALID_ARG;
+  if (int st = row_shape_status(M)) return st;
+  if (int st = row_shape_status(H)) return st;
+  if (!aligned(x, 16) || !aligned(W1, 16) || !aligned(W2, 16) || !aligned(hidden, 16) || !aligned(Y, 16)) return MOE_UNSUPPORTED;
+  if (dtype != MOE_BF16 || !grouped_gemm_mfma_supports(E, C, M, H, T)) return MOE_UNSUPPORTED;
+  hipStream_t s = (hipStream_t)stream;
+  if (launch_grouped_gemm_mfma(x, W1, b1, act, counts, E, C, M, H, hidden, s, slot_src, T) != hipSuccess) return MOE_HIP_ERROR;
+  if (launch_grouped_gemm(hidden, W2, b2, -1, dtype, counts, E, C, H, M, Y, s) != hipSuccess) return MOE_HIP_ERROR;
+  return MOE_OK;
+}
+
 int moe_decode(const void* Y, int dtype, const int32_t* idx, const int32_t* loc, const float* gate_w, int64_t T, int64_t M,
                int64_t E, int k, int64_t C, void* out, void* stream) {
   if (!Y || !idx || !loc || !gate_w || !out || !dtype_ok(dtype) || T < 1 || E < 1 || k < 1 || k > E || C < 1 ||
@@ -165,10 +182,13 @@ int moe_decode(const void* Y, int dtype, const int32_t* idx, const int32_t* loc,
   return launch_decode(Y, dtype, idx, loc, gate_w, T, M, E, k, C, out, (hipStream_t)stream) == hipSuccess ? MOE_OK : MOE_HIP_ERROR;
 }
 
-int moe_layer_forward(const void* x, const void* Wg, const float* gate_bias, const void* W1, const void* b1, const void* W2,
-                      const void* b2, int64_t T, int64_t M, int64_t H, int64_t E, int k, double f, int normalize, int act,
-                      int dtype, void* out, int32_t* idx, int32_t* loc, float* gate_w, int32_t* counts, float* logits,
-                      void* ws, size_t ws_bytes, void* stream, void* const* stage_events) {
+}  // extern "C"
+
+namespace {
+int layer_forward(const void* x, const void* Wg, const float* gate_bias, const void* W1, const void* b1, const void* W2,
+                  const void* b2, int64_t T, int64_t M, int64_t H, int64_t E, int k, double f, int normalize, int act, int dtype,
+                  void* out, int32_t* idx, int32_t* loc, float* gate_w, int32_t* counts, float* logits, void* ws,
+                  size_t ws_bytes, void* stream, void* const* stage_events, bool fuse_dispatch) {
   if (!x || !Wg || !W1 || !W2 || !out || !ws || !dtype_ok(dtype) || !act_ok(act) || !(f > 0.0)) return MOE_INVALID_ARG;
   if (int st = gate_shape_status(T, E, k)) return st;
   if (int st = row_shape_status(M)) return st;
@@ -201,11 +221,38 @@ int moe_layer_forward(const void* x, const void* Wg, const float* gate_bias, con
   if (launch_gate_logits(x, Wg, gate_bias, dtype, T, M, E, d_logits, s) != hipSuccess || !mark()) return MOE_HIP_ERROR;
   if (launch_gate_topk(d_logits, T, E, k, C, normalize, d_idx, d_gw, d_loc, d_counts, d_src, d_gws, s) != hipSuccess || !mark())
     return MOE_HIP_ERROR;
-  if (launch_encode(x, dtype, d_idx, d_loc, d_src, T, M, E, k, C, d_Z, s) != hipSuccess || !mark()) return MOE_HIP_ERROR;
-  if (launch_grouped_gemm(d_Z, W1, b1, act, dtype, d_counts, E, C, M, H, d_hidden, s) != hipSuccess || !mark()) return MOE_HIP_ERROR;
+  if (fuse_dispatch && dtype == MOE_BF16 && grouped_gemm_mfma_supports(E, C, M, H, T)) {
+    // the first expert GEMM gathers its rows from x through slot_src: the dispatch buffer is never materialised
+    if (!mark()) return MOE_HIP_ERROR;
+    if (launch_grouped_gemm_mfma(x, W1, b1, act, d_counts, E, C, M, H, d_hidden, s, d_src, T) != hipSuccess || !mark())
+      return MOE_HIP_ERROR;
+  } else {
+    if (launch_encode(x, dtype, d_idx, d_loc, d_src, T, M, E, k, C, d_Z, s) != hipSuccess || !mark()) return MOE_HIP_ERROR;
+    if (launch_grouped_gemm(d_Z, W1, b1, act, dtype, d_counts, E, C, M, H, d_hidden, s) != hipSuccess || !mark()) return MOE_HIP_ERROR;
+  }
   if (launch_grouped_gemm(d_hidden, W2, b2, -1, dtype, d_counts, E, C, H, M, d_Y, s) != hipSuccess || !mark()) return MOE_HIP_ERROR;
   if (launch_decode(d_Y, dtype, d_idx, d_loc, d_gw, T, M, E, k, C, out, s) != hipSuccess || !mark()) return MOE_HIP_ERROR;
   return MOE_OK;
+}
+}  // namespace
+
+extern "C" {
+
+int moe_layer_forward(const void* x, const void* Wg, const float* gate_bias, const void* W1, const void* b1, const void* W2,
+                      const void* b2, int64_t T, int64_t M, int64_t H, int64_t E, int k, double f, int normalize, int act,
+                      int dtype, void* out, int32_t* idx, int32_t* loc, float* gate_w, int32_t* counts, float* logits,
+                      void* ws, size_t ws_bytes, void* stream, void* const* stage_events) {
+  return layer_forward(x, Wg, gate_bias, W1, b1, W2, b2, T, M, H, E, k, f, normalize, act, dtype, out, idx, loc, gate_w, counts,
+                       logits, ws, ws_bytes, stream, stage_events, false);
+}
+
+int moe_layer_forward_fused(const void* x, const void* Wg, const float* gate_bias, const void* W1, const void* b1,
+                            const void* W2, const void* b2, int64_t T, int64_t M, int64_t H, int64_t E, int k, double f,
+                            int normalize, int act, int dtype, void* out, int32_t* idx, int32_t* loc, float* gate_w,
+                            int32_t* counts, float* logits, void* ws, size_t ws_bytes, void* stream,
+                            void* const* stage_events) {
+  return layer_forward(x, Wg, gate_bias, W1, b1, W2, b2, T, M, H, E, k, f, normalize, act, dtype, out, idx, loc, gate_w, counts,
+                       logits, ws, ws_bytes, stream, stage_events, true);
 }
 
 int moe_event_create(void** event) {

@@ -220,8 +220,9 @@ template <int ACT>
 __global__ __launch_bounds__(kThreads) void grouped_gemm_mfma_kernel(const uint16_t* __restrict__ A,
                                                                      const uint16_t* __restrict__ B,
                                                                      const uint16_t* __restrict__ bias,
-                                                                     const int32_t* __restrict__ counts, int E, int64_t C,
-                                                                     int K, int N, int MT, int NT,
+                                                                     const int32_t* __restrict__ counts,
+                                                                     const int32_t* __restrict__ gather, int gather_rows,
+                                                                     int E, int64_t C, int K, int N, int MT, int NT,
                                                                      uint16_t* __restrict__ out) {
   __shared__ __attribute__((aligned(1024))) char smem[2 * kStageBytes];
 
@@ -299,7 +300,10 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_mfma_kernel(const uint1
   // ---- global sources of this lane's direct-to-LDS loads (32-bit offsets from per-expert scalar bases) -------------
   // A: 1 KB block q*4+wave of the tile = rows 8(q*4+wave) .. +7, lane l writes row +l/8, chunk position l%8.
   // B: 1 KB block q*4+wave = k-rows 2(q*4+wave), +1, lane l writes k-row +l/32, chunk position l%32.
-  const char* a_base = (const char*)(A + (int64_t)e * C * K);
+  // With `gather` (the slot -> token map [E, C] of the dispatch), A is the token matrix [gather_rows, K] itself and row r
+  // of expert e's slab is token gather[e, r]: the dispatch buffer is never written or read.  Unfilled slots (-1) read
+  // token 0; their output rows lie past the expert's fill and are never used.
+  const char* a_base = gather ? (const char*)A : (const char*)(A + (int64_t)e * C * K);
   const char* b_base = (const char*)(B + (int64_t)e * K * N);
   uint32_t a_voff[8], b_voff[8];
   int a_mask = 0;                                                   // bit q: A block q of this wave holds at least one real row
@@ -309,6 +313,10 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_mfma_kernel(const uint1
     const int r = (q * 4 + wave) * 8 + (lane >> 3);
     int64_t row = m0 + r;
     row = row < C ? row : C - 1;                                    // rows past the slab are clamped (never stored)
+    if (gather) {
+      const int t = gather[(int64_t)e * C + row];
+      row = (unsigned)t < (unsigned)gather_rows ? t : 0;
+    }
     const int g = (lane & 7) ^ ((r >> 1) & 7);                      // global chunk that lands at position lane % 8
     a_voff[q] = (uint32_t)((row * K + g * 8) * 2);
     const int kr = (q * 4 + wave) * 2 + (lane >> 5);
@@ -386,21 +394,25 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_mfma_kernel(const uint1
   }
 }
 
-bool grouped_gemm_mfma_supports(int64_t E, int64_t C, int64_t K, int64_t N) {
+bool grouped_gemm_mfma_supports(int64_t E, int64_t C, int64_t K, int64_t N, int64_t gather_rows) {
   if (K % BK != 0 || N % BN != 0 || E > kMaxExperts) return false;
   const int64_t tiles = E * ceil_div(C, BM) * (N / BN);
-  // 32-bit byte offsets inside one expert's A slab and B matrix
-  return tiles < ((int64_t)1 << 30) && C * K * 2 < ((int64_t)1 << 32) && K * N * 2 < ((int64_t)1 << 32);
+  // 32-bit byte offsets inside one expert's A slab (or the whole token matrix when gathering) and B matrix
+  const int64_t a_rows = gather_rows > 0 ? gather_rows : C;
+  return tiles < ((int64_t)1 << 30) && a_rows * K * 2 < ((int64_t)1 << 32) && K * N * 2 < ((int64_t)1 << 32) &&
+         gather_rows < ((int64_t)1 << 31);
 }
 
 hipError_t launch_grouped_gemm_mfma(const void* A, const void* B, const void* bias, int act, const int32_t* counts,
-                                    int64_t E, int64_t C, int64_t K, int64_t N, void* out, hipStream_t s) {
+                                    int64_t E, int64_t C, int64_t K, int64_t N, void* out, hipStream_t s,
+                                    const int32_t* gather, int64_t gather_rows) {
   const int MT = (int)ceil_div(C, BM), NT = (int)(N / BN);
   const int64_t groups = E * ceil_div((int64_t)MT * NT, 32);                  // upper bound: every expert full
   const dim3 grid((unsigned)(ceil_div(groups, 8) * 256)), block(kThreads);    // 32 blocks per group, groups dealt to 8 XCDs
 #define MOE_LAUNCH_GEMM(ACT)                                                                                          \
   grouped_gemm_mfma_kernel<ACT><<<grid, block, 0, s>>>((const uint16_t*)A, (const uint16_t*)B, (const uint16_t*)bias, \
-                                                       counts, (int)E, C, (int)K, (int)N, MT, NT, (uint16_t*)out)
+                                                       counts, gather, (int)gather_rows, (int)E, C, (int)K, (int)N,  \
+                                                       MT, NT, (uint16_t*)out)
   switch (act) {
     case MOE_ACT_RELU: MOE_LAUNCH_GEMM(MOE_ACT_RELU); break;
     case MOE_ACT_GELU: MOE_LAUNCH_GEMM(MOE_ACT_GELU); break;

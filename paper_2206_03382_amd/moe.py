@@ -38,6 +38,9 @@ SIGNATURES = {
     "moe_decode": (_i32, [_vp, _i32, _vp, _vp, _vp, _i64, _i64, _i64, _i32, _i64, _vp, _vp]),
     "moe_layer_forward": (_i32, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _i64, _i32, _dbl, _i32, _i32, _i32,
                                  _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp, _c.POINTER(_vp)]),
+    "moe_layer_forward_fused": (_i32, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _i64, _i32, _dbl, _i32, _i32, _i32,
+                                       _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp, _c.POINTER(_vp)]),
+    "moe_expert_ffn_gather": (_i32, [_vp, _vp, _i64, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _i64, _i64, _i64, _i64, _vp, _vp, _vp]),
     "moe_event_create": (_i32, [_c.POINTER(_vp)]),
     "moe_event_destroy": (_i32, [_vp]),
     "moe_event_record": (_i32, [_vp, _vp]),
@@ -188,6 +191,19 @@ def expert_ffn(Z: torch.Tensor, W1: torch.Tensor, b1: Optional[torch.Tensor], W2
     return Y
 
 
+def expert_ffn_gather(x: torch.Tensor, slot_src: torch.Tensor, W1: torch.Tensor, b1: Optional[torch.Tensor], W2: torch.Tensor,
+                      b2: Optional[torch.Tensor], act: int, counts: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """encode + expert_ffn in one: the first GEMM reads row c of expert e from x[slot_src[e, c]]."""
+    T, M = x.shape
+    E, C = slot_src.shape
+    H = W1.shape[2]
+    Y = torch.empty((E, C, M), dtype=x.dtype, device=x.device)
+    hidden = torch.empty((E, C, H), dtype=x.dtype, device=x.device)
+    _check(lib().moe_expert_ffn_gather(_p(x), _p(slot_src), T, _p(W1), _p(b1), _p(W2), _p(b2), act, _dtype_code(x), _p(counts),
+                                       E, C, M, H, _p(hidden), _p(Y), _stream()), "moe_expert_ffn_gather")
+    return Y
+
+
 def decode(Y: torch.Tensor, idx: torch.Tensor, loc: torch.Tensor, gate_w: torch.Tensor) -> torch.Tensor:
     E, C, M = Y.shape
     T, k = idx.shape
@@ -248,13 +264,15 @@ class MoELayer:
                                 counts=torch.empty((self.E,), dtype=torch.int32, device=dev),
                                 logits=torch.empty((T, self.E), dtype=torch.float32, device=dev))
 
-    def forward(self, x: torch.Tensor, events: Optional[StageEvents] = None) -> torch.Tensor:
+    def forward(self, x: torch.Tensor, events: Optional[StageEvents] = None, fuse_dispatch: bool = False) -> torch.Tensor:
+        """One pass of the layer.  fuse_dispatch: let the first expert GEMM gather its rows from x (no dispatch buffer)."""
         if tuple(x.shape) != (self.T, self.M) or _dtype_code(x) != self.dtype:
             raise ValueError(f"x must be [{self.T}, {self.M}] in the layer's storage dtype")
         r = self.routing or {}
         ev = events.handles if events is not None else None
-        _check(lib().moe_layer_forward(_p(x), _p(self.Wg), _p(self.gate_bias), _p(self.W1), _p(self.b1), _p(self.W2), _p(self.b2),
-                                       self.T, self.M, self.H, self.E, self.k, self.f, self.normalize, self.act, self.dtype,
-                                       _p(self.out), _p(r.get("idx")), _p(r.get("loc")), _p(r.get("gate_w")), _p(r.get("counts")),
-                                       _p(r.get("logits")), _p(self.ws), self.ws.numel(), _stream(), ev), "moe_layer_forward")
+        entry = lib().moe_layer_forward_fused if fuse_dispatch else lib().moe_layer_forward
+        _check(entry(_p(x), _p(self.Wg), _p(self.gate_bias), _p(self.W1), _p(self.b1), _p(self.W2), _p(self.b2),
+                     self.T, self.M, self.H, self.E, self.k, self.f, self.normalize, self.act, self.dtype,
+                     _p(self.out), _p(r.get("idx")), _p(r.get("loc")), _p(r.get("gate_w")), _p(r.get("counts")),
+                     _p(r.get("logits")), _p(self.ws), self.ws.numel(), _stream(), ev), "moe_layer_forward")
         return self.out

@@ -234,6 +234,52 @@ def test_layer_small(moe, cfg, bias):
 
 
 # ----------------------------------------------------------------------------------------------------------------
+# dispatch fused into the first expert GEMM: same results as encode + FFN on the rows that exist
+# ----------------------------------------------------------------------------------------------------------------
+FUSED_LAYERS = [
+    synth.CONFIGS[1].scaled(T=1500, M=256, H=512, E=8),
+    synth.CONFIGS[2].scaled(T=1960, M=768, H=1024, E=32),
+    synth.CONFIGS[3].scaled(T=4096, M=256, H=512, E=64),
+    synth.CONFIGS[4].scaled(T=4096, M=512, H=256, E=128),
+    synth.CONFIGS[1].scaled(T=2000, M=264, H=520, E=8),                   # unsupported by the fused kernel: falls back
+]
+
+
+@pytest.mark.parametrize("cfg", FUSED_LAYERS, ids=lambda c: f"{c.name}-T{c.T}-M{c.M}-H{c.H}-E{c.E}")
+def test_layer_fused_dispatch(moe, cfg):
+    inp = synth.make_inputs(cfg, seed=5, bias_std=0.25)
+    ref = O.moe_layer(inp["x"], inp["Wg"], inp["gate_bias"], inp["W1"], inp["b1"], inp["W2"], inp["b2"],
+                      cfg.k, cfg.f, cfg.normalize, cfg.act, tier="sparse")
+    d = cfg.dtype
+    layer = moe.MoELayer(dev(inp["Wg"], d), None if inp["gate_bias"] is None else torch.from_numpy(inp["gate_bias"]).cuda(),
+                         dev(inp["W1"], d), dev(inp["b1"], d), dev(inp["W2"], d), dev(inp["b2"], d),
+                         T=cfg.T, k=cfg.k, f=cfg.f, normalize=cfg.normalize, act=cfg.act, keep_routing=True)
+    xd = dev(inp["x"], d)
+    plain = host(layer.forward(xd)).copy()
+    fused = host(layer.forward(xd, fuse_dispatch=True)).copy()
+    torch.cuda.synchronize()
+    assert_routing_equal(layer.routing, ref, ref["C"], cfg.name)
+    assert_close(fused, ref["out"], cfg.dtype, f"fused-dispatch layer output ({cfg.name})")
+    assert np.array_equal(fused.view(np.uint32), plain.view(np.uint32))       # same arithmetic on the same rows
+
+
+def test_expert_ffn_gather_matches_two_calls(moe):
+    cfg = synth.CONFIGS[1].scaled(T=1200, M=128, H=256, E=6)
+    inp = synth.make_inputs(cfg, seed=9, bias_std=0.25)
+    d = cfg.dtype
+    C = O.capacity(cfg.T, cfg.E, cfg.k, cfg.f)
+    logits = torch.from_numpy(O.gate_logits(inp["x"], inp["Wg"], inp["gate_bias"])).cuda()
+    r = moe.gate_topk(logits, cfg.k, C, cfg.normalize)
+    xd, W1, b1, W2, b2 = dev(inp["x"], d), dev(inp["W1"], d), dev(inp["b1"], d), dev(inp["W2"], d), dev(inp["b2"], d)
+    Y2 = moe.expert_ffn(moe.encode(xd, r["idx"], r["loc"], r["slot_src"], cfg.E, C), W1, b1, W2, b2, cfg.act, counts=r["counts"])
+    Y1 = moe.expert_ffn_gather(xd, r["slot_src"], W1, b1, W2, b2, cfg.act, counts=r["counts"])
+    torch.cuda.synchronize()
+    filled = (r["slot_src"] >= 0).cpu().numpy()
+    assert filled.sum() == int(np.minimum(r["counts"].cpu().numpy(), C).sum())
+    assert np.array_equal(host(Y1)[filled].view(np.uint32), host(Y2)[filled].view(np.uint32))
+
+
+# ----------------------------------------------------------------------------------------------------------------
 # dynamic capacity factor (capacity_setting 0, negative, positive): capacity chosen on the device from the arrivals
 # ----------------------------------------------------------------------------------------------------------------
 DYNAMIC_LAYERS = [
