@@ -256,14 +256,14 @@ hipError_t launch_gate_logits(const void* x, const void* Wg, const float* bias, 
 // index, so the result is unique and independent of the reduction tree.
 // ---------------------------------------------------------------------------------------------------------------
 template <int V>
-__global__ __launch_bounds__(256) void gate_topk_kernel(const float* __restrict__ logits, int64_t T, int E, int k, int G,
+__global__ __launch_bounds__(1024) void gate_topk_kernel(const float* __restrict__ logits, int64_t T, int E, int k, int G,
                                                         int normalize, int32_t* __restrict__ idx,
                                                         float* __restrict__ gate_w, int32_t* __restrict__ block_counts,
                                                         int NB) {
   extern __shared__ int hist[];                        // [k][E] arrivals of this block's tokens
-  for (int i = threadIdx.x; i < k * E; i += 256) hist[i] = 0;
+  for (int i = threadIdx.x; i < k * E; i += blockDim.x) hist[i] = 0;
   __syncthreads();
-  const int groups = 256 / G, g = threadIdx.x / G, gl = threadIdx.x % G;
+  const int groups = blockDim.x / G, g = threadIdx.x / G, gl = threadIdx.x % G;   // blockDim.x is a multiple of 64 >= G
   const float NEG_INF = -__builtin_inff();
   const int passes = (kGateTokensPerBlock + groups - 1) / groups;
   for (int it = 0; it < passes; ++it) {
@@ -323,7 +323,7 @@ __global__ __launch_bounds__(256) void gate_topk_kernel(const float* __restrict_
     }
   }
   __syncthreads();
-  for (int i = threadIdx.x; i < k * E; i += 256) {
+  for (int i = threadIdx.x; i < k * E; i += blockDim.x) {
     const int j = i / E, e = i % E;
     block_counts[((int64_t)j * NB + blockIdx.x) * E + e] = hist[i];
   }
@@ -399,11 +399,14 @@ hipError_t launch_gate_topk(const float* logits, int64_t T, int64_t E, int k, in
   while (G < E && G < 64) G <<= 1;
   const int V = (int)ceil_div(E, G);
   const size_t shmem = (size_t)k * E * sizeof(int);
+  // one lane group per token: as many threads as the block's 64 tokens need, so that (up to 16 experts) every token's
+  // logits are fetched in one round instead of one dependent round trip per pass
   const dim3 grid(NB), block(256);
-  if (V == 1) gate_topk_kernel<1><<<grid, block, shmem, s>>>(logits, T, (int)E, k, G, normalize, idx, gate_w, block_counts, NB);
-  else if (V == 2) gate_topk_kernel<2><<<grid, block, shmem, s>>>(logits, T, (int)E, k, G, normalize, idx, gate_w, block_counts, NB);
-  else if (V <= 4) gate_topk_kernel<4><<<grid, block, shmem, s>>>(logits, T, (int)E, k, G, normalize, idx, gate_w, block_counts, NB);
-  else gate_topk_kernel<8><<<grid, block, shmem, s>>>(logits, T, (int)E, k, G, normalize, idx, gate_w, block_counts, NB);
+  const dim3 tblock((unsigned)(64 * G < 256 ? 256 : (64 * G > 1024 ? 1024 : 64 * G)));
+  if (V == 1) gate_topk_kernel<1><<<grid, tblock, shmem, s>>>(logits, T, (int)E, k, G, normalize, idx, gate_w, block_counts, NB);
+  else if (V == 2) gate_topk_kernel<2><<<grid, tblock, shmem, s>>>(logits, T, (int)E, k, G, normalize, idx, gate_w, block_counts, NB);
+  else if (V <= 4) gate_topk_kernel<4><<<grid, tblock, shmem, s>>>(logits, T, (int)E, k, G, normalize, idx, gate_w, block_counts, NB);
+  else gate_topk_kernel<8><<<grid, tblock, shmem, s>>>(logits, T, (int)E, k, G, normalize, idx, gate_w, block_counts, NB);
   hipError_t err = hipGetLastError();
   if (err != hipSuccess) return err;
   gate_scan_kernel<<<dim3((unsigned)E), block, 0, s>>>(block_counts, k * NB, (int)E, C, counts, slot_src);
