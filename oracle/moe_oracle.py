@@ -28,6 +28,9 @@ Readings where the paper is silent (each listed again in the design notes):
   R6  encode copies rows unscaled; only decode applies the gate weight.  Unfilled slots are zero.
   R7  activations: ReLU; GeLU = 0.5 x (1 + erf(x / sqrt 2)); SiLU = x / (1 + exp(-x)).
   R8  a token whose choices were all dropped gets an all-zero output row.
+  R10 backward of encode / decode (Appendix B, the differentiable fast encode and decode operators; the figure with
+      the formulas is lost): the plain derivatives of the dense contractions.  encode is not scaled by the gate
+      weight here (R6), so its backward has no gate-weight gradient; idx and loc carry no gradient.
   R9  dynamic capacity (Sec. 4.1 "Dynamic Capacity Factor", capacity_setting x): x > 0 is the factor f itself;
       x = 0 means the smallest capacity that drops nothing, which is the arrival count of the fullest expert
       (Eq. 1 with the smallest such factor gives exactly that integer); x < 0 the same but never above the
@@ -215,6 +218,55 @@ def decode_sparse(Y: np.ndarray, idx: np.ndarray, loc: np.ndarray, gate_w: np.nd
         t = np.nonzero(loc[:, j] < C)[0]
         out[t] += gate_w[t, j][:, None] * Y[idx[t, j], loc[t, j]].astype(np.float64)
     return out
+
+
+# ---------------------------------------------------------------------------------------------------------------
+# Backward of encode / decode (Appendix B: differentiable fast encode and decode; reading R10).  The forward maps are
+# linear, Z = D^T x and out = W Y, so the backward maps are their transposes; the gate weight enters W linearly.
+# ---------------------------------------------------------------------------------------------------------------
+
+def encode_backward_dense(D: np.ndarray, dZ: np.ndarray) -> np.ndarray:
+    """dx[t,m] = sum_{e,c} dispatch_mask[t,e,c] dZ[e,c,m]   (einsum 'tec,ecm->tm')."""
+    T, E, C = D.shape
+    return D.reshape(T, E * C) @ np.asarray(dZ, dtype=np.float64).reshape(E * C, -1)
+
+
+def decode_backward_dense(W: np.ndarray, d_out: np.ndarray) -> np.ndarray:
+    """dY[e,c,m] = sum_t combine_w[t,e,c] d_out[t,m]   (einsum 'tec,tm->ecm')."""
+    T, E, C = W.shape
+    return (W.reshape(T, E * C).T @ np.asarray(d_out, dtype=np.float64)).reshape(E, C, -1)
+
+
+def gate_weight_grad(d_out: np.ndarray, Y: np.ndarray, idx: np.ndarray, loc: np.ndarray, C: int) -> np.ndarray:
+    """dgate_w[t,j] = sum_m d_out[t,m] Y[idx[t,j], loc[t,j], m] for a kept choice, 0 for a dropped one
+    (d out[t,m] / d gate_w[t,j] is the expert-output row of that choice)."""
+    T, k = idx.shape
+    g = np.zeros((T, k), dtype=np.float64)
+    do = np.asarray(d_out, dtype=np.float64)
+    for j in range(k):
+        t = np.nonzero(loc[:, j] < C)[0]
+        g[t, j] = (do[t] * np.asarray(Y[idx[t, j], loc[t, j]], dtype=np.float64)).sum(axis=1)
+    return g
+
+
+def encode_backward_sparse(dZ: np.ndarray, idx: np.ndarray, loc: np.ndarray, C: int) -> np.ndarray:
+    """The same sum as encode_backward_dense with the zero terms skipped."""
+    T, k = idx.shape
+    dx = np.zeros((T, dZ.shape[2]), dtype=np.float64)
+    for j in range(k):
+        t = np.nonzero(loc[:, j] < C)[0]
+        dx[t] += np.asarray(dZ[idx[t, j], loc[t, j]], dtype=np.float64)
+    return dx
+
+
+def decode_backward_sparse(d_out: np.ndarray, idx: np.ndarray, loc: np.ndarray, gate_w: np.ndarray, E: int, C: int) -> np.ndarray:
+    """The same sum as decode_backward_dense with the zero terms skipped (one term per filled slot)."""
+    T, k = idx.shape
+    dY = np.zeros((E, C, d_out.shape[1]), dtype=np.float64)
+    for j in range(k):
+        t = np.nonzero(loc[:, j] < C)[0]
+        dY[idx[t, j], loc[t, j]] = gate_w[t, j][:, None] * np.asarray(d_out[t], dtype=np.float64)
+    return dY
 
 
 # ---------------------------------------------------------------------------------------------------------------

@@ -311,7 +311,50 @@ def pin_dynamic_capacity(o):
     np.testing.assert_allclose(capped["out"], static["out"], rtol=1e-12, atol=1e-13)
 
 
-PINS = [pin_dynamic_capacity, pin_capacity_golden, pin_worked_routing_example, pin_fig2_even_top1, pin_exhaustive_top1_locations,
+def pin_encode_decode_backward(o):
+    """Appendix B, differentiable encode / decode: the backward maps are the adjoints of the (already pinned) forward
+    maps, the gate-weight gradient is the derivative of a map that is linear in the gate weight, and all of it agrees
+    with torch's autograd through the dense one-hot einsums."""
+    T, M, E, k = 26, 7, 4, 2
+    r_ = _rng(41)
+    logits = (r_.standard_normal((T, E)) + np.array([2.0, 0.5, 0.0, -2.0])[None, :]).astype(np.float32)
+    C = 12                                                  # a skewed gate: some drops and some unfilled slots
+    rt = o.route(logits, k, C, 1)
+    idx, loc, w = rt["idx"], rt["loc"], rt["gate_w"]
+    assert (~rt["kept"]).any() and (o.slot_source(idx, loc, E, C) < 0).any()
+    D, W = o.dense_masks(idx, loc, w, E, C)
+    x, dZ = r_.standard_normal((T, M)), r_.standard_normal((E, C, M))
+    Y, d_out = r_.standard_normal((E, C, M)), r_.standard_normal((T, M))
+    # adjoint identities against the forward maps
+    dx = o.encode_backward_dense(D, dZ)
+    np.testing.assert_allclose((dZ * o.encode_dense(D, x)).sum(), (dx * x).sum(), rtol=1e-12)
+    dY = o.decode_backward_dense(W, d_out)
+    np.testing.assert_allclose((d_out * o.decode_dense(W, Y)).sum(), (dY * Y).sum(), rtol=1e-12)
+    # out is linear in the gate weights: <d_out, out(w)> = sum_{t,j} w[t,j] dgate[t,j]
+    dg = o.gate_weight_grad(d_out, Y, idx, loc, C)
+    np.testing.assert_allclose((d_out * o.decode_dense(W, Y)).sum(), (w * dg).sum(), rtol=1e-12)
+    assert (dg[~rt["kept"]] == 0).all()
+    # torch autograd through the dense einsums
+    Dt, xt = torch.from_numpy(D), torch.from_numpy(x).requires_grad_(True)
+    torch.einsum("tec,tm->ecm", Dt, xt).backward(torch.from_numpy(dZ))
+    np.testing.assert_allclose(dx, xt.grad.numpy(), rtol=1e-12, atol=1e-13)
+    wt, Yt = torch.from_numpy(w).requires_grad_(True), torch.from_numpy(Y).requires_grad_(True)
+    Wt = torch.zeros((T, E, C), dtype=torch.float64)
+    for j in range(k):
+        t = torch.from_numpy(np.nonzero(rt["kept"][:, j])[0])
+        Wt = Wt.index_put((t, torch.from_numpy(idx[t.numpy(), j].astype(np.int64)), torch.from_numpy(loc[t.numpy(), j].astype(np.int64))),
+                          wt[t, j], accumulate=True)
+    torch.einsum("tec,ecm->tm", Wt, Yt).backward(torch.from_numpy(d_out))
+    np.testing.assert_allclose(dY, Yt.grad.numpy(), rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(dg, wt.grad.numpy(), rtol=1e-12, atol=1e-13)
+    # zero-skipping forms are the same sums
+    np.testing.assert_allclose(o.encode_backward_sparse(dZ, idx, loc, C), dx, rtol=1e-13, atol=1e-14)
+    np.testing.assert_allclose(o.decode_backward_sparse(d_out, idx, loc, w, E, C), dY, rtol=1e-13, atol=1e-14)
+    dead = (~rt["kept"]).all(axis=1)
+    assert (o.encode_backward_sparse(dZ, idx, loc, C)[dead] == 0).all()
+
+
+PINS = [pin_encode_decode_backward, pin_dynamic_capacity, pin_capacity_golden, pin_worked_routing_example, pin_fig2_even_top1, pin_exhaustive_top1_locations,
         pin_random_topk_vs_bruteforce, pin_invariants, pin_ties_lower_index, pin_gate_against_torch,
         pin_activations_and_ffn_against_torch, pin_no_drop_equals_weighted_sum_of_experts,
         pin_identity_experts_masked_scaling, pin_dense_equals_sparse_and_direct, pin_bruteforce_layer]
@@ -327,6 +370,18 @@ def test_pin(pin):
 # ----------------------------------------------------------------------------------------------------------------
 
 MISTAKES = {
+    "encode_bwd_untransposed": ("    return D.reshape(T, E * C) @ np.asarray(dZ, dtype=np.float64).reshape(E * C, -1)",
+                                "    return D.reshape(T, E * C)[:, ::-1] @ np.asarray(dZ, dtype=np.float64).reshape(E * C, -1)"),
+    "decode_bwd_unweighted": ("    return (W.reshape(T, E * C).T @ np.asarray(d_out, dtype=np.float64)).reshape(E, C, -1)",
+                              "    return ((W != 0).astype(np.float64).reshape(T, E * C).T @ np.asarray(d_out, dtype=np.float64)).reshape(E, C, -1)"),
+    "gate_grad_counts_dropped": ("        g[t, j] = (do[t] * np.asarray(Y[idx[t, j], loc[t, j]], dtype=np.float64)).sum(axis=1)",
+                                 "        g[:, j] = (do * np.asarray(Y[idx[:, j], np.minimum(loc[:, j], C - 1)], dtype=np.float64)).sum(axis=1)"),
+    "gate_grad_weighted_twice": ("        g[t, j] = (do[t] * np.asarray(Y[idx[t, j], loc[t, j]], dtype=np.float64)).sum(axis=1)",
+                                 "        g[t, j] = 2.0 * (do[t] * np.asarray(Y[idx[t, j], loc[t, j]], dtype=np.float64)).sum(axis=1)"),
+    "sparse_encode_bwd_keeps_dropped": ("        dx[t] += np.asarray(dZ[idx[t, j], loc[t, j]], dtype=np.float64)",
+                                        "        dx[:] += np.asarray(dZ[idx[:, j], np.minimum(loc[:, j], C - 1)], dtype=np.float64)"),
+    "sparse_decode_bwd_unweighted": ("        dY[idx[t, j], loc[t, j]] = gate_w[t, j][:, None] * np.asarray(d_out[t], dtype=np.float64)",
+                                     "        dY[idx[t, j], loc[t, j]] = np.asarray(d_out[t], dtype=np.float64)"),
     "dynamic_capacity_least_full_expert": ("needed = int(np.max(np.asarray(counts)))", "needed = int(np.min(np.asarray(counts)))"),
     "dynamic_capacity_mean_fill": ("needed = int(np.max(np.asarray(counts)))", "needed = int(math.ceil(np.mean(np.asarray(counts))))"),
     "dynamic_capacity_bound_ignored": ("    return min(needed, capacity(T, E, k, -x))", "    return needed"),
