@@ -49,6 +49,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", type=int, default=1, help="index into the five workloads (default 1: T=16384, M=H=2048, E=8, top-2)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--backward", action="store_true",
+                    help="also time the backward of encode and decode (moe_encode_backward, moe_decode_backward) on this "
+                         "workload's routing and report their HBM GB/s as `backward_dispatch`")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run plain 256 MiB device copies first, so that a rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE run of "
                          "this command can be scaled by what the same counter reads for a copy of known size")
@@ -141,6 +144,32 @@ def main() -> int:
         "fused_dispatch": {"ms_per_step": round(fused_ms, 5), "value": round(T / (fused_ms * 1e-3), 1), "unit": "tokens/s",
                            "stages": {name: round(float(ms), 5) for name, ms in zip(moe.STAGE_NAMES, fused_stage_ms)}},
     }
+
+    if args.backward:
+        r = layer.routing
+        slot_src = moe.slot_sources(r["idx"], r["loc"], E, C)
+        slabs = torch.randn((E, C, M), device="cuda").to(x.dtype)             # stands in for dZ and for the expert outputs
+        d_out = torch.randn((T, M), device="cuda").to(x.dtype)
+
+        def timed(fn):
+            for _ in range(args.warmup):
+                fn()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for _ in range(args.steps):
+                fn()
+            b.record()
+            torch.cuda.synchronize()
+            return a.elapsed_time(b) / args.steps
+
+        enc_b = timed(lambda: moe.encode_backward(slabs, r["idx"], r["loc"]))
+        dec_b = timed(lambda: moe.decode_backward(d_out, slabs, r["idx"], r["loc"], r["gate_w"], slot_src))
+        enc_b_bytes = (R + T) * M * es + 8 * T * k                 # read each kept slot row, write [T,M]
+        dec_b_bytes = (R + E * C) * M * es + (R + T) * M * es + 24 * T * k   # dY: read kept d_out rows, write all slots; dgate_w: d_out rows + kept Y rows
+        result["backward_dispatch"] = {
+            "encode_backward_ms": round(enc_b, 5), "encode_backward_frac_hbm": round(enc_b_bytes / (enc_b * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+            "decode_backward_ms": round(dec_b, 5), "decode_backward_frac_hbm": round(dec_b_bytes / (dec_b * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+            "note": "torch allocates the outputs inside the timed calls; algorithmic bytes as for encode/decode"}
 
     if not args.no_cpu_baseline:
         from oracle import moe_oracle as O

@@ -133,6 +133,22 @@ int moe_expert_ffn_gather(const void* x, const int32_t* slot_src, int64_t T, con
 int moe_decode(const void* Y, int dtype, const int32_t* idx, const int32_t* loc, const float* gate_w,
                int64_t T, int64_t M, int64_t E, int k, int64_t C, void* out, void* stream);
 
+/* Backward of fast encode (Appendix B, the differentiable fast encode and decode operators):
+ *   dx[t,:] = sum over the kept choices j of dZ[idx[t,j], loc[t,j], :]   (a token with no kept choice gets +0).
+ * dZ [E,C,M], dx [T,M] (output) in `dtype`; fp32 accumulation in rank order, one rounding.  encode copies rows
+ * unscaled, so it has no gate-weight gradient; idx and loc carry no gradient. */
+int moe_encode_backward(const void* dZ, int dtype, const int32_t* idx, const int32_t* loc, int64_t T, int64_t M, int64_t E,
+                        int k, int64_t C, void* dx, void* stream);
+
+/* Backward of fast decode (Appendix B):
+ *   dY[e,c,:]    = gate_w[t,j] * d_out[t,:] for the kept choice (t,j) with idx = e, loc = c; 0 for an unfilled slot;
+ *   dgate_w[t,j] = sum_m d_out[t,m] * Y[idx[t,j], loc[t,j], m] for a kept choice; 0 for a dropped one.
+ * d_out [T,M], Y and dY [E,C,M] in `dtype`; dgate_w [T,k] fp32 (fp32 accumulation, fixed summation order).
+ * Either output may be NULL (then Y, or gate_w and slot_src, may be NULL too).  slot_src [E,C] as in moe_encode. */
+int moe_decode_backward(const void* d_out, const void* Y, int dtype, const int32_t* idx, const int32_t* loc,
+                        const float* gate_w, const int32_t* slot_src, int64_t T, int64_t M, int64_t E, int k, int64_t C,
+                        void* dY, float* dgate_w, void* stream);
+
 /* The whole path on one stream: gate logits -> top-k + slots -> encode -> expert FFN (filled rows only) -> decode,
  * with C = moe_capacity(T,E,k,f).
  *   Inputs as in the entry points above.  out [T,M] (output, required).

@@ -182,6 +182,29 @@ int moe_decode(const void* Y, int dtype, const int32_t* idx, const int32_t* loc,
   return launch_decode(Y, dtype, idx, loc, gate_w, T, M, E, k, C, out, (hipStream_t)stream) == hipSuccess ? MOE_OK : MOE_HIP_ERROR;
 }
 
+int moe_encode_backward(const void* dZ, int dtype, const int32_t* idx, const int32_t* loc, int64_t T, int64_t M, int64_t E,
+                        int k, int64_t C, void* dx, void* stream) {
+  if (!dZ || !idx || !loc || !dx || !dtype_ok(dtype) || T < 1 || E < 1 || k < 1 || k > E || C < 1 || T > kMaxDim ||
+      E > kMaxDim || C > kMaxDim)
+    return MOE_INVALID_ARG;
+  if (int st = row_shape_status(M)) return st;
+  if (!aligned(dZ, 16) || !aligned(dx, 16)) return MOE_UNSUPPORTED;
+  // the sum of a token's kept slot rows: decode with unit weights
+  return launch_decode(dZ, dtype, idx, loc, nullptr, T, M, E, k, C, dx, (hipStream_t)stream) == hipSuccess ? MOE_OK : MOE_HIP_ERROR;
+}
+
+int moe_decode_backward(const void* d_out, const void* Y, int dtype, const int32_t* idx, const int32_t* loc,
+                        const float* gate_w, const int32_t* slot_src, int64_t T, int64_t M, int64_t E, int k, int64_t C,
+                        void* dY, float* dgate_w, void* stream) {
+  if (!d_out || !idx || !loc || !dtype_ok(dtype) || T < 1 || E < 1 || k < 1 || k > E || C < 1 || T > kMaxDim ||
+      E > kMaxDim || C > kMaxDim || (!dY && !dgate_w) || (dY && (!gate_w || !slot_src)) || (dgate_w && !Y))
+    return MOE_INVALID_ARG;
+  if (int st = row_shape_status(M)) return st;
+  if (!aligned(d_out, 16) || (dY && !aligned(dY, 16)) || (Y && !aligned(Y, 16))) return MOE_UNSUPPORTED;
+  return launch_decode_backward(d_out, Y, dtype, idx, loc, gate_w, slot_src, T, M, E, k, C, dY, dgate_w,
+                                (hipStream_t)stream) == hipSuccess ? MOE_OK : MOE_HIP_ERROR;
+}
+
 }  // extern "C"
 
 namespace {

@@ -123,7 +123,7 @@ __global__ __launch_bounds__(256) void decode_kernel(const uint4* __restrict__ Y
           if (j < k) {
             const int l = loc[t * k + j], e = idx[t * k + j];
             if (l >= 0 && l < C && (unsigned)e < (unsigned)E) {           // kept choice
-              w[u] = gate_w[t * k + j];
+              w[u] = gate_w ? gate_w[t * k + j] : 1.0f;               // no weights: backward of encode
               v[u] = Y[((int64_t)e * C + l) * cpr + c];
             }
           }
@@ -149,6 +149,114 @@ hipError_t launch_decode(const void* Y, int dtype, const int32_t* idx, const int
   const dim3 grid((unsigned)(blocks < 16384 ? blocks : 16384)), block(256);
   if (dtype == MOE_F32) decode_kernel<float><<<grid, block, 0, s>>>((const uint4*)Y, idx, loc, gate_w, T, (int)E, k, C, cpr, (uint4*)out);
   else decode_kernel<uint16_t><<<grid, block, 0, s>>>((const uint4*)Y, idx, loc, gate_w, T, (int)E, k, C, cpr, (uint4*)out);
+  return hipGetLastError();
+}
+
+// --- backward of decode (Appendix B, differentiable fast decode) ---------------------------------------------------
+// dY[e,c,:] = gate_w[t,j] * d_out[t,:] for the kept choice (t,j) that owns slot (e,c), zero for an unfilled slot.
+// Gather form over the slots, like encode: a wave moves ROWS adjacent slots; the owner's choice j is found by
+// comparing the token's k (expert, location) pairs with the slot.
+template <typename ET, int ROWS>
+__global__ __launch_bounds__(256) void decode_backward_rows_kernel(const uint4* __restrict__ d_out,
+                                                                   const int32_t* __restrict__ slot_src,
+                                                                   const int32_t* __restrict__ idx,
+                                                                   const int32_t* __restrict__ loc,
+                                                                   const float* __restrict__ gate_w, int64_t nrows, int64_t T,
+                                                                   int k, int64_t C, int cpr, uint4* __restrict__ dY) {
+  constexpr int N = Pack16<ET>::N;
+  const int lane = threadIdx.x & 63;
+  const int64_t wave = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * 4 + (threadIdx.x >> 6)));
+  const int64_t nwaves = (int64_t)gridDim.x * 4;
+  for (int64_t r0 = wave * ROWS; r0 < nrows; r0 += nwaves * ROWS) {
+    int src[ROWS];
+    float w[ROWS];
+#pragma unroll
+    for (int i = 0; i < ROWS; ++i) {
+      const int64_t slot = r0 + i;
+      src[i] = slot < nrows ? slot_src[slot] : -2;
+      w[i] = 0.f;
+      if (src[i] >= 0 && src[i] < T) {
+        const int e = (int)(slot / C), c = (int)(slot % C);
+        for (int j = 0; j < k; ++j) {                               // wave-uniform: the same slot in every lane
+          const int64_t p = (int64_t)src[i] * k + j;
+          if (idx[p] == e && loc[p] == c) w[i] = gate_w[p];
+        }
+      }
+    }
+    for (int ch = lane; ch < cpr; ch += 64) {
+      uint4 v[ROWS];
+#pragma unroll
+      for (int i = 0; i < ROWS; ++i) v[i] = (src[i] >= 0 && src[i] < T) ? d_out[(int64_t)src[i] * cpr + ch] : make_uint4(0, 0, 0, 0);
+#pragma unroll
+      for (int i = 0; i < ROWS; ++i) {
+        if (src[i] == -2) continue;
+        float f[N];
+        Pack16<ET>::unpack(v[i], f);
+#pragma unroll
+        for (int u = 0; u < N; ++u) f[u] = w[i] * f[u];
+        dY[(r0 + i) * cpr + ch] = (src[i] >= 0 && src[i] < T) ? Pack16<ET>::pack(f) : make_uint4(0, 0, 0, 0);
+      }
+    }
+  }
+}
+
+// dgate_w[t,j] = <d_out[t,:], Y[idx[t,j], loc[t,j], :]> for a kept choice, 0 for a dropped one.  One wave per token:
+// every lane sums its 16-byte pieces in fp32, then a fixed butterfly adds the 64 partial sums (deterministic).
+template <typename ET>
+__global__ __launch_bounds__(256) void gate_weight_grad_kernel(const uint4* __restrict__ d_out, const uint4* __restrict__ Y,
+                                                               const int32_t* __restrict__ idx,
+                                                               const int32_t* __restrict__ loc, int64_t T, int E, int k,
+                                                               int64_t C, int cpr, float* __restrict__ dgate_w) {
+  constexpr int N = Pack16<ET>::N;
+  const int lane = threadIdx.x & 63;
+  const int64_t wave = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * 4 + (threadIdx.x >> 6)));
+  const int64_t nwaves = (int64_t)gridDim.x * 4;
+  for (int64_t t = wave; t < T; t += nwaves) {
+    for (int j = 0; j < k; ++j) {
+      const int l = loc[t * k + j], e = idx[t * k + j];
+      float acc = 0.f;
+      if (l >= 0 && l < C && (unsigned)e < (unsigned)E) {           // kept choice (wave-uniform)
+        const int64_t row = (int64_t)e * C + l;
+        for (int ch = lane; ch < cpr; ch += 64) {
+          float a[N], b[N];
+          Pack16<ET>::unpack(d_out[t * cpr + ch], a);
+          Pack16<ET>::unpack(Y[row * cpr + ch], b);
+#pragma unroll
+          for (int u = 0; u < N; ++u) acc = fmaf(a[u], b[u], acc);
+        }
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) acc += __shfl_xor(acc, d, 64);
+      }
+      if (lane == 0) dgate_w[t * k + j] = acc;
+    }
+  }
+}
+
+hipError_t launch_decode_backward(const void* d_out, const void* Y, int dtype, const int32_t* idx, const int32_t* loc,
+                                  const float* gate_w, const int32_t* slot_src, int64_t T, int64_t M, int64_t E, int k,
+                                  int64_t C, void* dY, float* dgate_w, hipStream_t s) {
+  const int es = (dtype == MOE_F32) ? 4 : 2;
+  const int cpr = (int)(M * es / 16);
+  const dim3 block(256);
+  if (dY) {
+    constexpr int ROWS = 4;
+    const int64_t nrows = E * C, blocks = ceil_div(nrows, 4 * ROWS);
+    const dim3 grid((unsigned)(blocks < 8192 ? blocks : 8192));
+    if (dtype == MOE_F32)
+      decode_backward_rows_kernel<float, ROWS><<<grid, block, 0, s>>>((const uint4*)d_out, slot_src, idx, loc, gate_w, nrows, T, k, C, cpr, (uint4*)dY);
+    else
+      decode_backward_rows_kernel<uint16_t, ROWS><<<grid, block, 0, s>>>((const uint4*)d_out, slot_src, idx, loc, gate_w, nrows, T, k, C, cpr, (uint4*)dY);
+    const hipError_t err = hipGetLastError();
+    if (err != hipSuccess) return err;
+  }
+  if (dgate_w) {
+    const int64_t blocks = ceil_div(T, 4);
+    const dim3 grid((unsigned)(blocks < 16384 ? blocks : 16384));
+    if (dtype == MOE_F32)
+      gate_weight_grad_kernel<float><<<grid, block, 0, s>>>((const uint4*)d_out, (const uint4*)Y, idx, loc, T, (int)E, k, C, cpr, dgate_w);
+    else
+      gate_weight_grad_kernel<uint16_t><<<grid, block, 0, s>>>((const uint4*)d_out, (const uint4*)Y, idx, loc, T, (int)E, k, C, cpr, dgate_w);
+  }
   return hipGetLastError();
 }
 

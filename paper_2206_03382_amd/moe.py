@@ -38,6 +38,8 @@ SIGNATURES = {
     "moe_decode": (_i32, [_vp, _i32, _vp, _vp, _vp, _i64, _i64, _i64, _i32, _i64, _vp, _vp]),
     "moe_layer_forward": (_i32, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _i64, _i32, _dbl, _i32, _i32, _i32,
                                  _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp, _c.POINTER(_vp)]),
+    "moe_encode_backward": (_i32, [_vp, _i32, _vp, _vp, _i64, _i64, _i64, _i32, _i64, _vp, _vp]),
+    "moe_decode_backward": (_i32, [_vp, _vp, _i32, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _i32, _i64, _vp, _vp, _vp]),
     "moe_layer_forward_fused": (_i32, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _i64, _i32, _dbl, _i32, _i32, _i32,
                                        _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp, _c.POINTER(_vp)]),
     "moe_expert_ffn_gather": (_i32, [_vp, _vp, _i64, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _i64, _i64, _i64, _i64, _vp, _vp, _vp]),
@@ -210,6 +212,26 @@ def decode(Y: torch.Tensor, idx: torch.Tensor, loc: torch.Tensor, gate_w: torch.
     out = torch.empty((T, M), dtype=Y.dtype, device=Y.device)
     _check(lib().moe_decode(_p(Y), _dtype_code(Y), _p(idx), _p(loc), _p(gate_w), T, M, E, k, C, _p(out), _stream()), "moe_decode")
     return out
+
+
+def encode_backward(dZ: torch.Tensor, idx: torch.Tensor, loc: torch.Tensor) -> torch.Tensor:
+    E, C, M = dZ.shape
+    T, k = idx.shape
+    dx = torch.empty((T, M), dtype=dZ.dtype, device=dZ.device)
+    _check(lib().moe_encode_backward(_p(dZ), _dtype_code(dZ), _p(idx), _p(loc), T, M, E, k, C, _p(dx), _stream()), "moe_encode_backward")
+    return dx
+
+
+def decode_backward(d_out: torch.Tensor, Y: torch.Tensor, idx: torch.Tensor, loc: torch.Tensor, gate_w: torch.Tensor,
+                    slot_src: torch.Tensor) -> Tuple[torch.Tensor, torch.Tensor]:
+    """(dY [E,C,M], dgate_w [T,k])."""
+    E, C, M = Y.shape
+    T, k = idx.shape
+    dY = torch.empty_like(Y)
+    dgate_w = torch.empty((T, k), dtype=torch.float32, device=Y.device)
+    _check(lib().moe_decode_backward(_p(d_out), _p(Y), _dtype_code(Y), _p(idx), _p(loc), _p(gate_w), _p(slot_src), T, M, E, k, C,
+                                     _p(dY), _p(dgate_w), _stream()), "moe_decode_backward")
+    return dY, dgate_w
 
 
 class StageEvents:

@@ -145,6 +145,42 @@ def test_encode_decode(moe, dtype, T, M, E, k, f):
 
 
 # ----------------------------------------------------------------------------------------------------------------
+# backward of encode / decode (the differentiable fast encode and decode operators)
+# ----------------------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype", [synth.DT_F32, synth.DT_BF16])
+@pytest.mark.parametrize("T,M,E,k,f", DISPATCH_CASES)
+def test_encode_decode_backward(moe, dtype, T, M, E, k, f):
+    cfg = synth.CONFIGS[1].scaled(T=T, M=M, H=8, E=E, k=k, f=f, dtype=dtype, cfg_id=44)
+    logits = synth.make_logits(T, E, seed=T + 1, quantum=0.25)
+    C = O.capacity(T, E, k, f)
+    r = O.route(logits, k, C, 1)
+    g = moe.gate_topk(torch.from_numpy(logits).cuda(), k, C, 1)
+    assert_routing_equal(g, r, C)
+    d_out = synth.make_inputs(cfg, seed=M + 1)["x"]                                            # stands in for d(out)
+    slabs = synth.make_inputs(cfg.scaled(T=E * C, cfg_id=45), seed=8)["x"].reshape(E, C, M)   # stands in for dZ and for Y
+    # encode backward: sum of a token's kept slot rows; dead tokens get exact +0
+    dx = host(moe.encode_backward(dev(slabs, dtype), g["idx"], g["loc"]))
+    assert_close(dx, O.encode_backward_sparse(slabs, r["idx"], r["loc"], C), dtype, "encode backward")
+    dead = (~r["kept"]).all(axis=1)
+    assert (dx[dead].view(np.uint32) == 0).all()
+    # decode backward: weighted rows into the slots (unfilled slots exact +0), and the gate-weight gradient
+    dY, dgw = moe.decode_backward(dev(d_out, dtype), dev(slabs, dtype), g["idx"], g["loc"], g["gate_w"], g["slot_src"])
+    dY, dgw = host(dY), dgw.cpu().numpy()
+    # the oracle takes the gate weights it computed itself (fp64); the device's fp32 weights differ by rounding only
+    assert_close(dY, O.decode_backward_sparse(d_out, r["idx"], r["loc"], r["gate_w"], E, C), dtype, "decode backward, dY")
+    unfilled = O.slot_source(r["idx"], r["loc"], E, C) < 0
+    assert (dY[unfilled].view(np.uint32) == 0).all()
+    ref = O.gate_weight_grad(d_out, slabs, r["idx"], r["loc"], C)
+    scale = 0.0                                                # size of the sums: the largest sum of |terms| of a kept choice
+    for j in range(k):
+        t = np.nonzero(r["kept"][:, j])[0]
+        if len(t):
+            scale = max(scale, float(np.abs(d_out[t].astype(np.float64) * slabs[r["idx"][t, j], r["loc"][t, j]]).sum(axis=1).max()))
+    assert np.abs(dgw - ref).max() <= 1e-5 * max(scale, 1e-30), "gate-weight gradient"
+    assert (dgw[~r["kept"]] == 0).all()
+
+
+# ----------------------------------------------------------------------------------------------------------------
 # moe_expert_ffn
 # ----------------------------------------------------------------------------------------------------------------
 FFN_CASES = [
