@@ -31,6 +31,9 @@ Readings where the paper is silent (each listed again in the design notes):
   R10 backward of encode / decode (Appendix B, the differentiable fast encode and decode operators; the figure with
       the formulas is lost): the plain derivatives of the dense contractions.  encode is not scaled by the gate
       weight here (R6), so its backward has no gate-weight gradient; idx and loc carry no gradient.
+  R11 backward of the expert feed-forward layer (Sec. 3.2: the backward pass runs "the backward computation of the
+      expert"): the chain rule through y = act(z W1 + b1) W2 + b2, rows past an expert's fill contributing nothing;
+      ReLU'(0) = 0.
   R9  dynamic capacity (Sec. 4.1 "Dynamic Capacity Factor", capacity_setting x): x > 0 is the factor f itself;
       x = 0 means the smallest capacity that drops nothing, which is the arrival count of the fullest expert
       (Eq. 1 with the smallest such factor gives exactly that integer); x < 0 the same but never above the
@@ -293,6 +296,47 @@ def ffn_rows(z: np.ndarray, W1e, b1e, W2e, b2e, act: int) -> np.ndarray:
     if b2e is not None:
         y = y + np.asarray(b2e, dtype=np.float64)[None, :]
     return y
+
+
+def activation_grad(h: np.ndarray, act: int) -> np.ndarray:
+    """d act(h) / d h."""
+    if act == ACT_RELU:
+        return (h > 0.0).astype(np.float64)
+    if act == ACT_GELU:                                # d/dh [h Phi(h)] = Phi(h) + h phi(h)
+        return 0.5 * (1.0 + _erf(h / math.sqrt(2.0))) + h * np.exp(-0.5 * h * h) / math.sqrt(2.0 * math.pi)
+    if act == ACT_SILU:                                # d/dh [h s(h)] = s (1 + h (1 - s))
+        sg = 1.0 / (1.0 + np.exp(-h))
+        return sg * (1.0 + h * (1.0 - sg))
+    raise ValueError(f"unknown activation {act}")
+
+
+def ffn_rows_backward(z: np.ndarray, W1e, b1e, W2e, dy: np.ndarray, act: int) -> Dict[str, np.ndarray]:
+    """Chain rule through one expert on a [rows, M] slab (fp64): gradients of sum(dy * y) with y = ffn_rows(z, ...)."""
+    z = np.asarray(z, dtype=np.float64)
+    dy = np.asarray(dy, dtype=np.float64)
+    W1e, W2e = np.asarray(W1e, dtype=np.float64), np.asarray(W2e, dtype=np.float64)
+    pre = z @ W1e
+    if b1e is not None:
+        pre = pre + np.asarray(b1e, dtype=np.float64)[None, :]
+    h = activation(pre, act)
+    dh = dy @ W2e.T
+    dpre = dh * activation_grad(pre, act)
+    return dict(dz=dpre @ W1e.T, dW1=z.T @ dpre, db1=dpre.sum(axis=0), dW2=h.T @ dy, db2=dy.sum(axis=0))
+
+
+def expert_ffn_backward(Z: np.ndarray, W1, b1, W2, dY: np.ndarray, act: int,
+                        rows: Optional[Sequence[int]] = None) -> Dict[str, np.ndarray]:
+    """Backward of expert_ffn for every expert; only the first rows[e] rows of an expert exist (others: dZ = 0)."""
+    E, C, M = Z.shape
+    H = np.asarray(W1[0]).shape[1]
+    out = dict(dZ=np.zeros((E, C, M)), dW1=np.zeros((E, M, H)), db1=np.zeros((E, H)), dW2=np.zeros((E, H, M)), db2=np.zeros((E, M)))
+    for e in range(E):
+        n = C if rows is None else int(min(max(rows[e], 0), C))
+        g = ffn_rows_backward(Z[e, :n], W1[e], None if b1 is None else b1[e], W2[e], dY[e, :n], act)
+        out["dZ"][e, :n] = g["dz"]
+        for name in ("dW1", "db1", "dW2", "db2"):
+            out[name][e] = g[name]
+    return out
 
 
 def expert_ffn(Z: np.ndarray, W1, b1, W2, b2, act: int, rows: Optional[Sequence[int]] = None) -> np.ndarray:

@@ -354,7 +354,44 @@ def pin_encode_decode_backward(o):
     assert (o.encode_backward_sparse(dZ, idx, loc, C)[dead] == 0).all()
 
 
-PINS = [pin_encode_decode_backward, pin_dynamic_capacity, pin_capacity_golden, pin_worked_routing_example, pin_fig2_even_top1, pin_exhaustive_top1_locations,
+def pin_ffn_backward(o):
+    """Backward of the expert layer against torch autograd through an independent forward, and against central
+    finite differences of the oracle's own (pinned) forward; rows past the fill contribute nothing."""
+    E, C, M, H = 3, 9, 5, 7
+    r_ = _rng(53)
+    Z, dY = r_.standard_normal((E, C, M)), r_.standard_normal((E, C, M))
+    W1, W2 = r_.standard_normal((E, M, H)) / math.sqrt(M), r_.standard_normal((E, H, M)) / math.sqrt(H)
+    b1, b2 = r_.standard_normal((E, H)) * 0.3, r_.standard_normal((E, M)) * 0.3
+    rows = [9, 4, 0]
+    for act in (o.ACT_RELU, o.ACT_GELU, o.ACT_SILU):
+        g = o.expert_ffn_backward(Z, W1, b1, W2, dY, act, rows=rows)
+        tZ, tW1, tb1, tW2, tb2 = (torch.from_numpy(a.copy()).requires_grad_(True) for a in (Z, W1, b1, W2, b2))
+        loss = 0.0
+        for e in range(E):
+            n = rows[e]
+            y = _torch_act(tZ[e, :n] @ tW1[e] + tb1[e], act) @ tW2[e] + tb2[e]
+            loss = loss + (y * torch.from_numpy(dY[e, :n])).sum()
+        loss.backward()
+        for name, t in (("dZ", tZ), ("dW1", tW1), ("db1", tb1), ("dW2", tW2), ("db2", tb2)):
+            np.testing.assert_allclose(g[name], t.grad.numpy(), rtol=1e-9, atol=1e-11, err_msg=f"{name} act {act}")
+        assert (g["dZ"][1, 4:] == 0).all() and (g["dZ"][2] == 0).all() and (g["dW1"][2] == 0).all()
+        if act != o.ACT_RELU:                               # smooth activations: finite differences of the forward
+            def loss_of(Zp, W1p):
+                Y = o.expert_ffn(Zp, W1p, b1, W2, b2, act, rows=rows)
+                return sum((Y[e, :rows[e]] * dY[e, :rows[e]]).sum() for e in range(E))
+            eps = 1e-6
+            for (e, c, m) in ((0, 2, 1), (1, 3, 4)):
+                Zp, Zm = Z.copy(), Z.copy()
+                Zp[e, c, m] += eps
+                Zm[e, c, m] -= eps
+                np.testing.assert_allclose((loss_of(Zp, W1) - loss_of(Zm, W1)) / (2 * eps), g["dZ"][e, c, m], rtol=1e-6, atol=1e-8)
+            Wp, Wm = W1.copy(), W1.copy()
+            Wp[1, 2, 3] += eps
+            Wm[1, 2, 3] -= eps
+            np.testing.assert_allclose((loss_of(Z, Wp) - loss_of(Z, Wm)) / (2 * eps), g["dW1"][1, 2, 3], rtol=1e-6, atol=1e-8)
+
+
+PINS = [pin_ffn_backward, pin_encode_decode_backward, pin_dynamic_capacity, pin_capacity_golden, pin_worked_routing_example, pin_fig2_even_top1, pin_exhaustive_top1_locations,
         pin_random_topk_vs_bruteforce, pin_invariants, pin_ties_lower_index, pin_gate_against_torch,
         pin_activations_and_ffn_against_torch, pin_no_drop_equals_weighted_sum_of_experts,
         pin_identity_experts_masked_scaling, pin_dense_equals_sparse_and_direct, pin_bruteforce_layer]
@@ -370,6 +407,15 @@ def test_pin(pin):
 # ----------------------------------------------------------------------------------------------------------------
 
 MISTAKES = {
+    "ffn_bwd_gelu_grad_drops_density_term": ("        return 0.5 * (1.0 + _erf(h / math.sqrt(2.0))) + h * np.exp(-0.5 * h * h) / math.sqrt(2.0 * math.pi)",
+                                             "        return 0.5 * (1.0 + _erf(h / math.sqrt(2.0)))"),
+    "ffn_bwd_silu_grad_sign": ("        return sg * (1.0 + h * (1.0 - sg))", "        return sg * (1.0 - h * (1.0 - sg))"),
+    "ffn_bwd_act_grad_at_output": ("    dpre = dh * activation_grad(pre, act)", "    dpre = dh * activation_grad(h, act)"),
+    "ffn_bwd_w2_rows_reversed": ("    dh = dy @ W2e.T", "    dh = dy @ W2e.T[::-1]"),
+    "ffn_bwd_dw2_from_preactivation": ("dW2=h.T @ dy", "dW2=pre.T @ dy"),
+    "ffn_bwd_db1_from_dh": ("db1=dpre.sum(axis=0)", "db1=dh.sum(axis=0)"),
+    "ffn_bwd_counts_rows_past_fill": ("        n = C if rows is None else int(min(max(rows[e], 0), C))\n        g = ffn_rows_backward(",
+                                      "        n = C\n        g = ffn_rows_backward("),
     "encode_bwd_untransposed": ("    return D.reshape(T, E * C) @ np.asarray(dZ, dtype=np.float64).reshape(E * C, -1)",
                                 "    return D.reshape(T, E * C)[:, ::-1] @ np.asarray(dZ, dtype=np.float64).reshape(E * C, -1)"),
     "decode_bwd_unweighted": ("    return (W.reshape(T, E * C).T @ np.asarray(d_out, dtype=np.float64)).reshape(E, C, -1)",
