@@ -166,6 +166,14 @@ def main() -> int:
         dec_b = timed(lambda: moe.decode_backward(d_out, slabs, r["idx"], r["loc"], r["gate_w"], slot_src))
         enc_b_bytes = (R + T) * M * es + 8 * T * k                 # read each kept slot row, write [T,M]
         dec_b_bytes = (R + E * C) * M * es + (R + T) * M * es + 24 * T * k   # dY: read kept d_out rows, write all slots; dgate_w: d_out rows + kept Y rows
+        hidden = torch.empty((E, C, H), dtype=x.dtype, device="cuda")
+        Zb = moe.encode(x, r["idx"], r["loc"], slot_src, E, C)
+        moe.expert_ffn(Zb, layer.W1, layer.b1, layer.W2, layer.b2, cfg.act, counts=r["counts"], hidden=hidden)
+        ffn_b = timed(lambda: moe.expert_ffn_backward(Zb, layer.W1, layer.b1, layer.W2, hidden, slabs, cfg.act, counts=r["counts"]))
+        result["backward_ffn"] = {"ms": round(ffn_b, 5), "algorithmic_TFLOPs": round(4 * flop_per_gemm / (ffn_b * 1e-3) / 1e12, 1),
+                                  "note": "dZ, dW1, db1, dW2, db2; four GEMMs' worth of algorithmic flop (2*R*M*H each); the "
+                                          "time also holds the recomputed pre-activation GEMM, four transposes, two padded copies "
+                                          "and torch's allocation of workspace and outputs"}
         result["backward_dispatch"] = {
             "encode_backward_ms": round(enc_b, 5), "encode_backward_frac_hbm": round(enc_b_bytes / (enc_b * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
             "decode_backward_ms": round(dec_b, 5), "decode_backward_frac_hbm": round(dec_b_bytes / (dec_b * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),

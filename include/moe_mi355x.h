@@ -133,6 +133,24 @@ int moe_expert_ffn_gather(const void* x, const int32_t* slot_src, int64_t T, con
 int moe_decode(const void* Y, int dtype, const int32_t* idx, const int32_t* loc, const float* gate_w,
                int64_t T, int64_t M, int64_t E, int k, int64_t C, void* out, void* stream);
 
+/* Bytes of workspace moe_expert_ffn_backward needs (recomputed pre-activations, dP, one transposed weight matrix,
+ * one transposed and one row-padded activation slab).  0 on invalid arguments. */
+size_t moe_ffn_backward_workspace_bytes(int64_t E, int64_t C, int64_t M, int64_t H, int dtype);
+
+/* Backward of the local experts' feed-forward layer (Sec. 3.2: in the backward pass "the computation becomes the
+ * backward computation of the expert").  With Y[e] = act(Z[e] W1[e] + b1[e]) W2[e] + b2[e] and dY = dLoss/dY:
+ *   dP = (dY W2^T) * act'(Z W1 + b1);  dZ = dP W1^T;  dW1 = Z^T dP;  db1 = column sums of dP;
+ *   dW2 = hidden^T dY;  db2 = column sums of dY;     sums over the first min(counts[e], C) rows of each expert (all C
+ *   rows if counts is NULL).
+ *   Z, dY, dZ [E,C,M]; hidden [E,C,H] = act(Z W1 + b1) as moe_expert_ffn left it; W1, dW1 [E,M,H]; W2, dW2 [E,H,M];
+ *   b1 [E,H] or NULL (it enters the pre-activation); db1 [E,H]; db2 [E,M]; all in `dtype`, fp32 accumulation, each
+ *   output rounded once; intermediates (pre-activations, dP) are rounded to `dtype` as well.
+ *   Any of dZ, dW1, db1, dW2, db2 may be NULL (not computed).  Rows of dZ past an expert's fill are left untouched.
+ *   ws: at least moe_ffn_backward_workspace_bytes bytes, 16-byte aligned.  ReLU'(0) = 0. */
+int moe_expert_ffn_backward(const void* Z, const void* W1, const void* b1, const void* W2, const void* hidden, const void* dY,
+                            int act, int dtype, const int32_t* counts, int64_t E, int64_t C, int64_t M, int64_t H, void* ws,
+                            size_t ws_bytes, void* dZ, void* dW1, void* db1, void* dW2, void* db2, void* stream);
+
 /* Backward of fast encode (Appendix B, the differentiable fast encode and decode operators):
  *   dx[t,:] = sum over the kept choices j of dZ[idx[t,j], loc[t,j], :]   (a token with no kept choice gets +0).
  * dZ [E,C,M], dx [T,M] (output) in `dtype`; fp32 accumulation in rank order, one rounding.  encode copies rows

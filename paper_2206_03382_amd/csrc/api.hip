@@ -182,6 +182,26 @@ int moe_decode(const void* Y, int dtype, const int32_t* idx, const int32_t* loc,
   return launch_decode(Y, dtype, idx, loc, gate_w, T, M, E, k, C, out, (hipStream_t)stream) == hipSuccess ? MOE_OK : MOE_HIP_ERROR;
 }
 
+size_t moe_ffn_backward_workspace_bytes(int64_t E, int64_t C, int64_t M, int64_t H, int dtype) {
+  if (!dtype_ok(dtype) || E < 1 || C < 1 || E > 65535 || C > kMaxDim || row_shape_status(M) || row_shape_status(H)) return 0;
+  return ffn_backward_layout(E, C, M, H, dtype).total;
+}
+
+int moe_expert_ffn_backward(const void* Z, const void* W1, const void* b1, const void* W2, const void* hidden, const void* dY,
+                            int act, int dtype, const int32_t* counts, int64_t E, int64_t C, int64_t M, int64_t H, void* ws,
+                            size_t ws_bytes, void* dZ, void* dW1, void* db1, void* dW2, void* db2, void* stream) {
+  if (!Z || !W1 || !W2 || !hidden || !dY || !ws || !dtype_ok(dtype) || !act_ok(act) || E < 1 || C < 1 || E > 65535 ||
+      C > kMaxDim || (!dZ && !dW1 && !db1 && !dW2 && !db2))
+    return MOE_INVALID_ARG;
+  if (int st = row_shape_status(M)) return st;
+  if (int st = row_shape_status(H)) return st;
+  for (const void* p : {Z, W1, W2, hidden, dY, (const void*)ws, (const void*)dZ, (const void*)dW1, (const void*)dW2})
+    if (p && !aligned(p, 16)) return MOE_UNSUPPORTED;
+  if (ws_bytes < ffn_backward_layout(E, C, M, H, dtype).total) return MOE_WORKSPACE_TOO_SMALL;
+  return launch_expert_ffn_backward(Z, W1, b1, W2, hidden, dY, act, dtype, counts, E, C, M, H, ws, dZ, dW1, db1, dW2, db2,
+                                    (hipStream_t)stream) == hipSuccess ? MOE_OK : MOE_HIP_ERROR;
+}
+
 int moe_encode_backward(const void* dZ, int dtype, const int32_t* idx, const int32_t* loc, int64_t T, int64_t M, int64_t E,
                         int k, int64_t C, void* dx, void* stream) {
   if (!dZ || !idx || !loc || !dx || !dtype_ok(dtype) || T < 1 || E < 1 || k < 1 || k > E || C < 1 || T > kMaxDim ||

@@ -67,4 +67,15 @@ hipError_t launch_decode(const void* Y, int dtype, const int32_t* idx, const int
 hipError_t launch_grouped_gemm(const void* A, const void* B, const void* bias, int act, int dtype, const int32_t* counts,
                                int64_t E, int64_t C, int64_t K, int64_t N, void* out, hipStream_t s);
 
+// Backward of the expert feed-forward layer (ffn_backward.hip): byte offsets of its workspace pieces
+struct FfnBackwardWorkspace {
+  size_t pre, dP, Wt, At, Bp, total;
+  int64_t Cp;                                             // capacity padded to the GEMM's K step
+};
+FfnBackwardWorkspace ffn_backward_layout(int64_t E, int64_t C, int64_t M, int64_t H, int dtype);
+hipError_t launch_expert_ffn_backward(const void* Z, const void* W1, const void* b1, const void* W2, const void* hidden,
+                                      const void* dY, int act, int dtype, const int32_t* counts, int64_t E, int64_t C,
+                                      int64_t M, int64_t H, void* ws, void* dZ, void* dW1, void* db1, void* dW2, void* db2,
+                                      hipStream_t s);
+
 }  // namespace moe

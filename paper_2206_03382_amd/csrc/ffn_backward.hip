@@ -1,0 +1,187 @@
+// Backward of the local experts' feed-forward layer (arXiv 2206.03382 Sec. 3.2: the backward pass runs "the backward
+// computation of the expert" between the two all-to-alls):  y = act(z W1 + b1) W2 + b2  per expert, so
+//   dH = dY W2^T,  dP = dH * act'(z W1 + b1),  dZ = dP W1^T,  dW1 = Z^T dP,  db1 = colsum dP,  dW2 = hidden^T dY,
+//   db2 = colsum dY,  over the rows of an expert that exist.
+// Every product runs on the forward's grouped GEMM (C[e] = A[e] (rows x K) * B[e] (K x N), both row-major): the
+// operands that the chain rule wants transposed are first written out transposed (weights [K,N] -> [N,K]; activations
+// [C,W] -> [W,Cp] with the rows past the fill zeroed and the row count padded to the GEMM's K step).  This is the
+// functional first version: the transposes cost extra HBM passes that a transposed-operand GEMM would not need.
+#include "common.h"
+
+namespace moe {
+
+namespace {
+
+constexpr int kPadK = 64;                                  // K step of the matrix-core GEMM
+
+__device__ __forceinline__ int64_t live_rows(const int32_t* limit, int e, int64_t R) {
+  if (!limit) return R;
+  const int64_t c = limit[e];
+  return c < R ? (c > 0 ? c : 0) : R;
+}
+
+// dst[e, c, r] = src[e, r, c] for r < live rows of e, 0 for live <= r < Rp.   src [E,R,W], dst [E,W,Rp].
+template <typename ET>
+__global__ __launch_bounds__(256) void transpose_pad_kernel(const ET* __restrict__ src, const int32_t* __restrict__ limit,
+                                                            int64_t R, int64_t W, int64_t Rp, ET* __restrict__ dst) {
+  __shared__ ET tile[64][64 + 2];
+  const int e = blockIdx.z;
+  const int64_t r0 = (int64_t)blockIdx.x * 64, c0 = (int64_t)blockIdx.y * 64;
+  const int64_t rows = live_rows(limit, e, R);
+  const int ty = threadIdx.x >> 6, tx = threadIdx.x & 63;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    const int64_t r = r0 + ty * 16 + i, c = c0 + tx;
+    tile[ty * 16 + i][tx] = (r < rows && c < W) ? src[((int64_t)e * R + r) * W + c] : ET(0);
+  }
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    const int64_t c = c0 + ty * 16 + i, r = r0 + tx;
+    if (c < W && r < Rp) dst[((int64_t)e * W + c) * Rp + r] = tile[tx][ty * 16 + i];
+  }
+}
+
+// dst[e, r, :] = src[e, r, :] for r < live rows of e, 0 for live <= r < Cp.   src [E,C,W], dst [E,Cp,W]; 16-byte pieces.
+__global__ __launch_bounds__(256) void pad_rows_kernel(const uint4* __restrict__ src, const int32_t* __restrict__ limit,
+                                                       int64_t E, int64_t C, int64_t Cp, int cpr, uint4* __restrict__ dst) {
+  const int64_t n = E * Cp * cpr;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+    const int64_t row = i / cpr, ch = i % cpr;
+    const int e = (int)(row / Cp);
+    const int64_t r = row % Cp;
+    dst[i] = r < live_rows(limit, e, C) ? src[((int64_t)e * C + r) * cpr + ch] : make_uint4(0, 0, 0, 0);
+  }
+}
+
+__device__ __forceinline__ float act_grad(float p, int act) {
+  if (act == MOE_ACT_RELU) return p > 0.f ? 1.f : 0.f;
+  if (act == MOE_ACT_GELU) return 0.5f * (1.f + erff(p * 0.70710678118654752440f)) + p * expf(-0.5f * p * p) * 0.39894228040143267794f;
+  const float sg = 1.f / (1.f + expf(-p));                  // SiLU
+  return sg * (1.f + p * (1.f - sg));
+}
+
+// dP = dH * act'(pre) in place over the live rows.   dH, pre [E,C,H].
+template <typename ET>
+__global__ __launch_bounds__(256) void act_backward_kernel(ET* __restrict__ dH, const ET* __restrict__ pre,
+                                                           const int32_t* __restrict__ limit, int act, int64_t E, int64_t C,
+                                                           int64_t H) {
+  const int64_t n = E * C * H;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+    const int64_t row = i / H;
+    const int e = (int)(row / C);
+    if (row % C >= live_rows(limit, e, C)) continue;
+    const float g = load_as_f32<ET>(dH + i) * act_grad(load_as_f32<ET>(pre + i), act);
+    store_from_f32<ET>(dH + i, g);
+  }
+}
+
+// out[e, c] = sum over the live rows r of src[e, r, c], fp32, in a fixed order: four interleaved row classes summed
+// sequentially, then added in class order.   src [E,C,W], out [E,W].
+template <typename ET>
+__global__ __launch_bounds__(256) void colsum_kernel(const ET* __restrict__ src, const int32_t* __restrict__ limit, int64_t C,
+                                                     int64_t W, ET* __restrict__ out) {
+  __shared__ float part[4][64];
+  const int e = blockIdx.y;
+  const int g = threadIdx.x >> 6, tx = threadIdx.x & 63;
+  const int64_t c = (int64_t)blockIdx.x * 64 + tx;
+  const int64_t rows = live_rows(limit, e, C);
+  float s = 0.f;
+  if (c < W)
+    for (int64_t r = g; r < rows; r += 4) s += load_as_f32<ET>(src + ((int64_t)e * C + r) * W + c);
+  part[g][tx] = s;
+  __syncthreads();
+  if (g == 0 && c < W) store_from_f32<ET>(out + (int64_t)e * W + c, ((part[0][tx] + part[1][tx]) + part[2][tx]) + part[3][tx]);
+}
+
+inline size_t align256(size_t v) { return (v + 255) / 256 * 256; }
+
+template <typename ET>
+hipError_t transpose_pad(const void* src, const int32_t* limit, int64_t E, int64_t R, int64_t W, int64_t Rp, void* dst, hipStream_t s) {
+  const dim3 grid((unsigned)ceil_div(Rp, 64), (unsigned)ceil_div(W, 64), (unsigned)E);
+  transpose_pad_kernel<ET><<<grid, dim3(256), 0, s>>>((const ET*)src, limit, R, W, Rp, (ET*)dst);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+FfnBackwardWorkspace ffn_backward_layout(int64_t E, int64_t C, int64_t M, int64_t H, int dtype) {
+  const size_t es = dtype == MOE_F32 ? 4 : 2;
+  const int64_t Cp = ceil_div(C, kPadK) * kPadK;
+  FfnBackwardWorkspace w;
+  size_t o = 0;
+  w.pre = o;  o += align256((size_t)E * C * H * es);
+  w.dP = o;   o += align256((size_t)E * C * H * es);
+  w.Wt = o;   o += align256((size_t)E * M * H * es);       // W2^T, then W1^T
+  w.At = o;   o += align256((size_t)E * (M > H ? M : H) * Cp * es);   // hidden^T, then Z^T
+  w.Bp = o;   o += align256((size_t)E * Cp * (M > H ? M : H) * es);   // padded dY, then padded dP
+  w.total = o;
+  w.Cp = Cp;
+  return w;
+}
+
+template <typename ET>
+static hipError_t ffn_backward_t(const void* Z, const void* W1, const void* b1, const void* W2, const void* hidden,
+                                 const void* dY, int act, int dtype, const int32_t* counts, int64_t E, int64_t C, int64_t M,
+                                 int64_t H, char* ws, void* dZ, void* dW1, void* db1, void* dW2, void* db2, hipStream_t s) {
+  const FfnBackwardWorkspace w = ffn_backward_layout(E, C, M, H, dtype);
+  const int64_t Cp = w.Cp;
+  const int es = (int)sizeof(ET);
+  void *pre = ws + w.pre, *dP = ws + w.dP, *Wt = ws + w.Wt, *At = ws + w.At, *Bp = ws + w.Bp;
+  hipError_t err;
+#define MOE_TRY(x) do { err = (x); if (err != hipSuccess) return err; } while (0)
+  // pre-activations, recomputed (the forward keeps only act(pre))
+  MOE_TRY(launch_grouped_gemm(Z, W1, b1, -1, dtype, counts, E, C, M, H, pre, s));
+  // dH = dY W2^T, then dP = dH * act'(pre)
+  MOE_TRY(transpose_pad<ET>(W2, nullptr, E, H, M, H, Wt, s));                          // [E,H,M] -> [E,M,H]
+  MOE_TRY(launch_grouped_gemm(dY, Wt, nullptr, -1, dtype, counts, E, C, M, H, dP, s));
+  {
+    const int64_t n = E * C * H, blocks = ceil_div(n, 256 * 8);
+    act_backward_kernel<ET><<<dim3((unsigned)(blocks < 16384 ? blocks : 16384)), dim3(256), 0, s>>>((ET*)dP, (const ET*)pre, counts, act, E, C, H);
+    MOE_TRY(hipGetLastError());
+  }
+  // dZ = dP W1^T
+  if (dZ) {
+    MOE_TRY(transpose_pad<ET>(W1, nullptr, E, M, H, M, Wt, s));                        // [E,M,H] -> [E,H,M]
+    MOE_TRY(launch_grouped_gemm(dP, Wt, nullptr, -1, dtype, counts, E, C, H, M, dZ, s));
+  }
+  auto pad_rows = [&](const void* src, int64_t W, void* dst) -> hipError_t {
+    const int cpr = (int)(W * es / 16);
+    const int64_t n = E * Cp * cpr, blocks = ceil_div(n, 256 * 4);
+    pad_rows_kernel<<<dim3((unsigned)(blocks < 16384 ? blocks : 16384)), dim3(256), 0, s>>>((const uint4*)src, counts, E, C, Cp, cpr, (uint4*)dst);
+    return hipGetLastError();
+  };
+  // dW2[e] = hidden[e]^T dY[e]  (H x Cp times Cp x M)
+  if (dW2) {
+    MOE_TRY(transpose_pad<ET>(hidden, counts, E, C, H, Cp, At, s));
+    MOE_TRY(pad_rows(dY, M, Bp));
+    MOE_TRY(launch_grouped_gemm(At, Bp, nullptr, -1, dtype, nullptr, E, H, Cp, M, dW2, s));
+  }
+  // dW1[e] = Z[e]^T dP[e]  (M x Cp times Cp x H)
+  if (dW1) {
+    MOE_TRY(transpose_pad<ET>(Z, counts, E, C, M, Cp, At, s));
+    MOE_TRY(pad_rows(dP, H, Bp));
+    MOE_TRY(launch_grouped_gemm(At, Bp, nullptr, -1, dtype, nullptr, E, M, Cp, H, dW1, s));
+  }
+  if (db1) {
+    colsum_kernel<ET><<<dim3((unsigned)ceil_div(H, 64), (unsigned)E), dim3(256), 0, s>>>((const ET*)dP, counts, C, H, (ET*)db1);
+    MOE_TRY(hipGetLastError());
+  }
+  if (db2) {
+    colsum_kernel<ET><<<dim3((unsigned)ceil_div(M, 64), (unsigned)E), dim3(256), 0, s>>>((const ET*)dY, counts, C, M, (ET*)db2);
+    MOE_TRY(hipGetLastError());
+  }
+#undef MOE_TRY
+  return hipSuccess;
+}
+
+hipError_t launch_expert_ffn_backward(const void* Z, const void* W1, const void* b1, const void* W2, const void* hidden,
+                                      const void* dY, int act, int dtype, const int32_t* counts, int64_t E, int64_t C,
+                                      int64_t M, int64_t H, void* ws, void* dZ, void* dW1, void* db1, void* dW2, void* db2,
+                                      hipStream_t s) {
+  if (dtype == MOE_F32)
+    return ffn_backward_t<float>(Z, W1, b1, W2, hidden, dY, act, dtype, counts, E, C, M, H, (char*)ws, dZ, dW1, db1, dW2, db2, s);
+  return ffn_backward_t<uint16_t>(Z, W1, b1, W2, hidden, dY, act, dtype, counts, E, C, M, H, (char*)ws, dZ, dW1, db1, dW2, db2, s);
+}
+
+}  // namespace moe

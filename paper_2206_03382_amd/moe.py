@@ -38,6 +38,9 @@ SIGNATURES = {
     "moe_decode": (_i32, [_vp, _i32, _vp, _vp, _vp, _i64, _i64, _i64, _i32, _i64, _vp, _vp]),
     "moe_layer_forward": (_i32, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _i64, _i32, _dbl, _i32, _i32, _i32,
                                  _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp, _c.POINTER(_vp)]),
+    "moe_ffn_backward_workspace_bytes": (_sz, [_i64, _i64, _i64, _i64, _i32]),
+    "moe_expert_ffn_backward": (_i32, [_vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _i64, _i64, _i64, _i64, _vp, _sz,
+                                       _vp, _vp, _vp, _vp, _vp, _vp]),
     "moe_encode_backward": (_i32, [_vp, _i32, _vp, _vp, _i64, _i64, _i64, _i32, _i64, _vp, _vp]),
     "moe_decode_backward": (_i32, [_vp, _vp, _i32, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _i32, _i64, _vp, _vp, _vp]),
     "moe_layer_forward_fused": (_i32, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _i64, _i32, _dbl, _i32, _i32, _i32,
@@ -212,6 +215,24 @@ def decode(Y: torch.Tensor, idx: torch.Tensor, loc: torch.Tensor, gate_w: torch.
     out = torch.empty((T, M), dtype=Y.dtype, device=Y.device)
     _check(lib().moe_decode(_p(Y), _dtype_code(Y), _p(idx), _p(loc), _p(gate_w), T, M, E, k, C, _p(out), _stream()), "moe_decode")
     return out
+
+
+def expert_ffn_backward(Z: torch.Tensor, W1: torch.Tensor, b1: Optional[torch.Tensor], W2: torch.Tensor, hidden: torch.Tensor,
+                        dY: torch.Tensor, act: int, counts: Optional[torch.Tensor] = None) -> Dict[str, torch.Tensor]:
+    """dZ, dW1, db1, dW2, db2 of the expert layer; `hidden` is the activation buffer moe_expert_ffn filled."""
+    E, C, M = Z.shape
+    H = W1.shape[2]
+    code = _dtype_code(Z)
+    nbytes = int(lib().moe_ffn_backward_workspace_bytes(E, C, M, H, code))
+    if nbytes == 0:
+        raise MoEError(UNSUPPORTED, "moe_ffn_backward_workspace_bytes")
+    ws = torch.empty((nbytes,), dtype=torch.uint8, device=Z.device)
+    g = dict(dZ=torch.zeros_like(Z), dW1=torch.empty_like(W1), db1=torch.empty((E, H), dtype=Z.dtype, device=Z.device),
+             dW2=torch.empty_like(W2), db2=torch.empty((E, M), dtype=Z.dtype, device=Z.device))
+    _check(lib().moe_expert_ffn_backward(_p(Z), _p(W1), _p(b1), _p(W2), _p(hidden), _p(dY), act, code, _p(counts), E, C, M, H,
+                                         _p(ws), ws.numel(), _p(g["dZ"]), _p(g["dW1"]), _p(g["db1"]), _p(g["dW2"]), _p(g["db2"]),
+                                         _stream()), "moe_expert_ffn_backward")
+    return g
 
 
 def encode_backward(dZ: torch.Tensor, idx: torch.Tensor, loc: torch.Tensor) -> torch.Tensor:

@@ -224,6 +224,51 @@ def test_expert_ffn(moe, dtype, E, C, M, H, act, bias, use_counts):
 
 
 # ----------------------------------------------------------------------------------------------------------------
+# moe_expert_ffn_backward
+# ----------------------------------------------------------------------------------------------------------------
+FFN_BWD_CASES = [
+    # dtype, E, C, M, H, act, bias, use_counts
+    (synth.DT_F32, 1, 1, 8, 8, O.ACT_RELU, False, False),
+    (synth.DT_F32, 3, 70, 40, 72, O.ACT_GELU, True, True),
+    (synth.DT_F32, 2, 130, 264, 136, O.ACT_SILU, True, True),
+    (synth.DT_BF16, 2, 100, 72, 40, O.ACT_GELU, True, True),            # generic (non-MFMA) bf16 shapes
+    (synth.DT_BF16, 3, 300, 256, 256, O.ACT_RELU, False, False),        # MFMA GEMMs, capacity not a multiple of 64
+    (synth.DT_BF16, 2, 513, 512, 768, O.ACT_GELU, True, True),
+    (synth.DT_BF16, 5, 1000, 768, 1024, O.ACT_SILU, True, True),
+    (synth.DT_BF16, 9, 37, 256, 512, O.ACT_SILU, False, True),
+]
+
+
+@pytest.mark.parametrize("dtype,E,C,M,H,act,bias,use_counts", FFN_BWD_CASES)
+def test_expert_ffn_backward(moe, dtype, E, C, M, H, act, bias, use_counts):
+    cfg = synth.CONFIGS[1].scaled(T=E * C, M=M, H=H, E=E, dtype=dtype, act=act, cfg_id=46)
+    inp = synth.make_inputs(cfg, seed=C + 1, bias_std=0.25 if bias else 0.0)
+    Z = inp["x"].reshape(E, C, M)
+    dY = synth.make_inputs(cfg.scaled(cfg_id=47), seed=C + 2)["x"].reshape(E, C, M)
+    rows = None
+    if use_counts:
+        rows = np.array([(7 * e * C // (2 * max(E - 1, 1)) + (e % 3)) % (C + 3) for e in range(E)], dtype=np.int32)   # 0 .. above C
+    ref = O.expert_ffn_backward(Z, inp["W1"], inp["b1"], inp["W2"], dY, act, rows=rows)
+    Zd, W1, b1, W2, b2 = dev(Z, dtype), dev(inp["W1"], dtype), dev(inp["b1"], dtype), dev(inp["W2"], dtype), dev(inp["b2"], dtype)
+    counts = None if rows is None else torch.from_numpy(rows).cuda()
+    hidden = torch.empty((E, C, H), dtype=Zd.dtype, device="cuda")
+    moe.expert_ffn(Zd, W1, b1, W2, b2, act, counts=counts, hidden=hidden)
+    g = moe.expert_ffn_backward(Zd, W1, b1, W2, hidden, dev(dY, dtype), act, counts=counts)
+    torch.cuda.synchronize()
+    live = np.zeros((E, C), dtype=bool)
+    for e in range(E):
+        live[e, :C if rows is None else min(max(int(rows[e]), 0), C)] = True
+    if live.any():
+        assert_close(host(g["dZ"])[live], ref["dZ"][live], dtype, "dZ")
+    for name in ("dW1", "db1", "dW2", "db2"):
+        got = host(g[name])
+        if np.abs(ref[name]).max() == 0:
+            assert (got == 0).all(), name
+        else:
+            assert_close(got, ref[name], dtype, name)
+
+
+# ----------------------------------------------------------------------------------------------------------------
 # moe_layer_forward: reduced versions of the five workloads (several tiles + ragged tails), full element-wise check
 # ----------------------------------------------------------------------------------------------------------------
 def run_layer(moe, cfg, inp):
