@@ -34,6 +34,9 @@ Readings where the paper is silent (each listed again in the design notes):
   R11 backward of the expert feed-forward layer (Sec. 3.2: the backward pass runs "the backward computation of the
       expert"): the chain rule through y = act(z W1 + b1) W2 + b2, rows past an expert's fill contributing nothing;
       ReLU'(0) = 0.
+  R12 cosine router (Appendix, "A New Cosine Router", its Eq.): logits[t,e] = cos(W x_t, M_e) / tau with the
+      temperature clamped below at 0.01; the projection W x (dimension D) is rounded once to fp32 like the linear
+      gate's logits; norms are clamped below at 1e-12 (the paper gives no epsilon); the rest of the gate is unchanged.
   R9  dynamic capacity (Sec. 4.1 "Dynamic Capacity Factor", capacity_setting x): x > 0 is the factor f itself;
       x = 0 means the smallest capacity that drops nothing, which is the arrival count of the fullest expert
       (Eq. 1 with the smallest such factor gives exactly that integer); x < 0 the same but never above the
@@ -93,6 +96,17 @@ def gate_logits(x: np.ndarray, Wg: np.ndarray, bias: Optional[np.ndarray] = None
             acc = acc + bd[None, :]
         out[s:s + rows_per_pass] = acc.astype(np.float32)
     return out
+
+
+def cosine_gate_logits(x: np.ndarray, Wp: np.ndarray, Me: np.ndarray, tau: float, rows_per_pass: int = 8192) -> np.ndarray:
+    """Cosine router (Appendix, "A New Cosine Router"; reading R12): cos(x Wp, Me[e]) / max(tau, 0.01) in fp64 on the
+    fp32-rounded projection, rounded once to fp32.   x [T,M], Wp [M,D] (the projection, stored input-major), Me [E,D]."""
+    proj = gate_logits(x, Wp, None, rows_per_pass).astype(np.float64)          # x Wp: fp64 sums, one rounding to fp32
+    Md = np.asarray(Me, dtype=np.float64)
+    nx = np.maximum(np.sqrt((proj * proj).sum(axis=1)), 1e-12)
+    ne = np.maximum(np.sqrt((Md * Md).sum(axis=1)), 1e-12)
+    cos = (proj @ Md.T) / (nx[:, None] * ne[None, :])
+    return (cos / max(float(tau), 0.01)).astype(np.float32)
 
 
 def softmax_rows(logits: np.ndarray) -> np.ndarray:

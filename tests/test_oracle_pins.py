@@ -391,7 +391,36 @@ def pin_ffn_backward(o):
             np.testing.assert_allclose((loss_of(Z, Wp) - loss_of(Z, Wm)) / (2 * eps), g["dW1"][1, 2, 3], rtol=1e-6, atol=1e-8)
 
 
-PINS = [pin_ffn_backward, pin_encode_decode_backward, pin_dynamic_capacity, pin_capacity_golden, pin_worked_routing_example, pin_fig2_even_top1, pin_exhaustive_top1_locations,
+def pin_cosine_router(o):
+    """Appendix, cosine router: against torch's cosine_similarity, scale invariance, the bound |cos| <= 1, an expert
+    embedding parallel to a projected token scores 1 / tau, and the temperature floor of 0.01."""
+    T, M, D, E = 23, 12, 16, 5
+    r_ = _rng(61)
+    x = r_.standard_normal((T, M)).astype(np.float32)
+    Wp = (r_.standard_normal((M, D)) / math.sqrt(M)).astype(np.float32)
+    Me = r_.standard_normal((E, D)).astype(np.float32)
+    for tau in (0.07, 1.0):
+        got = o.cosine_gate_logits(x, Wp, Me, tau)
+        assert got.dtype == np.float32
+        proj = torch.from_numpy((x.astype(np.float64) @ Wp.astype(np.float64)).astype(np.float32).astype(np.float64))
+        ref = torch.nn.functional.cosine_similarity(proj[:, None, :], torch.from_numpy(Me.astype(np.float64))[None, :, :], dim=2) / tau
+        np.testing.assert_allclose(got, ref.numpy(), rtol=2e-7, atol=1e-7)
+        assert (np.abs(got) * tau <= 1.0 + 1e-6).all()
+        # scaling the tokens or the expert embeddings by powers of two changes nothing (exactly)
+        assert np.array_equal(got, o.cosine_gate_logits(4.0 * x, Wp, 0.5 * Me, tau))
+    # an embedding parallel to a token's projection: cosine 1
+    proj0 = (x[:1].astype(np.float64) @ Wp.astype(np.float64)).astype(np.float32)
+    Me2 = Me.copy()
+    Me2[3] = 3.0 * proj0[0]
+    np.testing.assert_allclose(o.cosine_gate_logits(x, Wp, Me2, 0.5)[0, 3], 2.0, rtol=1e-6)
+    Me2[4] = -proj0[0]
+    np.testing.assert_allclose(o.cosine_gate_logits(x, Wp, Me2, 0.5)[0, 4], -2.0, rtol=1e-6)
+    # temperatures below 0.01 act as 0.01
+    assert np.array_equal(o.cosine_gate_logits(x, Wp, Me, 0.001), o.cosine_gate_logits(x, Wp, Me, 0.01))
+    np.testing.assert_allclose(o.cosine_gate_logits(x, Wp, Me, 0.01), 100.0 * o.cosine_gate_logits(x, Wp, Me, 1.0).astype(np.float64), rtol=3e-7, atol=1e-6)
+
+
+PINS = [pin_cosine_router, pin_ffn_backward, pin_encode_decode_backward, pin_dynamic_capacity, pin_capacity_golden, pin_worked_routing_example, pin_fig2_even_top1, pin_exhaustive_top1_locations,
         pin_random_topk_vs_bruteforce, pin_invariants, pin_ties_lower_index, pin_gate_against_torch,
         pin_activations_and_ffn_against_torch, pin_no_drop_equals_weighted_sum_of_experts,
         pin_identity_experts_masked_scaling, pin_dense_equals_sparse_and_direct, pin_bruteforce_layer]
@@ -407,6 +436,13 @@ def test_pin(pin):
 # ----------------------------------------------------------------------------------------------------------------
 
 MISTAKES = {
+    "cosine_token_norm_dropped": ("    cos = (proj @ Md.T) / (nx[:, None] * ne[None, :])", "    cos = (proj @ Md.T) / ne[None, :]"),
+    "cosine_expert_norm_dropped": ("    cos = (proj @ Md.T) / (nx[:, None] * ne[None, :])", "    cos = (proj @ Md.T) / nx[:, None]"),
+    "cosine_norm_not_rooted": ("    nx = np.maximum(np.sqrt((proj * proj).sum(axis=1)), 1e-12)", "    nx = np.maximum((proj * proj).sum(axis=1), 1e-12)"),
+    "cosine_temperature_multiplies": ("    return (cos / max(float(tau), 0.01)).astype(np.float32)", "    return (cos * max(float(tau), 0.01)).astype(np.float32)"),
+    "cosine_temperature_floor_missing": ("    return (cos / max(float(tau), 0.01)).astype(np.float32)", "    return (cos / float(tau)).astype(np.float32)"),
+    "cosine_projection_rows_reversed": ("    proj = gate_logits(x, Wp, None, rows_per_pass).astype(np.float64)",
+                                        "    proj = gate_logits(x, np.asarray(Wp)[::-1], None, rows_per_pass).astype(np.float64)"),
     "ffn_bwd_gelu_grad_drops_density_term": ("        return 0.5 * (1.0 + _erf(h / math.sqrt(2.0))) + h * np.exp(-0.5 * h * h) / math.sqrt(2.0 * math.pi)",
                                              "        return 0.5 * (1.0 + _erf(h / math.sqrt(2.0)))"),
     "ffn_bwd_silu_grad_sign": ("        return sg * (1.0 + h * (1.0 - sg))", "        return sg * (1.0 - h * (1.0 - sg))"),
