@@ -52,6 +52,8 @@ def main() -> int:
     ap.add_argument("--backward", action="store_true",
                     help="also time the backward of encode and decode (moe_encode_backward, moe_decode_backward) on this "
                          "workload's routing and report their HBM GB/s as `backward_dispatch`")
+    ap.add_argument("--cosine", action="store_true",
+                    help="also time the cosine router's logits (moe_gate_logits_cosine, D = 256) on this workload's tokens")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run plain 256 MiB device copies first, so that a rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE run of "
                          "this command can be scaled by what the same counter reads for a copy of known size")
@@ -178,6 +180,23 @@ def main() -> int:
             "encode_backward_ms": round(enc_b, 5), "encode_backward_frac_hbm": round(enc_b_bytes / (enc_b * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
             "decode_backward_ms": round(dec_b, 5), "decode_backward_frac_hbm": round(dec_b_bytes / (dec_b * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
             "note": "torch allocates the outputs inside the timed calls; algorithmic bytes as for encode/decode"}
+
+    if args.cosine:
+        D = 256
+        Wp = (torch.randn((M, D), device="cuda") / M ** 0.5).to(x.dtype)
+        Me = torch.randn((E, D), device="cuda")
+        for _ in range(args.warmup):
+            moe.gate_logits_cosine(x, Wp, Me, 0.07)
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(args.steps):
+            moe.gate_logits_cosine(x, Wp, Me, 0.07)
+        b.record()
+        torch.cuda.synchronize()
+        ms = a.elapsed_time(b) / args.steps
+        result["cosine_router"] = {"ms": round(ms, 5), "D": D, "fp64_GFLOP": round(2.0 * T * M * D / 1e9, 2),
+                                   "fp64_TFLOPs": round(2.0 * T * M * D / (ms * 1e-3) / 1e12, 1),
+                                   "note": "projection on the fp64 matrix cores (peak 78.6 TFLOP/s) + fp64 cosine per (token, expert)"}
 
     if not args.no_cpu_baseline:
         from oracle import moe_oracle as O

@@ -61,6 +61,20 @@ size_t moe_layer_workspace_bytes(int64_t T, int64_t M, int64_t H, int64_t E, int
 int moe_gate_logits(const void* x, const void* Wg, const float* gate_bias, int dtype,
                     int64_t T, int64_t M, int64_t E, float* logits, void* stream);
 
+/* Bytes of workspace moe_gate_logits_cosine needs (the projection [T,D] fp32, the expert embeddings transposed in
+ * fp64, their norms).  0 on invalid arguments (D <= 4096, E <= 512). */
+size_t moe_cosine_gate_workspace_bytes(int64_t T, int64_t D, int64_t E);
+
+/* Cosine router (Appendix, "A New Cosine Router", its equation):
+ *   logits[t,e] = cos(W x_t, M_e) / tau = (W x_t . M_e) / (|W x_t| |M_e|) / tau;   P = softmax(logits) as usual.
+ *   x [T,M] and Wp [M,D] in `dtype`: the projection W of the paper stored input-major (Wp = W^T), D = 256 there;
+ *   Me [E,D] fp32: one embedding per expert;  tau: temperature, values below 0.01 act as 0.01;
+ *   logits [T,E] fp32 (output), to be passed to moe_gate_topk.
+ * The projection is accumulated in fp64 and rounded once to fp32 (as moe_gate_logits does), the cosine is computed
+ * in fp64 and rounded once; norms are clamped below at 1e-12.  ws: moe_cosine_gate_workspace_bytes, 256-byte aligned. */
+int moe_gate_logits_cosine(const void* x, const void* Wp, const float* Me, double tau, int dtype, int64_t T, int64_t M,
+                           int64_t D, int64_t E, float* logits, void* ws, size_t ws_bytes, void* stream);
+
 /* Gating function, decision part (Sec. 2.1; Sec. 4.1 "dynamic top-ANY gating": any 1 <= k <= E per call) and
  * capacity-limited slot assignment with the GShard logic the paper keeps (Sec. 2.1 "MoE Frameworks"; the
  * location scan of Appendix B).

@@ -104,6 +104,27 @@ int moe_gate_logits(const void* x, const void* Wg, const float* gate_bias, int d
   return launch_gate_logits(x, Wg, gate_bias, dtype, T, M, E, logits, (hipStream_t)stream) == hipSuccess ? MOE_OK : MOE_HIP_ERROR;
 }
 
+size_t moe_cosine_gate_workspace_bytes(int64_t T, int64_t D, int64_t E) {
+  if (T < 1 || T > kMaxDim || D < 1 || D > 4096 || E < 1 || E > 512) return 0;
+  return align_up((size_t)T * D * 4, 256) + align_up((size_t)D * E * 8, 256) + align_up((size_t)E * 8, 256);
+}
+
+int moe_gate_logits_cosine(const void* x, const void* Wp, const float* Me, double tau, int dtype, int64_t T, int64_t M,
+                           int64_t D, int64_t E, float* logits, void* ws, size_t ws_bytes, void* stream) {
+  if (!x || !Wp || !Me || !logits || !ws || !dtype_ok(dtype) || !(tau > 0.0) || T < 1 || T > kMaxDim || E < 1 || D < 1)
+    return MOE_INVALID_ARG;
+  if (int st = row_shape_status(M)) return st;
+  if (E > 512 || D > 4096 || !aligned(x, 16) || !aligned(ws, 256)) return MOE_UNSUPPORTED;
+  if (ws_bytes < moe_cosine_gate_workspace_bytes(T, D, E)) return MOE_WORKSPACE_TOO_SMALL;
+  char* base = (char*)ws;
+  float* proj = (float*)base;
+  double* MeT = (double*)(base + align_up((size_t)T * D * 4, 256));
+  double* norm = (double*)((char*)MeT + align_up((size_t)D * E * 8, 256));
+  const double tau_eff = tau < 0.01 ? 0.01 : tau;                   // the temperature is never below 0.01
+  return launch_gate_logits_cosine(x, Wp, Me, tau_eff, dtype, T, M, D, E, logits, proj, MeT, norm, (hipStream_t)stream) == hipSuccess
+             ? MOE_OK : MOE_HIP_ERROR;
+}
+
 int moe_gate_topk(const float* logits, int64_t T, int64_t E, int k, int64_t C, int normalize, int32_t* idx, float* gate_w,
                   int32_t* loc, int32_t* counts, int32_t* slot_src, void* ws, size_t ws_bytes, void* stream) {
   if (!logits || !idx || !gate_w || !loc || !counts || !ws || C < 1 || C > kMaxDim) return MOE_INVALID_ARG;

@@ -49,6 +49,9 @@ static inline size_t align_up(size_t a, size_t b) { return (a + b - 1) / b * b; 
 // ---- launchers (defined in gate.hip / dispatch.hip / ffn.hip); arguments are already validated ----------------
 hipError_t launch_gate_logits(const void* x, const void* Wg, const float* bias, int dtype, int64_t T, int64_t M,
                               int64_t E, float* logits, hipStream_t s);
+hipError_t launch_gate_logits_cosine(const void* x, const void* Wp, const float* Me, double tau, int dtype, int64_t T,
+                                     int64_t M, int64_t D, int64_t E, float* logits, float* proj, double* MeT, double* norm,
+                                     hipStream_t s);
 hipError_t launch_gate_topk(const float* logits, int64_t T, int64_t E, int k, int64_t C, int normalize, int32_t* idx,
                             float* gate_w, int32_t* loc, int32_t* counts, int32_t* slot_src, int32_t* block_counts,
                             hipStream_t s);

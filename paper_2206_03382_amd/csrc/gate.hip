@@ -469,4 +469,68 @@ hipError_t launch_slot_sources(const int32_t* idx, const int32_t* loc, int64_t T
   return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------------------------------------------
+// Cosine router (Appendix, "A New Cosine Router"): logits[t,e] = cos(W x_t, M_e) / tau.  The projection W x runs on the
+// fp64 matrix-core kernel above (rounded once to fp32); the cosine itself is a handful of fp64 operations per pair.
+// ---------------------------------------------------------------------------------------------------------------
+// One block per expert: MeT[d][e] = Me[e][d] widened to fp64, norm[e] = max(||Me[e]||, 1e-12).
+__global__ __launch_bounds__(256) void cosine_prepare_kernel(const float* __restrict__ Me, int E, int D,
+                                                             double* __restrict__ MeT, double* __restrict__ norm) {
+  __shared__ double part[256];
+  const int e = blockIdx.x;
+  double s = 0.0;
+  for (int d = threadIdx.x; d < D; d += 256) {
+    const double v = (double)Me[(int64_t)e * D + d];
+    MeT[(int64_t)d * E + e] = v;
+    s += v * v;
+  }
+  part[threadIdx.x] = s;
+  __syncthreads();
+  for (int off = 128; off >= 1; off >>= 1) {              // fixed tree: the same sum on every run
+    if (threadIdx.x < off) part[threadIdx.x] += part[threadIdx.x + off];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) norm[e] = fmax(sqrt(part[0]), 1e-12);
+}
+
+// One wave per token, one lane per expert: the token's projection is fetched 64 values at a time and broadcast lane by
+// lane; every lane accumulates its expert's dot product and the token's squared norm in fp64, in ascending d.
+__global__ __launch_bounds__(256) void cosine_logits_kernel(const float* __restrict__ proj, const double* __restrict__ MeT,
+                                                            const double* __restrict__ norm, double tau, int64_t T, int D,
+                                                            int E, float* __restrict__ logits) {
+  const int lane = threadIdx.x & 63;
+  const int64_t wave = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * 4 + (threadIdx.x >> 6)));
+  const int64_t nwaves = (int64_t)gridDim.x * 4;
+  for (int64_t t = wave; t < T; t += nwaves) {
+    for (int e0 = 0; e0 < E; e0 += 64) {
+      const int e = e0 + lane;
+      const int ec = e < E ? e : E - 1;                   // lanes past the last expert repeat it and store nothing
+      double dot = 0.0, nx2 = 0.0;
+      for (int d0 = 0; d0 < D; d0 += 64) {
+        const float pv = (d0 + lane < D) ? proj[t * D + d0 + lane] : 0.f;
+        const int n = (D - d0) < 64 ? (D - d0) : 64;
+        for (int dd = 0; dd < n; ++dd) {
+          const double sd = (double)__uint_as_float((uint32_t)__builtin_amdgcn_readlane((int)__float_as_uint(pv), dd));
+          dot = fma(sd, MeT[(int64_t)(d0 + dd) * E + ec], dot);
+          nx2 = fma(sd, sd, nx2);
+        }
+      }
+      if (e < E) logits[t * E + e] = (float)((dot / (fmax(sqrt(nx2), 1e-12) * norm[e])) / tau);
+    }
+  }
+}
+
+hipError_t launch_gate_logits_cosine(const void* x, const void* Wp, const float* Me, double tau, int dtype, int64_t T,
+                                     int64_t M, int64_t D, int64_t E, float* logits, float* proj, double* MeT, double* norm,
+                                     hipStream_t s) {
+  hipError_t err = launch_gate_logits(x, Wp, nullptr, dtype, T, M, D, proj, s);
+  if (err != hipSuccess) return err;
+  cosine_prepare_kernel<<<dim3((unsigned)E), dim3(256), 0, s>>>(Me, (int)E, (int)D, MeT, norm);
+  err = hipGetLastError();
+  if (err != hipSuccess) return err;
+  const int64_t blocks = ceil_div(T, 4);
+  cosine_logits_kernel<<<dim3((unsigned)(blocks < 16384 ? blocks : 16384)), dim3(256), 0, s>>>(proj, MeT, norm, tau, T, (int)D, (int)E, logits);
+  return hipGetLastError();
+}
+
 }  // namespace moe

@@ -30,6 +30,8 @@ SIGNATURES = {
     "moe_gate_workspace_bytes": (_sz, [_i64, _i64, _i32]),
     "moe_layer_workspace_bytes": (_sz, [_i64, _i64, _i64, _i64, _i32, _i64, _i32]),
     "moe_gate_logits": (_i32, [_vp, _vp, _vp, _i32, _i64, _i64, _i64, _vp, _vp]),
+    "moe_cosine_gate_workspace_bytes": (_sz, [_i64, _i64, _i64]),
+    "moe_gate_logits_cosine": (_i32, [_vp, _vp, _vp, _dbl, _i32, _i64, _i64, _i64, _i64, _vp, _vp, _sz, _vp]),
     "moe_gate_topk": (_i32, [_vp, _i64, _i64, _i32, _i64, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "moe_dynamic_capacity": (_i32, [_vp, _i64, _i64, _i32, _dbl, _vp, _vp]),
     "moe_slot_sources": (_i32, [_vp, _vp, _i64, _i64, _i32, _i64, _vp, _vp]),
@@ -119,6 +121,21 @@ def gate_logits(x: torch.Tensor, Wg: torch.Tensor, gate_bias: Optional[torch.Ten
     E = Wg.shape[1]
     logits = torch.empty((T, E), dtype=torch.float32, device=x.device)
     _check(lib().moe_gate_logits(_p(x), _p(Wg), _p(gate_bias), _dtype_code(x), T, M, E, _p(logits), _stream()), "moe_gate_logits")
+    return logits
+
+
+def gate_logits_cosine(x: torch.Tensor, Wp: torch.Tensor, Me: torch.Tensor, tau: float) -> torch.Tensor:
+    """Cosine-router logits cos(x Wp, Me[e]) / max(tau, 0.01); Wp [M,D] in x's dtype, Me [E,D] fp32."""
+    T, M = x.shape
+    D = Wp.shape[1]
+    E = Me.shape[0]
+    nbytes = int(lib().moe_cosine_gate_workspace_bytes(T, D, E))
+    if nbytes == 0:
+        raise MoEError(UNSUPPORTED, "moe_cosine_gate_workspace_bytes")
+    ws = torch.empty((nbytes,), dtype=torch.uint8, device=x.device)
+    logits = torch.empty((T, E), dtype=torch.float32, device=x.device)
+    _check(lib().moe_gate_logits_cosine(_p(x), _p(Wp), _p(Me), float(tau), _dtype_code(x), T, M, D, E, _p(logits), _p(ws),
+                                        ws.numel(), _stream()), "moe_gate_logits_cosine")
     return logits
 
 

@@ -116,6 +116,30 @@ def test_gate_logits(moe, dtype, T, M, E, bias):
 
 
 # ----------------------------------------------------------------------------------------------------------------
+# cosine router front-end (moe_gate_logits_cosine) followed by the usual top-k
+# ----------------------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype,T,M,D,E,k,tau", [
+    (synth.DT_BF16, 1000, 64, 256, 8, 2, 0.07), (synth.DT_F32, 777, 40, 48, 100, 3, 0.5), (synth.DT_BF16, 2048, 256, 256, 130, 4, 0.005),
+    (synth.DT_F32, 1, 8, 1, 1, 1, 1.0), (synth.DT_BF16, 300, 128, 70, 64, 1, 0.01)])
+def test_cosine_router(moe, dtype, T, M, D, E, k, tau):
+    cfg = synth.CONFIGS[1].scaled(T=T, M=M, H=8, E=max(E, k), k=k, dtype=dtype, cfg_id=48)
+    x = synth.make_inputs(cfg, seed=T)["x"]
+    rng = np.random.default_rng(T + D)
+    Wp = (rng.standard_normal((M, D)) / np.sqrt(M)).astype(np.float32)
+    if dtype == synth.DT_BF16:
+        Wp = synth.round_to_bf16(Wp)
+    Me = rng.standard_normal((E, D)).astype(np.float32)
+    ref = O.cosine_gate_logits(x, Wp, Me, tau)
+    got = moe.gate_logits_cosine(dev(x, dtype), dev(Wp, dtype), torch.from_numpy(Me).cuda(), tau)
+    g = got.cpu().numpy()
+    ulp = np.spacing(np.abs(ref).astype(np.float32))
+    assert (np.abs(g - ref) <= ulp).all() and (g != ref).mean() <= max(1e-4, 1.5 / g.size)
+    C = O.capacity(T, E, k, 1.25)
+    r = O.route(ref, k, C, 1)
+    assert_routing_equal(moe.gate_topk(got, k, C, 1), r, C, "cosine router")
+
+
+# ----------------------------------------------------------------------------------------------------------------
 # moe_encode / moe_decode
 # ----------------------------------------------------------------------------------------------------------------
 DISPATCH_CASES = [(1, 8, 1, 1, 1.0), (50, 24, 3, 2, 0.7), (1000, 256, 8, 2, 1.25), (777, 776, 5, 3, 0.5), (2049, 1536, 32, 1, 1.25),
