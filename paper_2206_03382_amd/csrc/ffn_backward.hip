@@ -61,37 +61,91 @@ __device__ __forceinline__ float act_grad(float p, int act) {
   return sg * (1.f + p * (1.f - sg));
 }
 
-// dP = dH * act'(pre) in place over the live rows.   dH, pre [E,C,H].
+// 16 bytes of `ET` as floats and back
+template <typename ET> struct Vec16;
+template <> struct Vec16<float> {
+  static constexpr int N = 4;
+  static __device__ __forceinline__ void unpack(const uint4& v, float (&f)[4]) {
+    f[0] = __uint_as_float(v.x); f[1] = __uint_as_float(v.y); f[2] = __uint_as_float(v.z); f[3] = __uint_as_float(v.w);
+  }
+  static __device__ __forceinline__ uint4 pack(const float (&f)[4]) {
+    return make_uint4(__float_as_uint(f[0]), __float_as_uint(f[1]), __float_as_uint(f[2]), __float_as_uint(f[3]));
+  }
+};
+template <> struct Vec16<uint16_t> {
+  static constexpr int N = 8;
+  static __device__ __forceinline__ void unpack(const uint4& v, float (&f)[8]) {
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      f[2 * i] = __uint_as_float(w[i] << 16);
+      f[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+    }
+  }
+  static __device__ __forceinline__ uint4 pack(const float (&f)[8]) {
+    uint32_t w[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) w[i] = pack_bf16x2(f[2 * i], f[2 * i + 1]);
+    return make_uint4(w[0], w[1], w[2], w[3]);
+  }
+};
+
+// dP = dH * act'(pre) in place over the live rows, 16 bytes per thread.   dH, pre [E,C,H] as rows of cpr pieces.
 template <typename ET>
-__global__ __launch_bounds__(256) void act_backward_kernel(ET* __restrict__ dH, const ET* __restrict__ pre,
+__global__ __launch_bounds__(256) void act_backward_kernel(uint4* __restrict__ dH, const uint4* __restrict__ pre,
                                                            const int32_t* __restrict__ limit, int act, int64_t E, int64_t C,
-                                                           int64_t H) {
-  const int64_t n = E * C * H;
+                                                           int cpr) {
+  constexpr int N = Vec16<ET>::N;
+  const int64_t n = E * C * cpr;
   for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
-    const int64_t row = i / H;
+    const int64_t row = i / cpr;
     const int e = (int)(row / C);
     if (row % C >= live_rows(limit, e, C)) continue;
-    const float g = load_as_f32<ET>(dH + i) * act_grad(load_as_f32<ET>(pre + i), act);
-    store_from_f32<ET>(dH + i, g);
+    float g[N], p[N];
+    Vec16<ET>::unpack(dH[i], g);
+    Vec16<ET>::unpack(pre[i], p);
+#pragma unroll
+    for (int u = 0; u < N; ++u) g[u] *= act_grad(p[u], act);
+    dH[i] = Vec16<ET>::pack(g);
   }
 }
 
-// out[e, c] = sum over the live rows r of src[e, r, c], fp32, in a fixed order: four interleaved row classes summed
-// sequentially, then added in class order.   src [E,C,W], out [E,W].
+// out[e, c] = sum over the live rows r of src[e, r, c], fp32, in a fixed order: 32 interleaved row classes, each summed
+// in ascending row order by one thread (16-byte pieces, 8 pieces = 64 or 32 columns per block), then added in class
+// order.   src [E,C,W] as rows of cpr pieces, out [E,W].
 template <typename ET>
-__global__ __launch_bounds__(256) void colsum_kernel(const ET* __restrict__ src, const int32_t* __restrict__ limit, int64_t C,
-                                                     int64_t W, ET* __restrict__ out) {
-  __shared__ float part[4][64];
+__global__ __launch_bounds__(256) void colsum_kernel(const uint4* __restrict__ src, const int32_t* __restrict__ limit,
+                                                     int64_t C, int cpr, ET* __restrict__ out) {
+  constexpr int N = Vec16<ET>::N;
+  __shared__ float part[32][8 * N + 1];
   const int e = blockIdx.y;
-  const int g = threadIdx.x >> 6, tx = threadIdx.x & 63;
-  const int64_t c = (int64_t)blockIdx.x * 64 + tx;
+  const int rc = threadIdx.x >> 3, pc = threadIdx.x & 7;
+  const int64_t piece = (int64_t)blockIdx.x * 8 + pc;
   const int64_t rows = live_rows(limit, e, C);
-  float s = 0.f;
-  if (c < W)
-    for (int64_t r = g; r < rows; r += 4) s += load_as_f32<ET>(src + ((int64_t)e * C + r) * W + c);
-  part[g][tx] = s;
+  float s[N];
+#pragma unroll
+  for (int u = 0; u < N; ++u) s[u] = 0.f;
+  if (piece < cpr) {
+#pragma unroll 4
+    for (int64_t r = rc; r < rows; r += 32) {
+      float f[N];
+      Vec16<ET>::unpack(src[((int64_t)e * C + r) * cpr + piece], f);
+#pragma unroll
+      for (int u = 0; u < N; ++u) s[u] += f[u];
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < N; ++u) part[rc][pc * N + u] = s[u];
   __syncthreads();
-  if (g == 0 && c < W) store_from_f32<ET>(out + (int64_t)e * W + c, ((part[0][tx] + part[1][tx]) + part[2][tx]) + part[3][tx]);
+  if (threadIdx.x < 8 * N) {
+    const int64_t col = (int64_t)blockIdx.x * 8 * N + threadIdx.x;
+    if (col < (int64_t)cpr * N) {
+      float t = 0.f;
+#pragma unroll
+      for (int k = 0; k < 32; ++k) t += part[k][threadIdx.x];
+      store_from_f32<ET>(out + (int64_t)e * cpr * N + col, t);
+    }
+  }
 }
 
 inline size_t align256(size_t v) { return (v + 255) / 256 * 256; }
@@ -136,8 +190,9 @@ static hipError_t ffn_backward_t(const void* Z, const void* W1, const void* b1, 
   MOE_TRY(transpose_pad<ET>(W2, nullptr, E, H, M, H, Wt, s));                          // [E,H,M] -> [E,M,H]
   MOE_TRY(launch_grouped_gemm(dY, Wt, nullptr, -1, dtype, counts, E, C, M, H, dP, s));
   {
-    const int64_t n = E * C * H, blocks = ceil_div(n, 256 * 8);
-    act_backward_kernel<ET><<<dim3((unsigned)(blocks < 16384 ? blocks : 16384)), dim3(256), 0, s>>>((ET*)dP, (const ET*)pre, counts, act, E, C, H);
+    const int cprH = (int)(H * es / 16);
+    const int64_t n = E * C * cprH, blocks = ceil_div(n, 256 * 4);
+    act_backward_kernel<ET><<<dim3((unsigned)(blocks < 16384 ? blocks : 16384)), dim3(256), 0, s>>>((uint4*)dP, (const uint4*)pre, counts, act, E, C, cprH);
     MOE_TRY(hipGetLastError());
   }
   // dZ = dP W1^T
@@ -164,11 +219,13 @@ static hipError_t ffn_backward_t(const void* Z, const void* W1, const void* b1, 
     MOE_TRY(launch_grouped_gemm(At, Bp, nullptr, -1, dtype, nullptr, E, M, Cp, H, dW1, s));
   }
   if (db1) {
-    colsum_kernel<ET><<<dim3((unsigned)ceil_div(H, 64), (unsigned)E), dim3(256), 0, s>>>((const ET*)dP, counts, C, H, (ET*)db1);
+    const int cprH = (int)(H * es / 16);
+    colsum_kernel<ET><<<dim3((unsigned)ceil_div(cprH, 8), (unsigned)E), dim3(256), 0, s>>>((const uint4*)dP, counts, C, cprH, (ET*)db1);
     MOE_TRY(hipGetLastError());
   }
   if (db2) {
-    colsum_kernel<ET><<<dim3((unsigned)ceil_div(M, 64), (unsigned)E), dim3(256), 0, s>>>((const ET*)dY, counts, C, M, (ET*)db2);
+    const int cprM = (int)(M * es / 16);
+    colsum_kernel<ET><<<dim3((unsigned)ceil_div(cprM, 8), (unsigned)E), dim3(256), 0, s>>>((const uint4*)dY, counts, C, cprM, (ET*)db2);
     MOE_TRY(hipGetLastError());
   }
 #undef MOE_TRY
