@@ -37,6 +37,10 @@ Readings where the paper is silent (each listed again in the design notes):
   R12 cosine router (Appendix, "A New Cosine Router", its Eq.): logits[t,e] = cos(W x_t, M_e) / tau with the
       temperature clamped below at 0.01; the projection W x (dimension D) is rounded once to fp32 like the linear
       gate's logits; norms are clamped below at 1e-12 (the paper gives no epsilon); the rest of the gate is unchanged.
+  R13 batch prioritized routing (named in Sec. 3.2 and the Appendix's routing ablation, defined in the work cited
+      there): slots are handed out in order of decreasing token priority instead of token order, rank j still
+      outermost; priority = the token's largest routing probability max_e p[t,e], rounded to fp32 (the comparison
+      is an integer-like decision, so both sides take it on the same fp32 key); equal priorities -> lower token.
   R9  dynamic capacity (Sec. 4.1 "Dynamic Capacity Factor", capacity_setting x): x > 0 is the factor f itself;
       x = 0 means the smallest capacity that drops nothing, which is the arrival count of the fullest expert
       (Eq. 1 with the smallest such factor gives exactly that integer); x < 0 the same but never above the
@@ -147,12 +151,25 @@ def gate_weights(p: np.ndarray, idx: np.ndarray, normalize: int) -> np.ndarray:
 # Slot assignment (GShard logic kept by the paper, Sec. 2.1; reading R4)
 # ---------------------------------------------------------------------------------------------------------------
 
-def slot_locations(idx: np.ndarray, E: int):
+def bpr_token_order(logits: np.ndarray) -> np.ndarray:
+    """Batch prioritized routing (reading R13): tokens in order of decreasing priority, priority = the largest softmax
+    probability of the token rounded to fp32; equal priorities keep token order."""
+    key = softmax_rows(logits).max(axis=1).astype(np.float32)
+    return np.argsort(-key.astype(np.float64), kind="stable")
+
+
+def slot_locations(idx: np.ndarray, E: int, order: Optional[np.ndarray] = None):
     """loc[t,j] and un-truncated counts[e].
 
     For each rank j: one-hot mask_j[t,e]; positions = inclusive cumsum over t minus 1; later ranks are offset by
-    all arrivals of earlier ranks at that expert.
+    all arrivals of earlier ranks at that expert.  With `order` (a permutation of the tokens) the tokens arrive in that
+    order instead of token order.
     """
+    if order is not None:
+        loc_o, counts = slot_locations(idx[order], E)
+        loc = np.empty_like(loc_o)
+        loc[order] = loc_o
+        return loc, counts
     T, k = idx.shape
     rows = np.arange(T)
     loc = np.empty((T, k), dtype=np.int64)
@@ -166,12 +183,12 @@ def slot_locations(idx: np.ndarray, E: int):
     return loc.astype(np.int32), counts.astype(np.int32)
 
 
-def route(logits: np.ndarray, k: int, C: int, normalize: int) -> Dict[str, np.ndarray]:
-    """Gate decisions from fp32 logits: idx, loc, kept, counts, gate_w (fp64), p (fp64)."""
+def route(logits: np.ndarray, k: int, C: int, normalize: int, bpr: bool = False) -> Dict[str, np.ndarray]:
+    """Gate decisions from fp32 logits: idx, loc, kept, counts, gate_w (fp64), p (fp64); bpr: batch prioritized order."""
     logits = np.asarray(logits, dtype=np.float32)
     E = logits.shape[1]
     idx = topk_experts(logits, k)
-    loc, counts = slot_locations(idx, E)
+    loc, counts = slot_locations(idx, E, bpr_token_order(logits) if bpr else None)
     p = softmax_rows(logits)
     w = gate_weights(p, idx, normalize)
     return dict(idx=idx, loc=loc, kept=(loc < C), counts=counts, gate_w=w, p=p)
@@ -430,9 +447,11 @@ def token_outputs_direct(tokens: Sequence[int], x, idx, loc, gate_w, C: int, W1,
 # Brute force, independent of everything above except `activation` (tiny inputs only)
 # ---------------------------------------------------------------------------------------------------------------
 
-def brute_force_route(logits: np.ndarray, k: int, C: int):
-    """Sequential arrival simulation with plain Python loops: for each rank, for each token, take the next slot."""
+def brute_force_route(logits: np.ndarray, k: int, C: int, order: Optional[Sequence[int]] = None):
+    """Sequential arrival simulation with plain Python loops: for each rank, for each token (in `order` if given), take
+    the next slot."""
     T, E = logits.shape
+    order = list(range(T)) if order is None else [int(t) for t in order]
     choice = [[-1] * k for _ in range(T)]
     for t in range(T):
         taken = set()
@@ -448,7 +467,7 @@ def brute_force_route(logits: np.ndarray, k: int, C: int):
     arrivals = [0] * E
     loc = [[-1] * k for _ in range(T)]
     for j in range(k):
-        for t in range(T):
+        for t in order:
             e = choice[t][j]
             loc[t][j] = arrivals[e]
             arrivals[e] += 1

@@ -420,7 +420,56 @@ def pin_cosine_router(o):
     np.testing.assert_allclose(o.cosine_gate_logits(x, Wp, Me, 0.01), 100.0 * o.cosine_gate_logits(x, Wp, Me, 1.0).astype(np.float64), rtol=3e-7, atol=1e-6)
 
 
-PINS = [pin_cosine_router, pin_ffn_backward, pin_encode_decode_backward, pin_dynamic_capacity, pin_capacity_golden, pin_worked_routing_example, pin_fig2_even_top1, pin_exhaustive_top1_locations,
+def _read_blocks(path):
+    blocks, name = {}, None
+    for line in open(path):
+        line = line.split("#")[0].strip()
+        if not line:
+            continue
+        if line[0].isalpha():
+            name = line
+            blocks[name] = []
+        else:
+            blocks[name].append([float(v) for v in line.split()])
+    return {k: np.array(v) for k, v in blocks.items()}
+
+
+def pin_batch_prioritized_routing(o):
+    """BPR: the hand-worked example; sequential simulation in priority order; the order is by decreasing largest
+    probability with ties to the lower token; with room for everybody it changes no decision; at an overfull expert the
+    dropped first choices are exactly the lowest-priority ones."""
+    b = _read_blocks(os.path.join(GOLDEN, "bpr_worked_example.txt"))
+    logits = b["logits"].astype(np.float32)
+    assert np.array_equal(o.bpr_token_order(logits), b["order"].astype(np.int64).ravel())
+    r = o.route(logits, 1, 2, 0, bpr=True)
+    assert np.array_equal(r["idx"], b["idx"].astype(np.int32)) and np.array_equal(r["loc"], b["loc"].astype(np.int32))
+    assert np.array_equal(r["kept"], b["kept"].astype(bool)) and np.array_equal(r["counts"], b["counts"].astype(np.int32).ravel())
+    plain = o.route(logits, 1, 2, 0)
+    assert not plain["kept"][4, 0] and plain["kept"][2, 0]            # token order drops the most confident token instead
+    r_ = _rng(71)
+    for T, E, k, C in ((40, 4, 2, 12), (33, 6, 3, 9), (25, 3, 1, 5)):
+        logits = (r_.standard_normal((T, E)) + np.linspace(1.0, 0.0, E)[None, :]).astype(np.float32)
+        logits[5] = logits[3]                                         # equal priorities: the lower token goes first
+        order = o.bpr_token_order(logits)
+        p = torch.softmax(torch.from_numpy(logits.astype(np.float64)), dim=1).max(dim=1).values.numpy().astype(np.float32)
+        assert sorted(order.tolist()) == list(range(T))
+        assert all(p[order[i]] > p[order[i + 1]] or (p[order[i]] == p[order[i + 1]] and order[i] < order[i + 1]) for i in range(T - 1))
+        assert list(order).index(3) + 1 == list(order).index(5)
+        r = o.route(logits, k, C, 1, bpr=True)
+        bi, bl, bk, bc = o.brute_force_route(logits, k, C, order=order)
+        assert np.array_equal(r["idx"], bi) and np.array_equal(r["loc"], bl) and np.array_equal(r["kept"], bk) and np.array_equal(r["counts"], bc)
+        big = o.route(logits, k, T * k, 1, bpr=True)
+        assert big["kept"].all() and np.array_equal(big["idx"], o.route(logits, k, T * k, 1)["idx"])
+        assert np.array_equal(r["counts"], o.route(logits, k, C, 1)["counts"])
+        # first choices at one expert: every kept token has priority >= every dropped token
+        for e in range(E):
+            first = np.nonzero(r["idx"][:, 0] == e)[0]
+            kept, dropped = first[r["kept"][first, 0]], first[~r["kept"][first, 0]]
+            if len(kept) and len(dropped):
+                assert p[kept].min() >= p[dropped].max()
+
+
+PINS = [pin_batch_prioritized_routing, pin_cosine_router, pin_ffn_backward, pin_encode_decode_backward, pin_dynamic_capacity, pin_capacity_golden, pin_worked_routing_example, pin_fig2_even_top1, pin_exhaustive_top1_locations,
         pin_random_topk_vs_bruteforce, pin_invariants, pin_ties_lower_index, pin_gate_against_torch,
         pin_activations_and_ffn_against_torch, pin_no_drop_equals_weighted_sum_of_experts,
         pin_identity_experts_masked_scaling, pin_dense_equals_sparse_and_direct, pin_bruteforce_layer]
@@ -436,6 +485,11 @@ def test_pin(pin):
 # ----------------------------------------------------------------------------------------------------------------
 
 MISTAKES = {
+    "bpr_lowest_priority_first": ("    return np.argsort(-key.astype(np.float64), kind=\"stable\")", "    return np.argsort(key.astype(np.float64), kind=\"stable\")"),
+    "bpr_priority_is_smallest_probability": ("    key = softmax_rows(logits).max(axis=1).astype(np.float32)", "    key = softmax_rows(logits).min(axis=1).astype(np.float32)"),
+    "bpr_priority_is_largest_logit": ("    key = softmax_rows(logits).max(axis=1).astype(np.float32)", "    key = np.asarray(logits, dtype=np.float32).max(axis=1)"),
+    "bpr_locations_not_scattered_back": ("        loc[order] = loc_o\n", "        loc[:] = loc_o\n"),
+    "bpr_order_ignored": ("    loc, counts = slot_locations(idx, E, bpr_token_order(logits) if bpr else None)", "    loc, counts = slot_locations(idx, E, None)"),
     "cosine_token_norm_dropped": ("    cos = (proj @ Md.T) / (nx[:, None] * ne[None, :])", "    cos = (proj @ Md.T) / ne[None, :]"),
     "cosine_expert_norm_dropped": ("    cos = (proj @ Md.T) / (nx[:, None] * ne[None, :])", "    cos = (proj @ Md.T) / nx[:, None]"),
     "cosine_norm_not_rooted": ("    nx = np.maximum(np.sqrt((proj * proj).sum(axis=1)), 1e-12)", "    nx = np.maximum((proj * proj).sum(axis=1), 1e-12)"),
