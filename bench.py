@@ -52,6 +52,8 @@ def main() -> int:
     ap.add_argument("--backward", action="store_true",
                     help="also time the backward of encode and decode (moe_encode_backward, moe_decode_backward) on this "
                          "workload's routing and report their HBM GB/s as `backward_dispatch`")
+    ap.add_argument("--bpr", action="store_true",
+                    help="also time top-k + slot assignment with batch prioritized routing (moe_gate_topk_bpr) on this workload")
     ap.add_argument("--cosine", action="store_true",
                     help="also time the cosine router's logits (moe_gate_logits_cosine, D = 256) on this workload's tokens")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -180,6 +182,24 @@ def main() -> int:
             "encode_backward_ms": round(enc_b, 5), "encode_backward_frac_hbm": round(enc_b_bytes / (enc_b * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
             "decode_backward_ms": round(dec_b, 5), "decode_backward_frac_hbm": round(dec_b_bytes / (dec_b * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
             "note": "torch allocates the outputs inside the timed calls; algorithmic bytes as for encode/decode"}
+
+    if args.bpr:
+        lg = layer.routing["logits"]
+
+        def timed_gate(bpr):
+            for _ in range(args.warmup):
+                moe.gate_topk(lg, k, C, cfg.normalize, bpr=bpr)
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for _ in range(args.steps):
+                moe.gate_topk(lg, k, C, cfg.normalize, bpr=bpr)
+            b.record()
+            torch.cuda.synchronize()
+            return a.elapsed_time(b) / args.steps
+
+        result["batch_prioritized_routing"] = {"gate_topk_ms": round(timed_gate(False), 5), "gate_topk_bpr_ms": round(timed_gate(True), 5),
+                                               "note": "standalone calls (torch allocates outputs and workspace inside); the "
+                                                       "prioritized order is found by exact O(T^2) counting"}
 
     if args.cosine:
         D = 256

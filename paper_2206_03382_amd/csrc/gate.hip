@@ -259,7 +259,7 @@ template <int V>
 __global__ __launch_bounds__(1024) void gate_topk_kernel(const float* __restrict__ logits, int64_t T, int E, int k, int G,
                                                         int normalize, int32_t* __restrict__ idx,
                                                         float* __restrict__ gate_w, int32_t* __restrict__ block_counts,
-                                                        int NB) {
+                                                        int NB, const int32_t* __restrict__ perm) {
   extern __shared__ int hist[];                        // [k][E] arrivals of this block's tokens
   for (int i = threadIdx.x; i < k * E; i += blockDim.x) hist[i] = 0;
   __syncthreads();
@@ -268,8 +268,10 @@ __global__ __launch_bounds__(1024) void gate_topk_kernel(const float* __restrict
   const int passes = (kGateTokensPerBlock + groups - 1) / groups;
   for (int it = 0; it < passes; ++it) {
     const int tb = it * groups + g;                    // token of this block handled by this lane group in this pass
-    const int64_t t = (int64_t)blockIdx.x * kGateTokensPerBlock + tb;
-    const bool valid = tb < kGateTokensPerBlock && t < T;
+    const int64_t tv = (int64_t)blockIdx.x * kGateTokensPerBlock + tb;   // position in arrival order
+    const bool valid = tb < kGateTokensPerBlock && tv < T;
+    int64_t t = tv;                                                     // the token that arrives at that position
+    if (valid && perm) { const int32_t p = perm[tv]; t = ((uint32_t)p < (uint64_t)T) ? p : tv; }   // clamp: never out of range
     float v[V];
 #pragma unroll
     for (int vi = 0; vi < V; ++vi) {
@@ -367,10 +369,13 @@ __global__ __launch_bounds__(kGateTokensPerBlock) void gate_assign_kernel(const 
                                                                           const int32_t* __restrict__ block_off, int64_t T,
                                                                           int E, int k, int64_t C, int NB,
                                                                           int32_t* __restrict__ loc,
-                                                                          int32_t* __restrict__ slot_src) {
+                                                                          int32_t* __restrict__ slot_src,
+                                                                          const int32_t* __restrict__ perm) {
   const int lane = threadIdx.x;
-  const int64_t t = (int64_t)blockIdx.x * kGateTokensPerBlock + lane;
-  const bool valid = t < T;
+  const int64_t tv = (int64_t)blockIdx.x * kGateTokensPerBlock + lane;   // position in arrival order
+  const bool valid = tv < T;
+  int64_t t = tv;
+  if (valid && perm) { const int32_t p = perm[tv]; t = ((uint32_t)p < (uint64_t)T) ? p : tv; }
   const unsigned long long below = (1ull << lane) - 1ull;
   for (int j = 0; j < k; ++j) {
     const int e = valid ? idx[t * k + j] : -1;
@@ -393,7 +398,7 @@ __global__ __launch_bounds__(kGateTokensPerBlock) void gate_assign_kernel(const 
 
 hipError_t launch_gate_topk(const float* logits, int64_t T, int64_t E, int k, int64_t C, int normalize, int32_t* idx,
                             float* gate_w, int32_t* loc, int32_t* counts, int32_t* slot_src, int32_t* block_counts,
-                            hipStream_t s) {
+                            hipStream_t s, const int32_t* perm) {
   const int NB = (int)ceil_div(T, kGateTokensPerBlock);
   int G = 1;
   while (G < E && G < 64) G <<= 1;
@@ -403,16 +408,16 @@ hipError_t launch_gate_topk(const float* logits, int64_t T, int64_t E, int k, in
   // logits are fetched in one round instead of one dependent round trip per pass
   const dim3 grid(NB), block(256);
   const dim3 tblock((unsigned)(64 * G < 256 ? 256 : (64 * G > 1024 ? 1024 : 64 * G)));
-  if (V == 1) gate_topk_kernel<1><<<grid, tblock, shmem, s>>>(logits, T, (int)E, k, G, normalize, idx, gate_w, block_counts, NB);
-  else if (V == 2) gate_topk_kernel<2><<<grid, tblock, shmem, s>>>(logits, T, (int)E, k, G, normalize, idx, gate_w, block_counts, NB);
-  else if (V <= 4) gate_topk_kernel<4><<<grid, tblock, shmem, s>>>(logits, T, (int)E, k, G, normalize, idx, gate_w, block_counts, NB);
-  else gate_topk_kernel<8><<<grid, tblock, shmem, s>>>(logits, T, (int)E, k, G, normalize, idx, gate_w, block_counts, NB);
+  if (V == 1) gate_topk_kernel<1><<<grid, tblock, shmem, s>>>(logits, T, (int)E, k, G, normalize, idx, gate_w, block_counts, NB, perm);
+  else if (V == 2) gate_topk_kernel<2><<<grid, tblock, shmem, s>>>(logits, T, (int)E, k, G, normalize, idx, gate_w, block_counts, NB, perm);
+  else if (V <= 4) gate_topk_kernel<4><<<grid, tblock, shmem, s>>>(logits, T, (int)E, k, G, normalize, idx, gate_w, block_counts, NB, perm);
+  else gate_topk_kernel<8><<<grid, tblock, shmem, s>>>(logits, T, (int)E, k, G, normalize, idx, gate_w, block_counts, NB, perm);
   hipError_t err = hipGetLastError();
   if (err != hipSuccess) return err;
   gate_scan_kernel<<<dim3((unsigned)E), block, 0, s>>>(block_counts, k * NB, (int)E, C, counts, slot_src);
   err = hipGetLastError();
   if (err != hipSuccess) return err;
-  gate_assign_kernel<<<grid, dim3(kGateTokensPerBlock), 0, s>>>(idx, block_counts, T, (int)E, k, C, NB, loc, slot_src);
+  gate_assign_kernel<<<grid, dim3(kGateTokensPerBlock), 0, s>>>(idx, block_counts, T, (int)E, k, C, NB, loc, slot_src, perm);
   return hipGetLastError();
 }
 
@@ -530,6 +535,64 @@ hipError_t launch_gate_logits_cosine(const void* x, const void* Wp, const float*
   if (err != hipSuccess) return err;
   const int64_t blocks = ceil_div(T, 4);
   cosine_logits_kernel<<<dim3((unsigned)(blocks < 16384 ? blocks : 16384)), dim3(256), 0, s>>>(proj, MeT, norm, tau, T, (int)D, (int)E, logits);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------------------------
+// Batch prioritized routing (named in Sec. 3.2 and the Appendix's routing ablation): tokens take their slots in order
+// of decreasing priority, priority = the token's largest routing probability 1 / sum_e exp(l_e - l_max), computed in
+// fp64 and rounded to fp32 so that the order is a decision on an exactly comparable key; ties -> lower token.
+// ---------------------------------------------------------------------------------------------------------------
+// The sort key is one 64-bit integer per token: the fp32 priority's bit pattern (priorities are positive, so the
+// pattern orders like the value) above the complemented token index, so that "goes before" is a single comparison.
+__global__ __launch_bounds__(256) void bpr_key_kernel(const float* __restrict__ logits, int64_t T, int E,
+                                                      uint64_t* __restrict__ key) {
+  const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (t >= T) return;
+  const float* row = logits + t * E;
+  float mx = row[0];
+  for (int e = 1; e < E; ++e) mx = fmaxf(mx, row[e]);
+  double se = 0.0;
+  for (int e = 0; e < E; ++e) se += exp((double)row[e] - (double)mx);
+  const float prio = (float)(1.0 / se);
+  key[t] = ((uint64_t)__float_as_uint(prio) << 32) | (uint64_t)(0xffffffffu - (uint32_t)t);
+}
+
+// Position of every token in the order by counting the tokens that go before it: O(T^2) comparisons, exact and
+// deterministic (integer atomics).  Block (x, y) counts, for 256 tokens, the keys of slice y that are larger.
+constexpr int kBprSlice = 2048;
+__global__ __launch_bounds__(256) void bpr_count_kernel(const uint64_t* __restrict__ key, int64_t T, int32_t* __restrict__ before) {
+  __shared__ uint64_t tile[kBprSlice];
+  const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int64_t base = (int64_t)blockIdx.y * kBprSlice;
+  for (int i = threadIdx.x; i < kBprSlice; i += 256) tile[i] = base + i < T ? key[base + i] : 0ull;   // 0 is below every key
+  __syncthreads();
+  if (t >= T) return;
+  const uint64_t mine = key[t];
+  int n = 0;
+#pragma unroll 16
+  for (int i = 0; i < kBprSlice; ++i) n += tile[i] > mine ? 1 : 0;
+  if (n) atomicAdd(&before[t], n);
+}
+
+__global__ __launch_bounds__(256) void bpr_scatter_kernel(const int32_t* __restrict__ before, int64_t T, int32_t* __restrict__ perm) {
+  const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (t < T && (uint32_t)before[t] < (uint64_t)T) perm[before[t]] = (int32_t)t;
+}
+
+hipError_t launch_bpr_order(const float* logits, int64_t T, int64_t E, uint64_t* key, int32_t* before, int32_t* perm,
+                            hipStream_t s) {
+  const dim3 grid((unsigned)ceil_div(T, 256)), block(256);
+  bpr_key_kernel<<<grid, block, 0, s>>>(logits, T, (int)E, key);
+  hipError_t err = hipGetLastError();
+  if (err != hipSuccess) return err;
+  fill_i32_kernel<<<dim3((unsigned)ceil_div(T, 1024)), block, 0, s>>>(before, T, 0);
+  err = hipGetLastError();
+  if (err != hipSuccess) return err;
+  bpr_count_kernel<<<dim3((unsigned)ceil_div(T, 256), (unsigned)ceil_div(T, kBprSlice)), block, 0, s>>>(key, T, before);
+  err = hipGetLastError();
+  if (err != hipSuccess) return err;
+  bpr_scatter_kernel<<<grid, block, 0, s>>>(before, T, perm);
   return hipGetLastError();
 }
 

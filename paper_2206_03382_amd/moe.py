@@ -33,6 +33,8 @@ SIGNATURES = {
     "moe_cosine_gate_workspace_bytes": (_sz, [_i64, _i64, _i64]),
     "moe_gate_logits_cosine": (_i32, [_vp, _vp, _vp, _dbl, _i32, _i64, _i64, _i64, _i64, _vp, _vp, _sz, _vp]),
     "moe_gate_topk": (_i32, [_vp, _i64, _i64, _i32, _i64, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "moe_gate_bpr_workspace_bytes": (_sz, [_i64, _i64, _i32]),
+    "moe_gate_topk_bpr": (_i32, [_vp, _i64, _i64, _i32, _i64, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "moe_dynamic_capacity": (_i32, [_vp, _i64, _i64, _i32, _dbl, _vp, _vp]),
     "moe_slot_sources": (_i32, [_vp, _vp, _i64, _i64, _i32, _i64, _vp, _vp]),
     "moe_encode": (_i32, [_vp, _i32, _vp, _vp, _vp, _i64, _i64, _i64, _i32, _i64, _vp, _vp]),
@@ -139,7 +141,9 @@ def gate_logits_cosine(x: torch.Tensor, Wp: torch.Tensor, Me: torch.Tensor, tau:
     return logits
 
 
-def gate_topk(logits: torch.Tensor, k: int, C: int, normalize: int, want_slot_src: bool = True) -> Dict[str, torch.Tensor]:
+def gate_topk(logits: torch.Tensor, k: int, C: int, normalize: int, want_slot_src: bool = True,
+              bpr: bool = False) -> Dict[str, torch.Tensor]:
+    """Top-k, gate weights and slot assignment; bpr: batch prioritized routing order instead of token order."""
     T, E = logits.shape
     dev = logits.device
     idx = torch.empty((T, k), dtype=torch.int32, device=dev)
@@ -147,10 +151,13 @@ def gate_topk(logits: torch.Tensor, k: int, C: int, normalize: int, want_slot_sr
     gate_w = torch.empty((T, k), dtype=torch.float32, device=dev)
     counts = torch.empty((E,), dtype=torch.int32, device=dev)
     slot_src = torch.empty((E, C), dtype=torch.int32, device=dev) if want_slot_src else None
-    nbytes = gate_workspace_bytes(T, E, k)
+    nbytes = int(lib().moe_gate_bpr_workspace_bytes(T, E, k)) if bpr else gate_workspace_bytes(T, E, k)
+    if bpr and nbytes == 0:
+        raise MoEError(UNSUPPORTED, "moe_gate_bpr_workspace_bytes")
     ws = torch.empty((max(nbytes, 16),), dtype=torch.uint8, device=dev)
-    _check(lib().moe_gate_topk(_p(logits), T, E, k, C, int(normalize), _p(idx), _p(gate_w), _p(loc), _p(counts), _p(slot_src),
-                               _p(ws), ws.numel(), _stream()), "moe_gate_topk")
+    entry = lib().moe_gate_topk_bpr if bpr else lib().moe_gate_topk
+    _check(entry(_p(logits), T, E, k, C, int(normalize), _p(idx), _p(gate_w), _p(loc), _p(counts), _p(slot_src),
+                 _p(ws), ws.numel(), _stream()), "moe_gate_topk_bpr" if bpr else "moe_gate_topk")
     return dict(idx=idx, loc=loc, gate_w=gate_w, counts=counts, slot_src=slot_src)
 
 

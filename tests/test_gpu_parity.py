@@ -86,6 +86,18 @@ def test_gate_topk(moe, T, E, k, f, normalize, quantum):
     assert np.array_equal(flat["idx"].cpu().numpy(), np.tile(np.arange(k, dtype=np.int32), (T, 1)))
 
 
+@pytest.mark.parametrize("T,E,k,f,normalize,quantum", GATE_CASES)
+def test_gate_topk_batch_prioritized(moe, T, E, k, f, normalize, quantum):
+    logits = synth.make_logits(T, E, seed=T + E + k + 100, quantum=quantum)       # quantised logits: many equal priorities
+    if quantum == 0.0 and E >= 4:
+        logits[:, 1] += 0.75
+    C = O.capacity(T, E, k, f)
+    ref = O.route(logits, k, C, normalize, bpr=True)
+    got = moe.gate_topk(torch.from_numpy(logits).cuda(), k, C, normalize, bpr=True)
+    assert_routing_equal(got, ref, C, f"BPR T={T} E={E} k={k}")
+    assert np.array_equal(got["slot_src"].cpu().numpy(), O.slot_source(ref["idx"], ref["loc"], E, C))
+
+
 def test_gate_topk_is_deterministic(moe):
     logits = torch.from_numpy(synth.make_logits(5000, 64, seed=3, quantum=0.25)).cuda()
     a = moe.gate_topk(logits, 4, 300, 1)
