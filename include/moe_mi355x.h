@@ -138,7 +138,7 @@ int moe_encode(const void* x, int dtype, const int32_t* idx, const int32_t* loc,
  *   bf16 once after the activation and Y once at the end.  fp32: plain fp32 FMA accumulation.
  *   counts [E] int32 or NULL: if given, only the first min(counts[e], C) rows of each expert are computed and the
  *   remaining rows of Y and hidden are left untouched (decode never reads them); if NULL all C rows are computed.
- *   act: ReLU, GeLU (exact erf form) or SiLU. */
+ *   act: ReLU, GeLU (the erf form v * Phi(v); the bf16 matrix-core path evaluates Phi to within 6e-7) or SiLU. */
 int moe_expert_ffn(const void* Z, const void* W1, const void* b1, const void* W2, const void* b2,
                    int act, int dtype, const int32_t* counts,
                    int64_t E, int64_t C, int64_t M, int64_t H, void* hidden, void* Y, void* stream);

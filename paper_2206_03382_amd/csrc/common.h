@@ -46,7 +46,7 @@ __device__ __forceinline__ float apply_act(float v, int act) {
 static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 static inline size_t align_up(size_t a, size_t b) { return (a + b - 1) / b * b; }
 
-// ---- launchers (defined in gate.hip / dispatch.hip / ffn.hip); arguments are already validated ----------------
+// ---- launchers (defined in gate.hip / dispatch.hip / ffn_*.hip / api.hip); arguments are already validated --------
 hipError_t launch_gate_logits(const void* x, const void* Wg, const float* bias, int dtype, int64_t T, int64_t M,
                               int64_t E, float* logits, hipStream_t s);
 hipError_t launch_gate_logits_cosine(const void* x, const void* Wp, const float* Me, double tau, int dtype, int64_t T,

@@ -7,6 +7,8 @@
 //                        marks unfilled slots of slot_src with -1
 //   gate_assign_kernel : per token and rank, position inside its block + scanned offset -> loc, slot_src
 // No order-dependent atomics: every integer output is a pure function of the logits.
+// Further down: the dynamic capacity factor and slot sources for a capacity chosen after routing (Sec. 4.1), the cosine
+// router (Appendix), and the token order of batch prioritized routing (Sec. 3.2 / Appendix ablation).
 #include "common.h"
 
 namespace moe {
