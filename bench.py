@@ -121,7 +121,7 @@ def main() -> int:
     bf16 = d == synth.DT_BF16
     peak = MFMA_BF16_PEAK_TFLOPS if bf16 else FP32_VECTOR_PEAK_TFLOPS
     achieved = flop_per_gemm / (gemm_ms * 1e-3) / 1e12
-    enc_bytes = (R + E * C) * M * es + 8 * T * k                 # read each kept row once, write every slot
+    enc_bytes = 2 * R * M * es + 4 * E * C                       # read each kept row once, write it once (the layer leaves unfilled slots alone)
     dec_bytes = (R + T) * M * es + 12 * T * k                    # read each kept expert-output row once, write [T,M]
     stages = {name: round(float(ms), 5) for name, ms in zip(moe.STAGE_NAMES, stage_ms)}
     stages["encode_GBps"] = round(enc_bytes / (stage_ms[2] * 1e-3) / 1e9, 1)

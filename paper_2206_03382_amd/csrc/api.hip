@@ -314,7 +314,8 @@ int layer_forward(const void* x, const void* Wg, const float* gate_bias, const v
     if (launch_grouped_gemm_mfma(x, W1, b1, act, d_counts, E, C, M, H, d_hidden, s, d_src, T) != hipSuccess || !mark())
       return MOE_HIP_ERROR;
   } else {
-    if (launch_encode(x, dtype, d_idx, d_loc, d_src, T, M, E, k, C, d_Z, s) != hipSuccess || !mark()) return MOE_HIP_ERROR;
+    // the dispatch buffer is internal here and the expert GEMM skips rows past an expert's fill: no zero rows needed
+    if (launch_encode(x, dtype, d_idx, d_loc, d_src, T, M, E, k, C, d_Z, s, false) != hipSuccess || !mark()) return MOE_HIP_ERROR;
     if (launch_grouped_gemm(d_Z, W1, b1, act, dtype, d_counts, E, C, M, H, d_hidden, s) != hipSuccess || !mark()) return MOE_HIP_ERROR;
   }
   if (launch_grouped_gemm(d_hidden, W2, b2, -1, dtype, d_counts, E, C, H, M, d_Y, s) != hipSuccess || !mark()) return MOE_HIP_ERROR;

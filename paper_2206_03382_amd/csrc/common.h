@@ -64,7 +64,8 @@ hipError_t launch_dynamic_capacity(const int32_t* counts, int64_t E, int64_t bou
 hipError_t launch_slot_sources(const int32_t* idx, const int32_t* loc, int64_t T, int64_t E, int k, int64_t C,
                                int32_t* slot_src, hipStream_t s);
 hipError_t launch_encode(const void* x, int dtype, const int32_t* idx, const int32_t* loc, const int32_t* slot_src,
-                         int64_t T, int64_t M, int64_t E, int k, int64_t C, void* Z, hipStream_t s);
+                         int64_t T, int64_t M, int64_t E, int k, int64_t C, void* Z, hipStream_t s,
+                         bool fill_unfilled = true);
 hipError_t launch_decode(const void* Y, int dtype, const int32_t* idx, const int32_t* loc, const float* gate_w,
                          int64_t T, int64_t M, int64_t E, int k, int64_t C, void* out, hipStream_t s);
 // One grouped GEMM: out[e] = epilogue(A[e] (rows_e x K) * B[e] (K x N) + bias[e]); A [E,C,K], B [E,K,N], out [E,C,N].

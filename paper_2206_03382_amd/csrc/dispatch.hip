@@ -6,7 +6,9 @@
 namespace moe {
 
 // --- encode, gather form: one pass over the [E*C] slots; slot_src says which token row (or none) lands there -----
-template <int ROWS>
+// FILL: unfilled slots are written as zero rows (the operator's contract); without it they are left untouched, which is
+// all the layer needs for its internal buffer (the expert GEMM never uses rows past an expert's fill).
+template <int ROWS, bool FILL>
 __global__ __launch_bounds__(256) void encode_gather_kernel(const uint4* __restrict__ x, const int32_t* __restrict__ slot_src,
                                                             int64_t nrows, int64_t T, int cpr, uint4* __restrict__ Z) {
   const int lane = threadIdx.x & 63;
@@ -16,6 +18,15 @@ __global__ __launch_bounds__(256) void encode_gather_kernel(const uint4* __restr
     int src[ROWS];
 #pragma unroll
     for (int i = 0; i < ROWS; ++i) src[i] = (r0 + i < nrows) ? slot_src[r0 + i] : -2;
+    if (!FILL) {
+      bool any = false;
+#pragma unroll
+      for (int i = 0; i < ROWS; ++i) {
+        if (src[i] < 0 || src[i] >= T) src[i] = -2;                 // nothing to do for this slot
+        any = any || src[i] != -2;
+      }
+      if (!any) continue;
+    }
     for (int c = lane; c < cpr; c += 64) {
       uint4 v[ROWS];
 #pragma unroll
@@ -49,7 +60,7 @@ __global__ __launch_bounds__(256) void encode_scatter_kernel(const uint4* __rest
 }
 
 hipError_t launch_encode(const void* x, int dtype, const int32_t* idx, const int32_t* loc, const int32_t* slot_src,
-                         int64_t T, int64_t M, int64_t E, int k, int64_t C, void* Z, hipStream_t s) {
+                         int64_t T, int64_t M, int64_t E, int k, int64_t C, void* Z, hipStream_t s, bool fill_unfilled) {
   const int es = (dtype == MOE_F32) ? 4 : 2;
   const int cpr = (int)(M * es / 16);
   const int64_t nrows = E * C;
@@ -57,7 +68,8 @@ hipError_t launch_encode(const void* x, int dtype, const int32_t* idx, const int
     constexpr int ROWS = 4;
     const int64_t blocks = ceil_div(nrows, 4 * ROWS);
     const unsigned grid = (unsigned)(blocks < 8192 ? blocks : 8192);
-    encode_gather_kernel<ROWS><<<dim3(grid), dim3(256), 0, s>>>((const uint4*)x, slot_src, nrows, T, cpr, (uint4*)Z);
+    if (fill_unfilled) encode_gather_kernel<ROWS, true><<<dim3(grid), dim3(256), 0, s>>>((const uint4*)x, slot_src, nrows, T, cpr, (uint4*)Z);
+    else encode_gather_kernel<ROWS, false><<<dim3(grid), dim3(256), 0, s>>>((const uint4*)x, slot_src, nrows, T, cpr, (uint4*)Z);
     return hipGetLastError();
   }
   const int64_t n16 = nrows * cpr;
