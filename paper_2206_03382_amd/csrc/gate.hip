@@ -239,8 +239,8 @@ static hipError_t launch_gate_logits_t(const XT* x, const XT* Wg, const float* b
   for (int64_t e_base = 0; e_base < E; e_base += 128) {
     const int64_t rem = E - e_base;
     if (rem <= 16) launch_gate_logits_one<XT, 1, 4, kNarrowGateTilesPerWave>(x, Wg, bias, T, M, E, e_base, logits, s);
-    else if (rem <= 32) launch_gate_logits_one<XT, 2, 4, 1>(x, Wg, bias, T, M, E, e_base, logits, s);
-    else if (rem <= 64) launch_gate_logits_one<XT, 4, 2, 1>(x, Wg, bias, T, M, E, e_base, logits, s);
+    else if (rem <= 32) launch_gate_logits_one<XT, 2, 4, 2>(x, Wg, bias, T, M, E, e_base, logits, s);
+    else if (rem <= 64) launch_gate_logits_one<XT, 4, 2, 2>(x, Wg, bias, T, M, E, e_base, logits, s);
     else launch_gate_logits_one<XT, 8, 1, 1>(x, Wg, bias, T, M, E, e_base, logits, s);
   }
   return hipGetLastError();

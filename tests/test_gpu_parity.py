@@ -441,7 +441,10 @@ def test_layer_full_size(moe, cfg):
     layer, out = run_layer(moe, cfg, inp)
     check_logits(layer.routing["logits"].cpu().numpy(), ref["logits"])
     assert_routing_equal(layer.routing, ref, ref["C"], cfg.name)
-    assert_close(host(out), ref["out"], cfg.dtype, f"layer output ({cfg.name})")
+    plain = host(out).copy()
+    assert_close(plain, ref["out"], cfg.dtype, f"layer output ({cfg.name})")
+    fused = host(layer.forward(dev(inp["x"], cfg.dtype), fuse_dispatch=True))
+    assert np.array_equal(fused.view(np.uint32), plain.view(np.uint32)), "fused dispatch must reproduce the plain path bit for bit"
 
 
 def test_layer_full_size_finegrained_sampled(moe):
