@@ -223,7 +223,8 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_mfma_kernel(const uint1
                                                                      const int32_t* __restrict__ counts,
                                                                      const int32_t* __restrict__ gather, int gather_rows,
                                                                      int E, int64_t C, int K, int N, int MT, int NT,
-                                                                     uint16_t* __restrict__ out) {
+                                                                     uint16_t* __restrict__ out,
+                                                                     unsigned long long* __restrict__ probe, int probe_blocks) {
   __shared__ __attribute__((aligned(1024))) char smem[2 * kStageBytes];
 
   // ---- which tile -------------------------------------------------------------------------------------------------
@@ -348,6 +349,8 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_mfma_kernel(const uint1
   // the number of live sub-tiles is a template argument, so that the loop body of a ragged tile is as branch-free as a
   // full one's (a wave with no rows still loads its share of B and joins the barriers)
 #define MOE_TILE_LOOP(NI) tile_main_loop<NI>(smem, a_base, b_base, a_voff, b_voff, a_step, b_step, a_off, b_off, a_swz, kg, a_mask, wave, K, bias_w, acc)
+  // measurement aid: shader-clock cycles and 100 MHz ticks spent in the main loop (two scalar counter reads each side)
+  const unsigned long long probe_c0 = __builtin_amdgcn_s_memtime(), probe_t0 = __builtin_amdgcn_s_memrealtime();
   switch (ni) {
     case 4: MOE_TILE_LOOP(4); break;
     case 3: MOE_TILE_LOOP(3); break;
@@ -356,6 +359,12 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_mfma_kernel(const uint1
     default: MOE_TILE_LOOP(0); break;
   }
 #undef MOE_TILE_LOOP
+  if (probe && threadIdx.x == 0 && (int)blockIdx.x < probe_blocks) {
+    // full tiles only (all four waves busy); others leave their entry at zero
+    const bool full_tile = rows - m0 >= BM;
+    probe[2 * blockIdx.x] = full_tile ? __builtin_amdgcn_s_memtime() - probe_c0 : 0ull;
+    probe[2 * blockIdx.x + 1] = full_tile ? __builtin_amdgcn_s_memrealtime() - probe_t0 : 0ull;
+  }
 
   // ---- epilogue: activation, bf16; transposed through LDS so that global stores are 16 bytes per lane and a
   // wave's store covers 4 rows x 256 contiguous bytes.  After the last barrier of the main loop no wave reads the
@@ -405,14 +414,14 @@ bool grouped_gemm_mfma_supports(int64_t E, int64_t C, int64_t K, int64_t N, int6
 
 hipError_t launch_grouped_gemm_mfma(const void* A, const void* B, const void* bias, int act, const int32_t* counts,
                                     int64_t E, int64_t C, int64_t K, int64_t N, void* out, hipStream_t s,
-                                    const int32_t* gather, int64_t gather_rows) {
+                                    const int32_t* gather, int64_t gather_rows, unsigned long long* probe, int probe_blocks) {
   const int MT = (int)ceil_div(C, BM), NT = (int)(N / BN);
   const int64_t groups = E * ceil_div((int64_t)MT * NT, 32);                  // upper bound: every expert full
   const dim3 grid((unsigned)(ceil_div(groups, 8) * 256)), block(kThreads);    // 32 blocks per group, groups dealt to 8 XCDs
 #define MOE_LAUNCH_GEMM(ACT)                                                                                          \
   grouped_gemm_mfma_kernel<ACT><<<grid, block, 0, s>>>((const uint16_t*)A, (const uint16_t*)B, (const uint16_t*)bias, \
                                                        counts, gather, (int)gather_rows, (int)E, C, (int)K, (int)N,  \
-                                                       MT, NT, (uint16_t*)out)
+                                                       MT, NT, (uint16_t*)out, probe, probe_blocks)
   switch (act) {
     case MOE_ACT_RELU: MOE_LAUNCH_GEMM(MOE_ACT_RELU); break;
     case MOE_ACT_GELU: MOE_LAUNCH_GEMM(MOE_ACT_GELU); break;

@@ -49,6 +49,7 @@ SIGNATURES = {
     "moe_decode_backward": (_i32, [_vp, _vp, _i32, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _i32, _i64, _vp, _vp, _vp]),
     "moe_layer_forward_fused": (_i32, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _i64, _i32, _dbl, _i32, _i32, _i32,
                                        _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp, _c.POINTER(_vp)]),
+    "moe_expert_ffn_clock_probe": (_i32, [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _i64, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _i32, _vp]),
     "moe_expert_ffn_gather": (_i32, [_vp, _vp, _i64, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _i64, _i64, _i64, _i64, _vp, _vp, _vp]),
     "moe_event_create": (_i32, [_c.POINTER(_vp)]),
     "moe_event_destroy": (_i32, [_vp]),
@@ -218,6 +219,27 @@ def expert_ffn(Z: torch.Tensor, W1: torch.Tensor, b1: Optional[torch.Tensor], W2
     _check(lib().moe_expert_ffn(_p(Z), _p(W1), _p(b1), _p(W2), _p(b2), act, _dtype_code(Z), _p(counts), E, C, M, H,
                                 _p(hidden), _p(Y), _stream()), "moe_expert_ffn")
     return Y
+
+
+def expert_ffn_clock_probe(Z: torch.Tensor, W1, b1, W2, b2, act: int, counts: Optional[torch.Tensor], probe_blocks: int = 4096):
+    """Runs the expert layer with the main-loop clock probe; returns per GEMM (shader GHz, cycles per 64-wide K-step)."""
+    E, C, M = Z.shape
+    H = W1.shape[2]
+    Y = torch.empty((E, C, M), dtype=Z.dtype, device=Z.device)
+    hidden = torch.empty((E, C, H), dtype=Z.dtype, device=Z.device)
+    p1 = torch.zeros((2 * probe_blocks,), dtype=torch.int64, device=Z.device)
+    p2 = torch.zeros_like(p1)
+    _check(lib().moe_expert_ffn_clock_probe(_p(Z), _p(W1), _p(b1), _p(W2), _p(b2), act, _dtype_code(Z), _p(counts), E, C, M, H,
+                                            _p(hidden), _p(Y), _p(p1), _p(p2), probe_blocks, _stream()), "moe_expert_ffn_clock_probe")
+    out = []
+    for p, K in ((p1, M), (p2, H)):
+        v = p.cpu().numpy().reshape(-1, 2).astype("float64")
+        v = v[v[:, 1] > 0]
+        if len(v) == 0:
+            out.append((float("nan"), float("nan")))
+        else:
+            out.append((float(v[:, 0].sum() / v[:, 1].sum() * 0.1), float(v[:, 0].mean() / (K / 64))))
+    return out
 
 
 def expert_ffn_gather(x: torch.Tensor, slot_src: torch.Tensor, W1: torch.Tensor, b1: Optional[torch.Tensor], W2: torch.Tensor,
