@@ -41,6 +41,9 @@ Readings where the paper is silent (each listed again in the design notes):
       there): slots are handed out in order of decreasing token priority instead of token order, rank j still
       outermost; priority = the token's largest routing probability max_e p[t,e], rounded to fp32 (the comparison
       is an integer-like decision, so both sides take it on the same fp32 key); equal priorities -> lower token.
+  R14 backward of the gate (the paper only says the backward pass mirrors the forward, Sec. 3.2): the chain rule through
+      gate weight = (optionally renormalised) softmax probability at the chosen experts, and through the linear layer;
+      the choice of experts and the slot assignment are integer decisions and carry no gradient.
   R9  dynamic capacity (Sec. 4.1 "Dynamic Capacity Factor", capacity_setting x): x > 0 is the factor f itself;
       x = 0 means the smallest capacity that drops nothing, which is the arrival count of the fullest expert
       (Eq. 1 with the smallest such factor gives exactly that integer); x < 0 the same but never above the
@@ -145,6 +148,33 @@ def gate_weights(p: np.ndarray, idx: np.ndarray, normalize: int) -> np.ndarray:
     if normalize:
         w = w / w.sum(axis=1, keepdims=True)
     return w
+
+
+def gate_backward(logits: np.ndarray, idx: np.ndarray, dgate_w: np.ndarray, normalize: int) -> np.ndarray:
+    """d loss / d logits given d loss / d gate_w (reading R14), fp64.
+
+    Forward: p = softmax(logits); g[t,j] = p[t, idx[t,j]]; gate_w = g / sum_j g if normalize else g.
+    """
+    p = softmax_rows(logits)
+    T, E = p.shape
+    rows = np.arange(T)[:, None]
+    g = p[rows, idx]
+    dw = np.asarray(dgate_w, dtype=np.float64)
+    if normalize:
+        S = g.sum(axis=1, keepdims=True)
+        w = g / S
+        dg = (dw - (dw * w).sum(axis=1, keepdims=True)) / S
+    else:
+        dg = dw
+    dp = np.zeros((T, E), dtype=np.float64)
+    np.add.at(dp, (np.broadcast_to(rows, idx.shape), idx), dg)
+    return p * (dp - (p * dp).sum(axis=1, keepdims=True))      # softmax Jacobian applied to dp
+
+
+def gate_logits_backward(x: np.ndarray, Wg: np.ndarray, dlogits: np.ndarray) -> Dict[str, np.ndarray]:
+    """Backward of logits = x Wg + bias: dx = dlogits Wg^T, dWg = x^T dlogits, dbias = column sums of dlogits (fp64)."""
+    xd, Wd, dl = np.asarray(x, dtype=np.float64), np.asarray(Wg, dtype=np.float64), np.asarray(dlogits, dtype=np.float64)
+    return dict(dx=dl @ Wd.T, dWg=xd.T @ dl, dbias=dl.sum(axis=0))
 
 
 # ---------------------------------------------------------------------------------------------------------------

@@ -469,7 +469,35 @@ def pin_batch_prioritized_routing(o):
                 assert p[kept].min() >= p[dropped].max()
 
 
-PINS = [pin_batch_prioritized_routing, pin_cosine_router, pin_ffn_backward, pin_encode_decode_backward, pin_dynamic_capacity, pin_capacity_golden, pin_worked_routing_example, pin_fig2_even_top1, pin_exhaustive_top1_locations,
+def pin_gate_backward(o):
+    """Backward of the gate against torch autograd through softmax -> gather -> renormalise and through the linear layer."""
+    T, M, E, k = 19, 6, 5, 3
+    r_ = _rng(83)
+    x = r_.standard_normal((T, M)).astype(np.float32)
+    Wg = r_.standard_normal((M, E)).astype(np.float32)
+    bias = r_.standard_normal(E).astype(np.float32)
+    logits = o.gate_logits(x, Wg, bias)
+    idx = o.topk_experts(logits, k)
+    dw = r_.standard_normal((T, k))
+    for normalize in (0, 1):
+        got = o.gate_backward(logits, idx, dw, normalize)
+        lt = torch.from_numpy(logits.astype(np.float64)).requires_grad_(True)
+        g = torch.softmax(lt, dim=1).gather(1, torch.from_numpy(idx.astype(np.int64)))
+        w = g / g.sum(dim=1, keepdim=True) if normalize else g
+        (w * torch.from_numpy(dw)).sum().backward()
+        np.testing.assert_allclose(got, lt.grad.numpy(), rtol=1e-10, atol=1e-13)
+        np.testing.assert_allclose(got.sum(axis=1), 0.0, atol=1e-13)          # softmax: gradients of a row sum to zero
+        np.testing.assert_allclose(o.gate_weights(o.softmax_rows(logits), idx, normalize), w.detach().numpy(), rtol=1e-12)
+    dl = r_.standard_normal((T, E))
+    xt, Wt, bt = (torch.from_numpy(a.astype(np.float64)).requires_grad_(True) for a in (x, Wg, bias))
+    ((xt @ Wt + bt) * torch.from_numpy(dl)).sum().backward()
+    gb = o.gate_logits_backward(x, Wg, dl)
+    np.testing.assert_allclose(gb["dx"], xt.grad.numpy(), rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(gb["dWg"], Wt.grad.numpy(), rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(gb["dbias"], bt.grad.numpy(), rtol=1e-12, atol=1e-13)
+
+
+PINS = [pin_gate_backward, pin_batch_prioritized_routing, pin_cosine_router, pin_ffn_backward, pin_encode_decode_backward, pin_dynamic_capacity, pin_capacity_golden, pin_worked_routing_example, pin_fig2_even_top1, pin_exhaustive_top1_locations,
         pin_random_topk_vs_bruteforce, pin_invariants, pin_ties_lower_index, pin_gate_against_torch,
         pin_activations_and_ffn_against_torch, pin_no_drop_equals_weighted_sum_of_experts,
         pin_identity_experts_masked_scaling, pin_dense_equals_sparse_and_direct, pin_bruteforce_layer]
@@ -485,6 +513,11 @@ def test_pin(pin):
 # ----------------------------------------------------------------------------------------------------------------
 
 MISTAKES = {
+    "gate_bwd_normalisation_term_dropped": ("        dg = (dw - (dw * w).sum(axis=1, keepdims=True)) / S", "        dg = dw / S"),
+    "gate_bwd_softmax_mean_term_dropped": ("    return p * (dp - (p * dp).sum(axis=1, keepdims=True))", "    return p * dp"),
+    "gate_bwd_scatter_overwrites": ("    np.add.at(dp, (np.broadcast_to(rows, idx.shape), idx), dg)", "    dp[np.broadcast_to(rows, idx.shape), idx[:, ::-1]] = dg"),
+    "gate_linear_bwd_dx_untransposed": ("dx=dl @ Wd.T,", "dx=dl @ Wd.T[::-1],"),
+    "gate_linear_bwd_dbias_mean": ("dbias=dl.sum(axis=0)", "dbias=dl.mean(axis=0)"),
     "bpr_lowest_priority_first": ("    return np.argsort(-key.astype(np.float64), kind=\"stable\")", "    return np.argsort(key.astype(np.float64), kind=\"stable\")"),
     "bpr_priority_is_smallest_probability": ("    key = softmax_rows(logits).max(axis=1).astype(np.float32)", "    key = softmax_rows(logits).min(axis=1).astype(np.float32)"),
     "bpr_priority_is_largest_logit": ("    key = softmax_rows(logits).max(axis=1).astype(np.float32)", "    key = np.asarray(logits, dtype=np.float32).max(axis=1)"),
