@@ -453,6 +453,23 @@ def moe_layer(x, Wg, gate_bias, W1, b1, W2, b2, k: int, f: float, normalize: int
     return r
 
 
+def moe_layer_backward(x, Wg, gate_bias, W1, b1, W2, b2, k: int, f: float, normalize: int, act: int,
+                       d_out: np.ndarray) -> Dict[str, np.ndarray]:
+    """Backward of moe_layer for a given d loss / d out [T,M] (fp64): the backward maps of decode, the expert layer,
+    encode and the gate chained in reverse order, with the routing decisions of the forward held fixed."""
+    r = moe_layer(x, Wg, gate_bias, W1, b1, W2, b2, k, f, normalize, act, tier="sparse")
+    E, C = W1.shape[0], r["C"]
+    idx, loc = r["idx"], r["loc"]
+    dY = decode_backward_sparse(d_out, idx, loc, r["gate_w"], E, C)
+    dgw = gate_weight_grad(d_out, r["Y"], idx, loc, C)
+    rows = np.minimum(r["counts"], C)
+    g = expert_ffn_backward(r["Z"], W1, b1, W2, dY, act, rows=rows)
+    dlogits = gate_backward(r["logits"], idx, dgw, normalize)
+    gb = gate_logits_backward(x, Wg, dlogits)
+    return dict(dx=encode_backward_sparse(g["dZ"], idx, loc, C) + gb["dx"], dWg=gb["dWg"], dgate_bias=gb["dbias"],
+                dW1=g["dW1"], db1=g["db1"], dW2=g["dW2"], db2=g["db2"], forward=r)
+
+
 def token_outputs_direct(tokens: Sequence[int], x, idx, loc, gate_w, C: int, W1, b1, W2, b2, act: int) -> np.ndarray:
     """out[t,:] = sum over kept choices j of gate_w[t,j] * FFN_{idx[t,j]}(x[t,:]), with no [E,C,M] buffers.
 

@@ -9,7 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmoe_mi355x.so")
-SOURCES = ["api.hip", "gate.hip", "dispatch.hip", "ffn_generic.hip", "ffn_mfma.hip", "ffn_backward.hip"]
+SOURCES = ["api.hip", "gate.hip", "dispatch.hip", "ffn_generic.hip", "ffn_mfma.hip", "ffn_backward.hip", "gate_backward.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-Wall", "-Wno-unused-function",
          # keep the compiler from forming packed fp32 math on its own

@@ -245,6 +245,25 @@ int moe_decode(const void* Y, int dtype, const int32_t* idx, const int32_t* loc,
   return launch_decode(Y, dtype, idx, loc, gate_w, T, M, E, k, C, out, (hipStream_t)stream) == hipSuccess ? MOE_OK : MOE_HIP_ERROR;
 }
 
+size_t moe_gate_backward_workspace_bytes(int64_t T, int64_t M, int64_t E, int k) {
+  if (gate_shape_status(T, E, k) != MOE_OK || row_shape_status(M) != MOE_OK) return 0;
+  return gate_backward_workspace_bytes(T, M, E);
+}
+
+int moe_gate_backward(const void* x, const void* Wg, const float* logits, const int32_t* idx, const float* dgate_w, int normalize,
+                      int dtype, int64_t T, int64_t M, int64_t E, int k, void* ws, size_t ws_bytes, void* dx, int accumulate_dx,
+                      void* dWg, float* dbias, float* dlogits, void* stream) {
+  if (!logits || !idx || !dgate_w || !ws || !dtype_ok(dtype) || (!dx && !dWg && !dbias && !dlogits) || (dx && !Wg) ||
+      (dWg && !x))
+    return MOE_INVALID_ARG;
+  if (int st = gate_shape_status(T, E, k)) return st;
+  if (int st = row_shape_status(M)) return st;
+  if (T > 65535 * (int64_t)1024 || !aligned(ws, 256)) return MOE_UNSUPPORTED;
+  if (ws_bytes < gate_backward_workspace_bytes(T, M, E)) return MOE_WORKSPACE_TOO_SMALL;
+  return launch_gate_backward(x, Wg, logits, idx, dgate_w, normalize, dtype, T, M, E, k, ws, dx, accumulate_dx, dWg, dbias, dlogits,
+                              (hipStream_t)stream) == hipSuccess ? MOE_OK : MOE_HIP_ERROR;
+}
+
 size_t moe_ffn_backward_workspace_bytes(int64_t E, int64_t C, int64_t M, int64_t H, int dtype) {
   if (!dtype_ok(dtype) || E < 1 || C < 1 || E > 65535 || C > kMaxDim || row_shape_status(M) || row_shape_status(H)) return 0;
   return ffn_backward_layout(E, C, M, H, dtype).total;

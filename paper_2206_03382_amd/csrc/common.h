@@ -73,6 +73,11 @@ hipError_t launch_decode(const void* Y, int dtype, const int32_t* idx, const int
 hipError_t launch_grouped_gemm(const void* A, const void* B, const void* bias, int act, int dtype, const int32_t* counts,
                                int64_t E, int64_t C, int64_t K, int64_t N, void* out, hipStream_t s);
 
+size_t gate_backward_workspace_bytes(int64_t T, int64_t M, int64_t E);
+hipError_t launch_gate_backward(const void* x, const void* Wg, const float* logits, const int32_t* idx, const float* dgate_w,
+                                int normalize, int dtype, int64_t T, int64_t M, int64_t E, int k, void* ws, void* dx,
+                                int accumulate_dx, void* dWg, float* dbias, float* dlogits, hipStream_t s);
+
 // Backward of the expert feed-forward layer (ffn_backward.hip): byte offsets of its workspace pieces
 struct FfnBackwardWorkspace {
   size_t pre, dP, Wt, At, Bp, total;

@@ -42,6 +42,8 @@ SIGNATURES = {
     "moe_decode": (_i32, [_vp, _i32, _vp, _vp, _vp, _i64, _i64, _i64, _i32, _i64, _vp, _vp]),
     "moe_layer_forward": (_i32, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _i64, _i32, _dbl, _i32, _i32, _i32,
                                  _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp, _c.POINTER(_vp)]),
+    "moe_gate_backward_workspace_bytes": (_sz, [_i64, _i64, _i64, _i32]),
+    "moe_gate_backward": (_i32, [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _i64, _i64, _i64, _i32, _vp, _sz, _vp, _i32, _vp, _vp, _vp, _vp]),
     "moe_ffn_backward_workspace_bytes": (_sz, [_i64, _i64, _i64, _i64, _i32]),
     "moe_expert_ffn_backward": (_i32, [_vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _i64, _i64, _i64, _i64, _vp, _sz,
                                        _vp, _vp, _vp, _vp, _vp, _vp]),
@@ -261,6 +263,27 @@ def decode(Y: torch.Tensor, idx: torch.Tensor, loc: torch.Tensor, gate_w: torch.
     out = torch.empty((T, M), dtype=Y.dtype, device=Y.device)
     _check(lib().moe_decode(_p(Y), _dtype_code(Y), _p(idx), _p(loc), _p(gate_w), T, M, E, k, C, _p(out), _stream()), "moe_decode")
     return out
+
+
+def gate_backward(x: torch.Tensor, Wg: torch.Tensor, logits: torch.Tensor, idx: torch.Tensor, dgate_w: torch.Tensor, normalize: int,
+                  dx: Optional[torch.Tensor] = None) -> Dict[str, torch.Tensor]:
+    """dlogits, dx (added to `dx` if given), dWg, dbias of the gate."""
+    T, M = x.shape
+    E = Wg.shape[1]
+    k = idx.shape[1]
+    nbytes = int(lib().moe_gate_backward_workspace_bytes(T, M, E, k))
+    if nbytes == 0:
+        raise MoEError(UNSUPPORTED, "moe_gate_backward_workspace_bytes")
+    ws = torch.empty((nbytes,), dtype=torch.uint8, device=x.device)
+    accumulate = dx is not None
+    if dx is None:
+        dx = torch.empty_like(x)
+    g = dict(dx=dx, dWg=torch.empty_like(Wg), dbias=torch.empty((E,), dtype=torch.float32, device=x.device),
+             dlogits=torch.empty((T, E), dtype=torch.float32, device=x.device))
+    _check(lib().moe_gate_backward(_p(x), _p(Wg), _p(logits), _p(idx), _p(dgate_w), int(normalize), _dtype_code(x), T, M, E, k,
+                                   _p(ws), ws.numel(), _p(g["dx"]), int(accumulate), _p(g["dWg"]), _p(g["dbias"]), _p(g["dlogits"]),
+                                   _stream()), "moe_gate_backward")
+    return g
 
 
 def expert_ffn_backward(Z: torch.Tensor, W1: torch.Tensor, b1: Optional[torch.Tensor], W2: torch.Tensor, hidden: torch.Tensor,

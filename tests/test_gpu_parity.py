@@ -260,6 +260,34 @@ def test_expert_ffn(moe, dtype, E, C, M, H, act, bias, use_counts):
 
 
 # ----------------------------------------------------------------------------------------------------------------
+# moe_gate_backward
+# ----------------------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype", [synth.DT_F32, synth.DT_BF16])
+@pytest.mark.parametrize("T,M,E,k,normalize", [(1, 8, 1, 1, 1), (70, 40, 4, 2, 1), (1000, 256, 8, 2, 1), (333, 776, 17, 5, 0),
+                                               (2500, 128, 128, 8, 1), (1025, 64, 300, 3, 1)])
+def test_gate_backward(moe, dtype, T, M, E, k, normalize):
+    cfg = synth.CONFIGS[1].scaled(T=T, M=M, H=8, E=E, k=k, dtype=dtype, cfg_id=50)
+    inp = synth.make_inputs(cfg, seed=T + 3)
+    x, Wg = inp["x"], inp["Wg"]
+    logits = O.gate_logits(x, Wg, None)
+    idx = O.topk_experts(logits, k)
+    rng = np.random.default_rng(T + E)
+    dgw = rng.standard_normal((T, k)).astype(np.float32)
+    base = synth.make_inputs(cfg.scaled(cfg_id=51), seed=T + 4)["x"]               # stands in for the dispatch path's dx
+    ref_dl = O.gate_backward(logits, idx, dgw, normalize)
+    ref = O.gate_logits_backward(x, Wg, ref_dl)
+    dxd = dev(base, dtype).clone()
+    g = moe.gate_backward(dev(x, dtype), dev(Wg, dtype), torch.from_numpy(logits).cuda(), torch.from_numpy(idx).cuda(),
+                          torch.from_numpy(dgw).cuda(), normalize, dx=dxd)
+    torch.cuda.synchronize()
+    dl = g["dlogits"].cpu().numpy()
+    assert np.abs(dl - ref_dl).max() <= 1e-5 * max(np.abs(ref_dl).max(), 1e-30)
+    assert_close(host(g["dx"]), base.astype(np.float64) + ref["dx"], dtype, "gate dx (accumulated)")
+    assert_close(host(g["dWg"]), ref["dWg"], dtype, "dWg")
+    assert np.abs(g["dbias"].cpu().numpy() - ref["dbias"]).max() <= 1e-5 * max(np.abs(ref_dl).sum(axis=0).max(), 1e-30)
+
+
+# ----------------------------------------------------------------------------------------------------------------
 # moe_expert_ffn_backward
 # ----------------------------------------------------------------------------------------------------------------
 FFN_BWD_CASES = [

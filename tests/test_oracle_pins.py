@@ -497,7 +497,45 @@ def pin_gate_backward(o):
     np.testing.assert_allclose(gb["dbias"], bt.grad.numpy(), rtol=1e-12, atol=1e-13)
 
 
-PINS = [pin_gate_backward, pin_batch_prioritized_routing, pin_cosine_router, pin_ffn_backward, pin_encode_decode_backward, pin_dynamic_capacity, pin_capacity_golden, pin_worked_routing_example, pin_fig2_even_top1, pin_exhaustive_top1_locations,
+def pin_layer_backward(o):
+    """The whole layer's backward against torch autograd through a dense one-hot-mask implementation of the layer with
+    the routing decisions held fixed."""
+    T, M, H, E, k = 22, 6, 9, 4, 2
+    x, Wg, gb, W1, b1, W2, b2 = _tiny_layer_inputs(91, T, M, H, E)
+    d_out = _rng(92).standard_normal((T, M))
+    for f, normalize, act in ((0.6, 1, o.ACT_GELU), (1.5, 0, o.ACT_SILU)):
+        got = o.moe_layer_backward(x, Wg, gb, W1, b1, W2, b2, k, f, normalize, act, d_out)
+        fw = got["forward"]
+        C = fw["C"]
+        tx, tWg, tgb, tW1, tb1, tW2, tb2 = (torch.from_numpy(a.astype(np.float64)).requires_grad_(True) for a in (x, Wg, gb, W1, b1, W2, b2))
+        lg = tx @ tWg + tgb
+        lg = lg + (torch.from_numpy(fw["logits"].astype(np.float64)) - lg).detach()    # the method's one rounding of the logits to fp32
+        p = torch.softmax(lg, dim=1)
+        idx_t = torch.from_numpy(fw["idx"].astype(np.int64))
+        g = p.gather(1, idx_t)
+        w = g / g.sum(dim=1, keepdim=True) if normalize else g
+        D = torch.zeros((T, E, C), dtype=torch.float64)
+        Wm = torch.zeros((T, E, C), dtype=torch.float64)
+        for j in range(k):
+            t = torch.from_numpy(np.nonzero(fw["kept"][:, j])[0])
+            e = idx_t[t, j]
+            l = torch.from_numpy(fw["loc"][t.numpy(), j].astype(np.int64))
+            D = D.index_put((t, e, l), torch.ones(len(t), dtype=torch.float64), accumulate=True)
+            Wm = Wm.index_put((t, e, l), w[t, j], accumulate=True)
+        Z = torch.einsum("tec,tm->ecm", D, tx)
+        Y = torch.stack([_torch_act(Z[e] @ tW1[e] + tb1[e], act) @ tW2[e] + tb2[e] for e in range(E)])
+        out = torch.einsum("tec,ecm->tm", Wm, Y)
+        np.testing.assert_allclose(out.detach().numpy(), fw["out"], rtol=1e-10, atol=1e-12)
+        (out * torch.from_numpy(d_out)).sum().backward()
+        for name, t in (("dx", tx), ("dWg", tWg), ("dgate_bias", tgb), ("dW1", tW1), ("db1", tb1), ("dW2", tW2)):
+            np.testing.assert_allclose(got[name], t.grad.numpy(), rtol=1e-8, atol=1e-10, err_msg=name)
+        # unfilled slots see b2 in the dense form but are combined with weight 0: db2 counts filled slots only
+        filled = (o.slot_source(fw["idx"], fw["loc"], E, C) >= 0)
+        np.testing.assert_allclose(got["db2"], tb2.grad.numpy(), rtol=1e-8, atol=1e-10)
+        assert filled.sum() == fw["kept"].sum()
+
+
+PINS = [pin_layer_backward, pin_gate_backward, pin_batch_prioritized_routing, pin_cosine_router, pin_ffn_backward, pin_encode_decode_backward, pin_dynamic_capacity, pin_capacity_golden, pin_worked_routing_example, pin_fig2_even_top1, pin_exhaustive_top1_locations,
         pin_random_topk_vs_bruteforce, pin_invariants, pin_ties_lower_index, pin_gate_against_torch,
         pin_activations_and_ffn_against_torch, pin_no_drop_equals_weighted_sum_of_experts,
         pin_identity_experts_masked_scaling, pin_dense_equals_sparse_and_direct, pin_bruteforce_layer]
