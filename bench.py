@@ -196,6 +196,11 @@ def main() -> int:
                                   "note": "dZ, dW1, db1, dW2, db2; four GEMMs' worth of algorithmic flop (2*R*M*H each); the "
                                           "time also holds the recomputed pre-activation GEMM, four transposes, two padded copies "
                                           "and torch's allocation of workspace and outputs"}
+        dgw = torch.randn((T, k), device="cuda")
+        dxb = torch.empty_like(x)
+        gate_b = timed(lambda: moe.gate_backward(x, layer.Wg, r["logits"], r["idx"], dgw, cfg.normalize, dx=dxb))
+        result["backward_gate_ms"] = round(gate_b, 5)
+        result["backward_total_ms"] = round(gate_b + ffn_b + enc_b + dec_b, 5)
         result["backward_dispatch"] = {
             "encode_backward_ms": round(enc_b, 5), "encode_backward_frac_hbm": round(enc_b_bytes / (enc_b * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
             "decode_backward_ms": round(dec_b, 5), "decode_backward_frac_hbm": round(dec_b_bytes / (dec_b * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),

@@ -258,7 +258,7 @@ int moe_gate_backward(const void* x, const void* Wg, const float* logits, const 
     return MOE_INVALID_ARG;
   if (int st = gate_shape_status(T, E, k)) return st;
   if (int st = row_shape_status(M)) return st;
-  if (T > 65535 * (int64_t)1024 || !aligned(ws, 256)) return MOE_UNSUPPORTED;
+  if (T > 65535 * (int64_t)128 || !aligned(ws, 256) || (dx && !aligned(dx, 16))) return MOE_UNSUPPORTED;   // one grid row per 128-token slice
   if (ws_bytes < gate_backward_workspace_bytes(T, M, E)) return MOE_WORKSPACE_TOO_SMALL;
   return launch_gate_backward(x, Wg, logits, idx, dgate_w, normalize, dtype, T, M, E, k, ws, dx, accumulate_dx, dWg, dbias, dlogits,
                               (hipStream_t)stream) == hipSuccess ? MOE_OK : MOE_HIP_ERROR;

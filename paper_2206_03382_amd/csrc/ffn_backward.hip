@@ -61,35 +61,6 @@ __device__ __forceinline__ float act_grad(float p, int act) {
   return sg * (1.f + p * (1.f - sg));
 }
 
-// 16 bytes of `ET` as floats and back
-template <typename ET> struct Vec16;
-template <> struct Vec16<float> {
-  static constexpr int N = 4;
-  static __device__ __forceinline__ void unpack(const uint4& v, float (&f)[4]) {
-    f[0] = __uint_as_float(v.x); f[1] = __uint_as_float(v.y); f[2] = __uint_as_float(v.z); f[3] = __uint_as_float(v.w);
-  }
-  static __device__ __forceinline__ uint4 pack(const float (&f)[4]) {
-    return make_uint4(__float_as_uint(f[0]), __float_as_uint(f[1]), __float_as_uint(f[2]), __float_as_uint(f[3]));
-  }
-};
-template <> struct Vec16<uint16_t> {
-  static constexpr int N = 8;
-  static __device__ __forceinline__ void unpack(const uint4& v, float (&f)[8]) {
-    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      f[2 * i] = __uint_as_float(w[i] << 16);
-      f[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
-    }
-  }
-  static __device__ __forceinline__ uint4 pack(const float (&f)[8]) {
-    uint32_t w[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) w[i] = pack_bf16x2(f[2 * i], f[2 * i + 1]);
-    return make_uint4(w[0], w[1], w[2], w[3]);
-  }
-};
-
 // dP = dH * act'(pre) in place over the live rows, 16 bytes per thread.   dH, pre [E,C,H] as rows of cpr pieces.
 template <typename ET>
 __global__ __launch_bounds__(256) void act_backward_kernel(uint4* __restrict__ dH, const uint4* __restrict__ pre,

@@ -9,7 +9,7 @@ namespace moe {
 
 namespace {
 
-constexpr int kDwSlice = 1024;                             // tokens per partial sum of dWg
+constexpr int kDwSlice = 128;                              // tokens per partial sum of dWg
 
 // One thread per token.  p = softmax(logits); g_j = p[idx_j]; gate_w = g / sum g (normalize) or g.
 __global__ __launch_bounds__(256) void gate_backward_kernel(const float* __restrict__ logits, const int32_t* __restrict__ idx,
@@ -43,18 +43,45 @@ __global__ __launch_bounds__(256) void gate_backward_kernel(const float* __restr
   }
 }
 
-// dx[t,m] = (accumulate ? dx[t,m] : 0) + sum_e dlogits[t,e] Wg[m,e].  One thread per (t, m); threads of a wave share t.
+// dx[t,m] = (accumulate ? dx[t,m] : 0) + sum_e dlogits[t,e] Wg[m,e].  One thread per (t, 16-byte piece of the row).
 template <typename ET>
 __global__ __launch_bounds__(256) void gate_dx_kernel(const float* __restrict__ dlogits, const ET* __restrict__ Wg, int64_t T,
-                                                      int M, int E, int accumulate, ET* __restrict__ dx) {
+                                                      int cpr, int E, int accumulate, uint4* __restrict__ dx) {
+  constexpr int N = Vec16<ET>::N;
   const int64_t t = blockIdx.x;
-  const int m = blockIdx.y * 256 + threadIdx.x;
-  if (m >= M) return;
+  const int piece = blockIdx.y * 256 + threadIdx.x;
+  if (piece >= cpr) return;
   const float* dl = dlogits + t * E;
-  const ET* w = Wg + (int64_t)m * E;
-  float acc = accumulate ? load_as_f32<ET>(dx + t * M + m) : 0.f;
-  for (int e = 0; e < E; ++e) acc = fmaf(dl[e], load_as_f32<ET>(w + e), acc);
-  store_from_f32<ET>(dx + t * M + m, acc);
+  const ET* w = Wg + (int64_t)piece * N * E;                // rows piece*N .. piece*N + N-1 of Wg, E values each
+  float acc[N];
+  if (accumulate) Vec16<ET>::unpack(dx[t * cpr + piece], acc);
+  else {
+#pragma unroll
+    for (int u = 0; u < N; ++u) acc[u] = 0.f;
+  }
+  if ((E % N) == 0 && (reinterpret_cast<uintptr_t>(Wg) & 15) == 0) {    // rows of Wg are whole 16-byte pieces
+    const uint4* wv = reinterpret_cast<const uint4*>(w);
+    const int rp = E / N;                                   // pieces per row
+    for (int q = 0; q < rp; ++q) {
+      float d[N];
+#pragma unroll
+      for (int i = 0; i < N; ++i) d[i] = dl[q * N + i];
+#pragma unroll
+      for (int u = 0; u < N; ++u) {
+        float f[N];
+        Vec16<ET>::unpack(wv[u * rp + q], f);
+#pragma unroll
+        for (int i = 0; i < N; ++i) acc[u] = fmaf(d[i], f[i], acc[u]);
+      }
+    }
+  } else {
+    for (int e = 0; e < E; ++e) {
+      const float d = dl[e];
+#pragma unroll
+      for (int u = 0; u < N; ++u) acc[u] = fmaf(d, load_as_f32<ET>(w + u * E + e), acc[u]);
+    }
+  }
+  dx[t * cpr + piece] = Vec16<ET>::pack(acc);
 }
 
 // partial[s][m][e] = sum over the tokens of slice s of x[t,m] dlogits[t,e]; thread = m, 8 experts per pass.
@@ -68,6 +95,7 @@ __global__ __launch_bounds__(256) void gate_dw_partial_kernel(const ET* __restri
   float acc[8];
 #pragma unroll
   for (int u = 0; u < 8; ++u) acc[u] = 0.f;
+#pragma unroll 4
   for (int64_t t = t0; t < t1; ++t) {
     const float xv = load_as_f32<ET>(x + t * M + m);
     const float* dl = dlogits + t * E + e0;
@@ -123,7 +151,8 @@ static hipError_t gate_backward_t(const void* x, const void* Wg, const float* lo
   gate_backward_kernel<<<dim3((unsigned)ceil_div(T, 256)), dim3(256), 0, s>>>(logits, idx, dgate_w, T, (int)E, k, normalize, dl);
   if ((err = hipGetLastError()) != hipSuccess) return err;
   if (dx) {
-    gate_dx_kernel<ET><<<dim3((unsigned)T, (unsigned)ceil_div(M, 256)), dim3(256), 0, s>>>(dl, (const ET*)Wg, T, (int)M, (int)E, accumulate_dx, (ET*)dx);
+    const int cpr = (int)(M * sizeof(ET) / 16);
+    gate_dx_kernel<ET><<<dim3((unsigned)T, (unsigned)ceil_div(cpr, 256)), dim3(256), 0, s>>>(dl, (const ET*)Wg, T, cpr, (int)E, accumulate_dx, (uint4*)dx);
     if ((err = hipGetLastError()) != hipSuccess) return err;
   }
   if (dWg) {

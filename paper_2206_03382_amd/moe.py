@@ -324,6 +324,26 @@ def decode_backward(d_out: torch.Tensor, Y: torch.Tensor, idx: torch.Tensor, loc
     return dY, dgate_w
 
 
+def layer_forward_backward(x, Wg, gate_bias, W1, b1, W2, b2, k: int, f: float, normalize: int, act: int,
+                           d_out: torch.Tensor) -> Dict[str, torch.Tensor]:
+    """One training pass of the layer through the separate entry points: forward (keeping what the backward needs), then
+    the backward of decode, of the experts, of encode and of the gate.  Returns out and all gradients."""
+    T, E = x.shape[0], W1.shape[0]
+    C = capacity(T, E, k, f)
+    logits = gate_logits(x, Wg, gate_bias)
+    r = gate_topk(logits, k, C, normalize)
+    Z = encode(x, r["idx"], r["loc"], r["slot_src"], E, C)
+    hidden = torch.empty((E, C, W1.shape[2]), dtype=x.dtype, device=x.device)
+    Y = expert_ffn(Z, W1, b1, W2, b2, act, counts=r["counts"], hidden=hidden)
+    out = decode(Y, r["idx"], r["loc"], r["gate_w"])
+    dY, dgate_w = decode_backward(d_out, Y, r["idx"], r["loc"], r["gate_w"], r["slot_src"])
+    g = expert_ffn_backward(Z, W1, b1, W2, hidden, dY, act, counts=r["counts"])
+    dx = encode_backward(g["dZ"], r["idx"], r["loc"])
+    gg = gate_backward(x, Wg, logits, r["idx"], dgate_w, normalize, dx=dx)
+    return dict(out=out, dx=gg["dx"], dWg=gg["dWg"], dgate_bias=gg["dbias"], dW1=g["dW1"], db1=g["db1"], dW2=g["dW2"],
+                db2=g["db2"], routing=r, logits=logits)
+
+
 class StageEvents:
     """MOE_NUM_STAGE_EVENTS HIP events, recorded by moe_layer_forward on its stream at the stage boundaries."""
 

@@ -379,6 +379,29 @@ def test_layer_small(moe, cfg, bias):
 
 
 # ----------------------------------------------------------------------------------------------------------------
+# forward + backward of the whole layer through the separate entry points
+# ----------------------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("cfg", [synth.CONFIGS[0].scaled(T=300, M=40, H=72, E=3), synth.CONFIGS[1].scaled(T=1500, M=256, H=512, E=8),
+                                 synth.CONFIGS[3].scaled(T=4096, M=256, H=512, E=64)], ids=lambda c: f"{c.name}-T{c.T}-E{c.E}")
+def test_layer_forward_backward(moe, cfg):
+    inp = synth.make_inputs(cfg, seed=11, bias_std=0.25)
+    d_out = synth.make_inputs(cfg.scaled(cfg_id=52), seed=12)["x"]
+    ref = O.moe_layer_backward(inp["x"], inp["Wg"], inp["gate_bias"], inp["W1"], inp["b1"], inp["W2"], inp["b2"],
+                               cfg.k, cfg.f, cfg.normalize, cfg.act, d_out)
+    d = cfg.dtype
+    gb = None if inp["gate_bias"] is None else torch.from_numpy(inp["gate_bias"]).cuda()
+    got = moe.layer_forward_backward(dev(inp["x"], d), dev(inp["Wg"], d), gb, dev(inp["W1"], d), dev(inp["b1"], d),
+                                     dev(inp["W2"], d), dev(inp["b2"], d), cfg.k, cfg.f, cfg.normalize, cfg.act, dev(d_out, d))
+    torch.cuda.synchronize()
+    assert_routing_equal(got["routing"], ref["forward"], ref["forward"]["C"], cfg.name)
+    assert_close(host(got["out"]), ref["forward"]["out"], d, "out")
+    for name in ("dx", "dWg", "dW1", "db1", "dW2", "db2"):
+        assert_close(host(got[name]), ref[name], d, name)
+    scale = np.abs(ref["dgate_bias"]).max()
+    assert np.abs(got["dgate_bias"].cpu().numpy() - ref["dgate_bias"]).max() <= (1e-4 if d == synth.DT_F32 else 2e-2) * max(scale, 1e-30)
+
+
+# ----------------------------------------------------------------------------------------------------------------
 # dispatch fused into the first expert GEMM: same results as encode + FFN on the rows that exist
 # ----------------------------------------------------------------------------------------------------------------
 FUSED_LAYERS = [
