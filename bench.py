@@ -194,7 +194,7 @@ def main() -> int:
         ffn_b = timed(lambda: moe.expert_ffn_backward(Zb, layer.W1, layer.b1, layer.W2, hidden, slabs, cfg.act, counts=r["counts"]))
         result["backward_ffn"] = {"ms": round(ffn_b, 5), "algorithmic_TFLOPs": round(4 * flop_per_gemm / (ffn_b * 1e-3) / 1e12, 1),
                                   "note": "dZ, dW1, db1, dW2, db2; four GEMMs' worth of algorithmic flop (2*R*M*H each); the "
-                                          "time also holds the recomputed pre-activation GEMM, four transposes, two padded copies "
+                                          "time also holds the recomputed pre-activation GEMM, the bias gradients' column sums "
                                           "and torch's allocation of workspace and outputs"}
         dgw = torch.randn((T, k), device="cuda")
         dxb = torch.empty_like(x)

@@ -43,6 +43,14 @@ __device__ __forceinline__ float apply_act(float v, int act) {
   return v / (1.0f + __expf(-v));
 }
 
+// derivative of the activation at pre-activation p
+__device__ __forceinline__ float apply_act_grad(float p, int act) {
+  if (act == MOE_ACT_RELU) return p > 0.f ? 1.f : 0.f;
+  if (act == MOE_ACT_GELU) return 0.5f * (1.f + erff(p * 0.70710678118654752440f)) + p * expf(-0.5f * p * p) * 0.39894228040143267794f;
+  const float sg = 1.f / (1.f + expf(-p));                  // SiLU
+  return sg * (1.f + p * (1.f - sg));
+}
+
 // 16 bytes of `ET` as floats and back
 template <typename ET> struct Vec16;
 template <> struct Vec16<float> {
@@ -101,6 +109,13 @@ hipError_t launch_decode(const void* Y, int dtype, const int32_t* idx, const int
 // act < 0 means no activation.
 hipError_t launch_grouped_gemm(const void* A, const void* B, const void* bias, int act, int dtype, const int32_t* counts,
                                int64_t E, int64_t C, int64_t K, int64_t N, void* out, hipStream_t s);
+
+// Matrix-core GEMM with transposed operands (ffn_mfma.hip), bf16 only; see there for the argument meaning.
+bool grouped_gemm_mfma_supports_backward(int64_t E, int64_t C, int64_t M, int64_t H);
+hipError_t launch_grouped_gemm_mfma_nt(const void* A, const void* Bt, const int32_t* counts, int64_t E, int64_t C,
+                                       int64_t K, int64_t N, void* out, const void* pre, int act, hipStream_t s);
+hipError_t launch_grouped_gemm_mfma_tn(const void* At, const void* B, const int32_t* kfill, int64_t E, int64_t C, int64_t R,
+                                       int64_t N, void* a_tail, void* b_tail, void* out, hipStream_t s);
 
 size_t gate_backward_workspace_bytes(int64_t T, int64_t M, int64_t E);
 hipError_t launch_gate_backward(const void* x, const void* Wg, const float* logits, const int32_t* idx, const float* dgate_w,

@@ -2,10 +2,12 @@
 // computation of the expert" between the two all-to-alls):  y = act(z W1 + b1) W2 + b2  per expert, so
 //   dH = dY W2^T,  dP = dH * act'(z W1 + b1),  dZ = dP W1^T,  dW1 = Z^T dP,  db1 = colsum dP,  dW2 = hidden^T dY,
 //   db2 = colsum dY,  over the rows of an expert that exist.
-// Every product runs on the forward's grouped GEMM (C[e] = A[e] (rows x K) * B[e] (K x N), both row-major): the
-// operands that the chain rule wants transposed are first written out transposed (weights [K,N] -> [N,K]; activations
-// [C,W] -> [W,Cp] with the rows past the fill zeroed and the row count padded to the GEMM's K step).  This is the
-// functional first version: the transposes cost extra HBM passes that a transposed-operand GEMM would not need.
+// bf16 shapes the matrix-core GEMM takes (M and H multiples of 256) use its transposed-operand layouts: the weights
+// are read as stored for the products with W^T, the activations as stored for the weight gradients (reduction over an
+// expert's slots up to its fill), and act' is applied in the epilogue of the dH product; nothing is copied.
+// Other shapes and fp32 run every product on the plain grouped GEMM (C[e] = A[e] (rows x K) * B[e] (K x N), both
+// row-major) after writing out transposed what the chain rule wants transposed (weights [K,N] -> [N,K]; activations
+// [C,W] -> [W,Cp] with the rows past the fill zeroed and the row count padded to the GEMM's K step).
 #include "common.h"
 
 namespace moe {
@@ -54,13 +56,6 @@ __global__ __launch_bounds__(256) void pad_rows_kernel(const uint4* __restrict__
   }
 }
 
-__device__ __forceinline__ float act_grad(float p, int act) {
-  if (act == MOE_ACT_RELU) return p > 0.f ? 1.f : 0.f;
-  if (act == MOE_ACT_GELU) return 0.5f * (1.f + erff(p * 0.70710678118654752440f)) + p * expf(-0.5f * p * p) * 0.39894228040143267794f;
-  const float sg = 1.f / (1.f + expf(-p));                  // SiLU
-  return sg * (1.f + p * (1.f - sg));
-}
-
 // dP = dH * act'(pre) in place over the live rows, 16 bytes per thread.   dH, pre [E,C,H] as rows of cpr pieces.
 template <typename ET>
 __global__ __launch_bounds__(256) void act_backward_kernel(uint4* __restrict__ dH, const uint4* __restrict__ pre,
@@ -76,7 +71,7 @@ __global__ __launch_bounds__(256) void act_backward_kernel(uint4* __restrict__ d
     Vec16<ET>::unpack(dH[i], g);
     Vec16<ET>::unpack(pre[i], p);
 #pragma unroll
-    for (int u = 0; u < N; ++u) g[u] *= act_grad(p[u], act);
+    for (int u = 0; u < N; ++u) g[u] *= apply_act_grad(p[u], act);
     dH[i] = Vec16<ET>::pack(g);
   }
 }
@@ -157,6 +152,25 @@ static hipError_t ffn_backward_t(const void* Z, const void* W1, const void* b1, 
 #define MOE_TRY(x) do { err = (x); if (err != hipSuccess) return err; } while (0)
   // pre-activations, recomputed (the forward keeps only act(pre))
   MOE_TRY(launch_grouped_gemm(Z, W1, b1, -1, dtype, counts, E, C, M, H, pre, s));
+  auto colsums = [&]() -> hipError_t {
+    if (db1) {
+      const int cprH = (int)(H * es / 16);
+      colsum_kernel<ET><<<dim3((unsigned)ceil_div(cprH, 8), (unsigned)E), dim3(256), 0, s>>>((const uint4*)dP, counts, C, cprH, (ET*)db1);
+    }
+    if (db2) {
+      const int cprM = (int)(M * es / 16);
+      colsum_kernel<ET><<<dim3((unsigned)ceil_div(cprM, 8), (unsigned)E), dim3(256), 0, s>>>((const uint4*)dY, counts, C, cprM, (ET*)db2);
+    }
+    return hipGetLastError();
+  };
+  if (dtype == MOE_BF16 && grouped_gemm_mfma_supports_backward(E, C, M, H)) {
+    // dP = (dY W2^T) * act'(pre);  dZ = dP W1^T;  dW2 = hidden^T dY;  dW1 = Z^T dP  (At / Bp hold the last K-steps)
+    MOE_TRY(launch_grouped_gemm_mfma_nt(dY, W2, counts, E, C, M, H, dP, pre, act, s));
+    if (dZ) MOE_TRY(launch_grouped_gemm_mfma_nt(dP, W1, counts, E, C, H, M, dZ, nullptr, -1, s));
+    if (dW2) MOE_TRY(launch_grouped_gemm_mfma_tn(hidden, dY, counts, E, C, H, M, At, Bp, dW2, s));
+    if (dW1) MOE_TRY(launch_grouped_gemm_mfma_tn(Z, dP, counts, E, C, M, H, At, Bp, dW1, s));
+    return colsums();
+  }
   // dH = dY W2^T, then dP = dH * act'(pre)
   MOE_TRY(transpose_pad<ET>(W2, nullptr, E, H, M, H, Wt, s));                          // [E,H,M] -> [E,M,H]
   MOE_TRY(launch_grouped_gemm(dY, Wt, nullptr, -1, dtype, counts, E, C, M, H, dP, s));
@@ -189,16 +203,7 @@ static hipError_t ffn_backward_t(const void* Z, const void* W1, const void* b1, 
     MOE_TRY(pad_rows(dP, H, Bp));
     MOE_TRY(launch_grouped_gemm(At, Bp, nullptr, -1, dtype, nullptr, E, M, Cp, H, dW1, s));
   }
-  if (db1) {
-    const int cprH = (int)(H * es / 16);
-    colsum_kernel<ET><<<dim3((unsigned)ceil_div(cprH, 8), (unsigned)E), dim3(256), 0, s>>>((const uint4*)dP, counts, C, cprH, (ET*)db1);
-    MOE_TRY(hipGetLastError());
-  }
-  if (db2) {
-    const int cprM = (int)(M * es / 16);
-    colsum_kernel<ET><<<dim3((unsigned)ceil_div(cprM, 8), (unsigned)E), dim3(256), 0, s>>>((const uint4*)dY, counts, C, cprM, (ET*)db2);
-    MOE_TRY(hipGetLastError());
-  }
+  MOE_TRY(colsums());
 #undef MOE_TRY
   return hipSuccess;
 }

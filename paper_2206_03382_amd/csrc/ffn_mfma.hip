@@ -21,6 +21,17 @@
 // 4 k x 16 n sub-blocks on the way out of LDS (source lane s of a 16-lane block supplies row k0 + s/4,
 // columns n0 + 4 (s%4) .. +3; result lane l holds column n0 + l, rows k0 .. k0+3).
 //
+// Operand layouts (MODE).  The forward products read A row-major with k contiguous and B row-major with n contiguous
+// (kNN).  The backward needs the other two combinations and gets them without any transposed copy in memory:
+//   kNT: B is given as [N, K] (k contiguous, e.g. a weight matrix used transposed): its tile is staged and read
+//        exactly like an A tile ([256 n][8 chunks of 8 k], ds_read_b128);
+//   kTN: A is given as [K, rows] (rows contiguous, e.g. activations used transposed for a weight gradient): its tile
+//        is staged and read exactly like a B tile ([64 k][32 chunks of 8 m], transposing reads).  Here the reduction
+//        runs over an expert's slots, so its length differs per expert: K-steps up to the last whole one come from
+//        the operands themselves and the last one from two small side buffers [E, 64, rows] / [E, 64, N] that hold
+//        the remaining slots followed by zeros (written by tail_rows_kernel below), so no read ever touches a slot
+//        past the fill.
+//
 // The two MFMA operands are passed swapped (B fragment first), so that a lane's accumulator registers hold four
 // consecutive output columns of one row: D'[n][m] with m = lane % 32, n = 8 (v/4) + 4 (lane/32) + v % 4.  The
 // epilogue packs them to 8 bytes, transposes the wave's 128 x 128 tile through LDS and stores whole 256-byte row pieces.
@@ -45,6 +56,7 @@ constexpr int kStageBytes = 65536;          // A tile 32 KB + B tile 32 KB
 constexpr int kATileBytes = 32768;
 constexpr int kLoadsPerWave = 16;           // 64 KB per K-step / (4 waves x 1 KB per wave-load)
 constexpr int kMaxExperts = 512;            // the tile search keeps one register per 64 experts
+constexpr int kNN = 0, kNT = 1, kTN = 2;    // operand layouts, see the head of this file
 
 #define LDS_PTR(T, p) ((__attribute__((address_space(3))) T*)(p))
 #define PIN() __builtin_amdgcn_sched_barrier(0)
@@ -73,6 +85,29 @@ __device__ __forceinline__ float fast_gelu(float v) {
   return v * (0.5f + d);
 }
 
+// gelu'(v) = Phi(v) + v phi(v) with the same Phi and phi(v) = exp2(-v^2 / (2 ln 2)) / sqrt(2 pi): two exponentials,
+// |error| < 3e-6.
+constexpr float kHalfLog2e = 0.72134752f, kInvSqrt2Pi = 0.39894228f;
+__device__ __forceinline__ float fast_gelu_grad(float v) {
+  const float y = fabsf(v);
+  float p = fmaf(kGeluC5, y, kGeluC4);
+  p = fmaf(p, y, kGeluC3);
+  p = fmaf(p, y, kGeluC2);
+  p = fmaf(p, y, kGeluC1);
+  const float e = __builtin_amdgcn_exp2f(-(p * y));
+  const float d = copysignf(fmaf(-0.5f, e, 0.5f), v);              // Phi(v) - 1/2
+  const float dens = __builtin_amdgcn_exp2f(-kHalfLog2e * v * v) * kInvSqrt2Pi;
+  return fmaf(v, dens, 0.5f + d);
+}
+
+// act'(p) for the epilogue that turns dH into dP (bf16 results: relative error far below the output resolution)
+template <int ACT> __device__ __forceinline__ float epilogue_act_grad(float p) {
+  if (ACT == MOE_ACT_RELU) return p > 0.f ? 1.f : 0.f;
+  if (ACT == MOE_ACT_GELU) return fast_gelu_grad(p);
+  const float sg = __builtin_amdgcn_rcpf(1.0f + __expf(-p));        // SiLU
+  return sg * fmaf(p, 1.f - sg, 1.f);
+}
+
 template <int ACT> __device__ __forceinline__ float epilogue_act(float v) {
   if (ACT == MOE_ACT_RELU) return fmaxf(v, 0.f);
   if (ACT == MOE_ACT_GELU) return fast_gelu(v);
@@ -92,55 +127,81 @@ struct Frags {
 // they may start only after the barrier that follows the last read of that stage (issued during sub-step 2): 8 of a
 // wave's 16 loads are issued in sub-step 3 of K-step kt, the other 8 in sub-step 0 of K-step kt+1, and they are
 // waited for before the barrier of K-step kt+1, two sub-steps later.
-template <int NI>
-__device__ __forceinline__ void tile_main_loop(char* smem, const char* a_base, const char* b_base,
-                                               const uint32_t (&a_voff)[8], const uint32_t (&b_voff)[8], int64_t a_step,
-                                               int64_t b_step, const int (&a_off)[4], const int (&b_off)[4], int a_swz,
-                                               int kg, int a_mask, int wave, int K, const uint16_t* bias_w,
+template <int NI, int MODE>
+__device__ __forceinline__ void tile_main_loop(char* smem, const char* a_base, const char* b_base, const char* a_last,
+                                               const char* b_last, const uint32_t (&a_voff)[8],
+                                               const uint32_t (&b_voff)[8], int64_t a_step, int64_t b_step,
+                                               const int (&a_off)[4], const int (&b_off)[4], int a_swz, int kg,
+                                               int a_mask, int wave, int KT, const uint16_t* bias_w,
                                                f32x16 (&acc)[4][4]) {
   constexpr bool FULL = NI == 4;
+  constexpr bool TRA = MODE == kTN;          // A through transposing reads (two per fragment)
+  constexpr bool TRB = MODE != kNT;          // B through transposing reads
+  constexpr int NRA = TRA ? 8 : 4, NRB = TRB ? 8 : 4, NR = NRA + NRB;   // LDS reads per sub-step
   Frags f[2];
   const uint32_t smem_addr = (uint32_t)(uintptr_t)LDS_PTR(char, smem);
-  const int KT = K / BK;
 
-  // read number r (0..11) of sub-step s from `stage` into fragment buffer `d`: 0-3 A rows, 4-11 B column halves
-  auto read = [&](const char* stage, int s, int r, Frags& d, short4v (&lo)[4]) {
-    if (r < 4) {
-      if (r < NI) d.a[r] = *LDS_PTR(bf16x8, stage + a_off[r] + (((2 * s + kg) ^ a_swz) << 4));
-    } else if (NI > 0) {
-      const int j = (r - 4) >> 1;
-      if (((r - 4) & 1) == 0) {
-        lo[j] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(short4v, stage + b_off[j] + (16 * s) * 512));
+  // read number r (0 .. NR-1) of sub-step s from `stage` into fragment buffer `d`: first A's, then B's.  A direct read
+  // fetches a lane's 8 k of one row (ds_read_b128); a transposed fragment takes two reads of 4 k each.
+  auto read_direct = [&](const char* stage, int off, int s) -> bf16x8 {
+    return *LDS_PTR(bf16x8, stage + off + (((2 * s + kg) ^ a_swz) << 4));
+  };
+  auto read_tr = [&](const char* stage, int off, int s, int half) -> short4v {
+    return __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(short4v, stage + off + (16 * s + 4 * half) * 512));
+  };
+  auto join = [](short4v lo, short4v hi) -> bf16x8 {
+    return __builtin_bit_cast(bf16x8, (short8v)__builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+  };
+  auto read = [&](const char* stage, int s, int r, Frags& d, short4v (&lo)[8]) {
+    if (r < NRA) {
+      if (!TRA) {
+        if (r < NI) d.a[r] = read_direct(stage, a_off[r], s);
       } else {
-        const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(short4v, stage + b_off[j] + (16 * s + 4) * 512));
-        d.b[j] = __builtin_bit_cast(bf16x8, (short8v)__builtin_shufflevector(lo[j], hi, 0, 1, 2, 3, 4, 5, 6, 7));
+        const int i = r >> 1;
+        if ((r & 1) == 0) lo[i] = read_tr(stage, a_off[i], s, 0);
+        else d.a[i] = join(lo[i], read_tr(stage, a_off[i], s, 1));
+      }
+    } else if (NI > 0) {
+      const int rb = r - NRA;
+      if (!TRB) {
+        d.b[rb] = read_direct(stage, b_off[rb], s);
+      } else {
+        const int j = rb >> 1;
+        if ((rb & 1) == 0) lo[4 + j] = read_tr(stage, b_off[j], s, 0);
+        else d.b[j] = join(lo[4 + j], read_tr(stage, b_off[j], s, 1));
       }
     }
   };
-  // direct load number idx (0..15: A0..A7, B0..B7) of K-step `tile` (the caller guarantees tile < KT)
+  // direct load number idx (0..15: A0..A7, B0..B7) of K-step `tile` (the caller guarantees tile < KT).  With a
+  // transposed A the last K-step comes from the zero-padded side buffers.
   auto dma = [&](int idx, int tile) {
     const int q = idx & 7;
     const uint32_t dst = smem_addr + (tile & 1) * kStageBytes + (q * 4 + wave) * 1024;
+    const bool last = MODE == kTN && tile == KT - 1;
     if (idx < 8) {
-      if (FULL || ((a_mask >> q) & 1)) global_to_lds_16(a_base + tile * a_step, a_voff[q], dst);   // skip rows past the slab's fill
-    } else global_to_lds_16(b_base + tile * b_step, b_voff[q], dst + kATileBytes);
+      const char* src = last ? a_last : a_base + tile * a_step;
+      if (FULL || ((a_mask >> q) & 1)) global_to_lds_16(src, a_voff[q], dst);   // skip rows past the slab's fill
+    } else {
+      const char* src = last ? b_last : b_base + tile * b_step;
+      global_to_lds_16(src, b_voff[q], dst + kATileBytes);
+    }
   };
   auto mfma = [&](int m, const Frags& c) {
     const int i = m >> 2, j = m & 3;
     if (i < NI) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(c.b[j], c.a[i], acc[i][j], 0, 0, 0);
   };
-  // one sub-step: 16 MFMAs from `c`, interleaved with the 12 reads of (stage, s_next) into `n` (if READS) and with the
+  // one sub-step: 16 MFMAs from `c`, interleaved with the NR reads of (stage, s_next) into `n` (if READS) and with the
   // direct loads dma_first .. dma_first+7 of K-step dma_tile (if DMA); both switches are compile-time so that the
   // steady-state loop body is branch-free
   auto substep = [&](auto reads_tag, auto dma_tag, const Frags& c, Frags& n, const char* stage, int s_next, int dma_first,
                      int dma_tile) {
     constexpr bool READS = decltype(reads_tag)::value, DMA = decltype(dma_tag)::value;
-    short4v lo[4];
+    short4v lo[8];
 #pragma unroll
     for (int m = 0; m < 16; ++m) {
       mfma(m, c);
       PIN();
-      if (READS && m < 12) read(stage, s_next, m, n, lo);
+      if (READS && m < NR) read(stage, s_next, m, n, lo);
       if (DMA && (m & 1) == 1) dma(dma_first + (m >> 1), dma_tile);
       PIN();
     }
@@ -197,9 +258,9 @@ __device__ __forceinline__ void tile_main_loop(char* smem, const char* a_base, c
   asm volatile("s_barrier" ::: "memory");
   PIN();
   {
-    short4v lo[4];
+    short4v lo[8];
 #pragma unroll
-    for (int r = 0; r < 12; ++r) read(smem, 0, r, f[0], lo);
+    for (int r = 0; r < NR; ++r) read(smem, 0, r, f[0], lo);
   }
   PIN();
 
@@ -216,7 +277,13 @@ __device__ __forceinline__ void tile_main_loop(char* smem, const char* a_base, c
   }
 }
 
-template <int ACT>
+// A weight-gradient product (kTN) reduces over an expert's slots: K-steps of 64 slots, the last one (whole or not) read
+// from the side buffers, which also covers an expert without any slot (one K-step of zeros).
+__host__ __device__ inline int slot_ksteps(int64_t fill) { return fill > 0 ? (int)((fill + BK - 1) / BK) : 1; }
+
+// GRAD (kNT only): the epilogue multiplies by act'(pre) read from `pre` [E,C,N], i.e. the product is the gradient with
+// respect to the pre-activations of a layer whose activation is ACT.
+template <int ACT, int MODE, bool GRAD>
 __global__ __launch_bounds__(kThreads) void grouped_gemm_mfma_kernel(const uint16_t* __restrict__ A,
                                                                      const uint16_t* __restrict__ B,
                                                                      const uint16_t* __restrict__ bias,
@@ -224,7 +291,11 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_mfma_kernel(const uint1
                                                                      const int32_t* __restrict__ gather, int gather_rows,
                                                                      int E, int64_t C, int K, int N, int MT, int NT,
                                                                      uint16_t* __restrict__ out,
-                                                                     unsigned long long* __restrict__ probe, int probe_blocks) {
+                                                                     unsigned long long* __restrict__ probe, int probe_blocks,
+                                                                     const int32_t* __restrict__ kfill,
+                                                                     const uint16_t* __restrict__ a_tail,
+                                                                     const uint16_t* __restrict__ b_tail,
+                                                                     const uint16_t* __restrict__ pre) {
   __shared__ __attribute__((aligned(1024))) char smem[2 * kStageBytes];
 
   // ---- which tile -------------------------------------------------------------------------------------------------
@@ -299,45 +370,73 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_mfma_kernel(const uint1
   const int wm = wave >> 1, wn = wave & 1;
 
   // ---- global sources of this lane's direct-to-LDS loads (32-bit offsets from per-expert scalar bases) -------------
-  // A: 1 KB block q*4+wave of the tile = rows 8(q*4+wave) .. +7, lane l writes row +l/8, chunk position l%8.
-  // B: 1 KB block q*4+wave = k-rows 2(q*4+wave), +1, lane l writes k-row +l/32, chunk position l%32.
+  // Row-major operand with k contiguous (A of kNN/kNT, B of kNT): 1 KB block q*4+wave of the tile = rows
+  //   8(q*4+wave) .. +7, lane l writes row +l/8, chunk position l%8.
+  // Operand with k as the slow index (B of kNN/kTN, A of kTN): 1 KB block q*4+wave = k-rows 2(q*4+wave), +1, lane l
+  //   writes k-row +l/32, chunk position l%32.
   // With `gather` (the slot -> token map [E, C] of the dispatch), A is the token matrix [gather_rows, K] itself and row r
   // of expert e's slab is token gather[e, r]: the dispatch buffer is never written or read.  Unfilled slots (-1) read
   // token 0; their output rows lie past the expert's fill and are never used.
-  const char* a_base = gather ? (const char*)A : (const char*)(A + (int64_t)e * C * K);
-  const char* b_base = (const char*)(B + (int64_t)e * K * N);
+  const char* a_base;
+  const char* b_base;
+  const char* a_last = nullptr;
+  const char* b_last = nullptr;
+  int KT = K / BK;
+  if (MODE == kTN) {                                                // A [E, K slots, C], B [E, K slots, N]
+    a_base = (const char*)(A + (int64_t)e * K * C);
+    b_base = (const char*)(B + (int64_t)e * K * N);
+    int64_t fill = K;
+    if (kfill) { const int64_t c = kfill[e]; fill = c < K ? (c > 0 ? c : 0) : K; }
+    KT = slot_ksteps(fill);
+    a_last = (const char*)(a_tail + (int64_t)e * BK * C);
+    b_last = (const char*)(b_tail + (int64_t)e * BK * N);
+  } else {
+    a_base = gather ? (const char*)A : (const char*)(A + (int64_t)e * C * K);
+    b_base = (const char*)(B + (int64_t)e * K * N);
+  }
   uint32_t a_voff[8], b_voff[8];
   int a_mask = 0;                                                   // bit q: A block q of this wave holds at least one real row
 #pragma unroll
   for (int q = 0; q < 8; ++q) {
-    if (m0 + (q * 4 + wave) * 8 < rows) a_mask |= 1 << q;
-    const int r = (q * 4 + wave) * 8 + (lane >> 3);
-    int64_t row = m0 + r;
-    row = row < C ? row : C - 1;                                    // rows past the slab are clamped (never stored)
-    if (gather) {
-      const int t = gather[(int64_t)e * C + row];
-      row = (unsigned)t < (unsigned)gather_rows ? t : 0;
-    }
+    const int r = (q * 4 + wave) * 8 + (lane >> 3);                 // row of a k-contiguous tile
     const int g = (lane & 7) ^ ((r >> 1) & 7);                      // global chunk that lands at position lane % 8
-    a_voff[q] = (uint32_t)((row * K + g * 8) * 2);
-    const int kr = (q * 4 + wave) * 2 + (lane >> 5);
+    const int kr = (q * 4 + wave) * 2 + (lane >> 5);                // k-row of a k-slow tile
     const int c = (lane & 31) ^ (4 * (kr & 3));
-    b_voff[q] = (uint32_t)(((int64_t)kr * N + n0 + c * 8) * 2);
+    if (MODE == kTN) {
+      a_mask |= 1 << q;
+      a_voff[q] = (uint32_t)(((int64_t)kr * C + m0 + c * 8) * 2);
+    } else {
+      if (m0 + (q * 4 + wave) * 8 < rows) a_mask |= 1 << q;
+      int64_t row = m0 + r;
+      row = row < C ? row : C - 1;                                  // rows past the slab are clamped (never stored)
+      if (gather) {
+        const int t = gather[(int64_t)e * C + row];
+        row = (unsigned)t < (unsigned)gather_rows ? t : 0;
+      }
+      a_voff[q] = (uint32_t)((row * K + g * 8) * 2);
+    }
+    if (MODE == kNT) b_voff[q] = (uint32_t)(((int64_t)(n0 + r) * K + g * 8) * 2);
+    else b_voff[q] = (uint32_t)(((int64_t)kr * N + n0 + c * 8) * 2);
   }
-  const int64_t a_step = (int64_t)BK * 2, b_step = (int64_t)BK * N * 2;
+  const int64_t a_step = MODE == kTN ? (int64_t)BK * C * 2 : (int64_t)BK * 2;
+  const int64_t b_step = MODE == kNT ? (int64_t)BK * 2 : (int64_t)BK * N * 2;
 
   // ---- LDS read offsets of this lane's MFMA fragments ------------------------------------------------------------
+  // direct (k-contiguous tile): row * 128, + ((2 s + kg) ^ a_swz) * 16 per sub-step s
+  // transposed (k-slow tile):   k-row * 512 + swizzled 16-byte chunk + 8-byte half, + (16 s + 4 half) * 512
   const int kg = lane >> 5;
   const int a_swz = ((lane & 31) >> 1) & 7;                         // ((row >> 1) & 7): tile-row offsets are multiples of 32
-  int a_off[4];                                                     // + ((2 s + kg) ^ a_swz) * 16
-#pragma unroll
-  for (int i = 0; i < 4; ++i) a_off[i] = (wm * 128 + i * 32 + (lane & 31)) * 128;
-  int b_off[4];                                                     // + (16 s + 4 rd) * 512
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    const int c = wn * 16 + j * 4 + ((lane >> 4) & 1) * 2 + ((lane & 3) >> 1);
+  auto direct_off = [&](int w, int t) { return (w * 128 + t * 32 + (lane & 31)) * 128; };
+  auto tr_off = [&](int w, int t) {
+    const int c = w * 16 + t * 4 + ((lane >> 4) & 1) * 2 + ((lane & 3) >> 1);
     const int swz = 4 * ((lane >> 2) & 3);                          // 4 (k & 3), k & 3 = (lane % 16) / 4
-    b_off[j] = kATileBytes + (kg * 8 + ((lane & 15) >> 2)) * 512 + ((c ^ swz) << 4) + ((lane & 1) << 3);
+    return (kg * 8 + ((lane & 15) >> 2)) * 512 + ((c ^ swz) << 4) + ((lane & 1) << 3);
+  };
+  int a_off[4], b_off[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    a_off[i] = MODE == kTN ? tr_off(wm, i) : direct_off(wm, i);
+    b_off[i] = kATileBytes + (MODE == kNT ? direct_off(wn, i) : tr_off(wn, i));
   }
   // 32-row sub-tiles of this wave that hold real rows (the last row tile of an expert is usually ragged)
   const int64_t wave_rows = rows - m0 - wm * 128;
@@ -348,15 +447,19 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_mfma_kernel(const uint1
 
   // the number of live sub-tiles is a template argument, so that the loop body of a ragged tile is as branch-free as a
   // full one's (a wave with no rows still loads its share of B and joins the barriers)
-#define MOE_TILE_LOOP(NI) tile_main_loop<NI>(smem, a_base, b_base, a_voff, b_voff, a_step, b_step, a_off, b_off, a_swz, kg, a_mask, wave, K, bias_w, acc)
+#define MOE_TILE_LOOP(NI) tile_main_loop<NI, MODE>(smem, a_base, b_base, a_last, b_last, a_voff, b_voff, a_step, b_step, a_off, b_off, a_swz, kg, a_mask, wave, KT, bias_w, acc)
   // measurement aid: shader-clock cycles and 100 MHz ticks spent in the main loop (two scalar counter reads each side)
   const unsigned long long probe_c0 = __builtin_amdgcn_s_memtime(), probe_t0 = __builtin_amdgcn_s_memrealtime();
-  switch (ni) {
-    case 4: MOE_TILE_LOOP(4); break;
-    case 3: MOE_TILE_LOOP(3); break;
-    case 2: MOE_TILE_LOOP(2); break;
-    case 1: MOE_TILE_LOOP(1); break;
-    default: MOE_TILE_LOOP(0); break;
+  if (MODE == kTN) {                                                // output rows are a weight dimension: never ragged
+    MOE_TILE_LOOP(4);
+  } else {
+    switch (ni) {
+      case 4: MOE_TILE_LOOP(4); break;
+      case 3: MOE_TILE_LOOP(3); break;
+      case 2: MOE_TILE_LOOP(2); break;
+      case 1: MOE_TILE_LOOP(1); break;
+      default: MOE_TILE_LOOP(0); break;
+    }
   }
 #undef MOE_TILE_LOOP
   if (probe && threadIdx.x == 0 && (int)blockIdx.x < probe_blocks) {
@@ -384,7 +487,7 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_mfma_kernel(const uint1
 #pragma unroll
         for (int u = 0; u < 4; ++u) v[u] = acc[i][j][4 * g + u];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) v[u] = epilogue_act<ACT>(v[u]);
+        for (int u = 0; u < 4; ++u) v[u] = epilogue_act<GRAD ? -1 : ACT>(v[u]);
         u32x2 pk;
         pk.x = pack_bf16x2(v[0], v[1]);
         pk.y = pack_bf16x2(v[2], v[3]);
@@ -398,9 +501,34 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_mfma_kernel(const uint1
   for (int it = 0; it < 32; ++it) {
     if (it * 4 >= ni * 32) break;
     const int r = it * 4 + (lane >> 4);
-    const u32x4 q = *LDS_PTR(u32x4, wtile + r * 256 + ((lane & 15) << 4));
-    if (r < live) *reinterpret_cast<u32x4*>(oute + (int64_t)r * N + (((lane & 15) ^ (r & 15)) << 3)) = q;
+    u32x4 q = *LDS_PTR(u32x4, wtile + r * 256 + ((lane & 15) << 4));
+    if (r < live) {
+      const int64_t at = (int64_t)r * N + (((lane & 15) ^ (r & 15)) << 3);
+      if (GRAD) {                                                   // times act'(pre), both factors as stored (bf16)
+        float g[8], pv[8];
+        Vec16<uint16_t>::unpack(__builtin_bit_cast(uint4, q), g);
+        Vec16<uint16_t>::unpack(*reinterpret_cast<const uint4*>(pre + (oute - out) + at), pv);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) g[u] *= epilogue_act_grad<ACT>(pv[u]);
+        q = __builtin_bit_cast(u32x4, Vec16<uint16_t>::pack(g));
+      }
+      *reinterpret_cast<u32x4*>(oute + at) = q;
+    }
   }
+}
+
+// dst[e, j, :] = src[e, 64 (KT_e - 1) + j, :] if that slot is below the expert's fill, else 0, for j < 64: the last
+// K-step of a kTN product.   src [E, C, W], dst [E, 64, W]; 16-byte pieces, one block per (expert, 4 slots).
+__global__ __launch_bounds__(256) void tail_rows_kernel(const uint4* __restrict__ src, const int32_t* __restrict__ kfill,
+                                                        int64_t C, int cpr, uint4* __restrict__ dst) {
+  const int e = blockIdx.y;
+  int64_t fill = C;
+  if (kfill) { const int64_t c = kfill[e]; fill = c < C ? (c > 0 ? c : 0) : C; }
+  const int64_t first = (int64_t)(slot_ksteps(fill) - 1) * BK;
+  const int j = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int64_t slot = first + j;
+  for (int ch = threadIdx.x & 63; ch < cpr; ch += 64)
+    dst[((int64_t)e * BK + j) * cpr + ch] = slot < fill ? src[((int64_t)e * C + slot) * cpr + ch] : make_uint4(0, 0, 0, 0);
 }
 
 bool grouped_gemm_mfma_supports(int64_t E, int64_t C, int64_t K, int64_t N, int64_t gather_rows) {
@@ -419,9 +547,9 @@ hipError_t launch_grouped_gemm_mfma(const void* A, const void* B, const void* bi
   const int64_t groups = E * ceil_div((int64_t)MT * NT, 32);                  // upper bound: every expert full
   const dim3 grid((unsigned)(ceil_div(groups, 8) * 256)), block(kThreads);    // 32 blocks per group, groups dealt to 8 XCDs
 #define MOE_LAUNCH_GEMM(ACT)                                                                                          \
-  grouped_gemm_mfma_kernel<ACT><<<grid, block, 0, s>>>((const uint16_t*)A, (const uint16_t*)B, (const uint16_t*)bias, \
-                                                       counts, gather, (int)gather_rows, (int)E, C, (int)K, (int)N,  \
-                                                       MT, NT, (uint16_t*)out, probe, probe_blocks)
+  grouped_gemm_mfma_kernel<ACT, kNN, false><<<grid, block, 0, s>>>(                                                   \
+      (const uint16_t*)A, (const uint16_t*)B, (const uint16_t*)bias, counts, gather, (int)gather_rows, (int)E, C,     \
+      (int)K, (int)N, MT, NT, (uint16_t*)out, probe, probe_blocks, nullptr, nullptr, nullptr, nullptr)
   switch (act) {
     case MOE_ACT_RELU: MOE_LAUNCH_GEMM(MOE_ACT_RELU); break;
     case MOE_ACT_GELU: MOE_LAUNCH_GEMM(MOE_ACT_GELU); break;
@@ -430,6 +558,52 @@ hipError_t launch_grouped_gemm_mfma(const void* A, const void* B, const void* bi
   }
 #undef MOE_LAUNCH_GEMM
   return hipGetLastError();
+}
+
+// out[e] = A[e] (rows_e x K) * Bt[e]^T, Bt [E, N, K]; with `pre` [E, C, N] the result is multiplied by act'(pre).
+hipError_t launch_grouped_gemm_mfma_nt(const void* A, const void* Bt, const int32_t* counts, int64_t E, int64_t C,
+                                       int64_t K, int64_t N, void* out, const void* pre, int act, hipStream_t s) {
+  const int MT = (int)ceil_div(C, BM), NT = (int)(N / BN);
+  const int64_t groups = E * ceil_div((int64_t)MT * NT, 32);
+  const dim3 grid((unsigned)(ceil_div(groups, 8) * 256)), block(kThreads);
+#define MOE_LAUNCH_GEMM(ACT, GRAD)                                                                                    \
+  grouped_gemm_mfma_kernel<ACT, kNT, GRAD><<<grid, block, 0, s>>>(                                                    \
+      (const uint16_t*)A, (const uint16_t*)Bt, nullptr, counts, nullptr, 0, (int)E, C, (int)K, (int)N, MT, NT,        \
+      (uint16_t*)out, nullptr, 0, nullptr, nullptr, nullptr, (const uint16_t*)pre)
+  if (!pre) MOE_LAUNCH_GEMM(-1, false);
+  else switch (act) {
+    case MOE_ACT_RELU: MOE_LAUNCH_GEMM(MOE_ACT_RELU, true); break;
+    case MOE_ACT_GELU: MOE_LAUNCH_GEMM(MOE_ACT_GELU, true); break;
+    default: MOE_LAUNCH_GEMM(MOE_ACT_SILU, true); break;
+  }
+#undef MOE_LAUNCH_GEMM
+  return hipGetLastError();
+}
+
+// out[e] (R x N) = At[e]^T * B[e] over the first min(kfill[e], C) of the C slots; At [E, C, R], B [E, C, N], R and N
+// multiples of 256.  a_tail [E, 64, R] and b_tail [E, 64, N] are scratch for the zero-padded last K-step.
+hipError_t launch_grouped_gemm_mfma_tn(const void* At, const void* B, const int32_t* kfill, int64_t E, int64_t C, int64_t R,
+                                       int64_t N, void* a_tail, void* b_tail, void* out, hipStream_t s) {
+  const int cprR = (int)(R / 8), cprN = (int)(N / 8);
+  tail_rows_kernel<<<dim3(BK / 4, (unsigned)E), dim3(256), 0, s>>>((const uint4*)At, kfill, C, cprR, (uint4*)a_tail);
+  tail_rows_kernel<<<dim3(BK / 4, (unsigned)E), dim3(256), 0, s>>>((const uint4*)B, kfill, C, cprN, (uint4*)b_tail);
+  hipError_t err = hipGetLastError();
+  if (err != hipSuccess) return err;
+  const int MT = (int)(R / BM), NT = (int)(N / BN);
+  const int64_t groups = E * ceil_div((int64_t)MT * NT, 32);
+  const dim3 grid((unsigned)(ceil_div(groups, 8) * 256)), block(kThreads);
+  grouped_gemm_mfma_kernel<-1, kTN, false><<<grid, block, 0, s>>>(
+      (const uint16_t*)At, (const uint16_t*)B, nullptr, nullptr, nullptr, 0, (int)E, R, (int)C, (int)N, MT, NT,
+      (uint16_t*)out, nullptr, 0, kfill, (const uint16_t*)a_tail, (const uint16_t*)b_tail, nullptr);
+  return hipGetLastError();
+}
+
+// Shapes for which the whole backward of the expert layer runs on the three layouts above.
+bool grouped_gemm_mfma_supports_backward(int64_t E, int64_t C, int64_t M, int64_t H) {
+  const int64_t W = M > H ? M : H;
+  const int64_t tiles = E * ceil_div(C > W ? C : W, BM) * (W / BN);
+  return M % BN == 0 && H % BN == 0 && E <= kMaxExperts && tiles < ((int64_t)1 << 30) &&
+         C * W * 2 < ((int64_t)1 << 32) && M * H * 2 < ((int64_t)1 << 32);
 }
 
 }  // namespace moe
