@@ -188,14 +188,17 @@ def main() -> int:
         dec_b = timed(lambda: moe.decode_backward(d_out, slabs, r["idx"], r["loc"], r["gate_w"], slot_src))
         enc_b_bytes = (R + T) * M * es + 8 * T * k                 # read each kept slot row, write [T,M]
         dec_b_bytes = (R + E * C) * M * es + (R + T) * M * es + 24 * T * k   # dY: read kept d_out rows, write all slots; dgate_w: d_out rows + kept Y rows
-        hidden = torch.empty((E, C, H), dtype=x.dtype, device="cuda")
         Zb = moe.encode(x, r["idx"], r["loc"], slot_src, E, C)
-        moe.expert_ffn(Zb, layer.W1, layer.b1, layer.W2, layer.b2, cfg.act, counts=r["counts"], hidden=hidden)
-        ffn_b = timed(lambda: moe.expert_ffn_backward(Zb, layer.W1, layer.b1, layer.W2, hidden, slabs, cfg.act, counts=r["counts"]))
+        ffn_f = timed(lambda: moe.expert_ffn_train(Zb, layer.W1, layer.b1, layer.W2, layer.b2, cfg.act, counts=r["counts"]))
+        _, hidden, pre = moe.expert_ffn_train(Zb, layer.W1, layer.b1, layer.W2, layer.b2, cfg.act, counts=r["counts"])
+        ffn_b = timed(lambda: moe.expert_ffn_backward(Zb, layer.W1, layer.b1, layer.W2, hidden, slabs, cfg.act, counts=r["counts"], pre=pre))
+        ffn_b_re = timed(lambda: moe.expert_ffn_backward(Zb, layer.W1, layer.b1, layer.W2, hidden, slabs, cfg.act, counts=r["counts"]))
         result["backward_ffn"] = {"ms": round(ffn_b, 5), "algorithmic_TFLOPs": round(4 * flop_per_gemm / (ffn_b * 1e-3) / 1e12, 1),
-                                  "note": "dZ, dW1, db1, dW2, db2; four GEMMs' worth of algorithmic flop (2*R*M*H each); the "
-                                          "time also holds the recomputed pre-activation GEMM, the bias gradients' column sums "
-                                          "and torch's allocation of workspace and outputs"}
+                                  "ms_recomputing_pre_activations": round(ffn_b_re, 5),
+                                  "training_forward_ffn_ms": round(ffn_f, 5),
+                                  "note": "dZ, dW1, db1, dW2, db2 from the pre-activations the training forward kept; four "
+                                          "GEMMs' worth of algorithmic flop (2*R*M*H each); the time also holds the bias "
+                                          "gradients' column sums and torch's allocation of workspace and outputs"}
         dgw = torch.randn((T, k), device="cuda")
         dxb = torch.empty_like(x)
         gate_b = timed(lambda: moe.gate_backward(x, layer.Wg, r["logits"], r["idx"], dgw, cfg.normalize, dx=dxb))

@@ -186,6 +186,14 @@ int moe_gate_backward(const void* x, const void* Wg, const float* logits, const 
                       int dtype, int64_t T, int64_t M, int64_t E, int k, void* ws, size_t ws_bytes, void* dx, int accumulate_dx,
                       void* dWg, float* dbias, float* dlogits, void* stream);
 
+/* moe_expert_ffn for a training step (Sec. 3.2 runs the experts' forward and backward): the same computation, which
+ * also keeps the first layer's values before the activation, pre[e] = Z[e] W1[e] + b1[e] rounded to `dtype`
+ * ([E,C,H], rows past an expert's fill untouched), for moe_expert_ffn_backward.  hidden and Y are bit-identical to
+ * moe_expert_ffn's.  Everything else as moe_expert_ffn. */
+int moe_expert_ffn_train(const void* Z, const void* W1, const void* b1, const void* W2, const void* b2, int act, int dtype,
+                         const int32_t* counts, int64_t E, int64_t C, int64_t M, int64_t H, void* pre, void* hidden, void* Y,
+                         void* stream);
+
 /* Bytes of workspace moe_expert_ffn_backward needs (recomputed pre-activations, dP, one transposed weight matrix,
  * one transposed and one row-padded activation slab).  0 on invalid arguments. */
 size_t moe_ffn_backward_workspace_bytes(int64_t E, int64_t C, int64_t M, int64_t H, int dtype);
@@ -198,11 +206,13 @@ size_t moe_ffn_backward_workspace_bytes(int64_t E, int64_t C, int64_t M, int64_t
  *   Z, dY, dZ [E,C,M]; hidden [E,C,H] = act(Z W1 + b1) as moe_expert_ffn left it; W1, dW1 [E,M,H]; W2, dW2 [E,H,M];
  *   b1 [E,H] or NULL (it enters the pre-activation); db1 [E,H]; db2 [E,M]; all in `dtype`, fp32 accumulation, each
  *   output rounded once; intermediates (pre-activations, dP) are rounded to `dtype` as well.
+ *   pre [E,C,H]: the pre-activations moe_expert_ffn_train kept, or NULL: then they are recomputed from Z, W1, b1
+ *   (one more product; the results are bit-identical either way).
  *   Any of dZ, dW1, db1, dW2, db2 may be NULL (not computed).  Rows of dZ past an expert's fill are left untouched.
  *   ws: at least moe_ffn_backward_workspace_bytes bytes, 16-byte aligned.  ReLU'(0) = 0. */
-int moe_expert_ffn_backward(const void* Z, const void* W1, const void* b1, const void* W2, const void* hidden, const void* dY,
-                            int act, int dtype, const int32_t* counts, int64_t E, int64_t C, int64_t M, int64_t H, void* ws,
-                            size_t ws_bytes, void* dZ, void* dW1, void* db1, void* dW2, void* db2, void* stream);
+int moe_expert_ffn_backward(const void* Z, const void* W1, const void* b1, const void* W2, const void* pre, const void* hidden,
+                            const void* dY, int act, int dtype, const int32_t* counts, int64_t E, int64_t C, int64_t M, int64_t H,
+                            void* ws, size_t ws_bytes, void* dZ, void* dW1, void* db1, void* dW2, void* db2, void* stream);
 
 /* Backward of fast encode (Appendix B, the differentiable fast encode and decode operators):
  *   dx[t,:] = sum over the kept choices j of dZ[idx[t,j], loc[t,j], :]   (a token with no kept choice gets +0).

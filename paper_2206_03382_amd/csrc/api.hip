@@ -10,13 +10,18 @@ hipError_t launch_grouped_gemm_generic(const void* A, const void* B, const void*
 hipError_t launch_grouped_gemm_mfma(const void* A, const void* B, const void* bias, int act, const int32_t* counts,
                                     int64_t E, int64_t C, int64_t K, int64_t N, void* out, hipStream_t s,
                                     const int32_t* gather = nullptr, int64_t gather_rows = 0,
-                                    unsigned long long* probe = nullptr, int probe_blocks = 0);
+                                    unsigned long long* probe = nullptr, int probe_blocks = 0, void* pre_out = nullptr);
 bool grouped_gemm_mfma_supports(int64_t E, int64_t C, int64_t K, int64_t N, int64_t gather_rows = 0);
 
 hipError_t launch_grouped_gemm(const void* A, const void* B, const void* bias, int act, int dtype, const int32_t* counts,
-                               int64_t E, int64_t C, int64_t K, int64_t N, void* out, hipStream_t s) {
+                               int64_t E, int64_t C, int64_t K, int64_t N, void* out, hipStream_t s, void* pre_out) {
+  if (act < 0) pre_out = nullptr;                                   // nothing to tell apart
   if (dtype == MOE_BF16 && grouped_gemm_mfma_supports(E, C, K, N))
-    return launch_grouped_gemm_mfma(A, B, bias, act, counts, E, C, K, N, out, s);
+    return launch_grouped_gemm_mfma(A, B, bias, act, counts, E, C, K, N, out, s, nullptr, 0, nullptr, 0, pre_out);
+  if (pre_out) {                                                    // the plain kernel has one output: run it twice
+    const hipError_t err = launch_grouped_gemm_generic(A, B, bias, -1, dtype, counts, E, C, K, N, pre_out, s);
+    if (err != hipSuccess) return err;
+  }
   return launch_grouped_gemm_generic(A, B, bias, act, dtype, counts, E, C, K, N, out, s);
 }
 
@@ -201,6 +206,21 @@ int moe_expert_ffn(const void* Z, const void* W1, const void* b1, const void* W2
   return MOE_OK;
 }
 
+int moe_expert_ffn_train(const void* Z, const void* W1, const void* b1, const void* W2, const void* b2, int act, int dtype,
+                         const int32_t* counts, int64_t E, int64_t C, int64_t M, int64_t H, void* pre, void* hidden, void* Y,
+                         void* stream) {
+  if (!Z || !W1 || !W2 || !pre || !hidden || !Y || !dtype_ok(dtype) || !act_ok(act) || E < 1 || C < 1 || E > 65535 || C > kMaxDim)
+    return MOE_INVALID_ARG;
+  if (int st = row_shape_status(M)) return st;
+  if (int st = row_shape_status(H)) return st;
+  if (!aligned(Z, 16) || !aligned(W1, 16) || !aligned(W2, 16) || !aligned(pre, 16) || !aligned(hidden, 16) || !aligned(Y, 16))
+    return MOE_UNSUPPORTED;
+  hipStream_t s = (hipStream_t)stream;
+  if (launch_grouped_gemm(Z, W1, b1, act, dtype, counts, E, C, M, H, hidden, s, pre) != hipSuccess) return MOE_HIP_ERROR;
+  if (launch_grouped_gemm(hidden, W2, b2, -1, dtype, counts, E, C, H, M, Y, s) != hipSuccess) return MOE_HIP_ERROR;
+  return MOE_OK;
+}
+
 int moe_expert_ffn_gather(const void* x, const int32_t* slot_src, int64_t T, const void* W1, const void* b1, const void* W2,
                           const void* b2, int act, int dtype, const int32_t* counts, int64_t E, int64_t C, int64_t M, int64_t H,
                           void* hidden, void* Y, void* stream) {
@@ -269,18 +289,18 @@ size_t moe_ffn_backward_workspace_bytes(int64_t E, int64_t C, int64_t M, int64_t
   return ffn_backward_layout(E, C, M, H, dtype).total;
 }
 
-int moe_expert_ffn_backward(const void* Z, const void* W1, const void* b1, const void* W2, const void* hidden, const void* dY,
-                            int act, int dtype, const int32_t* counts, int64_t E, int64_t C, int64_t M, int64_t H, void* ws,
-                            size_t ws_bytes, void* dZ, void* dW1, void* db1, void* dW2, void* db2, void* stream) {
+int moe_expert_ffn_backward(const void* Z, const void* W1, const void* b1, const void* W2, const void* pre, const void* hidden,
+                            const void* dY, int act, int dtype, const int32_t* counts, int64_t E, int64_t C, int64_t M, int64_t H,
+                            void* ws, size_t ws_bytes, void* dZ, void* dW1, void* db1, void* dW2, void* db2, void* stream) {
   if (!Z || !W1 || !W2 || !hidden || !dY || !ws || !dtype_ok(dtype) || !act_ok(act) || E < 1 || C < 1 || E > 65535 ||
       C > kMaxDim || (!dZ && !dW1 && !db1 && !dW2 && !db2))
     return MOE_INVALID_ARG;
   if (int st = row_shape_status(M)) return st;
   if (int st = row_shape_status(H)) return st;
-  for (const void* p : {Z, W1, W2, hidden, dY, (const void*)ws, (const void*)dZ, (const void*)dW1, (const void*)dW2})
+  for (const void* p : {Z, W1, W2, pre, hidden, dY, (const void*)ws, (const void*)dZ, (const void*)dW1, (const void*)dW2})
     if (p && !aligned(p, 16)) return MOE_UNSUPPORTED;
   if (ws_bytes < ffn_backward_layout(E, C, M, H, dtype).total) return MOE_WORKSPACE_TOO_SMALL;
-  return launch_expert_ffn_backward(Z, W1, b1, W2, hidden, dY, act, dtype, counts, E, C, M, H, ws, dZ, dW1, db1, dW2, db2,
+  return launch_expert_ffn_backward(Z, W1, b1, W2, pre, hidden, dY, act, dtype, counts, E, C, M, H, ws, dZ, dW1, db1, dW2, db2,
                                     (hipStream_t)stream) == hipSuccess ? MOE_OK : MOE_HIP_ERROR;
 }
 

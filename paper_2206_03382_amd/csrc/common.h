@@ -106,9 +106,9 @@ hipError_t launch_encode(const void* x, int dtype, const int32_t* idx, const int
 hipError_t launch_decode(const void* Y, int dtype, const int32_t* idx, const int32_t* loc, const float* gate_w,
                          int64_t T, int64_t M, int64_t E, int k, int64_t C, void* out, hipStream_t s);
 // One grouped GEMM: out[e] = epilogue(A[e] (rows_e x K) * B[e] (K x N) + bias[e]); A [E,C,K], B [E,K,N], out [E,C,N].
-// act < 0 means no activation.
+// act < 0 means no activation.  With `pre_out` [E,C,N] the values before the activation are written there as well.
 hipError_t launch_grouped_gemm(const void* A, const void* B, const void* bias, int act, int dtype, const int32_t* counts,
-                               int64_t E, int64_t C, int64_t K, int64_t N, void* out, hipStream_t s);
+                               int64_t E, int64_t C, int64_t K, int64_t N, void* out, hipStream_t s, void* pre_out = nullptr);
 
 // Matrix-core GEMM with transposed operands (ffn_mfma.hip), bf16 only; see there for the argument meaning.
 bool grouped_gemm_mfma_supports_backward(int64_t E, int64_t C, int64_t M, int64_t H);
@@ -128,9 +128,9 @@ struct FfnBackwardWorkspace {
   int64_t Cp;                                             // capacity padded to the GEMM's K step
 };
 FfnBackwardWorkspace ffn_backward_layout(int64_t E, int64_t C, int64_t M, int64_t H, int dtype);
-hipError_t launch_expert_ffn_backward(const void* Z, const void* W1, const void* b1, const void* W2, const void* hidden,
-                                      const void* dY, int act, int dtype, const int32_t* counts, int64_t E, int64_t C,
-                                      int64_t M, int64_t H, void* ws, void* dZ, void* dW1, void* db1, void* dW2, void* db2,
-                                      hipStream_t s);
+hipError_t launch_expert_ffn_backward(const void* Z, const void* W1, const void* b1, const void* W2, const void* pre,
+                                      const void* hidden, const void* dY, int act, int dtype, const int32_t* counts, int64_t E,
+                                      int64_t C, int64_t M, int64_t H, void* ws, void* dZ, void* dW1, void* db1, void* dW2,
+                                      void* db2, hipStream_t s);
 
 }  // namespace moe

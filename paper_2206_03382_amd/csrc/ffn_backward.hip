@@ -141,17 +141,18 @@ FfnBackwardWorkspace ffn_backward_layout(int64_t E, int64_t C, int64_t M, int64_
 }
 
 template <typename ET>
-static hipError_t ffn_backward_t(const void* Z, const void* W1, const void* b1, const void* W2, const void* hidden,
-                                 const void* dY, int act, int dtype, const int32_t* counts, int64_t E, int64_t C, int64_t M,
+static hipError_t ffn_backward_t(const void* Z, const void* W1, const void* b1, const void* W2, const void* saved_pre,
+                                 const void* hidden, const void* dY, int act, int dtype, const int32_t* counts, int64_t E, int64_t C, int64_t M,
                                  int64_t H, char* ws, void* dZ, void* dW1, void* db1, void* dW2, void* db2, hipStream_t s) {
   const FfnBackwardWorkspace w = ffn_backward_layout(E, C, M, H, dtype);
   const int64_t Cp = w.Cp;
   const int es = (int)sizeof(ET);
-  void *pre = ws + w.pre, *dP = ws + w.dP, *Wt = ws + w.Wt, *At = ws + w.At, *Bp = ws + w.Bp;
+  void *dP = ws + w.dP, *Wt = ws + w.Wt, *At = ws + w.At, *Bp = ws + w.Bp;
+  const void* pre = saved_pre ? saved_pre : ws + w.pre;
   hipError_t err;
 #define MOE_TRY(x) do { err = (x); if (err != hipSuccess) return err; } while (0)
-  // pre-activations, recomputed (the forward keeps only act(pre))
-  MOE_TRY(launch_grouped_gemm(Z, W1, b1, -1, dtype, counts, E, C, M, H, pre, s));
+  // pre-activations: the caller's (kept by the training forward), else recomputed
+  if (!saved_pre) MOE_TRY(launch_grouped_gemm(Z, W1, b1, -1, dtype, counts, E, C, M, H, ws + w.pre, s));
   auto colsums = [&]() -> hipError_t {
     if (db1) {
       const int cprH = (int)(H * es / 16);
@@ -208,13 +209,13 @@ static hipError_t ffn_backward_t(const void* Z, const void* W1, const void* b1, 
   return hipSuccess;
 }
 
-hipError_t launch_expert_ffn_backward(const void* Z, const void* W1, const void* b1, const void* W2, const void* hidden,
-                                      const void* dY, int act, int dtype, const int32_t* counts, int64_t E, int64_t C,
-                                      int64_t M, int64_t H, void* ws, void* dZ, void* dW1, void* db1, void* dW2, void* db2,
-                                      hipStream_t s) {
+hipError_t launch_expert_ffn_backward(const void* Z, const void* W1, const void* b1, const void* W2, const void* pre,
+                                      const void* hidden, const void* dY, int act, int dtype, const int32_t* counts, int64_t E,
+                                      int64_t C, int64_t M, int64_t H, void* ws, void* dZ, void* dW1, void* db1, void* dW2,
+                                      void* db2, hipStream_t s) {
   if (dtype == MOE_F32)
-    return ffn_backward_t<float>(Z, W1, b1, W2, hidden, dY, act, dtype, counts, E, C, M, H, (char*)ws, dZ, dW1, db1, dW2, db2, s);
-  return ffn_backward_t<uint16_t>(Z, W1, b1, W2, hidden, dY, act, dtype, counts, E, C, M, H, (char*)ws, dZ, dW1, db1, dW2, db2, s);
+    return ffn_backward_t<float>(Z, W1, b1, W2, pre, hidden, dY, act, dtype, counts, E, C, M, H, (char*)ws, dZ, dW1, db1, dW2, db2, s);
+  return ffn_backward_t<uint16_t>(Z, W1, b1, W2, pre, hidden, dY, act, dtype, counts, E, C, M, H, (char*)ws, dZ, dW1, db1, dW2, db2, s);
 }
 
 }  // namespace moe

@@ -283,7 +283,8 @@ __host__ __device__ inline int slot_ksteps(int64_t fill) { return fill > 0 ? (in
 
 // GRAD (kNT only): the epilogue multiplies by act'(pre) read from `pre` [E,C,N], i.e. the product is the gradient with
 // respect to the pre-activations of a layer whose activation is ACT.
-template <int ACT, int MODE, bool GRAD>
+// DUAL (kNN with an activation only): the values before the activation are written to `pre_out` as well.
+template <int ACT, int MODE, bool GRAD, bool DUAL = false>
 __global__ __launch_bounds__(kThreads) void grouped_gemm_mfma_kernel(const uint16_t* __restrict__ A,
                                                                      const uint16_t* __restrict__ B,
                                                                      const uint16_t* __restrict__ bias,
@@ -295,7 +296,8 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_mfma_kernel(const uint1
                                                                      const int32_t* __restrict__ kfill,
                                                                      const uint16_t* __restrict__ a_tail,
                                                                      const uint16_t* __restrict__ b_tail,
-                                                                     const uint16_t* __restrict__ pre) {
+                                                                     const uint16_t* __restrict__ pre,
+                                                                     uint16_t* __restrict__ pre_out) {
   __shared__ __attribute__((aligned(1024))) char smem[2 * kStageBytes];
 
   // ---- which tile -------------------------------------------------------------------------------------------------
@@ -474,47 +476,55 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_mfma_kernel(const uint1
   // stages and no direct load is in flight, so wave w may use the 32 KB at smem + 32 KB * w as its own
   // [128 rows][16 chunks of 8 columns]; chunk c of row r sits at position c ^ (r % 16), which makes both the 8-byte
   // writes (32 rows per instruction) and the 16-byte row-contiguous reads conflict-free.
+  // A DUAL kernel writes the tile twice: first the values before the activation (what a training step keeps for the
+  // backward pass), then the activated ones.
   char* wtile = smem + wave * 32768;
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    if (i >= ni) break;
-    const int r = i * 32 + (lane & 31);
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        float v[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) v[u] = acc[i][j][4 * g + u];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) v[u] = epilogue_act<GRAD ? -1 : ACT>(v[u]);
-        u32x2 pk;
-        pk.x = pack_bf16x2(v[0], v[1]);
-        pk.y = pack_bf16x2(v[2], v[3]);
-        *LDS_PTR(u32x2, wtile + r * 256 + (((4 * j + g) ^ (r & 15)) << 4) + 8 * kg) = pk;
-      }
-    }
-  }
-  uint16_t* oute = out + ((int64_t)e * C + m0 + wm * 128) * N + n0 + wn * 128;
+  const int64_t out_at = ((int64_t)e * C + m0 + wm * 128) * N + n0 + wn * 128;
   const int64_t live = rows - m0 - wm * 128;                        // rows of this wave's tile that exist
-#pragma unroll 8
-  for (int it = 0; it < 32; ++it) {
-    if (it * 4 >= ni * 32) break;
-    const int r = it * 4 + (lane >> 4);
-    u32x4 q = *LDS_PTR(u32x4, wtile + r * 256 + ((lane & 15) << 4));
-    if (r < live) {
-      const int64_t at = (int64_t)r * N + (((lane & 15) ^ (r & 15)) << 3);
-      if (GRAD) {                                                   // times act'(pre), both factors as stored (bf16)
-        float g[8], pv[8];
-        Vec16<uint16_t>::unpack(__builtin_bit_cast(uint4, q), g);
-        Vec16<uint16_t>::unpack(*reinterpret_cast<const uint4*>(pre + (oute - out) + at), pv);
+  auto write_tile = [&](auto raw_tag, uint16_t* dst) {
+    constexpr bool RAW = decltype(raw_tag)::value;
 #pragma unroll
-        for (int u = 0; u < 8; ++u) g[u] *= epilogue_act_grad<ACT>(pv[u]);
-        q = __builtin_bit_cast(u32x4, Vec16<uint16_t>::pack(g));
+    for (int i = 0; i < 4; ++i) {
+      if (i >= ni) break;
+      const int r = i * 32 + (lane & 31);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          float v[4];
+#pragma unroll
+          for (int u = 0; u < 4; ++u) v[u] = acc[i][j][4 * g + u];
+#pragma unroll
+          for (int u = 0; u < 4; ++u) v[u] = epilogue_act<(GRAD || RAW) ? -1 : ACT>(v[u]);
+          u32x2 pk;
+          pk.x = pack_bf16x2(v[0], v[1]);
+          pk.y = pack_bf16x2(v[2], v[3]);
+          *LDS_PTR(u32x2, wtile + r * 256 + (((4 * j + g) ^ (r & 15)) << 4) + 8 * kg) = pk;
+        }
       }
-      *reinterpret_cast<u32x4*>(oute + at) = q;
     }
-  }
+    uint16_t* oute = dst + out_at;
+#pragma unroll 8
+    for (int it = 0; it < 32; ++it) {
+      if (it * 4 >= ni * 32) break;
+      const int r = it * 4 + (lane >> 4);
+      u32x4 q = *LDS_PTR(u32x4, wtile + r * 256 + ((lane & 15) << 4));
+      if (r < live) {
+        const int64_t at = (int64_t)r * N + (((lane & 15) ^ (r & 15)) << 3);
+        if (GRAD && !RAW) {                                         // times act'(pre), both factors as stored (bf16)
+          float g[8], pv[8];
+          Vec16<uint16_t>::unpack(__builtin_bit_cast(uint4, q), g);
+          Vec16<uint16_t>::unpack(*reinterpret_cast<const uint4*>(pre + out_at + at), pv);
+#pragma unroll
+          for (int u = 0; u < 8; ++u) g[u] *= epilogue_act_grad<ACT>(pv[u]);
+          q = __builtin_bit_cast(u32x4, Vec16<uint16_t>::pack(g));
+        }
+        *reinterpret_cast<u32x4*>(oute + at) = q;
+      }
+    }
+  };
+  if (DUAL) write_tile(std::true_type{}, pre_out);
+  write_tile(std::false_type{}, out);
 }
 
 // dst[e, j, :] = src[e, 64 (KT_e - 1) + j, :] if that slot is below the expert's fill, else 0, for j < 64: the last
@@ -542,19 +552,29 @@ bool grouped_gemm_mfma_supports(int64_t E, int64_t C, int64_t K, int64_t N, int6
 
 hipError_t launch_grouped_gemm_mfma(const void* A, const void* B, const void* bias, int act, const int32_t* counts,
                                     int64_t E, int64_t C, int64_t K, int64_t N, void* out, hipStream_t s,
-                                    const int32_t* gather, int64_t gather_rows, unsigned long long* probe, int probe_blocks) {
+                                    const int32_t* gather, int64_t gather_rows, unsigned long long* probe, int probe_blocks,
+                                    void* pre_out) {
   const int MT = (int)ceil_div(C, BM), NT = (int)(N / BN);
   const int64_t groups = E * ceil_div((int64_t)MT * NT, 32);                  // upper bound: every expert full
   const dim3 grid((unsigned)(ceil_div(groups, 8) * 256)), block(kThreads);    // 32 blocks per group, groups dealt to 8 XCDs
-#define MOE_LAUNCH_GEMM(ACT)                                                                                          \
-  grouped_gemm_mfma_kernel<ACT, kNN, false><<<grid, block, 0, s>>>(                                                   \
+#define MOE_LAUNCH_GEMM(ACT, DUAL)                                                                                    \
+  grouped_gemm_mfma_kernel<ACT, kNN, false, DUAL><<<grid, block, 0, s>>>(                                             \
       (const uint16_t*)A, (const uint16_t*)B, (const uint16_t*)bias, counts, gather, (int)gather_rows, (int)E, C,     \
-      (int)K, (int)N, MT, NT, (uint16_t*)out, probe, probe_blocks, nullptr, nullptr, nullptr, nullptr)
-  switch (act) {
-    case MOE_ACT_RELU: MOE_LAUNCH_GEMM(MOE_ACT_RELU); break;
-    case MOE_ACT_GELU: MOE_LAUNCH_GEMM(MOE_ACT_GELU); break;
-    case MOE_ACT_SILU: MOE_LAUNCH_GEMM(MOE_ACT_SILU); break;
-    default: MOE_LAUNCH_GEMM(-1); break;
+      (int)K, (int)N, MT, NT, (uint16_t*)out, probe, probe_blocks, nullptr, nullptr, nullptr, nullptr,                \
+      (uint16_t*)pre_out)
+  if (pre_out && act >= 0) {
+    switch (act) {
+      case MOE_ACT_RELU: MOE_LAUNCH_GEMM(MOE_ACT_RELU, true); break;
+      case MOE_ACT_GELU: MOE_LAUNCH_GEMM(MOE_ACT_GELU, true); break;
+      default: MOE_LAUNCH_GEMM(MOE_ACT_SILU, true); break;
+    }
+  } else {
+    switch (act) {
+      case MOE_ACT_RELU: MOE_LAUNCH_GEMM(MOE_ACT_RELU, false); break;
+      case MOE_ACT_GELU: MOE_LAUNCH_GEMM(MOE_ACT_GELU, false); break;
+      case MOE_ACT_SILU: MOE_LAUNCH_GEMM(MOE_ACT_SILU, false); break;
+      default: MOE_LAUNCH_GEMM(-1, false); break;
+    }
   }
 #undef MOE_LAUNCH_GEMM
   return hipGetLastError();
@@ -569,7 +589,7 @@ hipError_t launch_grouped_gemm_mfma_nt(const void* A, const void* Bt, const int3
 #define MOE_LAUNCH_GEMM(ACT, GRAD)                                                                                    \
   grouped_gemm_mfma_kernel<ACT, kNT, GRAD><<<grid, block, 0, s>>>(                                                    \
       (const uint16_t*)A, (const uint16_t*)Bt, nullptr, counts, nullptr, 0, (int)E, C, (int)K, (int)N, MT, NT,        \
-      (uint16_t*)out, nullptr, 0, nullptr, nullptr, nullptr, (const uint16_t*)pre)
+      (uint16_t*)out, nullptr, 0, nullptr, nullptr, nullptr, (const uint16_t*)pre, nullptr)
   if (!pre) MOE_LAUNCH_GEMM(-1, false);
   else switch (act) {
     case MOE_ACT_RELU: MOE_LAUNCH_GEMM(MOE_ACT_RELU, true); break;
@@ -594,7 +614,7 @@ hipError_t launch_grouped_gemm_mfma_tn(const void* At, const void* B, const int3
   const dim3 grid((unsigned)(ceil_div(groups, 8) * 256)), block(kThreads);
   grouped_gemm_mfma_kernel<-1, kTN, false><<<grid, block, 0, s>>>(
       (const uint16_t*)At, (const uint16_t*)B, nullptr, nullptr, nullptr, 0, (int)E, R, (int)C, (int)N, MT, NT,
-      (uint16_t*)out, nullptr, 0, kfill, (const uint16_t*)a_tail, (const uint16_t*)b_tail, nullptr);
+      (uint16_t*)out, nullptr, 0, kfill, (const uint16_t*)a_tail, (const uint16_t*)b_tail, nullptr, nullptr);
   return hipGetLastError();
 }
 

@@ -45,7 +45,8 @@ SIGNATURES = {
     "moe_gate_backward_workspace_bytes": (_sz, [_i64, _i64, _i64, _i32]),
     "moe_gate_backward": (_i32, [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _i64, _i64, _i64, _i32, _vp, _sz, _vp, _i32, _vp, _vp, _vp, _vp]),
     "moe_ffn_backward_workspace_bytes": (_sz, [_i64, _i64, _i64, _i64, _i32]),
-    "moe_expert_ffn_backward": (_i32, [_vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _i64, _i64, _i64, _i64, _vp, _sz,
+    "moe_expert_ffn_train": (_i32, [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _i64, _i64, _i64, _i64, _vp, _vp, _vp, _vp]),
+    "moe_expert_ffn_backward": (_i32, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _i64, _i64, _i64, _i64, _vp, _sz,
                                        _vp, _vp, _vp, _vp, _vp, _vp]),
     "moe_encode_backward": (_i32, [_vp, _i32, _vp, _vp, _i64, _i64, _i64, _i32, _i64, _vp, _vp]),
     "moe_decode_backward": (_i32, [_vp, _vp, _i32, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _i32, _i64, _vp, _vp, _vp]),
@@ -286,9 +287,24 @@ def gate_backward(x: torch.Tensor, Wg: torch.Tensor, logits: torch.Tensor, idx: 
     return g
 
 
+def expert_ffn_train(Z: torch.Tensor, W1: torch.Tensor, b1: Optional[torch.Tensor], W2: torch.Tensor, b2: Optional[torch.Tensor],
+                     act: int, counts: Optional[torch.Tensor] = None):
+    """moe_expert_ffn that also keeps the pre-activations; returns (Y, hidden, pre)."""
+    E, C, M = Z.shape
+    H = W1.shape[2]
+    Y = torch.empty((E, C, M), dtype=Z.dtype, device=Z.device)
+    hidden = torch.empty((E, C, H), dtype=Z.dtype, device=Z.device)
+    pre = torch.empty((E, C, H), dtype=Z.dtype, device=Z.device)
+    _check(lib().moe_expert_ffn_train(_p(Z), _p(W1), _p(b1), _p(W2), _p(b2), act, _dtype_code(Z), _p(counts), E, C, M, H,
+                                      _p(pre), _p(hidden), _p(Y), _stream()), "moe_expert_ffn_train")
+    return Y, hidden, pre
+
+
 def expert_ffn_backward(Z: torch.Tensor, W1: torch.Tensor, b1: Optional[torch.Tensor], W2: torch.Tensor, hidden: torch.Tensor,
-                        dY: torch.Tensor, act: int, counts: Optional[torch.Tensor] = None) -> Dict[str, torch.Tensor]:
-    """dZ, dW1, db1, dW2, db2 of the expert layer; `hidden` is the activation buffer moe_expert_ffn filled."""
+                        dY: torch.Tensor, act: int, counts: Optional[torch.Tensor] = None,
+                        pre: Optional[torch.Tensor] = None) -> Dict[str, torch.Tensor]:
+    """dZ, dW1, db1, dW2, db2 of the expert layer; `hidden` is the activation buffer moe_expert_ffn filled, `pre` the
+    pre-activations moe_expert_ffn_train kept (recomputed when None)."""
     E, C, M = Z.shape
     H = W1.shape[2]
     code = _dtype_code(Z)
@@ -298,7 +314,7 @@ def expert_ffn_backward(Z: torch.Tensor, W1: torch.Tensor, b1: Optional[torch.Te
     ws = torch.empty((nbytes,), dtype=torch.uint8, device=Z.device)
     g = dict(dZ=torch.zeros_like(Z), dW1=torch.empty_like(W1), db1=torch.empty((E, H), dtype=Z.dtype, device=Z.device),
              dW2=torch.empty_like(W2), db2=torch.empty((E, M), dtype=Z.dtype, device=Z.device))
-    _check(lib().moe_expert_ffn_backward(_p(Z), _p(W1), _p(b1), _p(W2), _p(hidden), _p(dY), act, code, _p(counts), E, C, M, H,
+    _check(lib().moe_expert_ffn_backward(_p(Z), _p(W1), _p(b1), _p(W2), _p(pre), _p(hidden), _p(dY), act, code, _p(counts), E, C, M, H,
                                          _p(ws), ws.numel(), _p(g["dZ"]), _p(g["dW1"]), _p(g["db1"]), _p(g["dW2"]), _p(g["db2"]),
                                          _stream()), "moe_expert_ffn_backward")
     return g
@@ -333,11 +349,10 @@ def layer_forward_backward(x, Wg, gate_bias, W1, b1, W2, b2, k: int, f: float, n
     logits = gate_logits(x, Wg, gate_bias)
     r = gate_topk(logits, k, C, normalize)
     Z = encode(x, r["idx"], r["loc"], r["slot_src"], E, C)
-    hidden = torch.empty((E, C, W1.shape[2]), dtype=x.dtype, device=x.device)
-    Y = expert_ffn(Z, W1, b1, W2, b2, act, counts=r["counts"], hidden=hidden)
+    Y, hidden, pre = expert_ffn_train(Z, W1, b1, W2, b2, act, counts=r["counts"])
     out = decode(Y, r["idx"], r["loc"], r["gate_w"])
     dY, dgate_w = decode_backward(d_out, Y, r["idx"], r["loc"], r["gate_w"], r["slot_src"])
-    g = expert_ffn_backward(Z, W1, b1, W2, hidden, dY, act, counts=r["counts"])
+    g = expert_ffn_backward(Z, W1, b1, W2, hidden, dY, act, counts=r["counts"], pre=pre)
     dx = encode_backward(g["dZ"], r["idx"], r["loc"])
     gg = gate_backward(x, Wg, logits, r["idx"], dgate_w, normalize, dx=dx)
     return dict(out=out, dx=gg["dx"], dWg=gg["dWg"], dgate_bias=gg["dbias"], dW1=g["dW1"], db1=g["db1"], dW2=g["dW2"],

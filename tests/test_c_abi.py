@@ -67,6 +67,14 @@ def test_argument_validation_never_launches(moe):
     assert L.moe_encode(fake, 9, fake, fake, None, 8, 16, 4, 1, 2, fake, None) == moe.INVALID_ARG                      # dtype
     assert L.moe_encode(fake + 2, moe.BF16, fake, fake, None, 8, 16, 4, 1, 2, fake, None) == moe.UNSUPPORTED           # alignment
     assert L.moe_expert_ffn(fake, fake, None, fake, None, 5, moe.BF16, None, 4, 2, 16, 16, fake, fake, None) == moe.INVALID_ARG
+    assert L.moe_expert_ffn_train(fake, fake, None, fake, None, 0, moe.BF16, None, 4, 2, 16, 16, None, fake, fake, None) == moe.INVALID_ARG  # pre null
+    assert L.moe_expert_ffn_train(fake, fake, None, fake, None, 0, moe.BF16, None, 4, 2, 16, 12, fake, fake, fake, None) == moe.UNSUPPORTED  # H % 8
+    assert L.moe_expert_ffn_backward(fake, fake, None, fake, None, fake, fake, 0, moe.BF16, None, 4, 2, 16, 16, fake, 0,
+                                     fake, None, None, None, None, None) == moe.WORKSPACE_TOO_SMALL
+    assert L.moe_expert_ffn_backward(fake, fake, None, fake, fake + 4, fake, fake, 0, moe.BF16, None, 4, 2, 16, 16, fake, 1 << 30,
+                                     fake, None, None, None, None, None) == moe.UNSUPPORTED                            # pre misaligned
+    assert L.moe_expert_ffn_backward(fake, fake, None, fake, None, fake, fake, 0, moe.BF16, None, 4, 2, 16, 16, fake, 1 << 30,
+                                     None, None, None, None, None, None) == moe.INVALID_ARG                            # nothing asked for
     assert L.moe_decode(fake, moe.F32, fake, fake, None, 8, 16, 4, 1, 2, fake, None) == moe.INVALID_ARG               # gate_w null
     assert L.moe_dynamic_capacity(fake, 8, 4, 1, 1.25, fake, None) == moe.INVALID_ARG      # positive setting: moe_capacity
     assert L.moe_dynamic_capacity(None, 8, 4, 1, 0.0, fake, None) == moe.INVALID_ARG

@@ -316,12 +316,25 @@ def test_expert_ffn_backward(moe, dtype, E, C, M, H, act, bias, use_counts):
     Zd, W1, b1, W2, b2 = dev(Z, dtype), dev(inp["W1"], dtype), dev(inp["b1"], dtype), dev(inp["W2"], dtype), dev(inp["b2"], dtype)
     counts = None if rows is None else torch.from_numpy(rows).cuda()
     hidden = torch.empty((E, C, H), dtype=Zd.dtype, device="cuda")
-    moe.expert_ffn(Zd, W1, b1, W2, b2, act, counts=counts, hidden=hidden)
+    Y = moe.expert_ffn(Zd, W1, b1, W2, b2, act, counts=counts, hidden=hidden)
     g = moe.expert_ffn_backward(Zd, W1, b1, W2, hidden, dev(dY, dtype), act, counts=counts)
+    # the training forward keeps the pre-activations: same hidden and Y, and the same gradients as with the recompute
+    Yt, hidden_t, pre = moe.expert_ffn_train(Zd, W1, b1, W2, b2, act, counts=counts)
+    gs = moe.expert_ffn_backward(Zd, W1, b1, W2, hidden_t, dev(dY, dtype), act, counts=counts, pre=pre)
     torch.cuda.synchronize()
     live = np.zeros((E, C), dtype=bool)
     for e in range(E):
         live[e, :C if rows is None else min(max(int(rows[e]), 0), C)] = True
+    lv = torch.from_numpy(live).cuda()
+    assert torch.equal(Yt[lv], Y[lv]) and torch.equal(hidden_t[lv], hidden[lv])
+    if live.any():
+        ref_pre = np.einsum("ecm,emh->ech", Z.astype(np.float64), inp["W1"].astype(np.float64))
+        if inp["b1"] is not None:
+            ref_pre = ref_pre + inp["b1"].astype(np.float64)[:, None, :]
+        assert_close(host(pre)[live], ref_pre[live], dtype, "pre-activations")
+    for name in ("dZ", "dW1", "db1", "dW2", "db2"):
+        a, b = gs[name], g[name]
+        assert torch.equal(a[lv], b[lv]) if name == "dZ" else torch.equal(a, b), name
     if live.any():
         assert_close(host(g["dZ"])[live], ref["dZ"][live], dtype, "dZ")
     for name in ("dW1", "db1", "dW2", "db2"):
