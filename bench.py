@@ -204,6 +204,17 @@ def main() -> int:
         gate_b = timed(lambda: moe.gate_backward(x, layer.Wg, r["logits"], r["idx"], dgw, cfg.normalize, dx=dxb))
         result["backward_gate_ms"] = round(gate_b, 5)
         result["backward_total_ms"] = round(gate_b + ffn_b + enc_b + dec_b, 5)
+        # the whole training step through the two layer-level entry points (one state buffer, outputs preallocated)
+        tl = moe.TrainLayer(layer.Wg, layer.gate_bias, layer.W1, layer.b1, layer.W2, layer.b2, T=T, k=k, f=cfg.f,
+                            normalize=cfg.normalize, act=cfg.act)
+        tl.forward(x)
+        grads = tl.backward(x, d_out)
+        fwd_t = timed(lambda: tl.forward(x))
+        bwd_t = timed(lambda: tl.backward(x, d_out, grads))
+        result["training_step"] = {"forward_ms": round(fwd_t, 5), "backward_ms": round(bwd_t, 5),
+                                   "tokens_per_s": round(T / ((fwd_t + bwd_t) * 1e-3), 1),
+                                   "note": "moe_layer_forward_train + moe_layer_backward, all parameter gradients and dx"}
+        del tl, grads
         result["backward_dispatch"] = {
             "encode_backward_ms": round(enc_b, 5), "encode_backward_frac_hbm": round(enc_b_bytes / (enc_b * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
             "decode_backward_ms": round(dec_b, 5), "decode_backward_frac_hbm": round(dec_b_bytes / (dec_b * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),

@@ -252,6 +252,26 @@ int moe_layer_forward_fused(const void* x, const void* Wg, const float* gate_bia
                             int32_t* counts, float* logits, void* ws, size_t ws_bytes, void* stream,
                             void* const* stage_events);
 
+/* One training step of the layer (Sec. 3.2: forward, then the backward pass mirrors it).  moe_layer_forward_train
+ * computes what moe_layer_forward computes (`out` is bit-identical) and keeps in `state` what the backward needs:
+ * logits, routing, the dispatch buffer, the first layer's values before and after the activation, the expert outputs.
+ * moe_layer_backward then takes d_out = dLoss/d out [T,M] and the same x, weights and shape arguments, and writes
+ *   dx [T,M] (through encode and through the gate), dWg [M,E], dgate_bias [E] fp32, dW1 [E,M,H], db1 [E,H],
+ *   dW2 [E,H,M], db2 [E,M]   (any of dWg ... db2 may be NULL; dx is required),
+ * running moe_decode_backward, moe_expert_ffn_backward, moe_encode_backward and moe_gate_backward on the state's
+ * buffers.  The choice of experts, the slot assignment and dropped choices carry no gradient.
+ *   state: device memory of at least moe_layer_train_state_bytes(T, M, H, E, k, moe_capacity(T, E, k, f), dtype)
+ *   bytes, 256-byte aligned, owned by the caller; its layout is private; it must not change between the two calls.
+ *   One state serves one step at a time: two steps that overlap on different streams need two states. */
+size_t moe_layer_train_state_bytes(int64_t T, int64_t M, int64_t H, int64_t E, int k, int64_t C, int dtype);
+int moe_layer_forward_train(const void* x, const void* Wg, const float* gate_bias, const void* W1, const void* b1,
+                            const void* W2, const void* b2, int64_t T, int64_t M, int64_t H, int64_t E, int k, double f,
+                            int normalize, int act, int dtype, void* out, void* state, size_t state_bytes, void* stream);
+int moe_layer_backward(const void* x, const void* Wg, const void* W1, const void* b1, const void* W2, int64_t T, int64_t M,
+                       int64_t H, int64_t E, int k, double f, int normalize, int act, int dtype, const void* d_out, void* state,
+                       size_t state_bytes, void* dx, void* dWg, float* dgate_bias, void* dW1, void* db1, void* dW2, void* db2,
+                       void* stream);
+
 /* Thin wrappers over HIP events so that a caller without HIP headers can time on the library's stream.
  * moe_event_create stores a new hipEvent_t in *event; moe_event_elapsed_ms needs both events completed. */
 int moe_event_create(void** event);

@@ -330,6 +330,37 @@ int moe_decode_backward(const void* d_out, const void* Y, int dtype, const int32
 }  // extern "C"
 
 namespace {
+// State a training step keeps between moe_layer_forward_train and moe_layer_backward, followed by the backward's scratch.
+struct TrainState {
+  size_t logits, idx, loc, gate_w, counts, slot_src, gate_ws, Z, pre, hidden, Y;     // written by the forward
+  size_t dgate_w, dY, dZ, ffn_ws, gate_bwd_ws, total;                                // scratch of the backward
+};
+
+TrainState train_layout(int64_t T, int64_t M, int64_t H, int64_t E, int k, int64_t C, int dtype) {
+  TrainState w;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { const size_t at = off; off = align_up(off + bytes, 256); return at; };
+  const size_t es = esize(dtype);
+  w.logits = take((size_t)T * E * 4);
+  w.idx = take((size_t)T * k * 4);
+  w.loc = take((size_t)T * k * 4);
+  w.gate_w = take((size_t)T * k * 4);
+  w.counts = take((size_t)E * 4);
+  w.slot_src = take((size_t)E * C * 4);
+  w.gate_ws = take(moe_gate_workspace_bytes(T, E, k));
+  w.Z = take((size_t)E * C * M * es);
+  w.pre = take((size_t)E * C * H * es);
+  w.hidden = take((size_t)E * C * H * es);
+  w.Y = take((size_t)E * C * M * es);
+  w.dgate_w = take((size_t)T * k * 4);
+  w.dY = take((size_t)E * C * M * es);
+  w.dZ = take((size_t)E * C * M * es);
+  w.ffn_ws = take(ffn_backward_layout(E, C, M, H, dtype).total);
+  w.gate_bwd_ws = take(gate_backward_workspace_bytes(T, M, E));
+  w.total = off;
+  return w;
+}
+
 int layer_forward(const void* x, const void* Wg, const float* gate_bias, const void* W1, const void* b1, const void* W2,
                   const void* b2, int64_t T, int64_t M, int64_t H, int64_t E, int k, double f, int normalize, int act, int dtype,
                   void* out, int32_t* idx, int32_t* loc, float* gate_w, int32_t* counts, float* logits, void* ws,
@@ -399,6 +430,84 @@ int moe_layer_forward_fused(const void* x, const void* Wg, const float* gate_bia
                             void* const* stage_events) {
   return layer_forward(x, Wg, gate_bias, W1, b1, W2, b2, T, M, H, E, k, f, normalize, act, dtype, out, idx, loc, gate_w, counts,
                        logits, ws, ws_bytes, stream, stage_events, true);
+}
+
+size_t moe_layer_train_state_bytes(int64_t T, int64_t M, int64_t H, int64_t E, int k, int64_t C, int dtype) {
+  if (!dtype_ok(dtype) || gate_shape_status(T, E, k) || row_shape_status(M) || row_shape_status(H) || C < 1 || C > kMaxDim)
+    return 0;
+  return train_layout(T, M, H, E, k, C, dtype).total;
+}
+
+int moe_layer_forward_train(const void* x, const void* Wg, const float* gate_bias, const void* W1, const void* b1,
+                            const void* W2, const void* b2, int64_t T, int64_t M, int64_t H, int64_t E, int k, double f,
+                            int normalize, int act, int dtype, void* out, void* state, size_t state_bytes, void* stream) {
+  if (!x || !Wg || !W1 || !W2 || !out || !state || !dtype_ok(dtype) || !act_ok(act) || !(f > 0.0)) return MOE_INVALID_ARG;
+  if (int st = gate_shape_status(T, E, k)) return st;
+  if (int st = row_shape_status(M)) return st;
+  if (int st = row_shape_status(H)) return st;
+  const int64_t C = moe_capacity(T, E, k, f);
+  if (C < 1 || C > kMaxDim) return MOE_INVALID_ARG;
+  if (!aligned(x, 16) || !aligned(W1, 16) || !aligned(W2, 16) || !aligned(out, 16) || !aligned(state, 256)) return MOE_UNSUPPORTED;
+  const TrainState w = train_layout(T, M, H, E, k, C, dtype);
+  if (state_bytes < w.total) return MOE_WORKSPACE_TOO_SMALL;
+  char* base = (char*)state;
+  float* logits = (float*)(base + w.logits);
+  int32_t* idx = (int32_t*)(base + w.idx);
+  int32_t* loc = (int32_t*)(base + w.loc);
+  float* gw = (float*)(base + w.gate_w);
+  int32_t* counts = (int32_t*)(base + w.counts);
+  int32_t* src = (int32_t*)(base + w.slot_src);
+  hipStream_t s = (hipStream_t)stream;
+  if (launch_gate_logits(x, Wg, gate_bias, dtype, T, M, E, logits, s) != hipSuccess) return MOE_HIP_ERROR;
+  if (launch_gate_topk(logits, T, E, k, C, normalize, idx, gw, loc, counts, src, (int32_t*)(base + w.gate_ws), s) != hipSuccess)
+    return MOE_HIP_ERROR;
+  // the slabs are internal and every later stage stops at an expert's fill: no zero rows needed
+  if (launch_encode(x, dtype, idx, loc, src, T, M, E, k, C, base + w.Z, s, false) != hipSuccess) return MOE_HIP_ERROR;
+  if (launch_grouped_gemm(base + w.Z, W1, b1, act, dtype, counts, E, C, M, H, base + w.hidden, s, base + w.pre) != hipSuccess)
+    return MOE_HIP_ERROR;
+  if (launch_grouped_gemm(base + w.hidden, W2, b2, -1, dtype, counts, E, C, H, M, base + w.Y, s) != hipSuccess) return MOE_HIP_ERROR;
+  if (launch_decode(base + w.Y, dtype, idx, loc, gw, T, M, E, k, C, out, s) != hipSuccess) return MOE_HIP_ERROR;
+  return MOE_OK;
+}
+
+int moe_layer_backward(const void* x, const void* Wg, const void* W1, const void* b1, const void* W2, int64_t T, int64_t M,
+                       int64_t H, int64_t E, int k, double f, int normalize, int act, int dtype, const void* d_out, void* state,
+                       size_t state_bytes, void* dx, void* dWg, float* dgate_bias, void* dW1, void* db1, void* dW2, void* db2,
+                       void* stream) {
+  if (!x || !Wg || !W1 || !W2 || !d_out || !state || !dx || !dtype_ok(dtype) || !act_ok(act) || !(f > 0.0)) return MOE_INVALID_ARG;
+  if (int st = gate_shape_status(T, E, k)) return st;
+  if (int st = row_shape_status(M)) return st;
+  if (int st = row_shape_status(H)) return st;
+  const int64_t C = moe_capacity(T, E, k, f);
+  if (C < 1 || C > kMaxDim) return MOE_INVALID_ARG;
+  for (const void* p : {x, W1, W2, d_out, (const void*)dx, (const void*)dW1, (const void*)dW2})
+    if (p && !aligned(p, 16)) return MOE_UNSUPPORTED;
+  if (!aligned(state, 256) || T > 65535 * (int64_t)128) return MOE_UNSUPPORTED;
+  const TrainState w = train_layout(T, M, H, E, k, C, dtype);
+  if (state_bytes < w.total) return MOE_WORKSPACE_TOO_SMALL;
+  char* base = (char*)state;
+  const float* logits = (const float*)(base + w.logits);
+  const int32_t* idx = (const int32_t*)(base + w.idx);
+  const int32_t* loc = (const int32_t*)(base + w.loc);
+  const float* gw = (const float*)(base + w.gate_w);
+  const int32_t* counts = (const int32_t*)(base + w.counts);
+  const int32_t* src = (const int32_t*)(base + w.slot_src);
+  float* dgw = (float*)(base + w.dgate_w);
+  hipStream_t s = (hipStream_t)stream;
+  // decode: dY (every slot, zeros where unfilled) and the gate weights' gradient
+  if (launch_decode_backward(d_out, base + w.Y, dtype, idx, loc, gw, src, T, M, E, k, C, base + w.dY, dgw, s) != hipSuccess)
+    return MOE_HIP_ERROR;
+  // experts: dZ over the filled slots, parameter gradients
+  if (launch_expert_ffn_backward(base + w.Z, W1, b1, W2, base + w.pre, base + w.hidden, base + w.dY, act, dtype, counts, E, C, M,
+                                 H, base + w.ffn_ws, base + w.dZ, dW1, db1, dW2, db2, s) != hipSuccess)
+    return MOE_HIP_ERROR;
+  // encode: dx = sum of a token's kept slot rows of dZ (decode with unit weights)
+  if (launch_decode(base + w.dZ, dtype, idx, loc, nullptr, T, M, E, k, C, dx, s) != hipSuccess) return MOE_HIP_ERROR;
+  // gate: dx += dlogits Wg^T, dWg, dbias
+  if (launch_gate_backward(x, Wg, logits, idx, dgw, normalize, dtype, T, M, E, k, base + w.gate_bwd_ws, dx, 1, dWg, dgate_bias,
+                           nullptr, s) != hipSuccess)
+    return MOE_HIP_ERROR;
+  return MOE_OK;
 }
 
 int moe_event_create(void** event) {

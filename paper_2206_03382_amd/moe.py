@@ -54,6 +54,11 @@ SIGNATURES = {
                                        _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp, _c.POINTER(_vp)]),
     "moe_expert_ffn_clock_probe": (_i32, [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _i64, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _i32, _vp]),
     "moe_expert_ffn_gather": (_i32, [_vp, _vp, _i64, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _i64, _i64, _i64, _i64, _vp, _vp, _vp]),
+    "moe_layer_train_state_bytes": (_sz, [_i64, _i64, _i64, _i64, _i32, _i64, _i32]),
+    "moe_layer_forward_train": (_i32, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _i64, _i32, _dbl, _i32, _i32, _i32,
+                                       _vp, _vp, _sz, _vp]),
+    "moe_layer_backward": (_i32, [_vp, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _i64, _i32, _dbl, _i32, _i32, _i32, _vp, _vp, _sz,
+                                  _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
     "moe_event_create": (_i32, [_c.POINTER(_vp)]),
     "moe_event_destroy": (_i32, [_vp]),
     "moe_event_record": (_i32, [_vp, _vp]),
@@ -357,6 +362,42 @@ def layer_forward_backward(x, Wg, gate_bias, W1, b1, W2, b2, k: int, f: float, n
     gg = gate_backward(x, Wg, logits, r["idx"], dgate_w, normalize, dx=dx)
     return dict(out=out, dx=gg["dx"], dWg=gg["dWg"], dgate_bias=gg["dbias"], dW1=g["dW1"], db1=g["db1"], dW2=g["dW2"],
                 db2=g["db2"], routing=r, logits=logits)
+
+
+class TrainLayer:
+    """One MoE layer's training step through moe_layer_forward_train / moe_layer_backward; owns the state buffer."""
+
+    def __init__(self, Wg, gate_bias, W1, b1, W2, b2, T: int, k: int, f: float, normalize: int, act: int):
+        self.Wg, self.gate_bias, self.W1, self.b1, self.W2, self.b2 = Wg, gate_bias, W1, b1, W2, b2
+        self.T, self.k, self.f, self.normalize, self.act = T, k, f, int(normalize), act
+        self.E, self.M, self.H = W1.shape
+        self.C = capacity(T, self.E, k, f)
+        self.code = _dtype_code(W1)
+        nbytes = int(lib().moe_layer_train_state_bytes(T, self.M, self.H, self.E, k, self.C, self.code))
+        if nbytes == 0:
+            raise MoEError(UNSUPPORTED, "moe_layer_train_state_bytes")
+        self.state = torch.empty((nbytes,), dtype=torch.uint8, device=W1.device)
+
+    def forward(self, x: torch.Tensor) -> torch.Tensor:
+        out = torch.empty_like(x)
+        _check(lib().moe_layer_forward_train(_p(x), _p(self.Wg), _p(self.gate_bias), _p(self.W1), _p(self.b1), _p(self.W2),
+                                             _p(self.b2), self.T, self.M, self.H, self.E, self.k, self.f, self.normalize,
+                                             self.act, self.code, _p(out), _p(self.state), self.state.numel(), _stream()),
+               "moe_layer_forward_train")
+        return out
+
+    def backward(self, x: torch.Tensor, d_out: torch.Tensor, grads: Optional[Dict[str, torch.Tensor]] = None) -> Dict[str, torch.Tensor]:
+        g = grads
+        if g is None:
+            dev, dt = x.device, x.dtype
+            g = dict(dx=torch.empty_like(x), dWg=torch.empty_like(self.Wg), dgate_bias=torch.empty((self.E,), dtype=torch.float32, device=dev),
+                     dW1=torch.empty_like(self.W1), db1=torch.empty((self.E, self.H), dtype=dt, device=dev),
+                     dW2=torch.empty_like(self.W2), db2=torch.empty((self.E, self.M), dtype=dt, device=dev))
+        _check(lib().moe_layer_backward(_p(x), _p(self.Wg), _p(self.W1), _p(self.b1), _p(self.W2), self.T, self.M, self.H, self.E,
+                                        self.k, self.f, self.normalize, self.act, self.code, _p(d_out), _p(self.state),
+                                        self.state.numel(), _p(g["dx"]), _p(g["dWg"]), _p(g["dgate_bias"]), _p(g["dW1"]),
+                                        _p(g["db1"]), _p(g["dW2"]), _p(g["db2"]), _stream()), "moe_layer_backward")
+        return g
 
 
 class StageEvents:

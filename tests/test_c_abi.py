@@ -85,6 +85,16 @@ def test_argument_validation_never_launches(moe):
                                None, None, None, None, None, fake, 1 << 30, None, None) == moe.INVALID_ARG            # f <= 0
     assert L.moe_layer_forward(fake, fake, None, fake, None, fake, None, 8, 16, 16, 4, 1, 1.0, 0, 0, moe.F32, fake,
                                None, None, None, None, None, fake, 16, None, None) == moe.WORKSPACE_TOO_SMALL
+    assert L.moe_layer_train_state_bytes(8, 16, 16, 4, 1, 2, moe.F32) > 0
+    assert L.moe_layer_train_state_bytes(8, 12, 16, 4, 1, 2, moe.F32) == 0                                             # M % 8
+    assert L.moe_layer_forward_train(fake, fake, None, fake, None, fake, None, 8, 16, 16, 4, 1, 1.0, 0, 0, moe.F32, fake,
+                                     fake, 16, None) == moe.WORKSPACE_TOO_SMALL
+    assert L.moe_layer_forward_train(fake, fake, None, fake, None, fake, None, 8, 16, 16, 4, 1, 1.0, 0, 0, moe.F32, fake,
+                                     None, 1 << 30, None) == moe.INVALID_ARG                                           # no state
+    assert L.moe_layer_backward(fake, fake, fake, None, fake, 8, 16, 16, 4, 1, 1.0, 0, 0, moe.F32, fake, fake, 16,
+                                fake, None, None, None, None, None, None, None) == moe.WORKSPACE_TOO_SMALL
+    assert L.moe_layer_backward(fake, fake, fake, None, fake, 8, 16, 16, 4, 1, 1.0, 0, 0, moe.F32, fake, fake, 1 << 30,
+                                None, None, None, None, None, None, None, None) == moe.INVALID_ARG                     # dx required
 
 
 def test_missing_library_fails_loudly(moe, monkeypatch):

@@ -412,6 +412,18 @@ def test_layer_forward_backward(moe, cfg):
         assert_close(host(got[name]), ref[name], d, name)
     scale = np.abs(ref["dgate_bias"]).max()
     assert np.abs(got["dgate_bias"].cpu().numpy() - ref["dgate_bias"]).max() <= (1e-4 if d == synth.DT_F32 else 2e-2) * max(scale, 1e-30)
+    # the same step through the two layer-level entry points (one state buffer, no allocation in between): run twice
+    # on the same state; same kernels in the same order, so every result is bit-identical to the composed path
+    tl = moe.TrainLayer(dev(inp["Wg"], d), gb, dev(inp["W1"], d), dev(inp["b1"], d), dev(inp["W2"], d), dev(inp["b2"], d),
+                        T=cfg.T, k=cfg.k, f=cfg.f, normalize=cfg.normalize, act=cfg.act)
+    xd, dod = dev(inp["x"], d), dev(d_out, d)
+    for _ in range(2):
+        out2 = tl.forward(xd)
+        g2 = tl.backward(xd, dod)
+        torch.cuda.synchronize()
+        assert torch.equal(out2, got["out"])
+        for name in ("dx", "dWg", "dgate_bias", "dW1", "db1", "dW2", "db2"):
+            assert torch.equal(g2[name], got[name]), name
 
 
 # ----------------------------------------------------------------------------------------------------------------
