@@ -99,7 +99,8 @@ def main() -> int:
     elapsed = time.perf_counter() - t0
 
     ms_per_step = elapsed * 1e3 / args.steps
-    stage_ms = np.mean(np.array([e.stage_ms() for e in events]), axis=0)
+    per_step = np.array([e.stage_ms() for e in events])              # [steps, stages] from the library's own events
+    stage_ms = np.mean(per_step, axis=0)
 
     for _ in range(args.warmup):
         layer.forward(x, fuse_dispatch=True)
@@ -130,6 +131,50 @@ def main() -> int:
     stages["decode_frac_hbm"] = round(stages["decode_GBps"] / HBM_PEAK_GBS, 4)
     stages["ffn_TFLOPs_filled_rows"] = round(2 * flop_per_gemm / ((stage_ms[3] + stage_ms[4]) * 1e-3) / 1e12, 1)
 
+    # layer roofline: the stages run back to back on one stream, so their bounds add (HBM 8 TB/s for the data-movement
+    # stages, 2.5 PFLOP/s for the two GEMMs); algorithmic bytes and flop only
+    gate_bytes = T * M * es + M * E * es + 4 * T * E + (4 * T * E + 12 * T * k + 4 * E + 4 * E * C)
+    t_roof_ms = ((gate_bytes + enc_bytes + dec_bytes) / (HBM_PEAK_GBS * 1e9) + 2 * flop_per_gemm / (peak * 1e12)) * 1e3
+    step_from_events = per_step.sum(axis=1)
+
+    # an achievable streaming ceiling on this machine: a plain device copy of 256 MiB (read + write)
+    csrc = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
+    cdst = torch.empty_like(csrc)
+    for _ in range(3):
+        cdst.copy_(csrc)
+    ca, cb = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ca.record()
+    for _ in range(10):
+        cdst.copy_(csrc)
+    cb.record()
+    torch.cuda.synchronize()
+    copy_GBps = 2 * (256 << 20) * 10 / (ca.elapsed_time(cb) * 1e-3) / 1e9
+    del csrc, cdst
+    stages["copy_ceiling_GBps"] = round(copy_GBps, 1)
+    stages["encode_frac_copy_ceiling"] = round(stages["encode_GBps"] / copy_GBps, 4)
+    stages["decode_frac_copy_ceiling"] = round(stages["decode_GBps"] / copy_GBps, 4)
+
+    # cold-cache variant: three separate sets of inputs, weights and workspaces used in rotation, so that no step finds
+    # its operands in the 256 MB memory-side cache (the default loop reuses one set; caches are not flushed between steps)
+    cold_ms = None
+    if E * (M * H * 2) * es + T * M * es < (2 << 30):
+        sets = [(layer, x)]
+        for _ in range(2):
+            l2 = moe.MoELayer(layer.Wg.clone(), None if layer.gate_bias is None else layer.gate_bias.clone(), layer.W1.clone(),
+                              None if layer.b1 is None else layer.b1.clone(), layer.W2.clone(),
+                              None if layer.b2 is None else layer.b2.clone(), T=T, k=k, f=cfg.f, normalize=cfg.normalize,
+                              act=cfg.act, keep_routing=False)
+            sets.append((l2, x.clone()))
+        for i in range(6):
+            sets[i % 3][0].forward(sets[i % 3][1])
+        torch.cuda.synchronize()
+        c0 = time.perf_counter()
+        for i in range(args.steps):
+            sets[i % 3][0].forward(sets[i % 3][1])
+        torch.cuda.synchronize()
+        cold_ms = (time.perf_counter() - c0) * 1e3 / args.steps
+        del sets
+
     result = {
         "metric": "MoE layer fwd tokens/s on 1 MI355X",
         "value": round(T / (ms_per_step * 1e-3), 1),
@@ -145,6 +190,13 @@ def main() -> int:
                      "flop_per_launch": flop_per_gemm, "avg_launch_ms": round(gemm_ms, 5),
                      "traffic": MEASURED_GEMM_TRAFFIC_BYTES.get(cfg.name)},
         "stages": stages,
+        "layer_roofline": {"t_roofline_ms": round(t_roof_ms, 5), "frac": round(t_roof_ms / ms_per_step, 4),
+                           "step_ms_median": round(float(np.median(step_from_events)), 5),
+                           "step_ms_min": round(float(step_from_events.min()), 5),
+                           "cold_cache_ms_per_step": None if cold_ms is None else round(cold_ms, 5),
+                           "note": "sum over stages of max(algorithmic bytes / 8 TB/s, flop / peak); median and min over the "
+                                   "timed steps from the library's stage events; caches are not flushed between steps, the "
+                                   "cold variant rotates three sets of inputs, weights and workspaces"},
         "fused_dispatch": {"ms_per_step": round(fused_ms, 5), "value": round(T / (fused_ms * 1e-3), 1), "unit": "tokens/s",
                            "stages": {name: round(float(ms), 5) for name, ms in zip(moe.STAGE_NAMES, fused_stage_ms)}},
     }
