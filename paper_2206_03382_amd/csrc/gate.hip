@@ -402,8 +402,11 @@ hipError_t launch_gate_topk(const float* logits, int64_t T, int64_t E, int k, in
                             float* gate_w, int32_t* loc, int32_t* counts, int32_t* slot_src, int32_t* block_counts,
                             hipStream_t s, const int32_t* perm) {
   const int NB = (int)ceil_div(T, kGateTokensPerBlock);
+  // lane group per token: up to 16 experts one value per lane; from there on 16 lanes with up to 8 values each (4 tokens
+  // per wave and 4 cross-lane steps per reduction instead of 6), and a whole wave beyond 128 experts
   int G = 1;
-  while (G < E && G < 64) G <<= 1;
+  while (G < E && G < 16) G <<= 1;
+  if (E > 128) G = 64;
   const int V = (int)ceil_div(E, G);
   const size_t shmem = (size_t)k * E * sizeof(int);
   // one lane group per token: as many threads as the block's 64 tokens need, so that (up to 16 experts) every token's
