@@ -67,6 +67,7 @@ GATE_CASES = [
     (1000, 5, 3, 1.0, 1, 0.5), (1024, 8, 2, 1.25, 1, 0.0), (777, 12, 12, 0.5, 1, 0.25), (2049, 32, 1, 1.25, 0, 0.0),
     (4096, 64, 2, 1.0, 1, 0.125), (1500, 100, 5, 2.0, 1, 0.0), (3000, 128, 8, 2.0, 1, 0.0), (600, 200, 3, 1.0, 0, 0.5),
     (513, 512, 32, 1.0, 1, 0.0), (256, 16, 4, 8.0, 1, 0.0), (257, 16, 16, 0.1, 1, 1.0),
+    (500, 24, 2, 1.0, 1, 0.25), (900, 40, 3, 1.5, 1, 0.0), (700, 17, 17, 1.0, 0, 0.5),     # expert counts that leave lanes of a group partly empty
 ]
 
 
