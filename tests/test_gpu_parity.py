@@ -428,6 +428,33 @@ def test_layer_forward_backward(moe, cfg):
 
 
 # ----------------------------------------------------------------------------------------------------------------
+# the layer call allocates nothing, clears nothing by memset and never synchronises: it can be captured in a HIP graph
+# ----------------------------------------------------------------------------------------------------------------
+def test_layer_forward_in_hip_graph(moe):
+    cfg = synth.CONFIGS[1].scaled(T=1500, M=256, H=512, E=8)
+    inp = synth.make_inputs(cfg, seed=21, bias_std=0.25)
+    d = cfg.dtype
+    layer = moe.MoELayer(dev(inp["Wg"], d), None, dev(inp["W1"], d), dev(inp["b1"], d), dev(inp["W2"], d), dev(inp["b2"], d),
+                         T=cfg.T, k=cfg.k, f=cfg.f, normalize=cfg.normalize, act=cfg.act)
+    x = dev(inp["x"], d)
+    eager = layer.forward(x).clone()
+    torch.cuda.synchronize()
+    static_x = x.clone()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        static_out = layer.forward(static_x)
+    other = dev(synth.make_inputs(cfg, seed=22)["x"], d)
+    eager_other = layer.forward(other).clone()
+    for rep in range(3):                                            # replays with eager work and synchronisation in between
+        static_x.copy_(x if rep != 1 else other)
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(static_out, eager if rep != 1 else eager_other), rep
+        layer.forward(other)
+        torch.cuda.synchronize()
+
+
+# ----------------------------------------------------------------------------------------------------------------
 # dispatch fused into the first expert GEMM: same results as encode + FFN on the rows that exist
 # ----------------------------------------------------------------------------------------------------------------
 FUSED_LAYERS = [
