@@ -62,7 +62,7 @@ def main() -> int:
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures the single-GPU hot path only: run it with --gpus 1 "
-              "(this build has no cross-GPU all-to-all; see DESIGN.md, 'How it would shard').", file=sys.stderr)
+              "(this build has no cross-GPU all-to-all: the experts' exchange is not part of it).", file=sys.stderr)
         return 2
 
     import torch
@@ -218,6 +218,11 @@ def main() -> int:
         except moe.MoEError:
             pass                                                     # shapes the matrix-core kernel does not take
         del Zp
+        # what the matrix cores alone sustain at the board's power limit on random bf16 operands (about a second of
+        # register-only MFMA launches): the practical ceiling of `achieved`
+        sustained = moe.mfma_sustained_tflops(True, seconds=1.0)
+        result["roofline"]["mfma_only_sustained_TFLOPs"] = round(sustained, 1)
+        result["roofline"]["frac_of_mfma_only_sustained"] = round(achieved / sustained, 4)
 
     if args.backward:
         r = layer.routing

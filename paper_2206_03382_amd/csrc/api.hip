@@ -12,6 +12,7 @@ hipError_t launch_grouped_gemm_mfma(const void* A, const void* B, const void* bi
                                     const int32_t* gather = nullptr, int64_t gather_rows = 0,
                                     unsigned long long* probe = nullptr, int probe_blocks = 0, void* pre_out = nullptr);
 bool grouped_gemm_mfma_supports(int64_t E, int64_t C, int64_t K, int64_t N, int64_t gather_rows = 0);
+hipError_t launch_mfma_sustained_probe(int blocks, int iters, int random_operands, float* sink, hipStream_t s);
 
 hipError_t launch_grouped_gemm(const void* A, const void* B, const void* bias, int act, int dtype, const int32_t* counts,
                                int64_t E, int64_t C, int64_t K, int64_t N, void* out, hipStream_t s, void* pre_out) {
@@ -253,6 +254,12 @@ int moe_expert_ffn_clock_probe(const void* Z, const void* W1, const void* b1, co
   if (launch_grouped_gemm_mfma(hidden, W2, b2, -1, counts, E, C, H, M, Y, s, nullptr, 0, (unsigned long long*)probe2, probe_blocks) != hipSuccess)
     return MOE_HIP_ERROR;
   return MOE_OK;
+}
+
+int moe_mfma_sustained_probe(int blocks, int iters, int random_operands, float* sink, double* flop_per_launch, void* stream) {
+  if (blocks < 1 || blocks > 65536 || iters < 1 || iters > (1 << 20) || !sink) return MOE_INVALID_ARG;
+  if (flop_per_launch) *flop_per_launch = (double)blocks * 4.0 * iters * 32.0 * 2.0 * 32 * 32 * 16;
+  return launch_mfma_sustained_probe(blocks, iters, random_operands, sink, (hipStream_t)stream) == hipSuccess ? MOE_OK : MOE_HIP_ERROR;
 }
 
 int moe_decode(const void* Y, int dtype, const int32_t* idx, const int32_t* loc, const float* gate_w, int64_t T, int64_t M,

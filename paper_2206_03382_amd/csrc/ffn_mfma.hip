@@ -541,6 +541,62 @@ __global__ __launch_bounds__(256) void tail_rows_kernel(const uint4* __restrict_
     dst[((int64_t)e * BK + j) * cpr + ch] = slot < fill ? src[((int64_t)e * C + slot) * cpr + ch] : make_uint4(0, 0, 0, 0);
 }
 
+// Measurement aid: what the matrix cores alone sustain on this board.  Every wave of a full grid (one block of four
+// waves per compute unit) keeps 16 accumulator tiles in registers and issues `iters` rounds of the main loop's 32
+// MFMAs per K-slice pair on operand fragments that never change, with no memory traffic at all.  The operands are
+// random bf16 values (uniform sign and mantissa, magnitudes in [0.5, 1)) or all ones: the power a matrix core draws, and
+// with it the clock the board's power limit allows, depends on the bits that toggle.
+__device__ __forceinline__ uint32_t probe_hash(uint32_t x) {
+  x ^= x >> 16; x *= 0x7feb352du; x ^= x >> 15; x *= 0x846ca68bu; x ^= x >> 16;
+  return x;
+}
+__global__ __launch_bounds__(kThreads) void mfma_sustained_kernel(int iters, int random_operands, float* __restrict__ sink) {
+  const uint32_t tid = blockIdx.x * kThreads + threadIdx.x;
+  bf16x8 a[2][4], b[2][4];
+#pragma unroll
+  for (int p = 0; p < 2; ++p)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      u32x4 wa, wb;
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const uint32_t ha = probe_hash((tid * 64 + p * 8 + i) * 4 + u), hb = probe_hash((tid * 64 + 32 + p * 8 + i) * 4 + u);
+        wa[u] = random_operands ? (0x3f003f00u | (ha & 0x80ff80ffu)) : 0x3f803f80u;
+        wb[u] = random_operands ? (0x3f003f00u | (hb & 0x80ff80ffu)) : 0x3f803f80u;
+      }
+      a[p][i] = __builtin_bit_cast(bf16x8, wa);
+      b[p][i] = __builtin_bit_cast(bf16x8, wb);
+    }
+  f32x16 acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int p = 0; p < 2; ++p)
+#pragma unroll
+      for (int m = 0; m < 16; ++m)
+        acc[m >> 2][m & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[p][m & 3], a[p][m >> 2], acc[m >> 2][m & 3], 0, 0, 0);
+  }
+  float sum = 0.f;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) sum += acc[i][j][v];
+  if (sum == 12345.678f) sink[tid] = sum;                           // keeps the loop alive; never true in practice
+}
+
+// flop of one launch: blocks x 4 waves x iters x 32 MFMAs x 2 x 32 x 32 x 16
+hipError_t launch_mfma_sustained_probe(int blocks, int iters, int random_operands, float* sink, hipStream_t s) {
+  mfma_sustained_kernel<<<dim3((unsigned)blocks), dim3(kThreads), 0, s>>>(iters, random_operands, sink);
+  return hipGetLastError();
+}
+
 bool grouped_gemm_mfma_supports(int64_t E, int64_t C, int64_t K, int64_t N, int64_t gather_rows) {
   if (K % BK != 0 || N % BN != 0 || E > kMaxExperts) return false;
   const int64_t tiles = E * ceil_div(C, BM) * (N / BN);

@@ -59,6 +59,7 @@ SIGNATURES = {
                                        _vp, _vp, _sz, _vp]),
     "moe_layer_backward": (_i32, [_vp, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _i64, _i32, _dbl, _i32, _i32, _i32, _vp, _vp, _sz,
                                   _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
+    "moe_mfma_sustained_probe": (_i32, [_i32, _i32, _i32, _vp, _c.POINTER(_dbl), _vp]),
     "moe_event_create": (_i32, [_c.POINTER(_vp)]),
     "moe_event_destroy": (_i32, [_vp]),
     "moe_event_record": (_i32, [_vp, _vp]),
@@ -323,6 +324,31 @@ def expert_ffn_backward(Z: torch.Tensor, W1: torch.Tensor, b1: Optional[torch.Te
                                          _p(ws), ws.numel(), _p(g["dZ"]), _p(g["dW1"]), _p(g["db1"]), _p(g["dW2"]), _p(g["db2"]),
                                          _stream()), "moe_expert_ffn_backward")
     return g
+
+
+def mfma_sustained_tflops(random_operands: bool = True, seconds: float = 1.0, blocks: int = 256, iters: int = 2000) -> float:
+    """Sustained register-only MFMA rate (TFLOP/s) over about `seconds` of back-to-back launches; the last batch is timed."""
+    sink = torch.zeros((blocks * 256,), dtype=torch.float32, device="cuda")
+    flop = _dbl()
+
+    def launch():
+        _check(lib().moe_mfma_sustained_probe(blocks, iters, int(random_operands), _p(sink), ctypes.byref(flop), _stream()),
+               "moe_mfma_sustained_probe")
+
+    for _ in range(20):
+        launch()
+    torch.cuda.synchronize()
+    total, last = 0.0, 0.0
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    while total < seconds * 1e3:
+        a.record()
+        for _ in range(20):
+            launch()
+        b.record()
+        b.synchronize()
+        last = a.elapsed_time(b) / 20
+        total += last * 20
+    return flop.value / (last * 1e-3) / 1e12
 
 
 def encode_backward(dZ: torch.Tensor, idx: torch.Tensor, loc: torch.Tensor) -> torch.Tensor:

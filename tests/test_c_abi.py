@@ -75,6 +75,8 @@ def test_argument_validation_never_launches(moe):
                                      fake, None, None, None, None, None) == moe.UNSUPPORTED                            # pre misaligned
     assert L.moe_expert_ffn_backward(fake, fake, None, fake, None, fake, fake, 0, moe.BF16, None, 4, 2, 16, 16, fake, 1 << 30,
                                      None, None, None, None, None, None) == moe.INVALID_ARG                            # nothing asked for
+    assert L.moe_mfma_sustained_probe(0, 10, 1, fake, None, None) == moe.INVALID_ARG
+    assert L.moe_mfma_sustained_probe(256, 10, 1, None, None, None) == moe.INVALID_ARG
     assert L.moe_decode(fake, moe.F32, fake, fake, None, 8, 16, 4, 1, 2, fake, None) == moe.INVALID_ARG               # gate_w null
     assert L.moe_dynamic_capacity(fake, 8, 4, 1, 1.25, fake, None) == moe.INVALID_ARG      # positive setting: moe_capacity
     assert L.moe_dynamic_capacity(None, 8, 4, 1, 0.0, fake, None) == moe.INVALID_ARG
