@@ -504,22 +504,33 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_mfma_kernel(const uint1
       }
     }
     uint16_t* oute = dst + out_at;
-#pragma unroll 8
-    for (int it = 0; it < 32; ++it) {
-      if (it * 4 >= ni * 32) break;
-      const int r = it * 4 + (lane >> 4);
-      u32x4 q = *LDS_PTR(u32x4, wtile + r * 256 + ((lane & 15) << 4));
-      if (r < live) {
-        const int64_t at = (int64_t)r * N + (((lane & 15) ^ (r & 15)) << 3);
-        if (GRAD && !RAW) {                                         // times act'(pre), both factors as stored (bf16)
-          float g[8], pv[8];
-          Vec16<uint16_t>::unpack(__builtin_bit_cast(uint4, q), g);
-          Vec16<uint16_t>::unpack(*reinterpret_cast<const uint4*>(pre + out_at + at), pv);
+    for (int it0 = 0; it0 < 32; it0 += 8) {
+      if (it0 * 4 >= ni * 32) break;
+      uint4 pv8[8];
+      if (GRAD && !RAW) {                                           // this batch's pre-activations, all loads in flight at once
 #pragma unroll
-          for (int u = 0; u < 8; ++u) g[u] *= epilogue_act_grad<ACT>(pv[u]);
-          q = __builtin_bit_cast(u32x4, Vec16<uint16_t>::pack(g));
+        for (int u = 0; u < 8; ++u) {
+          const int r = (it0 + u) * 4 + (lane >> 4);
+          const int rr = r < live ? r : 0;                          // rows past the fill: any valid row, result unused
+          pv8[u] = *reinterpret_cast<const uint4*>(pre + out_at + (int64_t)rr * N + (((lane & 15) ^ (rr & 15)) << 3));
         }
-        *reinterpret_cast<u32x4*>(oute + at) = q;
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int r = (it0 + u) * 4 + (lane >> 4);
+        u32x4 q = *LDS_PTR(u32x4, wtile + r * 256 + ((lane & 15) << 4));
+        if (r < live) {
+          const int64_t at = (int64_t)r * N + (((lane & 15) ^ (r & 15)) << 3);
+          if (GRAD && !RAW) {                                       // times act'(pre), both factors as stored (bf16)
+            float g[8], pv[8];
+            Vec16<uint16_t>::unpack(__builtin_bit_cast(uint4, q), g);
+            Vec16<uint16_t>::unpack(pv8[u], pv);
+#pragma unroll
+            for (int v = 0; v < 8; ++v) g[v] *= epilogue_act_grad<ACT>(pv[v]);
+            q = __builtin_bit_cast(u32x4, Vec16<uint16_t>::pack(g));
+          }
+          *reinterpret_cast<u32x4*>(oute + at) = q;
+        }
       }
     }
   };

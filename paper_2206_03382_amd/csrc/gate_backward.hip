@@ -9,7 +9,7 @@ namespace moe {
 
 namespace {
 
-constexpr int kDwSlice = 128;                              // tokens per partial sum of dWg
+constexpr int kDwSlice = 64;                               // tokens per partial sum of dWg
 
 // One thread per token.  p = softmax(logits); g_j = p[idx_j]; gate_w = g / sum g (normalize) or g.
 __global__ __launch_bounds__(256) void gate_backward_kernel(const float* __restrict__ logits, const int32_t* __restrict__ idx,
@@ -43,69 +43,128 @@ __global__ __launch_bounds__(256) void gate_backward_kernel(const float* __restr
   }
 }
 
-// dx[t,m] = (accumulate ? dx[t,m] : 0) + sum_e dlogits[t,e] Wg[m,e].  One thread per (t, 16-byte piece of the row).
+constexpr int kDwThreads = 128;                            // threads (row pieces) per block of the dWg partial kernel
+constexpr int kDxTokens = 16;                              // tokens per block of the dx kernel
+
+// Eight consecutive entries of row `row` of Wg [M,E] starting at expert e0, as floats (0 past E).  With E a multiple of
+// the 16-byte piece the row pieces are fetched whole.
+template <typename ET>
+__device__ __forceinline__ void wg_row8(const ET* __restrict__ Wg, int64_t row, int E, int e0, bool vec, float (&out)[8]) {
+  constexpr int N = Vec16<ET>::N;
+  if (vec) {
+    const uint4* p = reinterpret_cast<const uint4*>(Wg + row * E + e0);
+#pragma unroll
+    for (int h = 0; h < 8 / N; ++h) {
+      float f[N];
+      Vec16<ET>::unpack(p[h], f);
+#pragma unroll
+      for (int i = 0; i < N; ++i) out[h * N + i] = f[i];
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) out[i] = e0 + i < E ? load_as_f32<ET>(Wg + row * E + e0 + i) : 0.f;
+  }
+}
+
+// dx[t,m] = (accumulate ? dx[t,m] : 0) + sum_e dlogits[t,e] Wg[m,e].  A thread owns one 16-byte piece of the rows (N
+// consecutive m) for kDxTokens tokens: the pieces of all its tokens are fetched at once and stay in registers while
+// its N rows of Wg pass by, 8 experts at a time; the block's dlogits go through LDS.
 template <typename ET>
 __global__ __launch_bounds__(256) void gate_dx_kernel(const float* __restrict__ dlogits, const ET* __restrict__ Wg, int64_t T,
                                                       int cpr, int E, int accumulate, uint4* __restrict__ dx) {
   constexpr int N = Vec16<ET>::N;
-  const int64_t t = blockIdx.x;
+  __shared__ float dls[kDxTokens][8];
+  const int64_t t0 = (int64_t)blockIdx.x * kDxTokens;
   const int piece = blockIdx.y * 256 + threadIdx.x;
-  if (piece >= cpr) return;
-  const float* dl = dlogits + t * E;
-  const ET* w = Wg + (int64_t)piece * N * E;                // rows piece*N .. piece*N + N-1 of Wg, E values each
-  float acc[N];
-  if (accumulate) Vec16<ET>::unpack(dx[t * cpr + piece], acc);
-  else {
+  const bool live = piece < cpr;                            // every thread joins the barriers
+  const bool vec = (E % 8) == 0 && (reinterpret_cast<uintptr_t>(Wg) & 15) == 0;
+  float acc[kDxTokens][N];
 #pragma unroll
-    for (int u = 0; u < N; ++u) acc[u] = 0.f;
+  for (int tt = 0; tt < kDxTokens; ++tt) {
+    if (live && accumulate && t0 + tt < T) Vec16<ET>::unpack(dx[(t0 + tt) * cpr + piece], acc[tt]);
+    else {
+#pragma unroll
+      for (int u = 0; u < N; ++u) acc[tt][u] = 0.f;
+    }
   }
-  if ((E % N) == 0 && (reinterpret_cast<uintptr_t>(Wg) & 15) == 0) {    // rows of Wg are whole 16-byte pieces
-    const uint4* wv = reinterpret_cast<const uint4*>(w);
-    const int rp = E / N;                                   // pieces per row
-    for (int q = 0; q < rp; ++q) {
-      float d[N];
+  for (int e0 = 0; e0 < E; e0 += 8) {
+    __syncthreads();                                        // the previous chunk's dlogits have been read
+    if (threadIdx.x < kDxTokens * 8) {
+      const int tt = threadIdx.x >> 3, i = threadIdx.x & 7;
+      dls[tt][i] = (t0 + tt < T && e0 + i < E) ? dlogits[(t0 + tt) * E + e0 + i] : 0.f;
+    }
+    __syncthreads();
+    if (live) {
+      float wr[N][8];
 #pragma unroll
-      for (int i = 0; i < N; ++i) d[i] = dl[q * N + i];
+      for (int u = 0; u < N; ++u) wg_row8<ET>(Wg, (int64_t)piece * N + u, E, e0, vec, wr[u]);
 #pragma unroll
-      for (int u = 0; u < N; ++u) {
-        float f[N];
-        Vec16<ET>::unpack(wv[u * rp + q], f);
+      for (int tt = 0; tt < kDxTokens; ++tt) {
 #pragma unroll
-        for (int i = 0; i < N; ++i) acc[u] = fmaf(d[i], f[i], acc[u]);
+        for (int u = 0; u < N; ++u)
+#pragma unroll
+          for (int i = 0; i < 8; ++i) acc[tt][u] = fmaf(dls[tt][i], wr[u][i], acc[tt][u]);
       }
     }
-  } else {
-    for (int e = 0; e < E; ++e) {
-      const float d = dl[e];
-#pragma unroll
-      for (int u = 0; u < N; ++u) acc[u] = fmaf(d, load_as_f32<ET>(w + u * E + e), acc[u]);
-    }
   }
-  dx[t * cpr + piece] = Vec16<ET>::pack(acc);
+  if (live) {
+#pragma unroll
+    for (int tt = 0; tt < kDxTokens; ++tt)
+      if (t0 + tt < T) dx[(t0 + tt) * cpr + piece] = Vec16<ET>::pack(acc[tt]);
+  }
 }
 
-// partial[s][m][e] = sum over the tokens of slice s of x[t,m] dlogits[t,e]; thread = m, 8 experts per pass.
+// partial[s][m][e] = sum over the tokens of slice s (ascending) of x[t,m] dlogits[t,e].  A thread owns one 16-byte piece
+// of the rows (N consecutive m) and 8 experts; the slice's dlogits go through LDS and the rows are fetched 16 at a time.
 template <typename ET>
-__global__ __launch_bounds__(256) void gate_dw_partial_kernel(const ET* __restrict__ x, const float* __restrict__ dlogits,
-                                                              int64_t T, int M, int E, float* __restrict__ partial) {
-  const int m = blockIdx.x * 256 + threadIdx.x;
-  const int64_t s = blockIdx.y, t0 = s * kDwSlice, t1 = (t0 + kDwSlice) < T ? (t0 + kDwSlice) : T;
+__global__ __launch_bounds__(kDwThreads) void gate_dw_partial_kernel(const uint4* __restrict__ x, const float* __restrict__ dlogits,
+                                                              int64_t T, int cpr, int E, float* __restrict__ partial) {
+  constexpr int N = Vec16<ET>::N;
+  __shared__ float dls[kDwSlice][8];
+  const int piece = blockIdx.x * kDwThreads + threadIdx.x;
+  const int64_t s = blockIdx.y, t0 = s * kDwSlice;
   const int e0 = blockIdx.z * 8;
-  if (m >= M) return;
-  float acc[8];
-#pragma unroll
-  for (int u = 0; u < 8; ++u) acc[u] = 0.f;
-#pragma unroll 4
-  for (int64_t t = t0; t < t1; ++t) {
-    const float xv = load_as_f32<ET>(x + t * M + m);
-    const float* dl = dlogits + t * E + e0;
-#pragma unroll
-    for (int u = 0; u < 8; ++u)
-      if (e0 + u < E) acc[u] = fmaf(xv, dl[u], acc[u]);
+  for (int i = threadIdx.x; i < kDwSlice * 8; i += kDwThreads) {
+    const int tt = i >> 3, ei = i & 7;
+    dls[tt][ei] = (t0 + tt < T && e0 + ei < E) ? dlogits[(t0 + tt) * E + e0 + ei] : 0.f;   // zeros past T: those rows add nothing
   }
+  __syncthreads();
+  if (piece >= cpr) return;
+  float acc[N][8];
 #pragma unroll
-  for (int u = 0; u < 8; ++u)
-    if (e0 + u < E) partial[((int64_t)s * M + m) * E + e0 + u] = acc[u];
+  for (int u = 0; u < N; ++u)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc[u][i] = 0.f;
+  for (int tb = 0; tb < kDwSlice; tb += 16) {
+    uint4 xr[16];
+#pragma unroll
+    for (int q = 0; q < 16; ++q) {
+      const int64_t t = t0 + tb + q;
+      xr[q] = x[(t < T ? t : T - 1) * cpr + piece];         // past T: a valid row, multiplied by zeros
+    }
+#pragma unroll
+    for (int q = 0; q < 16; ++q) {
+      float xv[N];
+      Vec16<ET>::unpack(xr[q], xv);
+#pragma unroll
+      for (int u = 0; u < N; ++u)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[u][i] = fmaf(xv[u], dls[tb + q][i], acc[u][i]);
+    }
+  }
+  const int64_t M = (int64_t)cpr * N;
+#pragma unroll
+  for (int u = 0; u < N; ++u) {
+    float* dst = partial + ((int64_t)s * M + (int64_t)piece * N + u) * E + e0;
+    if ((E & 7) == 0) {                                     // eight experts = 32 contiguous, aligned bytes
+      reinterpret_cast<float4*>(dst)[0] = make_float4(acc[u][0], acc[u][1], acc[u][2], acc[u][3]);
+      reinterpret_cast<float4*>(dst)[1] = make_float4(acc[u][4], acc[u][5], acc[u][6], acc[u][7]);
+    } else {
+#pragma unroll
+      for (int i = 0; i < 8; ++i)
+        if (e0 + i < E) dst[i] = acc[u][i];
+    }
+  }
 }
 
 // dWg[i] = sum over slices, in slice order, of partial[s][i]   (i over M*E)
@@ -115,17 +174,34 @@ __global__ __launch_bounds__(256) void gate_dw_reduce_kernel(const float* __rest
   const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (i >= n) return;
   float s = 0.f;
-  for (int k = 0; k < slices; ++k) s += partial[(int64_t)k * n + i];
+  int k = 0;
+  for (; k + 8 <= slices; k += 8) {                         // eight loads in flight, added in slice order
+    float v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = partial[(int64_t)(k + u) * n + i];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) s += v[u];
+  }
+  for (; k < slices; ++k) s += partial[(int64_t)k * n + i];
   store_from_f32<ET>(dWg + i, s);
 }
 
-// dbias[e] = sum_t dlogits[t,e]: one block per expert, 256 interleaved token classes summed in order, then a fixed tree.
+// dbias[e] = sum_t dlogits[t,e]: one block per expert, 256 interleaved token classes summed in ascending order (eight
+// loads in flight), then a fixed tree.
 __global__ __launch_bounds__(256) void gate_dbias_kernel(const float* __restrict__ dlogits, int64_t T, int E,
                                                          float* __restrict__ dbias) {
   __shared__ float part[256];
   const int e = blockIdx.x;
   float s = 0.f;
-  for (int64_t t = threadIdx.x; t < T; t += 256) s += dlogits[t * E + e];
+  int64_t t = threadIdx.x;
+  for (; t + 7 * 256 < T; t += 8 * 256) {
+    float v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = dlogits[(t + u * 256) * E + e];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) s += v[u];
+  }
+  for (; t < T; t += 256) s += dlogits[t * E + e];
   part[threadIdx.x] = s;
   __syncthreads();
   for (int off = 128; off >= 1; off >>= 1) {
@@ -152,13 +228,14 @@ static hipError_t gate_backward_t(const void* x, const void* Wg, const float* lo
   if ((err = hipGetLastError()) != hipSuccess) return err;
   if (dx) {
     const int cpr = (int)(M * sizeof(ET) / 16);
-    gate_dx_kernel<ET><<<dim3((unsigned)T, (unsigned)ceil_div(cpr, 256)), dim3(256), 0, s>>>(dl, (const ET*)Wg, T, cpr, (int)E, accumulate_dx, (uint4*)dx);
+    gate_dx_kernel<ET><<<dim3((unsigned)ceil_div(T, kDxTokens), (unsigned)ceil_div(cpr, 256)), dim3(256), 0, s>>>(dl, (const ET*)Wg, T, cpr, (int)E, accumulate_dx, (uint4*)dx);
     if ((err = hipGetLastError()) != hipSuccess) return err;
   }
   if (dWg) {
     const int slices = (int)ceil_div(T, kDwSlice);
-    gate_dw_partial_kernel<ET><<<dim3((unsigned)ceil_div(M, 256), (unsigned)slices, (unsigned)ceil_div(E, 8)), dim3(256), 0, s>>>(
-        (const ET*)x, dl, T, (int)M, (int)E, partial);
+    const int cprx = (int)(M * sizeof(ET) / 16);
+    gate_dw_partial_kernel<ET><<<dim3((unsigned)ceil_div(cprx, kDwThreads), (unsigned)slices, (unsigned)ceil_div(E, 8)), dim3(kDwThreads), 0, s>>>(
+        (const uint4*)x, dl, T, cprx, (int)E, partial);
     if ((err = hipGetLastError()) != hipSuccess) return err;
     const int64_t n = M * E;
     gate_dw_reduce_kernel<ET><<<dim3((unsigned)ceil_div(n, 256)), dim3(256), 0, s>>>(partial, n, slices, (ET*)dWg);
