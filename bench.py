@@ -6,6 +6,7 @@ of seeded synthetic input that is already resident in HBM.  Prints one JSON line
   value      layer forward tokens/s (T / mean step time)
   roofline   the dominant kernel (grouped bf16 MFMA GEMM of the expert FFN): algorithmic FLOP per launch divided by
              its mean launch time, measured with HIP events recorded on the library's stream inside the timed loop
+             (on every fifth timed step: the event records themselves cost stream time)
   stages     per-stage mean milliseconds and, for encode/decode, algorithmic HBM GB/s
   cpu_baseline  the CPU oracle timed on this machine's host cores on the same workload
   fused_dispatch  the same step through moe_layer_forward_fused (the first expert GEMM gathers its rows from the tokens,
@@ -80,7 +81,11 @@ def main() -> int:
     layer = moe.MoELayer(to_device(inp["Wg"], d), gate_bias, to_device(inp["W1"], d), to_device(inp["b1"], d),
                          to_device(inp["W2"], d), to_device(inp["b2"], d), T=cfg.T, k=cfg.k, f=cfg.f,
                          normalize=cfg.normalize, act=cfg.act, keep_routing=True)
-    events = [moe.StageEvents() for _ in range(args.steps)]
+    # Stage events are recorded on every `stride`-th timed step only: each of the seven records costs a few microseconds
+    # of stream time, and the steps in between run exactly as a caller without instrumentation would run them.
+    stride = 5 if args.steps >= 10 else 1
+    sampled = [i for i in range(args.steps) if i % stride == 0]
+    events = {i: moe.StageEvents() for i in sampled}
     if args.copy_calibration:
         src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").random_(0, 255)
         dst = torch.empty_like(src)
@@ -94,12 +99,12 @@ def main() -> int:
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
-        layer.forward(x, events[i])
+        layer.forward(x, events.get(i))
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
 
     ms_per_step = elapsed * 1e3 / args.steps
-    per_step = np.array([e.stage_ms() for e in events])              # [steps, stages] from the library's own events
+    per_step = np.array([events[i].stage_ms() for i in sampled])     # [sampled steps, stages] from the library's own events
     stage_ms = np.mean(per_step, axis=0)
 
     for _ in range(args.warmup):
@@ -107,11 +112,11 @@ def main() -> int:
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
-        layer.forward(x, events[i], fuse_dispatch=True)
+        layer.forward(x, events.get(i), fuse_dispatch=True)
     torch.cuda.synchronize()
     fused_ms = (time.perf_counter() - t0) * 1e3 / args.steps
-    fused_stage_ms = np.mean(np.array([e.stage_ms() for e in events]), axis=0)
-    for e in events:
+    fused_stage_ms = np.mean(np.array([events[i].stage_ms() for i in sampled]), axis=0)
+    for e in events.values():
         e.close()
     counts = layer.routing["counts"].cpu().numpy().astype(np.int64)
     C, T, M, H, E, k = layer.C, cfg.T, cfg.M, cfg.H, cfg.E, cfg.k
@@ -194,9 +199,11 @@ def main() -> int:
                            "step_ms_median": round(float(np.median(step_from_events)), 5),
                            "step_ms_min": round(float(step_from_events.min()), 5),
                            "cold_cache_ms_per_step": None if cold_ms is None else round(cold_ms, 5),
+                           "instrumented_steps": len(sampled),
                            "note": "sum over stages of max(algorithmic bytes / 8 TB/s, flop / peak); median and min over the "
-                                   "timed steps from the library's stage events; caches are not flushed between steps, the "
-                                   "cold variant rotates three sets of inputs, weights and workspaces"},
+                                   "instrumented steps (every fifth timed step records the library's stage events; they cost "
+                                   "stream time, so these are a little slower than ms_per_step); caches are not flushed between "
+                                   "steps, the cold variant rotates three sets of inputs, weights and workspaces"},
         "fused_dispatch": {"ms_per_step": round(fused_ms, 5), "value": round(T / (fused_ms * 1e-3), 1), "unit": "tokens/s",
                            "stages": {name: round(float(ms), 5) for name, ms in zip(moe.STAGE_NAMES, fused_stage_ms)}},
     }
