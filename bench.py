@@ -30,7 +30,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 FP32_VECTOR_PEAK_TFLOPS = 157.3
 # HBM bytes per grouped-GEMM launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (see profiles/), keyed by
 # workload name; None where no counter run has been recorded.
-MEASURED_GEMM_TRAFFIC_BYTES = {"mid_bf16": 563_350_661}     # profiles/bench_mid_bf16_hbm_traffic.txt
+MEASURED_GEMM_TRAFFIC_BYTES = {"mid_bf16": 563_358_861}     # profiles/bench_mid_bf16_hbm_traffic.txt
 
 
 def to_device(a, dtype_code):
