@@ -55,6 +55,20 @@ def test_workspace_sizes(moe):
     assert moe.layer_workspace_bytes(T, M, H, E, k, C, 7) == 0              # unknown dtype
 
 
+def test_layer_memory_grows_linearly_with_tokens(moe):
+    # the setting of the paper's memory table (Sec. 4.2: D = H = 4096, top-2, 2 local experts): no [T, E, C] mask exists,
+    # so the layer's workspace is linear in tokens/step where the dense formulation's grows with T^2
+    M = H = 4096
+    E = k = 2
+    sizes = []
+    for T in (4096, 8192, 16384, 32768):
+        C = moe.capacity(T, E, k, 1.0)
+        sizes.append(moe.layer_workspace_bytes(T, M, H, E, k, C, moe.BF16))
+        assert T < 16384 or sizes[-1] < T * E * C * 2                      # from 16384 tokens on, less than the dense mask alone
+    for a, b in zip(sizes, sizes[1:]):
+        assert 1.99 < b / a < 2.01
+
+
 def test_argument_validation_never_launches(moe):
     L = moe.lib()
     assert L.moe_status_string(moe.OK) == b"ok" and b"workspace" in L.moe_status_string(moe.WORKSPACE_TOO_SMALL)
