@@ -285,8 +285,7 @@ int moe_gate_backward(const void* x, const void* Wg, const float* logits, const 
     return MOE_INVALID_ARG;
   if (int st = gate_shape_status(T, E, k)) return st;
   if (int st = row_shape_status(M)) return st;
-  if (T > 65535 * (int64_t)64 || !aligned(ws, 256) || (dx && !aligned(dx, 16)) || (dWg && !aligned(x, 16)))
-    return MOE_UNSUPPORTED;                                         // one grid row per 64-token slice; rows read in 16-byte pieces
+  if (!aligned(ws, 256) || (dx && !aligned(dx, 16)) || (dWg && !aligned(x, 16))) return MOE_UNSUPPORTED;   // rows go in 16-byte pieces
   if (ws_bytes < gate_backward_workspace_bytes(T, M, E)) return MOE_WORKSPACE_TOO_SMALL;
   return launch_gate_backward(x, Wg, logits, idx, dgate_w, normalize, dtype, T, M, E, k, ws, dx, accumulate_dx, dWg, dbias, dlogits,
                               (hipStream_t)stream) == hipSuccess ? MOE_OK : MOE_HIP_ERROR;
@@ -490,7 +489,7 @@ int moe_layer_backward(const void* x, const void* Wg, const void* W1, const void
   if (C < 1 || C > kMaxDim) return MOE_INVALID_ARG;
   for (const void* p : {x, W1, W2, d_out, (const void*)dx, (const void*)dW1, (const void*)dW2})
     if (p && !aligned(p, 16)) return MOE_UNSUPPORTED;
-  if (!aligned(state, 256) || T > 65535 * (int64_t)64) return MOE_UNSUPPORTED;
+  if (!aligned(state, 256)) return MOE_UNSUPPORTED;
   const TrainState w = train_layout(T, M, H, E, k, C, dtype);
   if (state_bytes < w.total) return MOE_WORKSPACE_TOO_SMALL;
   char* base = (char*)state;

@@ -11,35 +11,58 @@ namespace {
 
 constexpr int kDwSlice = 64;                               // tokens per partial sum of dWg
 
-// One thread per token.  p = softmax(logits); g_j = p[idx_j]; gate_w = g / sum g (normalize) or g.
-__global__ __launch_bounds__(256) void gate_backward_kernel(const float* __restrict__ logits, const int32_t* __restrict__ idx,
-                                                            const float* __restrict__ dgate_w, int64_t T, int E, int k,
-                                                            int normalize, float* __restrict__ dlogits) {
-  const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (t >= T) return;
-  const float* row = logits + t * E;
-  float mx = row[0];
-  for (int e = 1; e < E; ++e) mx = fmaxf(mx, row[e]);
-  float se = 0.f;
-  for (int e = 0; e < E; ++e) se += expf(row[e] - mx);
-  const float inv = 1.0f / se;
-  const int32_t* id = idx + t * k;
-  const float* dw = dgate_w + t * k;
-  auto g_of = [&](int j) { const int e = id[j]; return ((unsigned)e < (unsigned)E) ? expf(row[e] - mx) * inv : 0.f; };
-  float S = 1.f, c1 = 0.f;
-  if (normalize) {
-    S = 0.f;
-    for (int j = 0; j < k; ++j) S += g_of(j);
-    for (int j = 0; j < k; ++j) c1 += dw[j] * (g_of(j) / S);
+constexpr int kGbTokens = 64;                              // tokens (= threads) per block of the dlogits kernel (16 for wide gates)
+
+// One thread per token.  p = softmax(logits); g_j = p[idx_j]; gate_w = g / sum g (normalize) or g.  The block's rows of
+// logits come in, and its rows of dlogits go out, through LDS (rows padded by one float) so that global accesses are
+// contiguous however many experts a row has.
+__global__ __launch_bounds__(kGbTokens) void gate_backward_kernel(const float* __restrict__ logits, const int32_t* __restrict__ idx,
+                                                                  const float* __restrict__ dgate_w, int64_t T, int E, int k,
+                                                                  int normalize, float* __restrict__ dlogits) {
+  extern __shared__ float rows[];                           // [tokens of the block][E + 1]
+  const int tb = blockDim.x;                                // tokens (= threads) per block
+  const int64_t t0 = (int64_t)blockIdx.x * tb;
+  const int nt = (int)((T - t0) < tb ? (T - t0) : tb);
+  const int ld = E + 1;
+  for (int i = threadIdx.x; i < nt * E; i += tb) rows[(i / E) * ld + i % E] = logits[t0 * E + i];
+  __syncthreads();
+  float own_mx = 0.f, own_inv = 0.f, own_c1 = 0.f, own_S = 1.f;
+  if ((int)threadIdx.x < nt) {
+    const int64_t t = t0 + threadIdx.x;
+    float* row = rows + threadIdx.x * ld;
+    float mx = row[0];
+    for (int e = 1; e < E; ++e) mx = fmaxf(mx, row[e]);
+    float se = 0.f;
+    for (int e = 0; e < E; ++e) se += expf(row[e] - mx);
+    const float inv = 1.0f / se;
+    const int32_t* id = idx + t * k;
+    const float* dw = dgate_w + t * k;
+    auto g_of = [&](int j) { const int e = id[j]; return ((unsigned)e < (unsigned)E) ? expf(row[e] - mx) * inv : 0.f; };
+    float S = 1.f, c1 = 0.f;
+    if (normalize) {
+      S = 0.f;
+      for (int j = 0; j < k; ++j) S += g_of(j);
+      for (int j = 0; j < k; ++j) c1 += dw[j] * (g_of(j) / S);
+    }
+    // dg_j = (dw_j - c1) / S;   c = sum_j g_j dg_j = sum_e p_e dp_e
+    float c = 0.f;
+    for (int j = 0; j < k; ++j) c += g_of(j) * ((dw[j] - c1) / S);
+    // every entry's -p_e c now; the chosen experts' own terms are added once the block's rows are in memory, from the
+    // logits re-read at the k chosen entries
+    for (int e = 0; e < E; ++e) row[e] = -(expf(row[e] - mx) * inv) * c;
+    own_mx = mx; own_inv = inv; own_c1 = c1; own_S = S;
   }
-  // dg_j = (dw_j - c1) / S;   c = sum_j g_j dg_j = sum_e p_e dp_e
-  float c = 0.f;
-  for (int j = 0; j < k; ++j) c += g_of(j) * ((dw[j] - c1) / S);
-  float* out = dlogits + t * E;
-  for (int e = 0; e < E; ++e) out[e] = -(expf(row[e] - mx) * inv) * c;
-  for (int j = 0; j < k; ++j) {                              // the chosen experts of a token are distinct
-    const int e = id[j];
-    if ((unsigned)e < (unsigned)E) out[e] += g_of(j) * ((dw[j] - c1) / S);
+  __syncthreads();
+  for (int i = threadIdx.x; i < nt * E; i += tb) dlogits[t0 * E + i] = rows[(i / E) * ld + i % E];
+  __syncthreads();                                          // the rows are in memory, visible to the whole block
+  if ((int)threadIdx.x < nt) {
+    const int64_t t = t0 + threadIdx.x;
+    for (int j = 0; j < k; ++j) {                            // the chosen experts of a token are distinct
+      const int e = idx[t * k + j];
+      if ((unsigned)e >= (unsigned)E) continue;
+      const float g = expf(logits[t * E + e] - own_mx) * own_inv;
+      dlogits[t * E + e] += g * ((dgate_w[t * k + j] - own_c1) / own_S);
+    }
   }
 }
 
@@ -114,54 +137,69 @@ __global__ __launch_bounds__(256) void gate_dx_kernel(const float* __restrict__ 
   }
 }
 
-// partial[s][m][e] = sum over the tokens of slice s (ascending) of x[t,m] dlogits[t,e].  A thread owns one 16-byte piece
-// of the rows (N consecutive m) and 8 experts; the slice's dlogits go through LDS and the rows are fetched 16 at a time.
-template <typename ET>
+// partial[s][m][e] = sum over the tokens of slice s (ascending) of x[t,m] dlogits[t,e], and (blocks of the first row
+// pieces) pbias[s][e] = sum over the slice of dlogits[t,e].  A thread owns one 16-byte piece of the rows (N consecutive m)
+// and EC experts; a slice is walked in runs of 64 tokens whose dlogits go through LDS, rows fetched 16 at a time.
+template <typename ET, int EC>
 __global__ __launch_bounds__(kDwThreads) void gate_dw_partial_kernel(const uint4* __restrict__ x, const float* __restrict__ dlogits,
-                                                              int64_t T, int cpr, int E, float* __restrict__ partial) {
+                                                                     int64_t T, int cpr, int E, int slice_len,
+                                                                     float* __restrict__ partial, float* __restrict__ pbias) {
   constexpr int N = Vec16<ET>::N;
-  __shared__ float dls[kDwSlice][8];
-  const int piece = blockIdx.x * kDwThreads + threadIdx.x;
-  const int64_t s = blockIdx.y, t0 = s * kDwSlice;
-  const int e0 = blockIdx.z * 8;
-  for (int i = threadIdx.x; i < kDwSlice * 8; i += kDwThreads) {
-    const int tt = i >> 3, ei = i & 7;
-    dls[tt][ei] = (t0 + tt < T && e0 + ei < E) ? dlogits[(t0 + tt) * E + e0 + ei] : 0.f;   // zeros past T: those rows add nothing
-  }
-  __syncthreads();
-  if (piece >= cpr) return;
-  float acc[N][8];
+  __shared__ float dls[kDwSlice][EC];
+  const int e0 = blockIdx.x * EC;                           // expert chunk fastest: the blocks that share rows of x run together
+  const int64_t s = blockIdx.y;
+  const int piece = blockIdx.z * kDwThreads + threadIdx.x;
+  const bool live = piece < cpr;
+  float acc[N][EC];
 #pragma unroll
   for (int u = 0; u < N; ++u)
 #pragma unroll
-    for (int i = 0; i < 8; ++i) acc[u][i] = 0.f;
-  for (int tb = 0; tb < kDwSlice; tb += 16) {
-    uint4 xr[16];
-#pragma unroll
-    for (int q = 0; q < 16; ++q) {
-      const int64_t t = t0 + tb + q;
-      xr[q] = x[(t < T ? t : T - 1) * cpr + piece];         // past T: a valid row, multiplied by zeros
+    for (int i = 0; i < EC; ++i) acc[u][i] = 0.f;
+  float bsum = 0.f;                                         // threads 0 .. EC-1 of the first piece block: column sums
+  for (int sub = 0; sub < slice_len; sub += kDwSlice) {
+    const int64_t t0 = s * slice_len + sub;
+    __syncthreads();                                        // the previous run's dlogits have been read
+    for (int i = threadIdx.x; i < kDwSlice * EC; i += kDwThreads) {
+      const int tt = i / EC, ei = i % EC;
+      dls[tt][ei] = (t0 + tt < T && e0 + ei < E) ? dlogits[(t0 + tt) * E + e0 + ei] : 0.f;   // zeros past T add nothing
     }
+    __syncthreads();
+    if (blockIdx.z == 0 && threadIdx.x < EC) {
+#pragma unroll 8
+      for (int tt = 0; tt < kDwSlice; ++tt) bsum += dls[tt][threadIdx.x];
+    }
+    if (!live || t0 >= T) continue;
+    for (int tb = 0; tb < kDwSlice; tb += 16) {
+      uint4 xr[16];
 #pragma unroll
-    for (int q = 0; q < 16; ++q) {
-      float xv[N];
-      Vec16<ET>::unpack(xr[q], xv);
+      for (int q = 0; q < 16; ++q) {
+        const int64_t t = t0 + tb + q;
+        xr[q] = x[(t < T ? t : T - 1) * cpr + piece];       // past T: a valid row, multiplied by zeros
+      }
 #pragma unroll
-      for (int u = 0; u < N; ++u)
+      for (int q = 0; q < 16; ++q) {
+        float xv[N];
+        Vec16<ET>::unpack(xr[q], xv);
 #pragma unroll
-        for (int i = 0; i < 8; ++i) acc[u][i] = fmaf(xv[u], dls[tb + q][i], acc[u][i]);
+        for (int u = 0; u < N; ++u)
+#pragma unroll
+          for (int i = 0; i < EC; ++i) acc[u][i] = fmaf(xv[u], dls[tb + q][i], acc[u][i]);
+      }
     }
   }
+  if (blockIdx.z == 0 && threadIdx.x < EC && e0 + threadIdx.x < E) pbias[s * E + e0 + threadIdx.x] = bsum;
+  if (!live) return;
   const int64_t M = (int64_t)cpr * N;
 #pragma unroll
   for (int u = 0; u < N; ++u) {
     float* dst = partial + ((int64_t)s * M + (int64_t)piece * N + u) * E + e0;
-    if ((E & 7) == 0) {                                     // eight experts = 32 contiguous, aligned bytes
-      reinterpret_cast<float4*>(dst)[0] = make_float4(acc[u][0], acc[u][1], acc[u][2], acc[u][3]);
-      reinterpret_cast<float4*>(dst)[1] = make_float4(acc[u][4], acc[u][5], acc[u][6], acc[u][7]);
+    if ((E % EC) == 0) {                                    // EC experts = EC * 4 contiguous, 16-byte aligned bytes
+#pragma unroll
+      for (int i = 0; i < EC; i += 4)
+        reinterpret_cast<float4*>(dst)[i / 4] = make_float4(acc[u][i], acc[u][i + 1], acc[u][i + 2], acc[u][i + 3]);
     } else {
 #pragma unroll
-      for (int i = 0; i < 8; ++i)
+      for (int i = 0; i < EC; ++i)
         if (e0 + i < E) dst[i] = acc[u][i];
     }
   }
@@ -186,63 +224,73 @@ __global__ __launch_bounds__(256) void gate_dw_reduce_kernel(const float* __rest
   store_from_f32<ET>(dWg + i, s);
 }
 
-// dbias[e] = sum_t dlogits[t,e]: one block per expert, 256 interleaved token classes summed in ascending order (eight
-// loads in flight), then a fixed tree.
-__global__ __launch_bounds__(256) void gate_dbias_kernel(const float* __restrict__ dlogits, int64_t T, int E,
-                                                         float* __restrict__ dbias) {
-  __shared__ float part[256];
-  const int e = blockIdx.x;
+// dbias[e] = sum over slices, in slice order, of pbias[s][e]
+__global__ __launch_bounds__(256) void gate_dbias_reduce_kernel(const float* __restrict__ pbias, int E, int slices,
+                                                                float* __restrict__ dbias) {
+  const int e = blockIdx.x * 256 + threadIdx.x;
+  if (e >= E) return;
   float s = 0.f;
-  int64_t t = threadIdx.x;
-  for (; t + 7 * 256 < T; t += 8 * 256) {
+  int k = 0;
+  for (; k + 8 <= slices; k += 8) {
     float v[8];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) v[u] = dlogits[(t + u * 256) * E + e];
+    for (int u = 0; u < 8; ++u) v[u] = pbias[(int64_t)(k + u) * E + e];
 #pragma unroll
     for (int u = 0; u < 8; ++u) s += v[u];
   }
-  for (; t < T; t += 256) s += dlogits[t * E + e];
-  part[threadIdx.x] = s;
-  __syncthreads();
-  for (int off = 128; off >= 1; off >>= 1) {
-    if (threadIdx.x < off) part[threadIdx.x] += part[threadIdx.x + off];
-    __syncthreads();
-  }
-  if (threadIdx.x == 0) dbias[e] = part[0];
+  for (; k < slices; ++k) s += pbias[(int64_t)k * E + e];
+  dbias[e] = s;
 }
+
+// Tokens per partial sum: 64 up to 16384 tokens, then as many as keep the number of slices at 256 (the partial sums
+// are written and read once, so their size is what the reduction costs).
+inline int64_t dw_slice_len(int64_t T) { return kDwSlice * (ceil_div(T, (int64_t)kDwSlice * 256) > 1 ? ceil_div(T, (int64_t)kDwSlice * 256) : 1); }
 
 }  // namespace
 
 size_t gate_backward_workspace_bytes(int64_t T, int64_t M, int64_t E) {
-  return align_up((size_t)T * E * 4, 256) + align_up((size_t)ceil_div(T, kDwSlice) * M * E * 4, 256);
+  const size_t slices = (size_t)ceil_div(T, dw_slice_len(T));
+  return align_up((size_t)T * E * 4, 256) + align_up(slices * M * E * 4, 256) + align_up(slices * E * 4, 256);
 }
 
 template <typename ET>
 static hipError_t gate_backward_t(const void* x, const void* Wg, const float* logits, const int32_t* idx, const float* dgate_w,
                                   int normalize, int64_t T, int64_t M, int64_t E, int k, char* ws, void* dx, int accumulate_dx,
                                   void* dWg, float* dbias, float* dlogits_out, hipStream_t s) {
+  const int64_t slice_len = dw_slice_len(T);
+  const int slices = (int)ceil_div(T, slice_len);
   float* dl = dlogits_out ? dlogits_out : (float*)ws;
   float* partial = (float*)(ws + align_up((size_t)T * E * 4, 256));
+  float* pbias = (float*)(ws + align_up((size_t)T * E * 4, 256) + align_up((size_t)slices * M * E * 4, 256));
   hipError_t err;
-  gate_backward_kernel<<<dim3((unsigned)ceil_div(T, 256)), dim3(256), 0, s>>>(logits, idx, dgate_w, T, (int)E, k, normalize, dl);
+  const int gb_tokens = E <= 240 ? kGbTokens : 16;              // LDS rows: at most 61 KB (gates up to 240 experts) or 33 KB
+  gate_backward_kernel<<<dim3((unsigned)ceil_div(T, gb_tokens)), dim3(gb_tokens), (size_t)gb_tokens * (E + 1) * sizeof(float), s>>>(
+      logits, idx, dgate_w, T, (int)E, k, normalize, dl);
   if ((err = hipGetLastError()) != hipSuccess) return err;
   if (dx) {
     const int cpr = (int)(M * sizeof(ET) / 16);
     gate_dx_kernel<ET><<<dim3((unsigned)ceil_div(T, kDxTokens), (unsigned)ceil_div(cpr, 256)), dim3(256), 0, s>>>(dl, (const ET*)Wg, T, cpr, (int)E, accumulate_dx, (uint4*)dx);
     if ((err = hipGetLastError()) != hipSuccess) return err;
   }
-  if (dWg) {
-    const int slices = (int)ceil_div(T, kDwSlice);
-    const int cprx = (int)(M * sizeof(ET) / 16);
-    gate_dw_partial_kernel<ET><<<dim3((unsigned)ceil_div(cprx, kDwThreads), (unsigned)slices, (unsigned)ceil_div(E, 8)), dim3(kDwThreads), 0, s>>>(
-        (const uint4*)x, dl, T, cprx, (int)E, partial);
+  if (dWg || dbias) {
+    // the partial sums serve both: one pass over x and dlogits (without dWg only the first row pieces are visited)
+    const int cprx = dWg ? (int)(M * sizeof(ET) / 16) : 0;        // no row pieces: x and the partial sums stay untouched
+    const unsigned zblocks = dWg ? (unsigned)ceil_div(cprx, kDwThreads) : 1u;
+    if (E > 8)
+      gate_dw_partial_kernel<ET, 16><<<dim3((unsigned)ceil_div(E, 16), (unsigned)slices, zblocks), dim3(kDwThreads), 0, s>>>(
+          (const uint4*)x, dl, T, cprx, (int)E, (int)slice_len, partial, pbias);
+    else
+      gate_dw_partial_kernel<ET, 8><<<dim3(1, (unsigned)slices, zblocks), dim3(kDwThreads), 0, s>>>(
+          (const uint4*)x, dl, T, cprx, (int)E, (int)slice_len, partial, pbias);
     if ((err = hipGetLastError()) != hipSuccess) return err;
+  }
+  if (dWg) {
     const int64_t n = M * E;
     gate_dw_reduce_kernel<ET><<<dim3((unsigned)ceil_div(n, 256)), dim3(256), 0, s>>>(partial, n, slices, (ET*)dWg);
     if ((err = hipGetLastError()) != hipSuccess) return err;
   }
   if (dbias) {
-    gate_dbias_kernel<<<dim3((unsigned)E), dim3(256), 0, s>>>(dl, T, (int)E, dbias);
+    gate_dbias_reduce_kernel<<<dim3((unsigned)ceil_div(E, 256)), dim3(256), 0, s>>>(pbias, (int)E, slices, dbias);
     if ((err = hipGetLastError()) != hipSuccess) return err;
   }
   return hipSuccess;
