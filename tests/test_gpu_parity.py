@@ -552,6 +552,31 @@ def test_layer_full_size(moe, cfg):
     assert np.array_equal(fused.view(np.uint32), plain.view(np.uint32)), "fused dispatch must reproduce the plain path bit for bit"
 
 
+def test_layer_backward_full_size(moe):
+    """The benchmark workload's whole training step (moe_layer_forward_train + moe_layer_backward) element by element
+    against the oracle's layer backward (about a minute of fp64 numpy)."""
+    cfg = synth.CONFIGS[1]
+    print("[backward full size] inputs and oracle", flush=True)
+    inp = synth.make_inputs(cfg, seed=0, bias_std=0.1)
+    d_out = synth.make_inputs(cfg.scaled(cfg_id=52), seed=12)["x"]
+    ref = O.moe_layer_backward(inp["x"], inp["Wg"], inp["gate_bias"], inp["W1"], inp["b1"], inp["W2"], inp["b2"],
+                               cfg.k, cfg.f, cfg.normalize, cfg.act, d_out)
+    print("[backward full size] HIP path", flush=True)
+    d = cfg.dtype
+    gb = None if inp["gate_bias"] is None else torch.from_numpy(inp["gate_bias"]).cuda()
+    tl = moe.TrainLayer(dev(inp["Wg"], d), gb, dev(inp["W1"], d), dev(inp["b1"], d), dev(inp["W2"], d), dev(inp["b2"], d),
+                        T=cfg.T, k=cfg.k, f=cfg.f, normalize=cfg.normalize, act=cfg.act)
+    xd = dev(inp["x"], d)
+    out = tl.forward(xd)
+    g = tl.backward(xd, dev(d_out, d))
+    torch.cuda.synchronize()
+    assert_close(host(out), ref["forward"]["out"], d, "out")
+    for name in ("dx", "dWg", "dW1", "db1", "dW2", "db2"):
+        assert_close(host(g[name]), ref[name], d, name)
+    scale = np.abs(ref["dgate_bias"]).max()
+    assert np.abs(g["dgate_bias"].cpu().numpy() - ref["dgate_bias"]).max() <= 2e-2 * max(scale, 1e-30)
+
+
 def test_layer_full_size_finegrained_sampled(moe):
     """T=131072, E=128, top-8: routing is checked in full; encode, FFN rows and outputs on samples the oracle
     evaluates one by one (the buffered fp64 oracle would need > 100 GB)."""
