@@ -618,3 +618,25 @@ def test_layer_full_size_finegrained_sampled(moe):
         cs = pick[pick[:, 0] == e, 1]
         want_y = O.ffn_rows(inp["x"][src[e, cs]], inp["W1"][e], None, inp["W2"][e], None, cfg.act)
         assert_close(host(Y[int(e)][torch.from_numpy(cs).cuda()]), want_y, d, f"sampled FFN rows of expert {e}")
+    # the training step at this size: the parameter gradients of two experts against the oracle's backward of those
+    # experts on their own slabs (dY of a slot = gate weight x d_out of its token; Appendix B)
+    del Z, Y, layer, out
+    torch.cuda.empty_cache()
+    print("[finegrained] training step", flush=True)
+    tl = moe.TrainLayer(dev(inp["Wg"], d), None, W1d, None, W2d, None, T=cfg.T, k=cfg.k, f=cfg.f,
+                        normalize=cfg.normalize, act=cfg.act)
+    d_out = synth.make_inputs(cfg.scaled(cfg_id=52), seed=12)["x"]
+    tl.forward(xd)
+    grads = tl.backward(xd, dev(d_out, d))
+    torch.cuda.synchronize()
+    fills = np.minimum(ref["counts"], C)
+    for e in (int(np.argmax(fills)), int(np.argmin(np.where(fills > 0, fills, C + 1)))):
+        n = int(fills[e])
+        toks = src[e, :n]
+        w = np.zeros(n)
+        for j in range(cfg.k):
+            hit = (ref["idx"][toks, j] == e) & (ref["loc"][toks, j] == np.arange(n))
+            w[hit] = ref["gate_w"][toks[hit], j]
+        want_g = O.ffn_rows_backward(inp["x"][toks], inp["W1"][e], None, inp["W2"][e], w[:, None] * d_out[toks].astype(np.float64), cfg.act)
+        for name in ("dW1", "db1", "dW2", "db2"):
+            assert_close(host(grads[name][e]), want_g[name], d, f"{name} of expert {e} ({n} slots)")
