@@ -178,8 +178,8 @@ int moe_expert_ffn_gather(const void* x, const int32_t* slot_src, int64_t T, con
 int moe_decode(const void* Y, int dtype, const int32_t* idx, const int32_t* loc, const float* gate_w,
                int64_t T, int64_t M, int64_t E, int k, int64_t C, void* out, void* stream);
 
-/* Bytes of workspace moe_gate_backward needs (dlogits [T,E] fp32 and the per-slice partial sums of dWg).  0 on
- * invalid arguments. */
+/* Bytes of workspace moe_gate_backward needs (dlogits [T,E] fp32 and the per-slice partial sums of dWg and of dbias;
+ * a slice is 64 tokens, or more so that there are at most 256 slices).  0 on invalid arguments. */
 size_t moe_gate_backward_workspace_bytes(int64_t T, int64_t M, int64_t E, int k);
 
 /* Backward of the gating function (Sec. 2.1 gate; Sec. 3.2: the backward pass mirrors the forward).  With
@@ -189,7 +189,8 @@ size_t moe_gate_backward_workspace_bytes(int64_t T, int64_t M, int64_t E, int k)
  *   dWg      = x^T dlogits;   dbias = column sums of dlogits.
  * x, dx [T,M] and Wg, dWg [M,E] in `dtype`; logits [T,E] fp32 and idx [T,k] as the forward produced them; dbias [E] and
  * dlogits [T,E] fp32.  Any of dx, dWg, dbias, dlogits may be NULL.  The choice of experts and the slot assignment carry
- * no gradient.  fp32 arithmetic, fixed summation orders.  ws: moe_gate_backward_workspace_bytes, 256-byte aligned. */
+ * no gradient.  fp32 arithmetic, fixed summation orders (within a token slice ascending, then slice by slice).
+ * ws: moe_gate_backward_workspace_bytes, 256-byte aligned; x and dx 16-byte aligned. */
 int moe_gate_backward(const void* x, const void* Wg, const float* logits, const int32_t* idx, const float* dgate_w, int normalize,
                       int dtype, int64_t T, int64_t M, int64_t E, int k, void* ws, size_t ws_bytes, void* dx, int accumulate_dx,
                       void* dWg, float* dbias, float* dlogits, void* stream);
