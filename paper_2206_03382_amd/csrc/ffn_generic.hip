@@ -29,17 +29,29 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(const ET* __restrict_
 #pragma unroll
     for (int j = 0; j < 4; ++j) acc[i][j] = 0.f;
 
-  for (int k0 = 0; k0 < K; k0 += BK) {
+  // the next K-step's operands are fetched into registers while this one is computed from LDS
+  float pa[4], pb[4];
+  auto fetch = [&](int k0) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int id = tid + i * 256;
       const int r = id / BK, kk = id % BK;                 // A tile: 64 rows x 16 k
       const int64_t row = m0 + r;
-      As[kk][r] = (row < rows && k0 + kk < K) ? load_as_f32<ET>(Ae + row * K + k0 + kk) : 0.f;
+      pa[i] = (row < rows && k0 + kk < K) ? load_as_f32<ET>(Ae + row * K + k0 + kk) : 0.f;
       const int kb = id / BN, c = id % BN;                 // B tile: 16 k x 64 cols
-      Bs[kb][c] = (k0 + kb < K && n0 + c < N) ? load_as_f32<ET>(Be + (int64_t)(k0 + kb) * N + n0 + c) : 0.f;
+      pb[i] = (k0 + kb < K && n0 + c < N) ? load_as_f32<ET>(Be + (int64_t)(k0 + kb) * N + n0 + c) : 0.f;
+    }
+  };
+  fetch(0);
+  for (int k0 = 0; k0 < K; k0 += BK) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int id = tid + i * 256;
+      As[id % BK][id / BK] = pa[i];
+      Bs[id / BN][id % BN] = pb[i];
     }
     __syncthreads();
+    if (k0 + BK < K) fetch(k0 + BK);
 #pragma unroll
     for (int kk = 0; kk < BK; ++kk) {
       float a[4], b[4];
