@@ -112,6 +112,7 @@ hipError_t launch_grouped_gemm(const void* A, const void* B, const void* bias, i
 
 // Matrix-core GEMM with transposed operands (ffn_mfma.hip), bf16 only; see there for the argument meaning.
 bool grouped_gemm_mfma_supports_backward(int64_t E, int64_t C, int64_t M, int64_t H);
+bool grouped_gemm_mfma_supports_nt(int64_t rows, int64_t K, int64_t N);
 hipError_t launch_grouped_gemm_mfma_nt(const void* A, const void* Bt, const int32_t* counts, int64_t E, int64_t C,
                                        int64_t K, int64_t N, void* out, const void* pre, int act, hipStream_t s);
 hipError_t launch_grouped_gemm_mfma_tn(const void* At, const void* B, const int32_t* kfill, int64_t E, int64_t C, int64_t R,

@@ -282,7 +282,9 @@ __device__ __forceinline__ void tile_main_loop(char* smem, const char* a_base, c
 __host__ __device__ inline int slot_ksteps(int64_t fill) { return fill > 0 ? (int)((fill + BK - 1) / BK) : 1; }
 
 // GRAD (kNT only): the epilogue multiplies by act'(pre) read from `pre` [E,C,N], i.e. the product is the gradient with
-// respect to the pre-activations of a layer whose activation is ACT.
+// respect to the pre-activations of a layer whose activation is ACT; with ACT < 0 it adds `pre` instead (a product
+// accumulated onto an existing matrix; `pre` may then be `out` itself, every element being read before it is written
+// by the same lane).
 // DUAL (kNN with an activation only): the values before the activation are written to `pre_out` as well.
 template <int ACT, int MODE, bool GRAD, bool DUAL = false>
 __global__ __launch_bounds__(kThreads) void grouped_gemm_mfma_kernel(const uint16_t* __restrict__ A,
@@ -291,12 +293,12 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_mfma_kernel(const uint1
                                                                      const int32_t* __restrict__ counts,
                                                                      const int32_t* __restrict__ gather, int gather_rows,
                                                                      int E, int64_t C, int K, int N, int MT, int NT,
-                                                                     uint16_t* __restrict__ out,
+                                                                     uint16_t* out,                 // may alias `pre`
                                                                      unsigned long long* __restrict__ probe, int probe_blocks,
                                                                      const int32_t* __restrict__ kfill,
                                                                      const uint16_t* __restrict__ a_tail,
                                                                      const uint16_t* __restrict__ b_tail,
-                                                                     const uint16_t* __restrict__ pre,
+                                                                     const uint16_t* pre,
                                                                      uint16_t* __restrict__ pre_out) {
   __shared__ __attribute__((aligned(1024))) char smem[2 * kStageBytes];
 
@@ -521,12 +523,12 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_mfma_kernel(const uint1
         u32x4 q = *LDS_PTR(u32x4, wtile + r * 256 + ((lane & 15) << 4));
         if (r < live) {
           const int64_t at = (int64_t)r * N + (((lane & 15) ^ (r & 15)) << 3);
-          if (GRAD && !RAW) {                                       // times act'(pre), both factors as stored (bf16)
+          if (GRAD && !RAW) {                                       // times act'(pre), both factors as stored (bf16); or plus `pre`
             float g[8], pv[8];
             Vec16<uint16_t>::unpack(__builtin_bit_cast(uint4, q), g);
             Vec16<uint16_t>::unpack(pv8[u], pv);
 #pragma unroll
-            for (int v = 0; v < 8; ++v) g[v] *= epilogue_act_grad<ACT>(pv[v]);
+            for (int v = 0; v < 8; ++v) g[v] = ACT < 0 ? g[v] + pv[v] : g[v] * epilogue_act_grad<ACT>(pv[v]);
             q = __builtin_bit_cast(u32x4, Vec16<uint16_t>::pack(g));
           }
           *reinterpret_cast<u32x4*>(oute + at) = q;
@@ -647,7 +649,8 @@ hipError_t launch_grouped_gemm_mfma(const void* A, const void* B, const void* bi
   return hipGetLastError();
 }
 
-// out[e] = A[e] (rows_e x K) * Bt[e]^T, Bt [E, N, K]; with `pre` [E, C, N] the result is multiplied by act'(pre).
+// out[e] = A[e] (rows_e x K) * Bt[e]^T, Bt [E, N, K]; with `pre` [E, C, N] the result is multiplied by act'(pre), or,
+// with act < 0, has `pre` added (pre == out accumulates in place).
 hipError_t launch_grouped_gemm_mfma_nt(const void* A, const void* Bt, const int32_t* counts, int64_t E, int64_t C,
                                        int64_t K, int64_t N, void* out, const void* pre, int act, hipStream_t s) {
   const int MT = (int)ceil_div(C, BM), NT = (int)(N / BN);
@@ -658,6 +661,7 @@ hipError_t launch_grouped_gemm_mfma_nt(const void* A, const void* Bt, const int3
       (const uint16_t*)A, (const uint16_t*)Bt, nullptr, counts, nullptr, 0, (int)E, C, (int)K, (int)N, MT, NT,        \
       (uint16_t*)out, nullptr, 0, nullptr, nullptr, nullptr, (const uint16_t*)pre, nullptr)
   if (!pre) MOE_LAUNCH_GEMM(-1, false);
+  else if (act < 0) MOE_LAUNCH_GEMM(-1, true);                      // out = product + pre
   else switch (act) {
     case MOE_ACT_RELU: MOE_LAUNCH_GEMM(MOE_ACT_RELU, true); break;
     case MOE_ACT_GELU: MOE_LAUNCH_GEMM(MOE_ACT_GELU, true); break;
@@ -683,6 +687,11 @@ hipError_t launch_grouped_gemm_mfma_tn(const void* At, const void* B, const int3
       (const uint16_t*)At, (const uint16_t*)B, nullptr, nullptr, nullptr, 0, (int)E, R, (int)C, (int)N, MT, NT,
       (uint16_t*)out, nullptr, 0, kfill, (const uint16_t*)a_tail, (const uint16_t*)b_tail, nullptr, nullptr);
   return hipGetLastError();
+}
+
+// One [rows, K] x [N, K]^T product (a single "expert"): shapes the kNT layout takes.
+bool grouped_gemm_mfma_supports_nt(int64_t rows, int64_t K, int64_t N) {
+  return grouped_gemm_mfma_supports(1, rows, K, N, 0) && N * K * 2 < ((int64_t)1 << 32);
 }
 
 // Shapes for which the whole backward of the expert layer runs on the three layouts above.

@@ -242,6 +242,14 @@ __global__ __launch_bounds__(256) void gate_dbias_reduce_kernel(const float* __r
   dbias[e] = s;
 }
 
+// dst = src rounded to bf16 (n a multiple of 4): dlogits for the matrix-core product below
+__global__ __launch_bounds__(256) void f32_to_bf16_kernel(const float4* __restrict__ src, int64_t n4, uint2* __restrict__ dst) {
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += (int64_t)gridDim.x * 256) {
+    const float4 v = src[i];
+    dst[i] = make_uint2(pack_bf16x2(v.x, v.y), pack_bf16x2(v.z, v.w));
+  }
+}
+
 // Tokens per partial sum: 64 up to 16384 tokens, then as many as keep the number of slices at 256 (the partial sums
 // are written and read once, so their size is what the reduction costs).
 inline int64_t dw_slice_len(int64_t T) { return kDwSlice * (ceil_div(T, (int64_t)kDwSlice * 256) > 1 ? ceil_div(T, (int64_t)kDwSlice * 256) : 1); }
@@ -250,7 +258,8 @@ inline int64_t dw_slice_len(int64_t T) { return kDwSlice * (ceil_div(T, (int64_t
 
 size_t gate_backward_workspace_bytes(int64_t T, int64_t M, int64_t E) {
   const size_t slices = (size_t)ceil_div(T, dw_slice_len(T));
-  return align_up((size_t)T * E * 4, 256) + align_up(slices * M * E * 4, 256) + align_up(slices * E * 4, 256);
+  return align_up((size_t)T * E * 4, 256) + align_up(slices * M * E * 4, 256) + align_up(slices * E * 4, 256) +
+         align_up((size_t)T * E * 2, 256);                  // dlogits, partial dWg, partial dbias, dlogits in bf16
 }
 
 template <typename ET>
@@ -267,7 +276,18 @@ static hipError_t gate_backward_t(const void* x, const void* Wg, const float* lo
   gate_backward_kernel<<<dim3((unsigned)ceil_div(T, gb_tokens)), dim3(gb_tokens), (size_t)gb_tokens * (E + 1) * sizeof(float), s>>>(
       logits, idx, dgate_w, T, (int)E, k, normalize, dl);
   if ((err = hipGetLastError()) != hipSuccess) return err;
-  if (dx) {
+  // Wide bf16 gates: dx (+)= dlogits Wg^T is a [T,E] x [E,M] product, run on the matrix cores with dlogits rounded to
+  // bf16 (Wg [M,E] is the transposed operand as stored; the accumulate form adds dx in the epilogue).
+  const bool dx_mfma = dx && sizeof(ET) == 2 && E % 64 == 0 && M % 256 == 0 && (reinterpret_cast<uintptr_t>(Wg) & 15) == 0 &&
+                       (reinterpret_cast<uintptr_t>(dl) & 15) == 0 && grouped_gemm_mfma_supports_nt(T, E, M);
+  if (dx_mfma) {
+    uint16_t* dl16 = (uint16_t*)(ws + align_up((size_t)T * E * 4, 256) + align_up((size_t)slices * M * E * 4, 256) +
+                                 align_up((size_t)slices * E * 4, 256));
+    const int64_t n4 = T * E / 4, cb = ceil_div(n4, 256 * 4);
+    f32_to_bf16_kernel<<<dim3((unsigned)(cb < 8192 ? cb : 8192)), dim3(256), 0, s>>>((const float4*)dl, n4, (uint2*)dl16);
+    if ((err = hipGetLastError()) != hipSuccess) return err;
+    if ((err = launch_grouped_gemm_mfma_nt(dl16, Wg, nullptr, 1, T, E, M, dx, accumulate_dx ? dx : nullptr, -1, s)) != hipSuccess) return err;
+  } else if (dx) {
     const int cpr = (int)(M * sizeof(ET) / 16);
     gate_dx_kernel<ET><<<dim3((unsigned)ceil_div(T, kDxTokens), (unsigned)ceil_div(cpr, 256)), dim3(256), 0, s>>>(dl, (const ET*)Wg, T, cpr, (int)E, accumulate_dx, (uint4*)dx);
     if ((err = hipGetLastError()) != hipSuccess) return err;
