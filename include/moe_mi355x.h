@@ -190,7 +190,7 @@ size_t moe_gate_backward_workspace_bytes(int64_t T, int64_t M, int64_t E, int k)
  * x, dx [T,M] and Wg, dWg [M,E] in `dtype`; logits [T,E] fp32 and idx [T,k] as the forward produced them; dbias [E] and
  * dlogits [T,E] fp32.  Any of dx, dWg, dbias, dlogits may be NULL.  The choice of experts and the slot assignment carry
  * no gradient.  fp32 arithmetic, fixed summation orders (within a token slice ascending, then slice by slice); for bf16
- * gates with a multiple of 64 experts and M % 256 == 0, dx is a matrix-core product of dlogits rounded to bf16 (fp32 sums).
+ * gates with 32 or more experts and M % 256 == 0, dx is a matrix-core product of dlogits rounded to bf16 (fp32 sums).
  * ws: moe_gate_backward_workspace_bytes, 256-byte aligned; x and dx 16-byte aligned. */
 int moe_gate_backward(const void* x, const void* Wg, const float* logits, const int32_t* idx, const float* dgate_w, int normalize,
                       int dtype, int64_t T, int64_t M, int64_t E, int k, void* ws, size_t ws_bytes, void* dx, int accumulate_dx,

@@ -242,11 +242,20 @@ __global__ __launch_bounds__(256) void gate_dbias_reduce_kernel(const float* __r
   dbias[e] = s;
 }
 
-// dst = src rounded to bf16 (n a multiple of 4): dlogits for the matrix-core product below
-__global__ __launch_bounds__(256) void f32_to_bf16_kernel(const float4* __restrict__ src, int64_t n4, uint2* __restrict__ dst) {
-  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += (int64_t)gridDim.x * 256) {
-    const float4 v = src[i];
-    dst[i] = make_uint2(pack_bf16x2(v.x, v.y), pack_bf16x2(v.z, v.w));
+// dst [rows, Ep] bf16 = src [rows, E] (fp32 or bf16) with the columns E .. Ep-1 zero; Ep a multiple of 8.  One thread
+// per 8 output columns.  Operands of the matrix-core product below (its reduction runs in steps of 64 experts).
+template <typename ST>
+__global__ __launch_bounds__(256) void pad_to_bf16_kernel(const ST* __restrict__ src, int64_t rows, int E, int Ep,
+                                                          uint4* __restrict__ dst) {
+  const int gpr = Ep / 8;
+  const int64_t n = rows * gpr;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+    const int64_t r = i / gpr;
+    const int e0 = (int)(i % gpr) * 8;
+    float f[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) f[u] = e0 + u < E ? load_as_f32<ST>(src + r * E + e0 + u) : 0.f;
+    dst[i] = Vec16<uint16_t>::pack(f);
   }
 }
 
@@ -259,7 +268,8 @@ inline int64_t dw_slice_len(int64_t T) { return kDwSlice * (ceil_div(T, (int64_t
 size_t gate_backward_workspace_bytes(int64_t T, int64_t M, int64_t E) {
   const size_t slices = (size_t)ceil_div(T, dw_slice_len(T));
   return align_up((size_t)T * E * 4, 256) + align_up(slices * M * E * 4, 256) + align_up(slices * E * 4, 256) +
-         align_up((size_t)T * E * 2, 256);                  // dlogits, partial dWg, partial dbias, dlogits in bf16
+         align_up((size_t)T * (ceil_div(E, 64) * 64) * 2, 256) + align_up((size_t)M * (ceil_div(E, 64) * 64) * 2, 256);
+  // dlogits, partial dWg, partial dbias; dlogits and Wg in bf16 with the experts padded to a multiple of 64
 }
 
 template <typename ET>
@@ -277,16 +287,25 @@ static hipError_t gate_backward_t(const void* x, const void* Wg, const float* lo
       logits, idx, dgate_w, T, (int)E, k, normalize, dl);
   if ((err = hipGetLastError()) != hipSuccess) return err;
   // Wide bf16 gates: dx (+)= dlogits Wg^T is a [T,E] x [E,M] product, run on the matrix cores with dlogits rounded to
-  // bf16 (Wg [M,E] is the transposed operand as stored; the accumulate form adds dx in the epilogue).
-  const bool dx_mfma = dx && sizeof(ET) == 2 && E % 64 == 0 && M % 256 == 0 && (reinterpret_cast<uintptr_t>(Wg) & 15) == 0 &&
-                       (reinterpret_cast<uintptr_t>(dl) & 15) == 0 && grouped_gemm_mfma_supports_nt(T, E, M);
+  // bf16 (Wg [M,E] is the transposed operand as stored; the accumulate form adds dx in the epilogue).  The reduction
+  // runs in steps of 64 experts: other expert counts get zero-padded copies of both operands.
+  const int64_t Ep = ceil_div(E, 64) * 64;
+  const bool dx_mfma = dx && sizeof(ET) == 2 && E >= 32 && M % 256 == 0 && (reinterpret_cast<uintptr_t>(Wg) & 15) == 0 &&
+                       grouped_gemm_mfma_supports_nt(T, Ep, M);
   if (dx_mfma) {
-    uint16_t* dl16 = (uint16_t*)(ws + align_up((size_t)T * E * 4, 256) + align_up((size_t)slices * M * E * 4, 256) +
-                                 align_up((size_t)slices * E * 4, 256));
-    const int64_t n4 = T * E / 4, cb = ceil_div(n4, 256 * 4);
-    f32_to_bf16_kernel<<<dim3((unsigned)(cb < 8192 ? cb : 8192)), dim3(256), 0, s>>>((const float4*)dl, n4, (uint2*)dl16);
+    char* extra = ws + align_up((size_t)T * E * 4, 256) + align_up((size_t)slices * M * E * 4, 256) + align_up((size_t)slices * E * 4, 256);
+    uint16_t* dl16 = (uint16_t*)extra;
+    uint16_t* wg16 = (uint16_t*)(extra + align_up((size_t)T * Ep * 2, 256));
+    auto blocks_for = [](int64_t n) { const int64_t b = ceil_div(n, 256 * 4); return (unsigned)(b < 8192 ? (b > 0 ? b : 1) : 8192); };
+    pad_to_bf16_kernel<float><<<dim3(blocks_for(T * Ep / 8)), dim3(256), 0, s>>>(dl, T, (int)E, (int)Ep, (uint4*)dl16);
     if ((err = hipGetLastError()) != hipSuccess) return err;
-    if ((err = launch_grouped_gemm_mfma_nt(dl16, Wg, nullptr, 1, T, E, M, dx, accumulate_dx ? dx : nullptr, -1, s)) != hipSuccess) return err;
+    const void* wgt = Wg;
+    if (Ep != E) {
+      pad_to_bf16_kernel<uint16_t><<<dim3(blocks_for(M * Ep / 8)), dim3(256), 0, s>>>((const uint16_t*)Wg, M, (int)E, (int)Ep, (uint4*)wg16);
+      if ((err = hipGetLastError()) != hipSuccess) return err;
+      wgt = wg16;
+    }
+    if ((err = launch_grouped_gemm_mfma_nt(dl16, wgt, nullptr, 1, T, Ep, M, dx, accumulate_dx ? dx : nullptr, -1, s)) != hipSuccess) return err;
   } else if (dx) {
     const int cpr = (int)(M * sizeof(ET) / 16);
     gate_dx_kernel<ET><<<dim3((unsigned)ceil_div(T, kDxTokens), (unsigned)ceil_div(cpr, 256)), dim3(256), 0, s>>>(dl, (const ET*)Wg, T, cpr, (int)E, accumulate_dx, (uint4*)dx);

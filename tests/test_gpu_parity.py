@@ -266,7 +266,8 @@ def test_expert_ffn(moe, dtype, E, C, M, H, act, bias, use_counts):
 @pytest.mark.parametrize("dtype", [synth.DT_F32, synth.DT_BF16])
 @pytest.mark.parametrize("T,M,E,k,normalize", [(1, 8, 1, 1, 1), (70, 40, 4, 2, 1), (1000, 256, 8, 2, 1), (333, 776, 17, 5, 0),
                                                (2500, 128, 128, 8, 1), (1025, 64, 300, 3, 1), (20000, 256, 64, 2, 1),
-                                               (900, 64, 24, 3, 0), (3000, 512, 128, 4, 1), (777, 256, 64, 2, 0)])
+                                               (900, 64, 24, 3, 0), (3000, 512, 128, 4, 1), (777, 256, 64, 2, 0),
+                                               (1500, 256, 40, 3, 1), (600, 512, 100, 5, 0)])
 def test_gate_backward(moe, dtype, T, M, E, k, normalize):
     cfg = synth.CONFIGS[1].scaled(T=T, M=M, H=8, E=E, k=k, dtype=dtype, cfg_id=50)
     inp = synth.make_inputs(cfg, seed=T + 3)
