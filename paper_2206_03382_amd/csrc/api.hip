@@ -501,8 +501,8 @@ int moe_layer_backward(const void* x, const void* Wg, const void* W1, const void
   const int32_t* src = (const int32_t*)(base + w.slot_src);
   float* dgw = (float*)(base + w.dgate_w);
   hipStream_t s = (hipStream_t)stream;
-  // decode: dY (every slot, zeros where unfilled) and the gate weights' gradient
-  if (launch_decode_backward(d_out, base + w.Y, dtype, idx, loc, gw, src, T, M, E, k, C, base + w.dY, dgw, s) != hipSuccess)
+  // decode: dY over the filled slots (the expert backward stops at an expert's fill) and the gate weights' gradient
+  if (launch_decode_backward(d_out, base + w.Y, dtype, idx, loc, gw, src, T, M, E, k, C, base + w.dY, dgw, s, false) != hipSuccess)
     return MOE_HIP_ERROR;
   // experts: dZ over the filled slots, parameter gradients
   if (launch_expert_ffn_backward(base + w.Z, W1, b1, W2, base + w.pre, base + w.hidden, base + w.dY, act, dtype, counts, E, C, M,

@@ -96,7 +96,7 @@ hipError_t launch_bpr_order(const float* logits, int64_t T, int64_t E, uint64_t*
                             hipStream_t s);
 hipError_t launch_decode_backward(const void* d_out, const void* Y, int dtype, const int32_t* idx, const int32_t* loc,
                                   const float* gate_w, const int32_t* slot_src, int64_t T, int64_t M, int64_t E, int k,
-                                  int64_t C, void* dY, float* dgate_w, hipStream_t s);
+                                  int64_t C, void* dY, float* dgate_w, hipStream_t s, bool fill_unfilled = true);
 hipError_t launch_dynamic_capacity(const int32_t* counts, int64_t E, int64_t bound, int64_t* out, hipStream_t s);
 hipError_t launch_slot_sources(const int32_t* idx, const int32_t* loc, int64_t T, int64_t E, int k, int64_t C,
                                int32_t* slot_src, hipStream_t s);

@@ -168,7 +168,7 @@ hipError_t launch_decode(const void* Y, int dtype, const int32_t* idx, const int
 // dY[e,c,:] = gate_w[t,j] * d_out[t,:] for the kept choice (t,j) that owns slot (e,c), zero for an unfilled slot.
 // Gather form over the slots, like encode: a wave moves ROWS adjacent slots; the owner's choice j is found by
 // comparing the token's k (expert, location) pairs with the slot.
-template <typename ET, int ROWS>
+template <typename ET, int ROWS, bool FILL>
 __global__ __launch_bounds__(256) void decode_backward_rows_kernel(const uint4* __restrict__ d_out,
                                                                    const int32_t* __restrict__ slot_src,
                                                                    const int32_t* __restrict__ idx,
@@ -187,6 +187,7 @@ __global__ __launch_bounds__(256) void decode_backward_rows_kernel(const uint4* 
       const int64_t slot = r0 + i;
       src[i] = slot < nrows ? slot_src[slot] : -2;
       w[i] = 0.f;
+      if (!FILL && !(src[i] >= 0 && src[i] < T)) src[i] = -2;          // unfilled slot: its row is left untouched
       if (src[i] >= 0 && src[i] < T) {
         const int e = (int)(slot / C), c = (int)(slot % C);
         for (int j = 0; j < k; ++j) {                               // wave-uniform: the same slot in every lane
@@ -246,7 +247,7 @@ __global__ __launch_bounds__(256) void gate_weight_grad_kernel(const uint4* __re
 
 hipError_t launch_decode_backward(const void* d_out, const void* Y, int dtype, const int32_t* idx, const int32_t* loc,
                                   const float* gate_w, const int32_t* slot_src, int64_t T, int64_t M, int64_t E, int k,
-                                  int64_t C, void* dY, float* dgate_w, hipStream_t s) {
+                                  int64_t C, void* dY, float* dgate_w, hipStream_t s, bool fill_unfilled) {
   const int es = (dtype == MOE_F32) ? 4 : 2;
   const int cpr = (int)(M * es / 16);
   const dim3 block(256);
@@ -254,10 +255,10 @@ hipError_t launch_decode_backward(const void* d_out, const void* Y, int dtype, c
     constexpr int ROWS = 4;
     const int64_t nrows = E * C, blocks = ceil_div(nrows, 4 * ROWS);
     const dim3 grid((unsigned)(blocks < 8192 ? blocks : 8192));
-    if (dtype == MOE_F32)
-      decode_backward_rows_kernel<float, ROWS><<<grid, block, 0, s>>>((const uint4*)d_out, slot_src, idx, loc, gate_w, nrows, T, k, C, cpr, (uint4*)dY);
-    else
-      decode_backward_rows_kernel<uint16_t, ROWS><<<grid, block, 0, s>>>((const uint4*)d_out, slot_src, idx, loc, gate_w, nrows, T, k, C, cpr, (uint4*)dY);
+#define MOE_LAUNCH_DBR(ET, FILL) decode_backward_rows_kernel<ET, ROWS, FILL><<<grid, block, 0, s>>>((const uint4*)d_out, slot_src, idx, loc, gate_w, nrows, T, k, C, cpr, (uint4*)dY)
+    if (dtype == MOE_F32) { if (fill_unfilled) MOE_LAUNCH_DBR(float, true); else MOE_LAUNCH_DBR(float, false); }
+    else { if (fill_unfilled) MOE_LAUNCH_DBR(uint16_t, true); else MOE_LAUNCH_DBR(uint16_t, false); }
+#undef MOE_LAUNCH_DBR
     const hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
   }
