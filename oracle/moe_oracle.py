@@ -28,30 +28,37 @@ Readings where the paper is silent (each listed again in the design notes):
   R6  encode copies rows unscaled; only decode applies the gate weight.  Unfilled slots are zero.
   R7  activations: ReLU; GeLU = 0.5 x (1 + erf(x / sqrt 2)); SiLU = x / (1 + exp(-x)).
   R8  a token whose choices were all dropped gets an all-zero output row.
-  R10 backward of encode / decode (Appendix B, the differentiable fast encode and decode operators; the figure with
-      the formulas is lost): the plain derivatives of the dense contractions.  encode is not scaled by the gate
-      weight here (R6), so its backward has no gate-weight gradient; idx and loc carry no gradient.
-  R11 backward of the expert feed-forward layer (Sec. 3.2: the backward pass runs "the backward computation of the
-      expert"): the chain rule through y = act(z W1 + b1) W2 + b2, rows past an expert's fill contributing nothing;
-      ReLU'(0) = 0.
-  R12 cosine router (Appendix, "A New Cosine Router", its Eq.): logits[t,e] = cos(W x_t, M_e) / tau with the
-      temperature clamped below at 0.01; the projection W x (dimension D) is rounded once to fp32 like the linear
-      gate's logits; norms are clamped below at 1e-12 (the paper gives no epsilon); the rest of the gate is unchanged.
-  R13 batch prioritized routing (named in Sec. 3.2 and the Appendix's routing ablation, defined in the work cited
-      there): slots are handed out in order of decreasing token priority instead of token order, rank j still
-      outermost; priority = the token's largest routing probability max_e p[t,e], rounded to fp32 (the comparison
-      is an integer-like decision, so both sides take it on the same fp32 key); equal priorities -> lower token.
-  R14 backward of the gate (the paper only says the backward pass mirrors the forward, Sec. 3.2): the chain rule through
-      gate weight = (optionally renormalised) softmax probability at the chosen experts, and through the linear layer;
-      the choice of experts and the slot assignment are integer decisions and carry no gradient.
-  R9  dynamic capacity (Sec. 4.1 "Dynamic Capacity Factor", capacity_setting x): x > 0 is the factor f itself;
+  R9  storage precision (bf16 workloads): the oracle takes the bf16 inputs as exact values and never rounds an
+      intermediate; what the device path rounds (hidden activations, expert outputs, the final sum) is absorbed by the
+      output tolerance.
+  R10 rows of unfilled slots carry no information: they are zero in Z and are not computed by the zero-skipping tiers.
+  R11 the gate's dot products are summed in fp64 and rounded once to fp32, so that the integer decisions taken on them
+      do not depend on a summation order.
+  R12 workload preparation (LayerNorm'd tokens, Zipf gate bias) belongs to the input generator, not to the method.
+  R13 dynamic capacity (Sec. 4.1 "Dynamic Capacity Factor", capacity_setting x): x > 0 is the factor f itself;
       x = 0 means the smallest capacity that drops nothing, which is the arrival count of the fullest expert
       (Eq. 1 with the smallest such factor gives exactly that integer); x < 0 the same but never above the
       capacity that factor -x gives.
+  R14 backward of encode / decode (Appendix B, the differentiable fast encode and decode operators; the figure with
+      the formulas is lost): the plain derivatives of the dense contractions.  encode is not scaled by the gate
+      weight here (R6), so its backward has no gate-weight gradient; idx and loc carry no gradient.
+  R15 cosine router (Appendix, "A New Cosine Router", its Eq.): logits[t,e] = cos(W x_t, M_e) / tau with the
+      temperature clamped below at 0.01; the projection W x (dimension D) is rounded once to fp32 like the linear
+      gate's logits; norms are clamped below at 1e-12 (the paper gives no epsilon); the rest of the gate is unchanged.
+  R16 batch prioritized routing (named in Sec. 3.2 and the Appendix's routing ablation, defined in the work cited
+      there): slots are handed out in order of decreasing token priority instead of token order, rank j still
+      outermost; priority = the token's largest routing probability max_e p[t,e], rounded to fp32 (the comparison
+      is an integer-like decision, so both sides take it on the same fp32 key); equal priorities -> lower token.
+  R17 backward of the expert feed-forward layer (Sec. 3.2: the backward pass runs "the backward computation of the
+      expert"): the chain rule through y = act(z W1 + b1) W2 + b2, rows past an expert's fill contributing nothing;
+      ReLU'(0) = 0.
+  R18 backward of the gate (the paper only says the backward pass mirrors the forward, Sec. 3.2): the chain rule through
+      gate weight = (optionally renormalised) softmax probability at the chosen experts, and through the linear layer;
+      the choice of experts and the slot assignment are integer decisions and carry no gradient.
 
 Pins (tests/test_oracle_*.py): Eq. 1 closed forms; the Fig. 2 worked shape; a hand-worked routing example;
 exhaustive/brute-force sequential-arrival simulation; invariants; tie cases; special cases that reduce to
-torch's linear/softmax/topk/activation routines; dense == sparse.  No function here is "parity unpinned".
+torch's linear/softmax/topk/activation routines; dense == sparse == streamed.  No function here is "parity unpinned".
 """
 from __future__ import annotations
 
@@ -74,7 +81,7 @@ def capacity(T: int, E: int, k: int, f: float) -> int:
 
 
 def dynamic_capacity(counts: np.ndarray, T: int, E: int, k: int, capacity_setting: float) -> int:
-    """Capacity under the dynamic capacity factor of Sec. 4.1 (reading R9); `counts` are the un-truncated arrivals."""
+    """Capacity under the dynamic capacity factor of Sec. 4.1 (reading R13); `counts` are the un-truncated arrivals."""
     x = float(capacity_setting)
     if x > 0:
         return capacity(T, E, k, x)
@@ -106,7 +113,7 @@ def gate_logits(x: np.ndarray, Wg: np.ndarray, bias: Optional[np.ndarray] = None
 
 
 def cosine_gate_logits(x: np.ndarray, Wp: np.ndarray, Me: np.ndarray, tau: float, rows_per_pass: int = 8192) -> np.ndarray:
-    """Cosine router (Appendix, "A New Cosine Router"; reading R12): cos(x Wp, Me[e]) / max(tau, 0.01) in fp64 on the
+    """Cosine router (Appendix, "A New Cosine Router"; reading R15): cos(x Wp, Me[e]) / max(tau, 0.01) in fp64 on the
     fp32-rounded projection, rounded once to fp32.   x [T,M], Wp [M,D] (the projection, stored input-major), Me [E,D]."""
     proj = gate_logits(x, Wp, None, rows_per_pass).astype(np.float64)          # x Wp: fp64 sums, one rounding to fp32
     Md = np.asarray(Me, dtype=np.float64)
@@ -151,7 +158,7 @@ def gate_weights(p: np.ndarray, idx: np.ndarray, normalize: int) -> np.ndarray:
 
 
 def gate_backward(logits: np.ndarray, idx: np.ndarray, dgate_w: np.ndarray, normalize: int) -> np.ndarray:
-    """d loss / d logits given d loss / d gate_w (reading R14), fp64.
+    """d loss / d logits given d loss / d gate_w (reading R18), fp64.
 
     Forward: p = softmax(logits); g[t,j] = p[t, idx[t,j]]; gate_w = g / sum_j g if normalize else g.
     """
@@ -182,7 +189,7 @@ def gate_logits_backward(x: np.ndarray, Wg: np.ndarray, dlogits: np.ndarray) -> 
 # ---------------------------------------------------------------------------------------------------------------
 
 def bpr_token_order(logits: np.ndarray) -> np.ndarray:
-    """Batch prioritized routing (reading R13): tokens in order of decreasing priority, priority = the largest softmax
+    """Batch prioritized routing (reading R16): tokens in order of decreasing priority, priority = the largest softmax
     probability of the token rounded to fp32; equal priorities keep token order."""
     key = softmax_rows(logits).max(axis=1).astype(np.float32)
     return np.argsort(-key.astype(np.float64), kind="stable")
@@ -285,7 +292,7 @@ def decode_sparse(Y: np.ndarray, idx: np.ndarray, loc: np.ndarray, gate_w: np.nd
 
 
 # ---------------------------------------------------------------------------------------------------------------
-# Backward of encode / decode (Appendix B: differentiable fast encode and decode; reading R10).  The forward maps are
+# Backward of encode / decode (Appendix B: differentiable fast encode and decode; reading R14).  The forward maps are
 # linear, Z = D^T x and out = W Y, so the backward maps are their transposes; the gate weight enters W linearly.
 # ---------------------------------------------------------------------------------------------------------------
 
@@ -468,6 +475,51 @@ def moe_layer_backward(x, Wg, gate_bias, W1, b1, W2, b2, k: int, f: float, norma
     gb = gate_logits_backward(x, Wg, dlogits)
     return dict(dx=encode_backward_sparse(g["dZ"], idx, loc, C) + gb["dx"], dWg=gb["dWg"], dgate_bias=gb["dbias"],
                 dW1=g["dW1"], db1=g["db1"], dW2=g["dW2"], db2=g["db2"], forward=r)
+
+
+def expert_slabs(x, idx, loc, gate_w, C: int, W1, b1, W2, b2, act: int):
+    """Zero-skipping tier streamed one expert at a time (for sizes whose [E,C,M] buffers do not fit in host memory).
+
+    Yields, for e = 0 .. E-1: (e, tokens, w, Z_e, Y_e) with tokens[c] = the token in slot (e, c) for c below the
+    expert's fill, w[c] = its gate weight there, Z_e = the dispatched rows x[tokens] (what encode puts into the
+    filled rows of slab e; Appendix B) and Y_e = FFN_e(Z_e) in fp64.  Nothing larger than one slab exists at a time.
+    """
+    E = W1.shape[0]
+    tt, jj = np.nonzero(loc < C)                      # kept (token, choice) pairs
+    ee, ll = idx[tt, jj], loc[tt, jj]
+    order = np.lexsort((ll, ee))                      # by expert, then by slot
+    tt, jj, ee, ll = tt[order], jj[order], ee[order], ll[order]
+    first = np.searchsorted(ee, np.arange(E + 1))
+    for e in range(E):
+        a, b = first[e], first[e + 1]
+        tokens = tt[a:b]
+        assert np.array_equal(ll[a:b], np.arange(b - a)), "kept locations of an expert must be 0 .. fill-1, each once"
+        Ze = np.asarray(x[tokens], dtype=np.float64)
+        Ye = ffn_rows(Ze, W1[e], None if b1 is None else b1[e], W2[e], None if b2 is None else b2[e], act) \
+            if b > a else np.zeros((0, W2.shape[2]))
+        yield e, tokens, np.asarray(gate_w[tokens, jj[a:b]], dtype=np.float64), Ze, Ye
+
+
+def moe_layer_streamed(x, Wg, gate_bias, W1, b1, W2, b2, k: int, f: float, normalize: int, act: int,
+                       logits: Optional[np.ndarray] = None, on_expert=None) -> Dict[str, np.ndarray]:
+    """moe_layer's result without any [E,C,M] buffer: the combine sum  out[t] = sum_{e,c} combine_w[t,e,c] Y[e,c]  of
+    the dense definition (Appendix B) visited expert by expert, slots ascending, zero terms skipped.
+
+    `on_expert(e, tokens, w, Z_e, Y_e)`, if given, sees every expert's filled slab as it is produced (the caller can
+    compare it with the device's slab and drop it).  Returns routing, logits, C and out (no Z, no Y).
+    """
+    T, E = x.shape[0], W1.shape[0]
+    if logits is None:
+        logits = gate_logits(x, Wg, gate_bias)
+    C = capacity(T, E, k, f)
+    r = route(logits, k, C, normalize)
+    out = np.zeros((T, W2.shape[2]), dtype=np.float64)
+    for e, tokens, w, Ze, Ye in expert_slabs(x, r["idx"], r["loc"], r["gate_w"], C, W1, b1, W2, b2, act):
+        if on_expert is not None:
+            on_expert(e, tokens, w, Ze, Ye)
+        out[tokens] += w[:, None] * Ye                # a token sits in at most one slot of an expert: no index repeats
+    r.update(C=C, logits=logits, out=out)
+    return r
 
 
 def token_outputs_direct(tokens: Sequence[int], x, idx, loc, gate_w, C: int, W1, b1, W2, b2, act: int) -> np.ndarray:

@@ -278,6 +278,44 @@ def pin_bruteforce_layer(o):
             np.testing.assert_allclose(r["out"], ref, rtol=1e-11, atol=1e-12)
 
 
+def pin_streamed_tier(o):
+    """The expert-by-expert tier gives the buffered tiers' result: slabs bit for bit, the output bit for bit with one
+    term per token (top-1) and to fp64 rounding of a reordered sum of at most k terms otherwise; also against the
+    independent per-token brute force."""
+    T, M, H, E = 60, 12, 20, 6
+    for k, f, norm, act in ((1, 1.0, 0, o.ACT_RELU), (1, 0.5, 0, o.ACT_GELU), (3, 0.5, 1, o.ACT_SILU), (2, 1.5, 1, o.ACT_GELU), (6, 1.0, 1, o.ACT_SILU)):
+        x, Wg, gb, W1, b1, W2, b2 = _tiny_layer_inputs(31 + k, T, M, H, E)
+        s = o.moe_layer(x, Wg, gb, W1, b1, W2, b2, k=k, f=f, normalize=norm, act=act, tier="sparse")
+        C = s["C"]
+        src = o.slot_source(s["idx"], s["loc"], E, C)
+        seen = []
+
+        def check(e, tokens, w, Ze, Ye):
+            n = len(tokens)
+            seen.append(e)
+            assert n == min(int(s["counts"][e]), C)
+            assert np.array_equal(tokens, src[e, :n]) and (src[e, n:] == -1).all()
+            assert np.array_equal(Ze, s["Z"][e, :n]) and np.array_equal(Ye, s["Y"][e, :n])
+            for c in range(n):                                       # the weight of the choice that owns the slot
+                j = [j for j in range(k) if s["idx"][tokens[c], j] == e and s["loc"][tokens[c], j] == c]
+                assert len(j) == 1 and w[c] == s["gate_w"][tokens[c], j[0]]
+
+        r = o.moe_layer_streamed(x, Wg, gb, W1, b1, W2, b2, k=k, f=f, normalize=norm, act=act, on_expert=check)
+        assert seen == list(range(E)) and r["C"] == C
+        for key in ("idx", "loc", "kept", "counts", "logits"):
+            assert np.array_equal(r[key], s[key]), key
+        if k == 1:
+            assert np.array_equal(r["out"], s["out"])
+        np.testing.assert_allclose(r["out"], s["out"], rtol=1e-13, atol=1e-14)
+        dead = (~s["kept"]).all(axis=1)
+        assert (r["out"][dead] == 0).all()
+    T, M, H, E = 10, 5, 7, 3
+    x, Wg, gb, W1, b1, W2, b2 = _tiny_layer_inputs(29, T, M, H, E)
+    ref = o.brute_force_layer(x, Wg, gb, W1, b1, W2, b2, 2, 0.75, 1, o.ACT_GELU)
+    r = o.moe_layer_streamed(x, Wg, gb, W1, b1, W2, b2, k=2, f=0.75, normalize=1, act=o.ACT_GELU)
+    np.testing.assert_allclose(r["out"], ref, rtol=1e-11, atol=1e-12)
+
+
 def pin_dynamic_capacity(o):
     """Sec. 4.1, dynamic capacity factor: x > 0 is Eq. 1 with f = x; x = 0 is the smallest capacity that drops no
     token (so one less must drop one); x < 0 is the same, capped by the capacity of factor -x."""
@@ -535,7 +573,7 @@ def pin_layer_backward(o):
         assert filled.sum() == fw["kept"].sum()
 
 
-PINS = [pin_layer_backward, pin_gate_backward, pin_batch_prioritized_routing, pin_cosine_router, pin_ffn_backward, pin_encode_decode_backward, pin_dynamic_capacity, pin_capacity_golden, pin_worked_routing_example, pin_fig2_even_top1, pin_exhaustive_top1_locations,
+PINS = [pin_streamed_tier, pin_layer_backward, pin_gate_backward, pin_batch_prioritized_routing, pin_cosine_router, pin_ffn_backward, pin_encode_decode_backward, pin_dynamic_capacity, pin_capacity_golden, pin_worked_routing_example, pin_fig2_even_top1, pin_exhaustive_top1_locations,
         pin_random_topk_vs_bruteforce, pin_invariants, pin_ties_lower_index, pin_gate_against_torch,
         pin_activations_and_ffn_against_torch, pin_no_drop_equals_weighted_sum_of_experts,
         pin_identity_experts_masked_scaling, pin_dense_equals_sparse_and_direct, pin_bruteforce_layer]
@@ -594,6 +632,11 @@ MISTAKES = {
     "dynamic_capacity_bound_ignored": ("    return min(needed, capacity(T, E, k, -x))", "    return needed"),
     "dynamic_capacity_bound_as_floor": ("    return min(needed, capacity(T, E, k, -x))", "    return max(needed, capacity(T, E, k, -x))"),
     "dynamic_capacity_zero_uses_static": ("    if x == 0:\n        return needed", "    if x == 0:\n        return capacity(T, E, k, 1.0)"),
+    "streamed_slots_in_token_order": ("    order = np.lexsort((ll, ee))                      # by expert, then by slot", "    order = np.lexsort((tt, ee))"),
+    "streamed_weight_of_first_choice": ("        yield e, tokens, np.asarray(gate_w[tokens, jj[a:b]], dtype=np.float64), Ze, Ye", "        yield e, tokens, np.asarray(gate_w[tokens, 0], dtype=np.float64), Ze, Ye"),
+    "streamed_keeps_dropped": ("    tt, jj = np.nonzero(loc < C)                      # kept (token, choice) pairs", "    tt, jj = np.nonzero(loc < C + 1)"),
+    "streamed_unweighted_sum": ("        out[tokens] += w[:, None] * Ye                # a token", "        out[tokens] += Ye                # a token"),
+    "streamed_overwrites_instead_of_adding": ("        out[tokens] += w[:, None] * Ye                # a token", "        out[tokens] = w[:, None] * Ye                # a token"),
     "capacity_floor": ("int(math.ceil(float(k)", "int(math.floor(float(k)"),
     "capacity_drops_k": ("math.ceil(float(k) * float(f)", "math.ceil(float(f)"),
     "ties_to_higher_index": ("idx[:, j] = np.argmax(work, axis=1)", "idx[:, j] = E - 1 - np.argmax(work[:, ::-1], axis=1)"),
