@@ -2,21 +2,25 @@
 """Benchmark of the MoE-layer hot path on one MI355X: `python bench.py [--gpus 1] [--steps K] [--warmup W]`.
 
 One step = one pass of the whole path (gate logits -> top-k + slots -> encode -> expert FFN -> decode) over one batch
-of seeded synthetic input that is already resident in HBM.  Prints one JSON line:
+of seeded synthetic input that is already resident in HBM.  The bench line is the largest of the five workloads
+(T=131072, M=4096, H=1024, E=128, top-8; `--config N` picks another).  Prints one JSON line:
   value      layer forward tokens/s (T / mean step time)
   roofline   the dominant kernel (grouped bf16 MFMA GEMM of the expert FFN): algorithmic FLOP per launch divided by
              its mean launch time, measured with HIP events recorded on the library's stream inside the timed loop
-             (on every fifth timed step: the event records themselves cost stream time)
+             (on every fifth timed step: the event records themselves cost stream time); `traffic` is read from the
+             rocprofv3 counter summary of the same workload under profiles/ (null where none is recorded)
   stages     per-stage mean milliseconds and, for encode/decode, algorithmic HBM GB/s
-  cpu_baseline  the CPU oracle timed on this machine's host cores on the same workload
+  cpu_baseline  the CPU oracle timed on this machine's host cores on a bounded sample of the same workload
   fused_dispatch  the same step through moe_layer_forward_fused (the first expert GEMM gathers its rows from the tokens,
              no dispatch buffer), timed in a second loop of the same length; information only, `value` is the plain path
+  other_workloads  the other four workloads measured the same way in the same run (not bench lines)
 """
 from __future__ import annotations
 
 import argparse
 import json
 import os
+import re
 import sys
 import time
 
@@ -28,9 +32,7 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 FP32_VECTOR_PEAK_TFLOPS = 157.3
-# HBM bytes per grouped-GEMM launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (see profiles/), keyed by
-# workload name; None where no counter run has been recorded.
-MEASURED_GEMM_TRAFFIC_BYTES = {"mid_bf16": 563_358_861}     # profiles/bench_mid_bf16_hbm_traffic.txt
+HEADLINE_CONFIG = 4
 
 
 def to_device(a, dtype_code):
@@ -43,13 +45,179 @@ def to_device(a, dtype_code):
     return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
 
 
+def recorded_gemm_traffic(workload: str):
+    """HBM bytes per grouped-GEMM launch from the rocprofv3 --pmc summary of this workload under profiles/, or None."""
+    path = os.path.join(ROOT, "profiles", f"bench_{workload}_hbm_traffic.txt")
+    if not os.path.exists(path):
+        return None
+    m = re.search(r"^gemm_traffic_bytes_per_launch:\s*(\d+)", open(path).read(), flags=re.M)
+    return int(m.group(1)) if m else None
+
+
+def workload_name(cfg, C):
+    return (f"{cfg.name}: T={cfg.T} M={cfg.M} H={cfg.H} E={cfg.E} top-{cfg.k} f={cfg.f} C={C} "
+            f"act={('relu', 'gelu', 'silu')[cfg.act]}")
+
+
+def measure(cfg, inp, steps: int, warmup: int, cold: bool = True):
+    """Times `steps` passes of moe_layer_forward (and of the fused-dispatch variant) on one workload."""
+    import torch
+    from paper_2206_03382_amd import moe, synth
+
+    d = cfg.dtype
+    x = to_device(inp["x"], d)
+    gate_bias = None if inp["gate_bias"] is None else torch.from_numpy(inp["gate_bias"]).cuda()
+    layer = moe.MoELayer(to_device(inp["Wg"], d), gate_bias, to_device(inp["W1"], d), to_device(inp["b1"], d),
+                         to_device(inp["W2"], d), to_device(inp["b2"], d), T=cfg.T, k=cfg.k, f=cfg.f,
+                         normalize=cfg.normalize, act=cfg.act, keep_routing=True)
+    # Stage events are recorded on every `stride`-th timed step only: each of the seven records costs a few microseconds
+    # of stream time, and the steps in between run exactly as a caller without instrumentation would run them.
+    stride = 5 if steps >= 10 else 1
+    sampled = [i for i in range(steps) if i % stride == 0]
+    events = {i: moe.StageEvents() for i in sampled}
+
+    for _ in range(warmup):
+        layer.forward(x)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        layer.forward(x, events.get(i))
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / steps
+    per_step = np.array([events[i].stage_ms() for i in sampled])     # [sampled steps, stages] from the library's own events
+    stage_ms = np.mean(per_step, axis=0)
+
+    for _ in range(warmup):
+        layer.forward(x, fuse_dispatch=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        layer.forward(x, events.get(i), fuse_dispatch=True)
+    torch.cuda.synchronize()
+    fused_ms = (time.perf_counter() - t0) * 1e3 / steps
+    fused_stage_ms = np.mean(np.array([events[i].stage_ms() for i in sampled]), axis=0)
+    for e in events.values():
+        e.close()
+
+    counts = layer.routing["counts"].cpu().numpy().astype(np.int64)
+    C, T, M, H, E, k = layer.C, cfg.T, cfg.M, cfg.H, cfg.E, cfg.k
+    es = 4 if d == synth.DT_F32 else 2
+    R = int(np.minimum(counts, C).sum())                         # filled slots = kept (token, choice) pairs
+    flop_per_gemm = 2.0 * R * M * H                              # GEMM1 [R,M]x[M,H] and GEMM2 [R,H]x[H,M]: same count
+    gemm_ms = float(stage_ms[3] + stage_ms[4]) / 2.0
+    bf16 = d == synth.DT_BF16
+    peak = MFMA_BF16_PEAK_TFLOPS if bf16 else FP32_VECTOR_PEAK_TFLOPS
+    achieved = flop_per_gemm / (gemm_ms * 1e-3) / 1e12
+    enc_bytes = 2 * R * M * es + 4 * E * C                       # read each kept row once, write it once (the layer leaves unfilled slots alone)
+    dec_bytes = (R + T) * M * es + 12 * T * k                    # read each kept expert-output row once, write [T,M]
+    logit_bytes = T * M * es + M * E * es + 4 * T * E            # read every token row once, write the logits
+    topk_bytes = 4 * T * E + 12 * T * k + 4 * E + 4 * E * C
+    stages = {name: round(float(ms), 5) for name, ms in zip(moe.STAGE_NAMES, stage_ms)}
+    stages["gate_logits_frac_hbm"] = round(logit_bytes / (stage_ms[0] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
+    stages["gate_topk_frac_hbm"] = round(topk_bytes / (stage_ms[1] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
+    stages["encode_GBps"] = round(enc_bytes / (stage_ms[2] * 1e-3) / 1e9, 1)
+    stages["decode_GBps"] = round(dec_bytes / (stage_ms[5] * 1e-3) / 1e9, 1)
+    stages["encode_frac_hbm"] = round(stages["encode_GBps"] / HBM_PEAK_GBS, 4)
+    stages["decode_frac_hbm"] = round(stages["decode_GBps"] / HBM_PEAK_GBS, 4)
+    stages["ffn_gemm1_TFLOPs"] = round(flop_per_gemm / (stage_ms[3] * 1e-3) / 1e12, 1)
+    stages["ffn_gemm2_TFLOPs"] = round(flop_per_gemm / (stage_ms[4] * 1e-3) / 1e12, 1)
+
+    # layer roofline: the stages run back to back on one stream, so their bounds add (HBM 8 TB/s for the data-movement
+    # stages, 2.5 PFLOP/s for the two GEMMs); algorithmic bytes and flop only
+    t_roof_ms = ((logit_bytes + topk_bytes + enc_bytes + dec_bytes) / (HBM_PEAK_GBS * 1e9) + 2 * flop_per_gemm / (peak * 1e12)) * 1e3
+    step_from_events = per_step.sum(axis=1)
+
+    # cold-cache variant: three separate sets of inputs, weights and workspaces used in rotation, so that no step finds
+    # its operands in the 256 MB memory-side cache (the default loop reuses one set; caches are not flushed between steps)
+    cold_ms = None
+    if cold and E * (M * H * 2) * es + T * M * es < (2 << 30):
+        sets = [(layer, x)]
+        for _ in range(2):
+            l2 = moe.MoELayer(layer.Wg.clone(), None if layer.gate_bias is None else layer.gate_bias.clone(), layer.W1.clone(),
+                              None if layer.b1 is None else layer.b1.clone(), layer.W2.clone(),
+                              None if layer.b2 is None else layer.b2.clone(), T=T, k=k, f=cfg.f, normalize=cfg.normalize,
+                              act=cfg.act, keep_routing=False)
+            sets.append((l2, x.clone()))
+        for i in range(6):
+            sets[i % 3][0].forward(sets[i % 3][1])
+        torch.cuda.synchronize()
+        c0 = time.perf_counter()
+        for i in range(steps):
+            sets[i % 3][0].forward(sets[i % 3][1])
+        torch.cuda.synchronize()
+        cold_ms = (time.perf_counter() - c0) * 1e3 / steps
+        del sets
+
+    res = {
+        "workload": workload_name(cfg, C), "filled_slots": R, "slots": E * C,
+        "ms_per_step": round(ms_per_step, 5), "tokens_per_s": round(T / (ms_per_step * 1e-3), 1),
+        "roofline": {"bound": "mfma" if bf16 else "alu", "kernel": "grouped_gemm_mfma_kernel" if bf16 else "gemm_generic_kernel",
+                     "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
+                     "flop_per_launch": flop_per_gemm, "avg_launch_ms": round(gemm_ms, 5),
+                     "traffic": recorded_gemm_traffic(cfg.name)},
+        "stages": stages,
+        "layer_roofline": {"t_roofline_ms": round(t_roof_ms, 5), "frac": round(t_roof_ms / ms_per_step, 4),
+                           "step_ms_median": round(float(np.median(step_from_events)), 5),
+                           "step_ms_min": round(float(step_from_events.min()), 5),
+                           "cold_cache_ms_per_step": None if cold_ms is None else round(cold_ms, 5),
+                           "instrumented_steps": len(sampled)},
+        "fused_dispatch": {"ms_per_step": round(fused_ms, 5), "value": round(T / (fused_ms * 1e-3), 1), "unit": "tokens/s",
+                           "stages": {name: round(float(ms), 5) for name, ms in zip(moe.STAGE_NAMES, fused_stage_ms)}},
+    }
+    return res, layer, x
+
+
+def cpu_baseline(cfg, inp, budget_s: float = 12.0):
+    """The oracle as it stands on this machine's host cores.  Workloads the oracle finishes in seconds run whole (repeated for
+    about 10 s); the large ones run the gate and the routing in full and the expert-by-expert tier (dispatch, FFN,
+    combine of one expert at a time) on the first experts until the budget is spent, scaled to all experts."""
+    from oracle import moe_oracle as O
+    from threadpoolctl import threadpool_info
+    blas = [p["num_threads"] for p in threadpool_info() if p.get("user_api") == "blas"]
+    threads = max(blas) if blas else (os.cpu_count() or 1)     # the oracle's time is in numpy's BLAS matmuls
+    T, E = cfg.T, cfg.E
+    C = O.capacity(T, E, cfg.k, cfg.f)
+    if 4.0 * min(T * cfg.k, E * C) * cfg.M * cfg.H < 2e12:       # a few seconds of fp64 BLAS per pass
+        reps, c0 = 0, time.perf_counter()
+        while reps == 0 or time.perf_counter() - c0 < 10.0:
+            O.moe_layer(inp["x"], inp["Wg"], inp["gate_bias"], inp["W1"], inp["b1"], inp["W2"], inp["b2"],
+                        cfg.k, cfg.f, cfg.normalize, cfg.act, tier="sparse")
+            reps += 1
+        cpu_s = time.perf_counter() - c0
+        return {"value": round(T * reps / cpu_s, 1), "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+                "sample": f"the full workload {reps} times (all {T} tokens each, fp64 numpy, zero-skipping tier), {cpu_s:.1f} s"}
+    c0 = time.perf_counter()
+    logits = O.gate_logits(inp["x"], inp["Wg"], inp["gate_bias"])
+    r = O.route(logits, cfg.k, C, cfg.normalize)
+    gate_s = time.perf_counter() - c0
+    out = np.zeros((T, cfg.M), dtype=np.float64)
+    rows_done, experts_done, c1 = 0, 0, time.perf_counter()
+    for e, tokens, w, Ze, Ye in O.expert_slabs(inp["x"], r["idx"], r["loc"], r["gate_w"], C, inp["W1"], inp["b1"], inp["W2"],
+                                               inp["b2"], cfg.act):
+        out[tokens] += w[:, None] * Ye
+        rows_done += len(tokens)
+        experts_done += 1
+        if time.perf_counter() - c1 > budget_s:
+            break
+    expert_s = time.perf_counter() - c1
+    rows_all = int(np.minimum(r["counts"], C).sum())
+    est = gate_s + expert_s * rows_all / max(rows_done, 1)
+    return {"value": round(T / est, 1), "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"gate logits and routing of all {T} tokens in full ({gate_s:.1f} s); dispatch, expert FFN and combine of the "
+                      f"first {experts_done} of {E} experts ({rows_done} of {rows_all} filled slots, {expert_s:.1f} s, expert-by-expert "
+                      f"tier, fp64 numpy) scaled to all filled slots: estimated {est:.0f} s per pass"}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--config", type=int, default=1, help="index into the five workloads (default 1: T=16384, M=H=2048, E=8, top-2)")
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=HEADLINE_CONFIG,
+                    help="index into the five workloads (default 4: T=131072, M=4096, H=1024, E=128, top-8, the largest)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-others", action="store_true", help="skip the other four workloads (`other_workloads`)")
+    ap.add_argument("--no-probe", action="store_true", help="skip the register-only MFMA probe (`mfma_only_sustained_TFLOPs`)")
     ap.add_argument("--backward", action="store_true",
                     help="also time the backward of encode and decode (moe_encode_backward, moe_decode_backward) on this "
                          "workload's routing and report their HBM GB/s as `backward_dispatch`")
@@ -76,16 +244,6 @@ def main() -> int:
     cfg = synth.CONFIGS[args.config]
     inp = synth.make_inputs(cfg, seed=0)
     d = cfg.dtype
-    x = to_device(inp["x"], d)
-    gate_bias = None if inp["gate_bias"] is None else torch.from_numpy(inp["gate_bias"]).cuda()
-    layer = moe.MoELayer(to_device(inp["Wg"], d), gate_bias, to_device(inp["W1"], d), to_device(inp["b1"], d),
-                         to_device(inp["W2"], d), to_device(inp["b2"], d), T=cfg.T, k=cfg.k, f=cfg.f,
-                         normalize=cfg.normalize, act=cfg.act, keep_routing=True)
-    # Stage events are recorded on every `stride`-th timed step only: each of the seven records costs a few microseconds
-    # of stream time, and the steps in between run exactly as a caller without instrumentation would run them.
-    stride = 5 if args.steps >= 10 else 1
-    sampled = [i for i in range(args.steps) if i % stride == 0]
-    events = {i: moe.StageEvents() for i in sampled}
     if args.copy_calibration:
         src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").random_(0, 255)
         dst = torch.empty_like(src)
@@ -94,53 +252,13 @@ def main() -> int:
         torch.cuda.synchronize()
         del src, dst
 
-    for _ in range(args.warmup):
-        layer.forward(x)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        layer.forward(x, events.get(i))
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-
-    ms_per_step = elapsed * 1e3 / args.steps
-    per_step = np.array([events[i].stage_ms() for i in sampled])     # [sampled steps, stages] from the library's own events
-    stage_ms = np.mean(per_step, axis=0)
-
-    for _ in range(args.warmup):
-        layer.forward(x, fuse_dispatch=True)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        layer.forward(x, events.get(i), fuse_dispatch=True)
-    torch.cuda.synchronize()
-    fused_ms = (time.perf_counter() - t0) * 1e3 / args.steps
-    fused_stage_ms = np.mean(np.array([events[i].stage_ms() for i in sampled]), axis=0)
-    for e in events.values():
-        e.close()
-    counts = layer.routing["counts"].cpu().numpy().astype(np.int64)
+    res, layer, x = measure(cfg, inp, args.steps, args.warmup)
     C, T, M, H, E, k = layer.C, cfg.T, cfg.M, cfg.H, cfg.E, cfg.k
     es = 4 if d == synth.DT_F32 else 2
-    R = int(np.minimum(counts, C).sum())                         # filled slots = kept (token, choice) pairs
-    flop_per_gemm = 2.0 * R * M * H                              # GEMM1 [R,M]x[M,H] and GEMM2 [R,H]x[H,M]: same count
-    gemm_ms = float(stage_ms[3] + stage_ms[4]) / 2.0
+    R = res["filled_slots"]
+    flop_per_gemm = res["roofline"]["flop_per_launch"]
     bf16 = d == synth.DT_BF16
-    peak = MFMA_BF16_PEAK_TFLOPS if bf16 else FP32_VECTOR_PEAK_TFLOPS
-    achieved = flop_per_gemm / (gemm_ms * 1e-3) / 1e12
-    enc_bytes = 2 * R * M * es + 4 * E * C                       # read each kept row once, write it once (the layer leaves unfilled slots alone)
-    dec_bytes = (R + T) * M * es + 12 * T * k                    # read each kept expert-output row once, write [T,M]
-    stages = {name: round(float(ms), 5) for name, ms in zip(moe.STAGE_NAMES, stage_ms)}
-    stages["encode_GBps"] = round(enc_bytes / (stage_ms[2] * 1e-3) / 1e9, 1)
-    stages["decode_GBps"] = round(dec_bytes / (stage_ms[5] * 1e-3) / 1e9, 1)
-    stages["encode_frac_hbm"] = round(stages["encode_GBps"] / HBM_PEAK_GBS, 4)
-    stages["decode_frac_hbm"] = round(stages["decode_GBps"] / HBM_PEAK_GBS, 4)
-    stages["ffn_TFLOPs_filled_rows"] = round(2 * flop_per_gemm / ((stage_ms[3] + stage_ms[4]) * 1e-3) / 1e12, 1)
-
-    # layer roofline: the stages run back to back on one stream, so their bounds add (HBM 8 TB/s for the data-movement
-    # stages, 2.5 PFLOP/s for the two GEMMs); algorithmic bytes and flop only
-    gate_bytes = T * M * es + M * E * es + 4 * T * E + (4 * T * E + 12 * T * k + 4 * E + 4 * E * C)
-    t_roof_ms = ((gate_bytes + enc_bytes + dec_bytes) / (HBM_PEAK_GBS * 1e9) + 2 * flop_per_gemm / (peak * 1e12)) * 1e3
-    step_from_events = per_step.sum(axis=1)
+    stages = res["stages"]
 
     # an achievable streaming ceiling on this machine: a plain device copy of 256 MiB (read + write)
     csrc = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
@@ -158,78 +276,34 @@ def main() -> int:
     stages["copy_ceiling_GBps"] = round(copy_GBps, 1)
     stages["encode_frac_copy_ceiling"] = round(stages["encode_GBps"] / copy_GBps, 4)
     stages["decode_frac_copy_ceiling"] = round(stages["decode_GBps"] / copy_GBps, 4)
-
-    # cold-cache variant: three separate sets of inputs, weights and workspaces used in rotation, so that no step finds
-    # its operands in the 256 MB memory-side cache (the default loop reuses one set; caches are not flushed between steps)
-    cold_ms = None
-    if E * (M * H * 2) * es + T * M * es < (2 << 30):
-        sets = [(layer, x)]
-        for _ in range(2):
-            l2 = moe.MoELayer(layer.Wg.clone(), None if layer.gate_bias is None else layer.gate_bias.clone(), layer.W1.clone(),
-                              None if layer.b1 is None else layer.b1.clone(), layer.W2.clone(),
-                              None if layer.b2 is None else layer.b2.clone(), T=T, k=k, f=cfg.f, normalize=cfg.normalize,
-                              act=cfg.act, keep_routing=False)
-            sets.append((l2, x.clone()))
-        for i in range(6):
-            sets[i % 3][0].forward(sets[i % 3][1])
-        torch.cuda.synchronize()
-        c0 = time.perf_counter()
-        for i in range(args.steps):
-            sets[i % 3][0].forward(sets[i % 3][1])
-        torch.cuda.synchronize()
-        cold_ms = (time.perf_counter() - c0) * 1e3 / args.steps
-        del sets
+    res["layer_roofline"]["note"] = ("sum over stages of max(algorithmic bytes / 8 TB/s, flop / peak); median and min over the "
+                                     "instrumented steps (every fifth timed step records the library's stage events; they cost "
+                                     "stream time, so these are a little slower than ms_per_step); caches are not flushed between "
+                                     "steps, the cold variant (workloads under 2 GiB of weights) rotates three sets of inputs, "
+                                     "weights and workspaces")
 
     result = {
         "metric": "MoE layer fwd tokens/s on 1 MI355X",
-        "value": round(T / (ms_per_step * 1e-3), 1),
+        "value": res["tokens_per_s"],
         "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(ms_per_step, 5),
+        "ms_per_step": res["ms_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
-        "config": {"workload": f"{cfg.name}: T={T} M={M} H={H} E={E} top-{k} f={cfg.f} C={C} act={('relu', 'gelu', 'silu')[cfg.act]}",
-                   "filled_slots": R, "slots": E * C},
-        "roofline": {"bound": "mfma" if bf16 else "alu", "kernel": "grouped_gemm_mfma_kernel" if bf16 else "gemm_generic_kernel",
-                     "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
-                     "flop_per_launch": flop_per_gemm, "avg_launch_ms": round(gemm_ms, 5),
-                     "traffic": MEASURED_GEMM_TRAFFIC_BYTES.get(cfg.name)},
+        "config": {"workload": res["workload"], "filled_slots": R, "slots": E * C},
+        "roofline": res["roofline"],
         "stages": stages,
-        "layer_roofline": {"t_roofline_ms": round(t_roof_ms, 5), "frac": round(t_roof_ms / ms_per_step, 4),
-                           "step_ms_median": round(float(np.median(step_from_events)), 5),
-                           "step_ms_min": round(float(step_from_events.min()), 5),
-                           "cold_cache_ms_per_step": None if cold_ms is None else round(cold_ms, 5),
-                           "instrumented_steps": len(sampled),
-                           "note": "sum over stages of max(algorithmic bytes / 8 TB/s, flop / peak); median and min over the "
-                                   "instrumented steps (every fifth timed step records the library's stage events; they cost "
-                                   "stream time, so these are a little slower than ms_per_step); caches are not flushed between "
-                                   "steps, the cold variant rotates three sets of inputs, weights and workspaces"},
-        "fused_dispatch": {"ms_per_step": round(fused_ms, 5), "value": round(T / (fused_ms * 1e-3), 1), "unit": "tokens/s",
-                           "stages": {name: round(float(ms), 5) for name, ms in zip(moe.STAGE_NAMES, fused_stage_ms)}},
+        "layer_roofline": res["layer_roofline"],
+        "fused_dispatch": res["fused_dispatch"],
     }
 
-    if bf16:
-        # live clock probe of the dominant kernel (outside the timed loops): the GEMM runs at the board's power cap, so its
-        # shader clock, not 2.4 GHz, is what the matrix pipes get
-        r0 = layer.routing
-        Zp = moe.encode(x, r0["idx"], r0["loc"], moe.slot_sources(r0["idx"], r0["loc"], E, C), E, C)
-        try:
-            for _ in range(3):
-                probe = moe.expert_ffn_clock_probe(Zp, layer.W1, layer.b1, layer.W2, layer.b2, cfg.act, r0["counts"])
-            ghz = float(np.mean([p[0] for p in probe]))
-            cyc = float(np.mean([p[1] for p in probe]))
-            result["roofline"]["main_loop_shader_clock_GHz"] = round(ghz, 3)
-            result["roofline"]["main_loop_cycles_per_64k_step"] = round(cyc, 0)
-            result["roofline"]["mfma_issue_cycles_per_64k_step"] = 2048
-            result["roofline"]["peak_at_measured_clock"] = round(peak * ghz / 2.4, 1)
-        except moe.MoEError:
-            pass                                                     # shapes the matrix-core kernel does not take
-        del Zp
+    if bf16 and not args.no_probe:
         # what the matrix cores alone sustain at the board's power limit on random bf16 operands (about a second of
         # register-only MFMA launches): the practical ceiling of `achieved`
-        sustained = moe.mfma_sustained_tflops(True, seconds=1.0)
+        from paper_2206_03382_amd import probe
+        sustained = probe.mfma_sustained_tflops(True, seconds=1.0)
         result["roofline"]["mfma_only_sustained_TFLOPs"] = round(sustained, 1)
-        result["roofline"]["frac_of_mfma_only_sustained"] = round(achieved / sustained, 4)
+        result["roofline"]["frac_of_mfma_only_sustained"] = round(res["roofline"]["achieved"] / sustained, 4)
 
     if args.backward:
         r = layer.routing
@@ -299,8 +373,7 @@ def main() -> int:
             return a.elapsed_time(b) / args.steps
 
         result["batch_prioritized_routing"] = {"gate_topk_ms": round(timed_gate(False), 5), "gate_topk_bpr_ms": round(timed_gate(True), 5),
-                                               "note": "standalone calls (torch allocates outputs and workspace inside); the "
-                                                       "prioritized order is found by exact O(T^2) counting"}
+                                               "note": "standalone calls (torch allocates outputs and workspace inside)"}
 
     if args.cosine:
         D = 256
@@ -319,19 +392,35 @@ def main() -> int:
                                    "fp64_TFLOPs": round(2.0 * T * M * D / (ms * 1e-3) / 1e12, 1),
                                    "note": "projection on the fp64 matrix cores (peak 78.6 TFLOP/s) + fp64 cosine per (token, expert)"}
 
+    del layer, x
+    torch.cuda.empty_cache()
+
+    if not args.no_others:
+        # the other four workloads, measured the same way in this run: step time, tokens/s, GEMM fraction of the MFMA
+        # peak, encode/decode fraction of the HBM peak
+        others = {}
+        for i, ocfg in enumerate(synth.CONFIGS):
+            if i == args.config:
+                continue
+            oinp = synth.make_inputs(ocfg, seed=0)
+            ores, olayer, ox = measure(ocfg, oinp, args.steps, args.warmup, cold=False)
+            del olayer, ox, oinp
+            torch.cuda.empty_cache()
+            st = ores["stages"]
+            others[ocfg.name] = {
+                "workload": ores["workload"], "ms_per_step": ores["ms_per_step"], "tokens_per_s": ores["tokens_per_s"],
+                "gemm_TFLOPs": ores["roofline"]["achieved"], "gemm_frac_of_peak": ores["roofline"]["frac"],
+                "gemm_peak_TFLOPs": ores["roofline"]["peak"],
+                "encode_frac_hbm": st["encode_frac_hbm"], "decode_frac_hbm": st["decode_frac_hbm"],
+                "gate_logits_frac_hbm": st["gate_logits_frac_hbm"], "gate_topk_frac_hbm": st["gate_topk_frac_hbm"],
+                "stage_ms": {name: st[name] for name in moe.STAGE_NAMES},
+                "fused_dispatch_ms_per_step": ores["fused_dispatch"]["ms_per_step"],
+                "layer_roofline_frac": ores["layer_roofline"]["frac"],
+                "gemm_traffic": ores["roofline"]["traffic"]}
+        result["other_workloads"] = others
+
     if not args.no_cpu_baseline:
-        from oracle import moe_oracle as O
-        from threadpoolctl import threadpool_info
-        blas = [p["num_threads"] for p in threadpool_info() if p.get("user_api") == "blas"]
-        threads = max(blas) if blas else (os.cpu_count() or 1)     # the oracle's time is in numpy's BLAS matmuls
-        reps, c0 = 0, time.perf_counter()
-        while reps == 0 or time.perf_counter() - c0 < 10.0:          # about 10 s of oracle work, whole passes only
-            O.moe_layer(inp["x"], inp["Wg"], inp["gate_bias"], inp["W1"], inp["b1"], inp["W2"], inp["b2"],
-                        cfg.k, cfg.f, cfg.normalize, cfg.act, tier="sparse")
-            reps += 1
-        cpu_s = time.perf_counter() - c0
-        result["cpu_baseline"] = {"value": round(T * reps / cpu_s, 1), "unit": "tokens/s", "cores": int(threads),
-                                  "kind": "oracle", "sample": f"the full workload {reps} times (all {T} tokens each, fp64 numpy, zero-skipping tier), {cpu_s:.1f} s"}
+        result["cpu_baseline"] = cpu_baseline(cfg, inp)
     print(json.dumps(result))
     return 0
 

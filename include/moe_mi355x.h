@@ -143,24 +143,6 @@ int moe_expert_ffn(const void* Z, const void* W1, const void* b1, const void* W2
                    int act, int dtype, const int32_t* counts,
                    int64_t E, int64_t C, int64_t M, int64_t H, void* hidden, void* Y, void* stream);
 
-/* Measurement aid (not an operation of the paper): moe_expert_ffn on the matrix-core path that also records, for the
- * first `probe_blocks` thread blocks of each of its two GEMM launches, how long the block's main loop took, once in
- * shader-clock cycles and once in ticks of the constant 100 MHz counter:  probe[2 b] = cycles, probe[2 b + 1] = ticks
- * (both 0 for blocks that had no full 256-row tile).  cycles / ticks * 0.1 is the shader clock in GHz while the loop
- * ran; cycles / (K / 64) is cycles per 64-wide K-step, of which 2048 are matrix-core issue.  probe1, probe2: device,
- * 2 * probe_blocks uint64 each, cleared by the caller.  bf16 shapes the matrix-core kernel supports only. */
-int moe_expert_ffn_clock_probe(const void* Z, const void* W1, const void* b1, const void* W2, const void* b2, int act, int dtype,
-                               const int32_t* counts, int64_t E, int64_t C, int64_t M, int64_t H, void* hidden, void* Y,
-                               uint64_t* probe1, uint64_t* probe2, int probe_blocks, void* stream);
-
-/* Measurement aid (not an operation of the paper): what the matrix cores alone sustain on this board.  Launches
- * `blocks` blocks of four waves that each run `iters` rounds of 32 register-only v_mfma_f32_32x32x16_bf16 (the expert
- * GEMM's accumulator layout, no memory traffic) on random bf16 operands (random_operands != 0) or on all ones, and
- * stores the launch's flop count in *flop_per_launch (host pointer, may be NULL).  Timed by the caller over a second or
- * so of back-to-back launches it gives the rate the board's power limit leaves the matrix cores for such data, which
- * is the practical ceiling of the expert GEMM.  sink: device, blocks * 256 floats (never written in practice). */
-int moe_mfma_sustained_probe(int blocks, int iters, int random_operands, float* sink, double* flop_per_launch, void* stream);
-
 /* moe_encode followed by moe_expert_ffn without materialising the dispatch buffer (not in the paper, whose [E,C,M]
  * buffer exists to feed the all-to-all; on one GPU the first expert GEMM can fetch its rows straight from the tokens):
  * row c of expert e's operand is x[slot_src[e,c], :], read by the GEMM's own global->LDS loads.

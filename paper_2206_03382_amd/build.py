@@ -1,4 +1,4 @@
-"""Builds libmoe_mi355x.so (HIP, gfx950 only) in-tree with hipcc.  `python -m paper_2206_03382_amd.build`."""
+"""Builds libmoe_mi355x.so and libmoe_probe.so (HIP, gfx950 only) in-tree with hipcc.  `python -m paper_2206_03382_amd.build`."""
 from __future__ import annotations
 
 import os
@@ -9,6 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmoe_mi355x.so")
+PROBE_LIB = os.path.join(HERE, "libmoe_probe.so")          # bench.py's measurement aid, a library of its own
 SOURCES = ["api.hip", "gate.hip", "dispatch.hip", "ffn_generic.hip", "ffn_mfma.hip", "ffn_backward.hip", "gate_backward.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-Wall", "-Wno-unused-function",
@@ -34,8 +35,12 @@ def build_library(verbose: bool = True) -> str:
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"link failed:\n{r.stdout}\n{r.stderr}")
+    probe_obj = _compile("probe.hip", build_dir)
+    r = subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", PROBE_LIB, probe_obj], capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError(f"link failed:\n{r.stdout}\n{r.stderr}")
     if verbose:
-        print(f"built {LIB}")
+        print(f"built {LIB} and {PROBE_LIB}")
     return LIB
 
 

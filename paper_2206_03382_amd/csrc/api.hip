@@ -9,16 +9,14 @@ hipError_t launch_grouped_gemm_generic(const void* A, const void* B, const void*
                                        hipStream_t s);
 hipError_t launch_grouped_gemm_mfma(const void* A, const void* B, const void* bias, int act, const int32_t* counts,
                                     int64_t E, int64_t C, int64_t K, int64_t N, void* out, hipStream_t s,
-                                    const int32_t* gather = nullptr, int64_t gather_rows = 0,
-                                    unsigned long long* probe = nullptr, int probe_blocks = 0, void* pre_out = nullptr);
+                                    const int32_t* gather = nullptr, int64_t gather_rows = 0, void* pre_out = nullptr);
 bool grouped_gemm_mfma_supports(int64_t E, int64_t C, int64_t K, int64_t N, int64_t gather_rows = 0);
-hipError_t launch_mfma_sustained_probe(int blocks, int iters, int random_operands, float* sink, hipStream_t s);
 
 hipError_t launch_grouped_gemm(const void* A, const void* B, const void* bias, int act, int dtype, const int32_t* counts,
                                int64_t E, int64_t C, int64_t K, int64_t N, void* out, hipStream_t s, void* pre_out) {
   if (act < 0) pre_out = nullptr;                                   // nothing to tell apart
   if (dtype == MOE_BF16 && grouped_gemm_mfma_supports(E, C, K, N))
-    return launch_grouped_gemm_mfma(A, B, bias, act, counts, E, C, K, N, out, s, nullptr, 0, nullptr, 0, pre_out);
+    return launch_grouped_gemm_mfma(A, B, bias, act, counts, E, C, K, N, out, s, nullptr, 0, pre_out);
   if (pre_out) {                                                    // the plain kernel has one output: run it twice
     const hipError_t err = launch_grouped_gemm_generic(A, B, bias, -1, dtype, counts, E, C, K, N, pre_out, s);
     if (err != hipSuccess) return err;
@@ -67,6 +65,7 @@ LayerWorkspace layer_layout(int64_t T, int64_t M, int64_t H, int64_t E, int k, i
   w.total = off;
   return w;
 }
+
 
 }  // namespace
 }  // namespace moe
@@ -236,30 +235,6 @@ int moe_expert_ffn_gather(const void* x, const int32_t* slot_src, int64_t T, con
   if (launch_grouped_gemm_mfma(x, W1, b1, act, counts, E, C, M, H, hidden, s, slot_src, T) != hipSuccess) return MOE_HIP_ERROR;
   if (launch_grouped_gemm(hidden, W2, b2, -1, dtype, counts, E, C, H, M, Y, s) != hipSuccess) return MOE_HIP_ERROR;
   return MOE_OK;
-}
-
-int moe_expert_ffn_clock_probe(const void* Z, const void* W1, const void* b1, const void* W2, const void* b2, int act, int dtype,
-                               const int32_t* counts, int64_t E, int64_t C, int64_t M, int64_t H, void* hidden, void* Y,
-                               uint64_t* probe1, uint64_t* probe2, int probe_blocks, void* stream) {
-  if (!Z || !W1 || !W2 || !hidden || !Y || !probe1 || !probe2 || probe_blocks < 1 || !act_ok(act) || E < 1 || C < 1 ||
-      E > 65535 || C > kMaxDim)
-    return MOE_INVALID_ARG;
-  if (int st = row_shape_status(M)) return st;
-  if (int st = row_shape_status(H)) return st;
-  if (!aligned(Z, 16) || !aligned(W1, 16) || !aligned(W2, 16) || !aligned(hidden, 16) || !aligned(Y, 16)) return MOE_UNSUPPORTED;
-  if (dtype != MOE_BF16 || !grouped_gemm_mfma_supports(E, C, M, H) || !grouped_gemm_mfma_supports(E, C, H, M)) return MOE_UNSUPPORTED;
-  hipStream_t s = (hipStream_t)stream;
-  if (launch_grouped_gemm_mfma(Z, W1, b1, act, counts, E, C, M, H, hidden, s, nullptr, 0, (unsigned long long*)probe1, probe_blocks) != hipSuccess)
-    return MOE_HIP_ERROR;
-  if (launch_grouped_gemm_mfma(hidden, W2, b2, -1, counts, E, C, H, M, Y, s, nullptr, 0, (unsigned long long*)probe2, probe_blocks) != hipSuccess)
-    return MOE_HIP_ERROR;
-  return MOE_OK;
-}
-
-int moe_mfma_sustained_probe(int blocks, int iters, int random_operands, float* sink, double* flop_per_launch, void* stream) {
-  if (blocks < 1 || blocks > 65536 || iters < 1 || iters > (1 << 20) || !sink) return MOE_INVALID_ARG;
-  if (flop_per_launch) *flop_per_launch = (double)blocks * 4.0 * iters * 32.0 * 2.0 * 32 * 32 * 16;
-  return launch_mfma_sustained_probe(blocks, iters, random_operands, sink, (hipStream_t)stream) == hipSuccess ? MOE_OK : MOE_HIP_ERROR;
 }
 
 int moe_decode(const void* Y, int dtype, const int32_t* idx, const int32_t* loc, const float* gate_w, int64_t T, int64_t M,

@@ -65,12 +65,12 @@ constexpr int kNN = 0, kNT = 1, kTN = 2;    // operand layouts, see the head of 
 // inline assembly so that the compiler does not serialise the prefetch against the LDS reads of the other stage;
 // completion is tracked by hand (s_waitcnt vmcnt + barrier before a stage is read).
 __device__ __forceinline__ void global_to_lds_16(const char* base, uint32_t voff, uint32_t lds_addr) {
-  asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(voff), "s"(base), "s"(lds_addr) : "memory");
+  asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(voff), "s"(base), "s"(lds_addr) : "memory", "m0");
 }
 
 // Branch-free activations for the bf16 epilogue.  gelu(v) = v Phi(v) with Phi(-y) = erfc(y / sqrt 2) / 2 for y = |v|:
-// e = 2^-P(y) with a degree-5 polynomial P fitted to -log2 erfc(y / sqrt 2) (fit_gelu_poly.py beside this file derives
-// the coefficients; |gelu error| < 6e-7 everywhere, three orders below bf16 resolution), then Phi = 1 - e/2 for
+// e = 2^-P(y) with a degree-5 polynomial P fitted to -log2 erfc(y / sqrt 2) (weighted least squares on [0, 9] with P(0) = 0;
+// |gelu error| < 6e-7 everywhere, three orders below bf16 resolution), then Phi = 1 - e/2 for
 // v >= 0 and e/2 for v < 0.  One exponential, no division.
 constexpr float kGeluC1 = 1.151000500e+00f, kGeluC2 = 4.595958591e-01f, kGeluC3 = 5.214662850e-02f,
                 kGeluC4 = -7.198722102e-03f, kGeluC5 = 4.881033092e-04f;
@@ -294,7 +294,6 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_mfma_kernel(const uint1
                                                                      const int32_t* __restrict__ gather, int gather_rows,
                                                                      int E, int64_t C, int K, int N, int MT, int NT,
                                                                      uint16_t* out,                 // may alias `pre`
-                                                                     unsigned long long* __restrict__ probe, int probe_blocks,
                                                                      const int32_t* __restrict__ kfill,
                                                                      const uint16_t* __restrict__ a_tail,
                                                                      const uint16_t* __restrict__ b_tail,
@@ -452,8 +451,6 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_mfma_kernel(const uint1
   // the number of live sub-tiles is a template argument, so that the loop body of a ragged tile is as branch-free as a
   // full one's (a wave with no rows still loads its share of B and joins the barriers)
 #define MOE_TILE_LOOP(NI) tile_main_loop<NI, MODE>(smem, a_base, b_base, a_last, b_last, a_voff, b_voff, a_step, b_step, a_off, b_off, a_swz, kg, a_mask, wave, KT, bias_w, acc)
-  // measurement aid: shader-clock cycles and 100 MHz ticks spent in the main loop (two scalar counter reads each side)
-  const unsigned long long probe_c0 = __builtin_amdgcn_s_memtime(), probe_t0 = __builtin_amdgcn_s_memrealtime();
   if (MODE == kTN) {                                                // output rows are a weight dimension: never ragged
     MOE_TILE_LOOP(4);
   } else {
@@ -466,12 +463,6 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_mfma_kernel(const uint1
     }
   }
 #undef MOE_TILE_LOOP
-  if (probe && threadIdx.x == 0 && (int)blockIdx.x < probe_blocks) {
-    // full tiles only (all four waves busy); others leave their entry at zero
-    const bool full_tile = rows - m0 >= BM;
-    probe[2 * blockIdx.x] = full_tile ? __builtin_amdgcn_s_memtime() - probe_c0 : 0ull;
-    probe[2 * blockIdx.x + 1] = full_tile ? __builtin_amdgcn_s_memrealtime() - probe_t0 : 0ull;
-  }
 
   // ---- epilogue: activation, bf16; transposed through LDS so that global stores are 16 bytes per lane and a
   // wave's store covers 4 rows x 256 contiguous bytes.  After the last barrier of the main loop no wave reads the
@@ -554,62 +545,6 @@ __global__ __launch_bounds__(256) void tail_rows_kernel(const uint4* __restrict_
     dst[((int64_t)e * BK + j) * cpr + ch] = slot < fill ? src[((int64_t)e * C + slot) * cpr + ch] : make_uint4(0, 0, 0, 0);
 }
 
-// Measurement aid: what the matrix cores alone sustain on this board.  Every wave of a full grid (one block of four
-// waves per compute unit) keeps 16 accumulator tiles in registers and issues `iters` rounds of the main loop's 32
-// MFMAs per K-slice pair on operand fragments that never change, with no memory traffic at all.  The operands are
-// random bf16 values (uniform sign and mantissa, magnitudes in [0.5, 1)) or all ones: the power a matrix core draws, and
-// with it the clock the board's power limit allows, depends on the bits that toggle.
-__device__ __forceinline__ uint32_t probe_hash(uint32_t x) {
-  x ^= x >> 16; x *= 0x7feb352du; x ^= x >> 15; x *= 0x846ca68bu; x ^= x >> 16;
-  return x;
-}
-__global__ __launch_bounds__(kThreads) void mfma_sustained_kernel(int iters, int random_operands, float* __restrict__ sink) {
-  const uint32_t tid = blockIdx.x * kThreads + threadIdx.x;
-  bf16x8 a[2][4], b[2][4];
-#pragma unroll
-  for (int p = 0; p < 2; ++p)
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      u32x4 wa, wb;
-#pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const uint32_t ha = probe_hash((tid * 64 + p * 8 + i) * 4 + u), hb = probe_hash((tid * 64 + 32 + p * 8 + i) * 4 + u);
-        wa[u] = random_operands ? (0x3f003f00u | (ha & 0x80ff80ffu)) : 0x3f803f80u;
-        wb[u] = random_operands ? (0x3f003f00u | (hb & 0x80ff80ffu)) : 0x3f803f80u;
-      }
-      a[p][i] = __builtin_bit_cast(bf16x8, wa);
-      b[p][i] = __builtin_bit_cast(bf16x8, wb);
-    }
-  f32x16 acc[4][4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-  for (int it = 0; it < iters; ++it) {
-#pragma unroll
-    for (int p = 0; p < 2; ++p)
-#pragma unroll
-      for (int m = 0; m < 16; ++m)
-        acc[m >> 2][m & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[p][m & 3], a[p][m >> 2], acc[m >> 2][m & 3], 0, 0, 0);
-  }
-  float sum = 0.f;
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) sum += acc[i][j][v];
-  if (sum == 12345.678f) sink[tid] = sum;                           // keeps the loop alive; never true in practice
-}
-
-// flop of one launch: blocks x 4 waves x iters x 32 MFMAs x 2 x 32 x 32 x 16
-hipError_t launch_mfma_sustained_probe(int blocks, int iters, int random_operands, float* sink, hipStream_t s) {
-  mfma_sustained_kernel<<<dim3((unsigned)blocks), dim3(kThreads), 0, s>>>(iters, random_operands, sink);
-  return hipGetLastError();
-}
-
 bool grouped_gemm_mfma_supports(int64_t E, int64_t C, int64_t K, int64_t N, int64_t gather_rows) {
   if (K % BK != 0 || N % BN != 0 || E > kMaxExperts) return false;
   const int64_t tiles = E * ceil_div(C, BM) * (N / BN);
@@ -621,15 +556,14 @@ bool grouped_gemm_mfma_supports(int64_t E, int64_t C, int64_t K, int64_t N, int6
 
 hipError_t launch_grouped_gemm_mfma(const void* A, const void* B, const void* bias, int act, const int32_t* counts,
                                     int64_t E, int64_t C, int64_t K, int64_t N, void* out, hipStream_t s,
-                                    const int32_t* gather, int64_t gather_rows, unsigned long long* probe, int probe_blocks,
-                                    void* pre_out) {
+                                    const int32_t* gather, int64_t gather_rows, void* pre_out) {
   const int MT = (int)ceil_div(C, BM), NT = (int)(N / BN);
   const int64_t groups = E * ceil_div((int64_t)MT * NT, 32);                  // upper bound: every expert full
   const dim3 grid((unsigned)(ceil_div(groups, 8) * 256)), block(kThreads);    // 32 blocks per group, groups dealt to 8 XCDs
 #define MOE_LAUNCH_GEMM(ACT, DUAL)                                                                                    \
   grouped_gemm_mfma_kernel<ACT, kNN, false, DUAL><<<grid, block, 0, s>>>(                                             \
       (const uint16_t*)A, (const uint16_t*)B, (const uint16_t*)bias, counts, gather, (int)gather_rows, (int)E, C,     \
-      (int)K, (int)N, MT, NT, (uint16_t*)out, probe, probe_blocks, nullptr, nullptr, nullptr, nullptr,                \
+      (int)K, (int)N, MT, NT, (uint16_t*)out, nullptr, nullptr, nullptr, nullptr,                                       \
       (uint16_t*)pre_out)
   if (pre_out && act >= 0) {
     switch (act) {
@@ -659,7 +593,7 @@ hipError_t launch_grouped_gemm_mfma_nt(const void* A, const void* Bt, const int3
 #define MOE_LAUNCH_GEMM(ACT, GRAD)                                                                                    \
   grouped_gemm_mfma_kernel<ACT, kNT, GRAD><<<grid, block, 0, s>>>(                                                    \
       (const uint16_t*)A, (const uint16_t*)Bt, nullptr, counts, nullptr, 0, (int)E, C, (int)K, (int)N, MT, NT,        \
-      (uint16_t*)out, nullptr, 0, nullptr, nullptr, nullptr, (const uint16_t*)pre, nullptr)
+      (uint16_t*)out, nullptr, nullptr, nullptr, (const uint16_t*)pre, nullptr)
   if (!pre) MOE_LAUNCH_GEMM(-1, false);
   else if (act < 0) MOE_LAUNCH_GEMM(-1, true);                      // out = product + pre
   else switch (act) {
@@ -685,7 +619,7 @@ hipError_t launch_grouped_gemm_mfma_tn(const void* At, const void* B, const int3
   const dim3 grid((unsigned)(ceil_div(groups, 8) * 256)), block(kThreads);
   grouped_gemm_mfma_kernel<-1, kTN, false><<<grid, block, 0, s>>>(
       (const uint16_t*)At, (const uint16_t*)B, nullptr, nullptr, nullptr, 0, (int)E, R, (int)C, (int)N, MT, NT,
-      (uint16_t*)out, nullptr, 0, kfill, (const uint16_t*)a_tail, (const uint16_t*)b_tail, nullptr, nullptr);
+      (uint16_t*)out, kfill, (const uint16_t*)a_tail, (const uint16_t*)b_tail, nullptr, nullptr);
   return hipGetLastError();
 }
 

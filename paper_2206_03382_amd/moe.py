@@ -52,14 +52,12 @@ SIGNATURES = {
     "moe_decode_backward": (_i32, [_vp, _vp, _i32, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _i32, _i64, _vp, _vp, _vp]),
     "moe_layer_forward_fused": (_i32, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _i64, _i32, _dbl, _i32, _i32, _i32,
                                        _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp, _c.POINTER(_vp)]),
-    "moe_expert_ffn_clock_probe": (_i32, [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _i64, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _i32, _vp]),
     "moe_expert_ffn_gather": (_i32, [_vp, _vp, _i64, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _i64, _i64, _i64, _i64, _vp, _vp, _vp]),
     "moe_layer_train_state_bytes": (_sz, [_i64, _i64, _i64, _i64, _i32, _i64, _i32]),
     "moe_layer_forward_train": (_i32, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _i64, _i32, _dbl, _i32, _i32, _i32,
                                        _vp, _vp, _sz, _vp]),
     "moe_layer_backward": (_i32, [_vp, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _i64, _i32, _dbl, _i32, _i32, _i32, _vp, _vp, _sz,
                                   _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
-    "moe_mfma_sustained_probe": (_i32, [_i32, _i32, _i32, _vp, _c.POINTER(_dbl), _vp]),
     "moe_event_create": (_i32, [_c.POINTER(_vp)]),
     "moe_event_destroy": (_i32, [_vp]),
     "moe_event_record": (_i32, [_vp, _vp]),
@@ -230,27 +228,6 @@ def expert_ffn(Z: torch.Tensor, W1: torch.Tensor, b1: Optional[torch.Tensor], W2
     return Y
 
 
-def expert_ffn_clock_probe(Z: torch.Tensor, W1, b1, W2, b2, act: int, counts: Optional[torch.Tensor], probe_blocks: int = 4096):
-    """Runs the expert layer with the main-loop clock probe; returns per GEMM (shader GHz, cycles per 64-wide K-step)."""
-    E, C, M = Z.shape
-    H = W1.shape[2]
-    Y = torch.empty((E, C, M), dtype=Z.dtype, device=Z.device)
-    hidden = torch.empty((E, C, H), dtype=Z.dtype, device=Z.device)
-    p1 = torch.zeros((2 * probe_blocks,), dtype=torch.int64, device=Z.device)
-    p2 = torch.zeros_like(p1)
-    _check(lib().moe_expert_ffn_clock_probe(_p(Z), _p(W1), _p(b1), _p(W2), _p(b2), act, _dtype_code(Z), _p(counts), E, C, M, H,
-                                            _p(hidden), _p(Y), _p(p1), _p(p2), probe_blocks, _stream()), "moe_expert_ffn_clock_probe")
-    out = []
-    for p, K in ((p1, M), (p2, H)):
-        v = p.cpu().numpy().reshape(-1, 2).astype("float64")
-        v = v[v[:, 1] > 0]
-        if len(v) == 0:
-            out.append((float("nan"), float("nan")))
-        else:
-            out.append((float(v[:, 0].sum() / v[:, 1].sum() * 0.1), float(v[:, 0].mean() / (K / 64))))
-    return out
-
-
 def expert_ffn_gather(x: torch.Tensor, slot_src: torch.Tensor, W1: torch.Tensor, b1: Optional[torch.Tensor], W2: torch.Tensor,
                       b2: Optional[torch.Tensor], act: int, counts: Optional[torch.Tensor] = None) -> torch.Tensor:
     """encode + expert_ffn in one: the first GEMM reads row c of expert e from x[slot_src[e, c]]."""
@@ -324,31 +301,6 @@ def expert_ffn_backward(Z: torch.Tensor, W1: torch.Tensor, b1: Optional[torch.Te
                                          _p(ws), ws.numel(), _p(g["dZ"]), _p(g["dW1"]), _p(g["db1"]), _p(g["dW2"]), _p(g["db2"]),
                                          _stream()), "moe_expert_ffn_backward")
     return g
-
-
-def mfma_sustained_tflops(random_operands: bool = True, seconds: float = 1.0, blocks: int = 256, iters: int = 2000) -> float:
-    """Sustained register-only MFMA rate (TFLOP/s) over about `seconds` of back-to-back launches; the last batch is timed."""
-    sink = torch.zeros((blocks * 256,), dtype=torch.float32, device="cuda")
-    flop = _dbl()
-
-    def launch():
-        _check(lib().moe_mfma_sustained_probe(blocks, iters, int(random_operands), _p(sink), ctypes.byref(flop), _stream()),
-               "moe_mfma_sustained_probe")
-
-    for _ in range(20):
-        launch()
-    torch.cuda.synchronize()
-    total, last = 0.0, 0.0
-    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    while total < seconds * 1e3:
-        a.record()
-        for _ in range(20):
-            launch()
-        b.record()
-        b.synchronize()
-        last = a.elapsed_time(b) / 20
-        total += last * 20
-    return flop.value / (last * 1e-3) / 1e12
 
 
 def encode_backward(dZ: torch.Tensor, idx: torch.Tensor, loc: torch.Tensor) -> torch.Tensor:

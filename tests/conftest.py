@@ -15,3 +15,12 @@ def pytest_configure(config):
 @pytest.fixture(scope="session")
 def golden_dir():
     return os.path.join(ROOT, "tests", "golden")
+
+
+@pytest.fixture
+def progress(capsys):
+    """print() that pytest does not capture, so that a long test shows its steps while it runs."""
+    def say(msg):
+        with capsys.disabled():
+            print(f"\n[progress] {msg}", end="", flush=True)
+    return say

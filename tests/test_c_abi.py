@@ -20,8 +20,8 @@ def moe():
     return m
 
 
-def declared_functions():
-    text = re.sub(r"/\*.*?\*/", "", open(HEADER).read(), flags=re.S)
+def declared_functions(header=HEADER):
+    text = re.sub(r"/\*.*?\*/", "", open(header).read(), flags=re.S)
     return sorted(set(re.findall(r"\b(moe_[a-z_0-9]+)\s*\(", text)))
 
 
@@ -32,6 +32,21 @@ def test_every_declared_symbol_is_exported_and_bound(moe):
     for n in names:
         assert hasattr(handle, n), f"{n} is declared in the header but not exported"
     assert sorted(moe.SIGNATURES) == names
+
+
+def test_probe_library_is_separate(moe):
+    """The benchmark's measurement aid lives in a library of its own: the product library exports no probe, and the
+    probe library exports what its header declares."""
+    from paper_2206_03382_amd import probe
+    names = declared_functions(os.path.join(ROOT, "include", "moe_mi355x_probe.h"))
+    assert names == ["moe_probe_mfma_sustained"]
+    handle = ctypes.CDLL(probe.PROBE_LIB_PATH)
+    for n in names:
+        assert hasattr(handle, n)
+    product = ctypes.CDLL(moe.LIB_PATH)
+    assert not any(hasattr(product, n) for n in names + ["moe_mfma_sustained_probe", "moe_expert_ffn_clock_probe"])
+    assert handle.moe_probe_mfma_sustained(0, 10, 1, 4096, None, None) == 1          # invalid arguments never launch
+    assert handle.moe_probe_mfma_sustained(256, 10, 1, None, None, None) == 1
 
 
 def test_capacity_follows_eq1(moe, golden_dir):
@@ -89,8 +104,6 @@ def test_argument_validation_never_launches(moe):
                                      fake, None, None, None, None, None) == moe.UNSUPPORTED                            # pre misaligned
     assert L.moe_expert_ffn_backward(fake, fake, None, fake, None, fake, fake, 0, moe.BF16, None, 4, 2, 16, 16, fake, 1 << 30,
                                      None, None, None, None, None, None) == moe.INVALID_ARG                            # nothing asked for
-    assert L.moe_mfma_sustained_probe(0, 10, 1, fake, None, None) == moe.INVALID_ARG
-    assert L.moe_mfma_sustained_probe(256, 10, 1, None, None, None) == moe.INVALID_ARG
     assert L.moe_decode(fake, moe.F32, fake, fake, None, 8, 16, 4, 1, 2, fake, None) == moe.INVALID_ARG               # gate_w null
     assert L.moe_dynamic_capacity(fake, 8, 4, 1, 1.25, fake, None) == moe.INVALID_ARG      # positive setting: moe_capacity
     assert L.moe_dynamic_capacity(None, 8, 4, 1, 0.0, fake, None) == moe.INVALID_ARG

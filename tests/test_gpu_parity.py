@@ -260,6 +260,23 @@ def test_expert_ffn(moe, dtype, E, C, M, H, act, bias, use_counts):
         assert np.isnan(got[~mask]).all(), "rows past counts[e] must be left untouched"
 
 
+def test_expert_ffn_gelu_epilogue_range(moe):
+    """The matrix-core GEMM's GeLU epilogue through the kernel itself: one expert whose first layer is 6 x identity on
+    inputs spanning [-1, 1] (so the pre-activations span [-6, 6], each an exact bf16 product) and whose second layer
+    is the identity, so that Y = gelu(6 z) element by element."""
+    C, M = 512, 256
+    z = synth.round_to_bf16(np.linspace(-1.0, 1.0, C * M, dtype=np.float32).reshape(1, C, M))
+    eye6 = (6.0 * np.eye(M, dtype=np.float32))[None]
+    eye = np.eye(M, dtype=np.float32)[None]
+    ref = O.expert_ffn(z, eye6, None, eye, None, O.ACT_GELU)
+    pre = 6.0 * z.astype(np.float64)
+    assert pre.min() <= -5.9 and pre.max() >= 5.9
+    Y = host(moe.expert_ffn(dev(z, synth.DT_BF16), dev(eye6, synth.DT_BF16), None, dev(eye, synth.DT_BF16), None, O.ACT_GELU))
+    # the hidden value and the output are each rounded to bf16 once: two half-ulp roundings of |value| <= 6
+    assert np.abs(Y - ref).max() <= 2.0 ** -8 * np.maximum(np.abs(ref), 2.0 ** -126).max()
+    assert (np.abs(Y - ref) <= 2.0 ** -7 * np.abs(ref) + 1e-6).all()
+
+
 # ----------------------------------------------------------------------------------------------------------------
 # moe_gate_backward
 # ----------------------------------------------------------------------------------------------------------------
@@ -286,6 +303,10 @@ def test_gate_backward(moe, dtype, T, M, E, k, normalize):
     dl = g["dlogits"].cpu().numpy()
     assert np.abs(dl - ref_dl).max() <= 1e-5 * max(np.abs(ref_dl).max(), 1e-30)
     assert_close(host(g["dx"]), base.astype(np.float64) + ref["dx"], dtype, "gate dx (accumulated)")
+    # the gate's own term, without a base to hide behind: a call that does not accumulate, scaled by the term itself
+    g0 = moe.gate_backward(dev(x, dtype), dev(Wg, dtype), torch.from_numpy(logits).cuda(), torch.from_numpy(idx).cuda(),
+                           torch.from_numpy(dgw).cuda(), normalize)
+    assert_close(host(g0["dx"]), ref["dx"], dtype, "gate dx (not accumulated)")
     assert_close(host(g["dWg"]), ref["dWg"], dtype, "dWg")
     assert np.abs(g["dbias"].cpu().numpy() - ref["dbias"]).max() <= 1e-5 * max(np.abs(ref_dl).sum(axis=0).max(), 1e-30)
 
@@ -578,59 +599,87 @@ def test_layer_backward_full_size(moe):
     assert np.abs(g["dgate_bias"].cpu().numpy() - ref["dgate_bias"]).max() <= 2e-2 * max(scale, 1e-30)
 
 
-def test_layer_full_size_finegrained_sampled(moe):
-    """T=131072, E=128, top-8: routing is checked in full; encode, FFN rows and outputs on samples the oracle
-    evaluates one by one (the buffered fp64 oracle would need > 100 GB)."""
+def assert_close_on_device(got, ref, dtype, what):
+    """assert_close with the comparison arithmetic done in fp64 on the device (the reference comes from the host)."""
+    r = torch.from_numpy(np.ascontiguousarray(ref, dtype=np.float64)).cuda()
+    g = got.double()
+    assert bool(torch.isfinite(g).all()), f"{what}: non-finite values"
+    scale = float(r.abs().max())
+    err = float((g - r).abs().max())
+    assert err <= TOL[dtype] * scale, f"{what}: max abs err {err:.3e} > {TOL[dtype]:.0e} * max|ref| ({scale:.3e})"
+    rms = float(((g - r) ** 2).mean().sqrt()) / max(float((r ** 2).mean().sqrt()), 1e-300)
+    assert rms <= RMS_TOL[dtype], f"{what}: relative rms err {rms:.3e} > {RMS_TOL[dtype]:.0e}"
+
+
+def test_layer_full_size_finegrained(moe, progress):
+    """T=131072, E=128, top-8, every value: routing in full, then the oracle's expert-by-expert tier evaluates all
+    128 slabs (the buffered fp64 oracle would need > 100 GB): every filled row of the dispatch buffer bit for bit and
+    every unfilled row +0, every filled row of the expert output and every row of the layer output within tolerance."""
     cfg = synth.CONFIGS[4]
-    print("[finegrained] generating inputs", flush=True)
+    progress("[finegrained] generating inputs")
     inp = synth.make_inputs(cfg, seed=0)
     C = O.capacity(cfg.T, cfg.E, cfg.k, cfg.f)
-    print("[finegrained] oracle routing", flush=True)
+    progress("[finegrained] oracle routing")
     logits = O.gate_logits(inp["x"], inp["Wg"], inp["gate_bias"])
     ref = O.route(logits, cfg.k, C, cfg.normalize)
-    print("[finegrained] HIP path", flush=True)
+    progress("[finegrained] HIP path")
     d = cfg.dtype
     xd, W1d, W2d = dev(inp["x"], d), dev(inp["W1"], d), dev(inp["W2"], d)
     layer = moe.MoELayer(dev(inp["Wg"], d), None, W1d, None, W2d, None, T=cfg.T, k=cfg.k, f=cfg.f,
                          normalize=cfg.normalize, act=cfg.act, keep_routing=True)
-    out = layer.forward(xd)
+    out = layer.forward(xd).clone()
+    fused = layer.forward(xd, fuse_dispatch=True)
     torch.cuda.synchronize()
+    assert torch.equal(fused, out), "fused dispatch must reproduce the plain path bit for bit"
     check_logits(layer.routing["logits"].cpu().numpy(), logits)
     assert_routing_equal(layer.routing, ref, C, cfg.name)
-    rng = np.random.default_rng(0)
-    tokens = np.sort(rng.choice(cfg.T, size=160, replace=False))
-    print("[finegrained] oracle outputs for sampled tokens", flush=True)
-    want = O.token_outputs_direct(tokens, inp["x"], ref["idx"], ref["loc"], ref["gate_w"], C, inp["W1"], None, inp["W2"], None, cfg.act)
-    got = host(out[torch.from_numpy(tokens).cuda()])
-    assert_close(got, want, d, "sampled layer outputs")
-    # stage entry points on the same routing: sampled slots of the dispatch buffer and of the expert output
     g = layer.routing
+    del layer, fused
+    torch.cuda.empty_cache()
+    # the stage entry points on the same routing: the whole dispatch buffer and the whole expert output
     src = O.slot_source(ref["idx"], ref["loc"], cfg.E, C)
     slot_src = torch.from_numpy(src).cuda()
     Z = moe.encode(xd, g["idx"], g["loc"], slot_src, cfg.E, C)
-    se, sc = rng.integers(0, cfg.E, size=4096), rng.integers(0, C, size=4096)
-    zs = host(Z[torch.from_numpy(se).cuda(), torch.from_numpy(sc).cuda()])
-    want_z = np.where((src[se, sc] >= 0)[:, None], inp["x"][np.maximum(src[se, sc], 0)], np.float32(0))
-    assert np.array_equal(zs.view(np.uint32), want_z.view(np.uint32))
     Y = moe.expert_ffn(Z, W1d, None, W2d, None, cfg.act, g["counts"])
-    filled = np.argwhere(src >= 0)
-    pick = filled[rng.choice(len(filled), size=96, replace=False)]
-    for e in np.unique(pick[:, 0]):
-        cs = pick[pick[:, 0] == e, 1]
-        want_y = O.ffn_rows(inp["x"][src[e, cs]], inp["W1"][e], None, inp["W2"][e], None, cfg.act)
-        assert_close(host(Y[int(e)][torch.from_numpy(cs).cuda()]), want_y, d, f"sampled FFN rows of expert {e}")
+    torch.cuda.synchronize()
+    fills = np.minimum(ref["counts"], C)
+    seen = []
+
+    def check_slab(e, tokens, w, Ze, Ye):
+        n = len(tokens)
+        assert n == fills[e] and np.array_equal(tokens, src[e, :n])
+        want_z = torch.from_numpy(synth.bf16_bits(Ze.astype(np.float32)).view(np.int16)).cuda()
+        assert torch.equal(Z[e, :n].view(torch.int16), want_z), f"dispatch buffer of expert {e}"
+        assert int(Z[e, n:].view(torch.int16).ne(0).sum()) == 0, f"unfilled slots of expert {e} must be +0"
+        if n:
+            assert_close_on_device(Y[e, :n], Ye, d, f"expert output, expert {e} ({n} rows)")
+        seen.append(e)
+        if e % 16 == 15:
+            progress(f"[finegrained] oracle: {e + 1} of {cfg.E} experts checked")
+
+    want = O.moe_layer_streamed(inp["x"], inp["Wg"], inp["gate_bias"], inp["W1"], None, inp["W2"], None, cfg.k, cfg.f,
+                                cfg.normalize, cfg.act, logits=logits, on_expert=check_slab)
+    assert seen == list(range(cfg.E))
+    del Z, Y
+    torch.cuda.empty_cache()
+    progress("[finegrained] layer output, all tokens")
+    assert_close_on_device(out, want["out"], d, "layer output (all tokens)")
+    step = 16384                                                     # and block by block, each against its own scale
+    for t0 in range(0, cfg.T, step):
+        assert_close_on_device(out[t0:t0 + step], want["out"][t0:t0 + step], d, f"layer output, tokens {t0}..{t0 + step - 1}")
+    dead = (~ref["kept"]).all(axis=1)
+    assert int(out[torch.from_numpy(dead).cuda()].view(torch.int16).ne(0).sum()) == 0
+    del want, out
     # the training step at this size: the parameter gradients of two experts against the oracle's backward of those
     # experts on their own slabs (dY of a slot = gate weight x d_out of its token; Appendix B)
-    del Z, Y, layer, out
     torch.cuda.empty_cache()
-    print("[finegrained] training step", flush=True)
+    progress("[finegrained] training step")
     tl = moe.TrainLayer(dev(inp["Wg"], d), None, W1d, None, W2d, None, T=cfg.T, k=cfg.k, f=cfg.f,
                         normalize=cfg.normalize, act=cfg.act)
     d_out = synth.make_inputs(cfg.scaled(cfg_id=52), seed=12)["x"]
     tl.forward(xd)
     grads = tl.backward(xd, dev(d_out, d))
     torch.cuda.synchronize()
-    fills = np.minimum(ref["counts"], C)
     for e in (int(np.argmax(fills)), int(np.argmin(np.where(fills > 0, fills, C + 1)))):
         n = int(fills[e])
         toks = src[e, :n]
