@@ -31,7 +31,8 @@
 extern "C" {
 #endif
 
-enum { MOE_OK = 0, MOE_INVALID_ARG = 1, MOE_UNSUPPORTED = 2, MOE_WORKSPACE_TOO_SMALL = 3, MOE_HIP_ERROR = 4 };
+enum { MOE_OK = 0, MOE_INVALID_ARG = 1, MOE_UNSUPPORTED = 2, MOE_WORKSPACE_TOO_SMALL = 3, MOE_HIP_ERROR = 4,
+       MOE_SCRATCH_TOO_SMALL = 5 };
 enum { MOE_F32 = 0, MOE_BF16 = 1 };
 enum { MOE_ACT_RELU = 0, MOE_ACT_GELU = 1, MOE_ACT_SILU = 2 };
 
@@ -93,6 +94,18 @@ int moe_gate_logits_cosine(const void* x, const void* Wp, const float* Me, doubl
 int moe_gate_topk(const float* logits, int64_t T, int64_t E, int k, int64_t C, int normalize,
                   int32_t* idx, float* gate_w, int32_t* loc, int32_t* counts, int32_t* slot_src,
                   void* ws, size_t ws_bytes, void* stream);
+
+/* moe_gate_topk for callers that cannot allocate device memory or bring a workspace (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): the same kernels and the same outputs, with the arrival
+ * counters in a device array of fixed size that the library holds on every GPU it runs on until the process ends.
+ * Calls no hipMalloc, hipFree or other allocating routine.  Arguments as moe_gate_topk, without ws / ws_bytes.
+ * Limit: moe_gate_workspace_bytes(T, E, k) <= moe_gate_topk_static_max_bytes() (8 MiB: k * ceil(T / 64) * E <= 2^21),
+ * else MOE_SCRATCH_TOO_SMALL and nothing is launched.  Every call on one GPU shares that GPU's array: calls that
+ * overlap on one GPU (different streams, or threads) race; order them on one stream or with events.  Nothing in the
+ * array has to start from zero (each call writes every counter before reading it). */
+size_t moe_gate_topk_static_max_bytes(void);
+int moe_gate_topk_static(const float* logits, int64_t T, int64_t E, int k, int64_t C, int normalize,
+                         int32_t* idx, float* gate_w, int32_t* loc, int32_t* counts, int32_t* slot_src, void* stream);
 
 /* Bytes of workspace moe_gate_topk_bpr needs.  0 on invalid arguments or T > 2^18. */
 size_t moe_gate_bpr_workspace_bytes(int64_t T, int64_t E, int k);

@@ -1,5 +1,6 @@
 // C ABI of the MoE hot-path library: argument validation, workspace layout, stage sequencing.
 #include <cmath>
+#include <mutex>
 
 #include "common.h"
 
@@ -67,6 +68,28 @@ LayerWorkspace layer_layout(int64_t T, int64_t M, int64_t H, int64_t E, int k, i
 }
 
 
+// Scratch of the entry point that allocates nothing (moe_gate_topk_static): the gate's per-block arrival counters live
+// in a file-scope device array instead of a caller's workspace.  Every GPU the library runs on holds its own copy at its
+// own address; host code must use the address hipGetSymbolAddress returns for the current device, never the array's name.
+constexpr size_t kStaticScratchBytes = (size_t)8 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices] = {};
+std::mutex g_scratch_mutex;
+
+// Device address of `scratch` on the current device (looked up once per device), or nullptr on failure.
+void* static_scratch_ptr() {
+  int device = -1;
+  if (hipGetDevice(&device) != hipSuccess || device < 0 || device >= kMaxDevices) return nullptr;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[device]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return nullptr;
+    g_scratch_ptr[device] = p;
+  }
+  return g_scratch_ptr[device];
+}
+
 }  // namespace
 }  // namespace moe
 
@@ -81,6 +104,7 @@ const char* moe_status_string(int status) {
     case MOE_UNSUPPORTED: return "unsupported shape, dtype or alignment";
     case MOE_WORKSPACE_TOO_SMALL: return "workspace too small";
     case MOE_HIP_ERROR: return "HIP runtime error";
+    case MOE_SCRATCH_TOO_SMALL: return "problem too large for the library's static scratch buffer";
     default: return "unknown status";
   }
 }
@@ -137,6 +161,20 @@ int moe_gate_topk(const float* logits, int64_t T, int64_t E, int k, int64_t C, i
   if (int st = gate_shape_status(T, E, k)) return st;
   if (!aligned(ws, 16)) return MOE_UNSUPPORTED;
   if (ws_bytes < moe_gate_workspace_bytes(T, E, k)) return MOE_WORKSPACE_TOO_SMALL;
+  return launch_gate_topk(logits, T, E, k, C, normalize, idx, gate_w, loc, counts, slot_src, (int32_t*)ws,
+                          (hipStream_t)stream) == hipSuccess ? MOE_OK : MOE_HIP_ERROR;
+}
+
+size_t moe_gate_topk_static_max_bytes(void) { return kStaticScratchBytes; }
+
+int moe_gate_topk_static(const float* logits, int64_t T, int64_t E, int k, int64_t C, int normalize, int32_t* idx, float* gate_w,
+                         int32_t* loc, int32_t* counts, int32_t* slot_src, void* stream) {
+  if (!logits || !idx || !gate_w || !loc || !counts || C < 1 || C > kMaxDim) return MOE_INVALID_ARG;
+  if (int st = gate_shape_status(T, E, k)) return st;
+  if (moe_gate_workspace_bytes(T, E, k) > kStaticScratchBytes) return MOE_SCRATCH_TOO_SMALL;
+  void* ws = static_scratch_ptr();
+  if (!ws) return MOE_HIP_ERROR;
+  // the kernels write every counter they later read, so the last call's contents need no clearing
   return launch_gate_topk(logits, T, E, k, C, normalize, idx, gate_w, loc, counts, slot_src, (int32_t*)ws,
                           (hipStream_t)stream) == hipSuccess ? MOE_OK : MOE_HIP_ERROR;
 }

@@ -12,7 +12,7 @@ from typing import Tuple, Dict, Optional, Sequence
 
 import torch
 
-OK, INVALID_ARG, UNSUPPORTED, WORKSPACE_TOO_SMALL, HIP_ERROR = range(5)
+OK, INVALID_ARG, UNSUPPORTED, WORKSPACE_TOO_SMALL, HIP_ERROR, SCRATCH_TOO_SMALL = range(6)
 F32, BF16 = 0, 1
 ACT_RELU, ACT_GELU, ACT_SILU = 0, 1, 2
 NUM_STAGE_EVENTS = 7
@@ -33,6 +33,8 @@ SIGNATURES = {
     "moe_cosine_gate_workspace_bytes": (_sz, [_i64, _i64, _i64]),
     "moe_gate_logits_cosine": (_i32, [_vp, _vp, _vp, _dbl, _i32, _i64, _i64, _i64, _i64, _vp, _vp, _sz, _vp]),
     "moe_gate_topk": (_i32, [_vp, _i64, _i64, _i32, _i64, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "moe_gate_topk_static_max_bytes": (_sz, []),
+    "moe_gate_topk_static": (_i32, [_vp, _i64, _i64, _i32, _i64, _i32, _vp, _vp, _vp, _vp, _vp, _vp]),
     "moe_gate_bpr_workspace_bytes": (_sz, [_i64, _i64, _i32]),
     "moe_gate_topk_bpr": (_i32, [_vp, _i64, _i64, _i32, _i64, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "moe_dynamic_capacity": (_i32, [_vp, _i64, _i64, _i32, _dbl, _vp, _vp]),
@@ -167,6 +169,14 @@ def gate_topk(logits: torch.Tensor, k: int, C: int, normalize: int, want_slot_sr
     _check(entry(_p(logits), T, E, k, C, int(normalize), _p(idx), _p(gate_w), _p(loc), _p(counts), _p(slot_src),
                  _p(ws), ws.numel(), _stream()), "moe_gate_topk_bpr" if bpr else "moe_gate_topk")
     return dict(idx=idx, loc=loc, gate_w=gate_w, counts=counts, slot_src=slot_src)
+
+
+def gate_topk_static(logits: torch.Tensor, k: int, C: int, normalize: int, out: Dict[str, torch.Tensor]) -> Dict[str, torch.Tensor]:
+    """moe_gate_topk_static into caller-provided outputs (idx, loc, gate_w, counts, slot_src): nothing is allocated."""
+    T, E = logits.shape
+    _check(lib().moe_gate_topk_static(_p(logits), T, E, k, C, int(normalize), _p(out["idx"]), _p(out["gate_w"]), _p(out["loc"]),
+                                      _p(out["counts"]), _p(out.get("slot_src")), _stream()), "moe_gate_topk_static")
+    return out
 
 
 def dynamic_capacity(counts: torch.Tensor, T: int, k: int, capacity_setting: float) -> Tuple[int, int]:
