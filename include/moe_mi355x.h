@@ -35,6 +35,7 @@ enum { MOE_OK = 0, MOE_INVALID_ARG = 1, MOE_UNSUPPORTED = 2, MOE_WORKSPACE_TOO_S
        MOE_SCRATCH_TOO_SMALL = 5 };
 enum { MOE_F32 = 0, MOE_BF16 = 1 };
 enum { MOE_ACT_RELU = 0, MOE_ACT_GELU = 1, MOE_ACT_SILU = 2 };
+enum { MOE_ROUTER_LINEAR = 0, MOE_ROUTER_COSINE = 1 };
 
 /* Number of events moe_layer_forward records when `stage_events` is given:
  * [0] start, [1] after gate logits, [2] after top-k + slot assignment, [3] after encode,
@@ -126,8 +127,9 @@ int moe_gate_topk_bpr(const float* logits, int64_t T, int64_t E, int k, int64_t 
  *   counts [E] int32 (device): un-truncated arrivals from moe_gate_topk (which may be called with slot_src = NULL and
  *          any valid C: idx, gate_w, loc and counts do not depend on C).
  *   C_out  [2] int64 (device, output): C_out[0] = capacity to use, C_out[1] = needed capacity max_e counts[e].
- * The caller reads C_out back (one synchronisation), sizes the [E,C,M] buffers, builds slot_src with
- * moe_slot_sources and continues with moe_encode / moe_expert_ffn / moe_decode. */
+ * A caller composing the path from the stage entry points reads C_out back (one synchronisation), sizes the [E,C,M]
+ * buffers, builds slot_src with moe_slot_sources and continues with moe_encode / moe_expert_ffn / moe_decode;
+ * moe_layer_forward_dynamic runs the same flow without that synchronisation. */
 int moe_dynamic_capacity(const int32_t* counts, int64_t T, int64_t E, int k, double capacity_setting, int64_t* C_out,
                          void* stream);
 
@@ -256,6 +258,31 @@ int moe_layer_forward_fused(const void* x, const void* Wg, const float* gate_bia
                             int normalize, int act, int dtype, void* out, int32_t* idx, int32_t* loc, float* gate_w,
                             int32_t* counts, float* logits, void* ws, size_t ws_bytes, void* stream,
                             void* const* stage_events);
+
+/* The whole path with the dynamic capacity factor (Sec. 4.1 "Dynamic Capacity Factor") on one stream and without any
+ * host synchronisation (so the call can be captured in a HIP graph), with the routing variants as options.
+ *   capacity_setting > 0: the capacity factor f itself (Eq. 1); = 0: the smallest capacity that drops no token
+ *   (the arrivals of the fullest expert); < 0: the same, but never above the capacity that factor -capacity_setting gives.
+ *   C_max: the capacity the caller sized the workspace for.  The capacity is chosen on the device after the arrivals are
+ *   counted and is never above C_max: every internal buffer keeps its [E, C_max, ...] layout and the kernels read the
+ *   chosen capacity from device memory (a choice is kept iff loc < C).  C_max = T can hold any routing; with a smaller
+ *   C_max the setting 0 behaves like a negative setting whose bound is C_max.  A positive setting whose capacity
+ *   exceeds C_max is MOE_INVALID_ARG.
+ *   router: MOE_ROUTER_LINEAR (Wg [M,E], gate_bias [E] or NULL; Me, D, tau ignored) or MOE_ROUTER_COSINE (Appendix, the
+ *   cosine router: Wg is the projection [M,D], Me [E,D] fp32, temperature tau; gate_bias must be NULL).
+ *   bpr != 0: batch prioritized routing (moe_gate_topk_bpr) instead of token order.
+ *   out [T,M] (required).  Optional outputs (NULL or device): idx, loc [T,k]; gate_w [T,k]; counts [E] (un-truncated
+ *   arrivals); logits [T,E]; C_out [2] int64, 8-byte aligned: C_out[0] = chosen capacity, C_out[1] = needed capacity.
+ *   ws: moe_layer_dynamic_workspace_bytes(T,M,H,E,k,C_max,dtype,router,D,bpr) bytes, 256-byte aligned (0 = invalid or
+ *   unsupported arguments). */
+size_t moe_layer_dynamic_workspace_bytes(int64_t T, int64_t M, int64_t H, int64_t E, int k, int64_t C_max, int dtype, int router,
+                                         int64_t D, int bpr);
+int moe_layer_forward_dynamic(const void* x, const void* Wg, const float* gate_bias, const void* W1, const void* b1,
+                              const void* W2, const void* b2, int64_t T, int64_t M, int64_t H, int64_t E, int k,
+                              double capacity_setting, int64_t C_max, int normalize, int act, int dtype, int router,
+                              const float* Me, int64_t D, double tau, int bpr, void* out, int32_t* idx, int32_t* loc,
+                              float* gate_w, int32_t* counts, float* logits, int64_t* C_out, void* ws, size_t ws_bytes,
+                              void* stream);
 
 /* One training step of the layer (Sec. 3.2: forward, then the backward pass mirrors it).  moe_layer_forward_train
  * computes what moe_layer_forward computes (`out` is bit-identical) and keeps in `state` what the backward needs:

@@ -452,6 +452,111 @@ int moe_layer_forward_fused(const void* x, const void* Wg, const float* gate_bia
                        logits, ws, ws_bytes, stream, stage_events, true);
 }
 
+namespace {
+struct DynamicWorkspace {
+  size_t logits, idx, loc, gate_w, counts, fills, C_dev, slot_src, gate_ws, cosine_ws, Z, hidden, Y, total;
+};
+
+DynamicWorkspace dynamic_layout(int64_t T, int64_t M, int64_t H, int64_t E, int k, int64_t C_max, int dtype, int router, int64_t D,
+                                int bpr) {
+  DynamicWorkspace w;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { const size_t at = off; off = align_up(off + bytes, 256); return at; };
+  w.logits = take((size_t)T * E * 4);
+  w.idx = take((size_t)T * k * 4);
+  w.loc = take((size_t)T * k * 4);
+  w.gate_w = take((size_t)T * k * 4);
+  w.counts = take((size_t)E * 4);
+  w.fills = take((size_t)E * 4);
+  w.C_dev = take(2 * sizeof(int64_t));
+  w.slot_src = take((size_t)E * C_max * 4);
+  w.gate_ws = take(bpr ? moe_gate_bpr_workspace_bytes(T, E, k) : moe_gate_workspace_bytes(T, E, k));
+  w.cosine_ws = take(router == MOE_ROUTER_COSINE ? moe_cosine_gate_workspace_bytes(T, D, E) : 0);
+  w.Z = take((size_t)E * C_max * M * esize(dtype));
+  w.hidden = take((size_t)E * C_max * H * esize(dtype));
+  w.Y = take((size_t)E * C_max * M * esize(dtype));
+  w.total = off;
+  return w;
+}
+
+int dynamic_shape_status(int64_t T, int64_t M, int64_t H, int64_t E, int k, int64_t C_max, int dtype, int router, int64_t D, int bpr) {
+  if (!dtype_ok(dtype) || C_max < 1 || C_max > kMaxDim || (router != MOE_ROUTER_LINEAR && router != MOE_ROUTER_COSINE))
+    return MOE_INVALID_ARG;
+  if (int st = gate_shape_status(T, E, k)) return st;
+  if (int st = row_shape_status(M)) return st;
+  if (int st = row_shape_status(H)) return st;
+  if (E * C_max > kMaxDim) return MOE_INVALID_ARG;
+  if (router == MOE_ROUTER_COSINE && (D < 1 || moe_cosine_gate_workspace_bytes(T, D, E) == 0)) return D < 1 ? MOE_INVALID_ARG : MOE_UNSUPPORTED;
+  if (bpr && moe_gate_bpr_workspace_bytes(T, E, k) == 0) return MOE_UNSUPPORTED;
+  return MOE_OK;
+}
+}  // namespace
+
+size_t moe_layer_dynamic_workspace_bytes(int64_t T, int64_t M, int64_t H, int64_t E, int k, int64_t C_max, int dtype, int router,
+                                         int64_t D, int bpr) {
+  if (dynamic_shape_status(T, M, H, E, k, C_max, dtype, router, D, bpr) != MOE_OK) return 0;
+  return dynamic_layout(T, M, H, E, k, C_max, dtype, router, D, bpr).total;
+}
+
+int moe_layer_forward_dynamic(const void* x, const void* Wg, const float* gate_bias, const void* W1, const void* b1, const void* W2,
+                              const void* b2, int64_t T, int64_t M, int64_t H, int64_t E, int k, double capacity_setting,
+                              int64_t C_max, int normalize, int act, int dtype, int router, const float* Me, int64_t D, double tau,
+                              int bpr, void* out, int32_t* idx, int32_t* loc, float* gate_w, int32_t* counts, float* logits,
+                              int64_t* C_out, void* ws, size_t ws_bytes, void* stream) {
+  if (!x || !Wg || !W1 || !W2 || !out || !ws || !act_ok(act) || capacity_setting != capacity_setting) return MOE_INVALID_ARG;
+  if (int st = dynamic_shape_status(T, M, H, E, k, C_max, dtype, router, D, bpr)) return st;
+  if (router == MOE_ROUTER_COSINE && (!Me || gate_bias || !(tau > 0.0))) return MOE_INVALID_ARG;
+  if (!aligned(x, 16) || !aligned(W1, 16) || !aligned(W2, 16) || !aligned(out, 16) || !aligned(ws, 256) || (C_out && !aligned(C_out, 8)))
+    return MOE_UNSUPPORTED;
+  // what the host knows of the capacity: a fixed one (positive setting) or an upper bound (the caller's C_max and, for a
+  // negative setting, what Eq. 1 gives for the factor -setting)
+  int64_t fixed = 0, bound = C_max;
+  if (capacity_setting > 0.0) {
+    fixed = moe_capacity(T, E, k, capacity_setting);
+    if (fixed < 1 || fixed > C_max) return MOE_INVALID_ARG;            // the buffers the caller sized cannot hold it
+  } else if (capacity_setting < 0.0) {
+    const int64_t b = moe_capacity(T, E, k, -capacity_setting);
+    if (b < 1) return MOE_INVALID_ARG;
+    bound = b < C_max ? b : C_max;
+  }
+  const DynamicWorkspace w = dynamic_layout(T, M, H, E, k, C_max, dtype, router, D, bpr);
+  if (ws_bytes < w.total) return MOE_WORKSPACE_TOO_SMALL;
+  char* base = (char*)ws;
+  float* d_logits = logits ? logits : (float*)(base + w.logits);
+  int32_t* d_idx = idx ? idx : (int32_t*)(base + w.idx);
+  int32_t* d_loc = loc ? loc : (int32_t*)(base + w.loc);
+  float* d_gw = gate_w ? gate_w : (float*)(base + w.gate_w);
+  int32_t* d_counts = counts ? counts : (int32_t*)(base + w.counts);
+  int32_t* d_fills = (int32_t*)(base + w.fills);
+  int64_t* d_C = C_out ? C_out : (int64_t*)(base + w.C_dev);
+  int32_t* d_src = (int32_t*)(base + w.slot_src);
+  hipStream_t s = (hipStream_t)stream;
+
+  int st;
+  if (router == MOE_ROUTER_COSINE)
+    st = moe_gate_logits_cosine(x, Wg, Me, tau, dtype, T, M, D, E, d_logits, base + w.cosine_ws, moe_cosine_gate_workspace_bytes(T, D, E), stream);
+  else
+    st = launch_gate_logits(x, Wg, gate_bias, dtype, T, M, E, d_logits, s) == hipSuccess ? MOE_OK : MOE_HIP_ERROR;
+  if (st != MOE_OK) return st;
+  // arrivals do not depend on the capacity: count them first (no slot sources yet), then choose the capacity on the device
+  if (bpr)
+    st = moe_gate_topk_bpr(d_logits, T, E, k, C_max, normalize, d_idx, d_gw, d_loc, d_counts, nullptr, base + w.gate_ws,
+                           moe_gate_bpr_workspace_bytes(T, E, k), stream);
+  else
+    st = launch_gate_topk(d_logits, T, E, k, C_max, normalize, d_idx, d_gw, d_loc, d_counts, nullptr, (int32_t*)(base + w.gate_ws), s) == hipSuccess
+             ? MOE_OK : MOE_HIP_ERROR;
+  if (st != MOE_OK) return st;
+  if (launch_dynamic_capacity(d_counts, E, bound, d_C, s, fixed, d_fills) != hipSuccess) return MOE_HIP_ERROR;
+  // every buffer keeps the layout the caller's bound gives ([E, C_max, ...]); the chosen capacity only narrows which
+  // choices are kept (loc < C, read from device memory) and how many rows of a slab are filled
+  if (launch_slot_sources(d_idx, d_loc, T, E, k, C_max, d_src, s, d_C) != hipSuccess) return MOE_HIP_ERROR;
+  if (launch_encode(x, dtype, d_idx, d_loc, d_src, T, M, E, k, C_max, base + w.Z, s, false) != hipSuccess) return MOE_HIP_ERROR;
+  if (launch_grouped_gemm(base + w.Z, W1, b1, act, dtype, d_fills, E, C_max, M, H, base + w.hidden, s) != hipSuccess) return MOE_HIP_ERROR;
+  if (launch_grouped_gemm(base + w.hidden, W2, b2, -1, dtype, d_fills, E, C_max, H, M, base + w.Y, s) != hipSuccess) return MOE_HIP_ERROR;
+  if (launch_decode(base + w.Y, dtype, d_idx, d_loc, d_gw, T, M, E, k, C_max, out, s, d_C) != hipSuccess) return MOE_HIP_ERROR;
+  return MOE_OK;
+}
+
 size_t moe_layer_train_state_bytes(int64_t T, int64_t M, int64_t H, int64_t E, int k, int64_t C, int dtype) {
   if (!dtype_ok(dtype) || gate_shape_status(T, E, k) || row_shape_status(M) || row_shape_status(H) || C < 1 || C > kMaxDim)
     return 0;

@@ -97,14 +97,20 @@ hipError_t launch_bpr_order(const float* logits, int64_t T, int64_t E, uint64_t*
 hipError_t launch_decode_backward(const void* d_out, const void* Y, int dtype, const int32_t* idx, const int32_t* loc,
                                   const float* gate_w, const int32_t* slot_src, int64_t T, int64_t M, int64_t E, int k,
                                   int64_t C, void* dY, float* dgate_w, hipStream_t s, bool fill_unfilled = true);
-hipError_t launch_dynamic_capacity(const int32_t* counts, int64_t E, int64_t bound, int64_t* out, hipStream_t s);
+// out[0] = capacity: `fixed` if > 0, else max_e counts[e]; never above `bound` (if > 0); out[1] = max_e counts[e];
+// fills[e] (optional) = min(counts[e], out[0])
+hipError_t launch_dynamic_capacity(const int32_t* counts, int64_t E, int64_t bound, int64_t* out, hipStream_t s,
+                                   int64_t fixed = 0, int32_t* fills = nullptr);
+// C_dev (optional, device): only choices with loc < min(*C_dev, C) are kept; slot_src keeps its [E, C] layout
 hipError_t launch_slot_sources(const int32_t* idx, const int32_t* loc, int64_t T, int64_t E, int k, int64_t C,
-                               int32_t* slot_src, hipStream_t s);
+                               int32_t* slot_src, hipStream_t s, const int64_t* C_dev = nullptr);
 hipError_t launch_encode(const void* x, int dtype, const int32_t* idx, const int32_t* loc, const int32_t* slot_src,
                          int64_t T, int64_t M, int64_t E, int k, int64_t C, void* Z, hipStream_t s,
                          bool fill_unfilled = true);
+// C_dev (optional, device): only choices with loc < min(*C_dev, C) are kept; Y keeps its [E, C, M] layout
 hipError_t launch_decode(const void* Y, int dtype, const int32_t* idx, const int32_t* loc, const float* gate_w,
-                         int64_t T, int64_t M, int64_t E, int k, int64_t C, void* out, hipStream_t s);
+                         int64_t T, int64_t M, int64_t E, int k, int64_t C, void* out, hipStream_t s,
+                         const int64_t* C_dev = nullptr);
 // One grouped GEMM: out[e] = epilogue(A[e] (rows_e x K) * B[e] (K x N) + bias[e]); A [E,C,K], B [E,K,N], out [E,C,N].
 // act < 0 means no activation.  With `pre_out` [E,C,N] the values before the activation are written there as well.
 hipError_t launch_grouped_gemm(const void* A, const void* B, const void* bias, int act, int dtype, const int32_t* counts,

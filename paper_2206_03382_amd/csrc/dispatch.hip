@@ -114,11 +114,14 @@ template <> struct Pack16<uint16_t> {
 template <typename ET>
 __global__ __launch_bounds__(256) void decode_kernel(const uint4* __restrict__ Y, const int32_t* __restrict__ idx,
                                                      const int32_t* __restrict__ loc, const float* __restrict__ gate_w,
-                                                     int64_t T, int E, int k, int64_t C, int cpr, uint4* __restrict__ out) {
+                                                     int64_t T, int E, int k, int64_t C, int cpr, uint4* __restrict__ out,
+                                                     const int64_t* __restrict__ C_dev) {
   constexpr int N = Pack16<ET>::N;
   const int lane = threadIdx.x & 63;
   const int64_t wave = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * 4 + (threadIdx.x >> 6)));
   const int64_t nwaves = (int64_t)gridDim.x * 4;
+  const int64_t stride = C;                                          // slabs are [E, C, M]; a capacity chosen on the device only
+  if (C_dev) { const int64_t c = *C_dev; C = c < C ? c : C; }        // narrows the kept test
   for (int64_t t = wave; t < T; t += nwaves) {
     for (int c = lane; c < cpr; c += 64) {
       float acc[N];
@@ -136,7 +139,7 @@ __global__ __launch_bounds__(256) void decode_kernel(const uint4* __restrict__ Y
             const int l = loc[t * k + j], e = idx[t * k + j];
             if (l >= 0 && l < C && (unsigned)e < (unsigned)E) {           // kept choice
               w[u] = gate_w ? gate_w[t * k + j] : 1.0f;               // no weights: backward of encode
-              v[u] = Y[((int64_t)e * C + l) * cpr + c];
+              v[u] = Y[((int64_t)e * stride + l) * cpr + c];
             }
           }
         }
@@ -154,13 +157,14 @@ __global__ __launch_bounds__(256) void decode_kernel(const uint4* __restrict__ Y
 }
 
 hipError_t launch_decode(const void* Y, int dtype, const int32_t* idx, const int32_t* loc, const float* gate_w,
-                         int64_t T, int64_t M, int64_t E, int k, int64_t C, void* out, hipStream_t s) {
+                         int64_t T, int64_t M, int64_t E, int k, int64_t C, void* out, hipStream_t s,
+                         const int64_t* C_dev) {
   const int es = (dtype == MOE_F32) ? 4 : 2;
   const int cpr = (int)(M * es / 16);
   const int64_t blocks = ceil_div(T, 4);
   const dim3 grid((unsigned)(blocks < 16384 ? blocks : 16384)), block(256);
-  if (dtype == MOE_F32) decode_kernel<float><<<grid, block, 0, s>>>((const uint4*)Y, idx, loc, gate_w, T, (int)E, k, C, cpr, (uint4*)out);
-  else decode_kernel<uint16_t><<<grid, block, 0, s>>>((const uint4*)Y, idx, loc, gate_w, T, (int)E, k, C, cpr, (uint4*)out);
+  if (dtype == MOE_F32) decode_kernel<float><<<grid, block, 0, s>>>((const uint4*)Y, idx, loc, gate_w, T, (int)E, k, C, cpr, (uint4*)out, C_dev);
+  else decode_kernel<uint16_t><<<grid, block, 0, s>>>((const uint4*)Y, idx, loc, gate_w, T, (int)E, k, C, cpr, (uint4*)out, C_dev);
   return hipGetLastError();
 }
 

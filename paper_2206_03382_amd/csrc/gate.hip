@@ -431,8 +431,12 @@ hipError_t launch_gate_topk(const float* logits, int64_t T, int64_t E, int k, in
 // bound > 0: capacity that the factor's upper bound gives (setting < 0); bound = 0: no upper bound (setting = 0).
 // ---------------------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void dynamic_capacity_kernel(const int32_t* __restrict__ counts, int E, int64_t bound,
-                                                               int64_t* __restrict__ out) {
+                                                               int64_t fixed, int64_t* __restrict__ out,
+                                                               int32_t* __restrict__ fills) {
+  // fixed > 0: that capacity whatever the arrivals are (a static factor); else the needed capacity, at most `bound`
+  // (if bound > 0).  fills (optional): min(counts[e], chosen capacity) per expert.
   __shared__ int part[4];
+  __shared__ int64_t chosen;
   int m = 0;
   for (int e = threadIdx.x; e < E; e += 256) m = max(m, counts[e]);
 #pragma unroll
@@ -441,13 +445,26 @@ __global__ __launch_bounds__(256) void dynamic_capacity_kernel(const int32_t* __
   __syncthreads();
   if (threadIdx.x == 0) {
     const int64_t needed = max(max(part[0], part[1]), max(part[2], part[3]));
-    out[0] = (bound > 0 && needed > bound) ? bound : needed;
+    int64_t C = fixed > 0 ? fixed : needed;
+    if (bound > 0 && C > bound) C = bound;
+    if (C < 1) C = 1;                                   // an empty layer still has one (unfilled) slot per expert
+    out[0] = C;
     out[1] = needed;
+    chosen = C;
+  }
+  __syncthreads();
+  if (fills) {
+    const int64_t C = chosen;
+    for (int e = threadIdx.x; e < E; e += 256) {
+      const int64_t c = counts[e];
+      fills[e] = (int32_t)(c < C ? (c > 0 ? c : 0) : C);
+    }
   }
 }
 
-hipError_t launch_dynamic_capacity(const int32_t* counts, int64_t E, int64_t bound, int64_t* out, hipStream_t s) {
-  dynamic_capacity_kernel<<<dim3(1), dim3(256), 0, s>>>(counts, (int)E, bound, out);
+hipError_t launch_dynamic_capacity(const int32_t* counts, int64_t E, int64_t bound, int64_t* out, hipStream_t s,
+                                   int64_t fixed, int32_t* fills) {
+  dynamic_capacity_kernel<<<dim3(1), dim3(256), 0, s>>>(counts, (int)E, bound, fixed, out, fills);
   return hipGetLastError();
 }
 
@@ -459,23 +476,26 @@ __global__ __launch_bounds__(256) void fill_i32_kernel(int32_t* __restrict__ p, 
   for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) p[i] = v;
 }
 
+// C_dev (optional): the capacity chosen on the device; slots then sit `stride` apart per expert (the caller's bound)
 __global__ __launch_bounds__(256) void slot_sources_kernel(const int32_t* __restrict__ idx, const int32_t* __restrict__ loc,
-                                                           int64_t pairs, int k, int E, int64_t C,
+                                                           int64_t pairs, int k, int E, int64_t C, int64_t stride,
+                                                           const int64_t* __restrict__ C_dev,
                                                            int32_t* __restrict__ slot_src) {
+  if (C_dev) { const int64_t c = *C_dev; C = c < C ? c : C; }
   for (int64_t p = (int64_t)blockIdx.x * 256 + threadIdx.x; p < pairs; p += (int64_t)gridDim.x * 256) {
     const int e = idx[p], l = loc[p];
-    if (l >= 0 && l < C && (unsigned)e < (unsigned)E) slot_src[(int64_t)e * C + l] = (int32_t)(p / k);
+    if (l >= 0 && l < C && (unsigned)e < (unsigned)E) slot_src[(int64_t)e * stride + l] = (int32_t)(p / k);
   }
 }
 
 hipError_t launch_slot_sources(const int32_t* idx, const int32_t* loc, int64_t T, int64_t E, int k, int64_t C,
-                               int32_t* slot_src, hipStream_t s) {
+                               int32_t* slot_src, hipStream_t s, const int64_t* C_dev) {
   const int64_t n = E * C, fb = ceil_div(n, 256 * 4);
   fill_i32_kernel<<<dim3((unsigned)(fb < 8192 ? fb : 8192)), dim3(256), 0, s>>>(slot_src, n, -1);
   hipError_t err = hipGetLastError();
   if (err != hipSuccess) return err;
   const int64_t pairs = T * k, sb = ceil_div(pairs, 256);
-  slot_sources_kernel<<<dim3((unsigned)(sb < 8192 ? sb : 8192)), dim3(256), 0, s>>>(idx, loc, pairs, k, (int)E, C, slot_src);
+  slot_sources_kernel<<<dim3((unsigned)(sb < 8192 ? sb : 8192)), dim3(256), 0, s>>>(idx, loc, pairs, k, (int)E, C, C, C_dev, slot_src);
   return hipGetLastError();
 }
 

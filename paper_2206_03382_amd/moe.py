@@ -15,6 +15,7 @@ import torch
 OK, INVALID_ARG, UNSUPPORTED, WORKSPACE_TOO_SMALL, HIP_ERROR, SCRATCH_TOO_SMALL = range(6)
 F32, BF16 = 0, 1
 ACT_RELU, ACT_GELU, ACT_SILU = 0, 1, 2
+ROUTER_LINEAR, ROUTER_COSINE = 0, 1
 NUM_STAGE_EVENTS = 7
 STAGE_NAMES = ("gate_logits", "gate_topk", "encode", "ffn_gemm1", "ffn_gemm2", "decode")
 
@@ -55,6 +56,9 @@ SIGNATURES = {
     "moe_layer_forward_fused": (_i32, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _i64, _i32, _dbl, _i32, _i32, _i32,
                                        _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp, _c.POINTER(_vp)]),
     "moe_expert_ffn_gather": (_i32, [_vp, _vp, _i64, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _i64, _i64, _i64, _i64, _vp, _vp, _vp]),
+    "moe_layer_dynamic_workspace_bytes": (_sz, [_i64, _i64, _i64, _i64, _i32, _i64, _i32, _i32, _i64, _i32]),
+    "moe_layer_forward_dynamic": (_i32, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _i64, _i32, _dbl, _i64, _i32, _i32, _i32,
+                                         _i32, _vp, _i64, _dbl, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "moe_layer_train_state_bytes": (_sz, [_i64, _i64, _i64, _i64, _i32, _i64, _i32]),
     "moe_layer_forward_train": (_i32, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _i64, _i32, _dbl, _i32, _i32, _i32,
                                        _vp, _vp, _sz, _vp]),
@@ -195,24 +199,53 @@ def slot_sources(idx: torch.Tensor, loc: torch.Tensor, E: int, C: int) -> torch.
     return slot_src
 
 
-def layer_forward_dynamic(x, Wg, gate_bias, W1, b1, W2, b2, k: int, capacity_setting: float, normalize: int,
-                          act: int) -> Dict[str, torch.Tensor]:
-    """The layer with the dynamic capacity factor: route, choose the capacity from the arrivals (one read-back), then
-    dispatch, experts and combine at that capacity.  A positive setting is the static factor."""
-    T, E = x.shape[0], W1.shape[0]
-    logits = gate_logits(x, Wg, gate_bias)
-    if capacity_setting > 0:
-        C = capacity(T, E, k, capacity_setting)
-        r = gate_topk(logits, k, C, normalize)
-        needed = None
-    else:
-        r = gate_topk(logits, k, 1, normalize, want_slot_src=False)      # arrivals do not depend on the capacity
-        C, needed = dynamic_capacity(r["counts"], T, k, capacity_setting)
-        r["slot_src"] = slot_sources(r["idx"], r["loc"], E, C)
-    Z = encode(x, r["idx"], r["loc"], r["slot_src"], E, C)
-    Y = expert_ffn(Z, W1, b1, W2, b2, act, counts=r["counts"])
-    out = decode(Y, r["idx"], r["loc"], r["gate_w"])
-    r.update(C=C, needed_capacity=needed, logits=logits, Z=Z, out=out)
+class DynamicLayer:
+    """The layer with the dynamic capacity factor through moe_layer_forward_dynamic: owns workspace and outputs sized for
+    C_max, so that `forward` allocates nothing and never synchronises (the chosen capacity stays on the device)."""
+
+    def __init__(self, Wg, gate_bias, W1, b1, W2, b2, T: int, k: int, capacity_setting: float, normalize: int, act: int,
+                 C_max: Optional[int] = None, bpr: bool = False, cosine_Me: Optional[torch.Tensor] = None, cosine_tau: float = 0.07):
+        self.Wg, self.gate_bias, self.W1, self.b1, self.W2, self.b2 = Wg, gate_bias, W1, b1, W2, b2
+        self.E, self.M, self.H = W1.shape
+        self.T, self.k, self.setting, self.normalize, self.act = T, k, float(capacity_setting), int(normalize), int(act)
+        self.C_max = int(T if C_max is None else C_max)
+        self.bpr = int(bool(bpr))
+        self.Me, self.tau = cosine_Me, float(cosine_tau)
+        self.router = ROUTER_LINEAR if cosine_Me is None else ROUTER_COSINE
+        self.D = 0 if cosine_Me is None else int(cosine_Me.shape[1])
+        self.dtype = _dtype_code(W1)
+        nbytes = int(lib().moe_layer_dynamic_workspace_bytes(T, self.M, self.H, self.E, k, self.C_max, self.dtype, self.router, self.D, self.bpr))
+        if nbytes == 0:
+            raise MoEError(UNSUPPORTED, "moe_layer_dynamic_workspace_bytes")
+        dev = W1.device
+        self.ws = torch.empty((nbytes,), dtype=torch.uint8, device=dev)
+        self.out = torch.empty((T, self.M), dtype=W1.dtype, device=dev)
+        self.routing = dict(idx=torch.empty((T, k), dtype=torch.int32, device=dev), loc=torch.empty((T, k), dtype=torch.int32, device=dev),
+                            gate_w=torch.empty((T, k), dtype=torch.float32, device=dev),
+                            counts=torch.empty((self.E,), dtype=torch.int32, device=dev),
+                            logits=torch.empty((T, self.E), dtype=torch.float32, device=dev),
+                            C=torch.empty((2,), dtype=torch.int64, device=dev))
+
+    def forward(self, x: torch.Tensor) -> torch.Tensor:
+        r = self.routing
+        _check(lib().moe_layer_forward_dynamic(_p(x), _p(self.Wg), _p(self.gate_bias), _p(self.W1), _p(self.b1), _p(self.W2), _p(self.b2),
+                                               self.T, self.M, self.H, self.E, self.k, self.setting, self.C_max, self.normalize,
+                                               self.act, self.dtype, self.router, _p(self.Me), self.D, self.tau, self.bpr,
+                                               _p(self.out), _p(r["idx"]), _p(r["loc"]), _p(r["gate_w"]), _p(r["counts"]),
+                                               _p(r["logits"]), _p(r["C"]), _p(self.ws), self.ws.numel(), _stream()),
+               "moe_layer_forward_dynamic")
+        return self.out
+
+
+def layer_forward_dynamic(x, Wg, gate_bias, W1, b1, W2, b2, k: int, capacity_setting: float, normalize: int, act: int,
+                          C_max: Optional[int] = None, bpr: bool = False, cosine_Me: Optional[torch.Tensor] = None,
+                          cosine_tau: float = 0.07) -> Dict[str, torch.Tensor]:
+    """One call of moe_layer_forward_dynamic; the chosen and the needed capacity are read back afterwards for the caller."""
+    layer = DynamicLayer(Wg, gate_bias, W1, b1, W2, b2, x.shape[0], k, capacity_setting, normalize, act, C_max, bpr, cosine_Me, cosine_tau)
+    out = layer.forward(x)
+    r = dict(layer.routing)
+    C, needed = r.pop("C").cpu().tolist()
+    r.update(C=int(C), needed_capacity=int(needed), out=out)
     return r
 
 

@@ -114,6 +114,18 @@ def test_argument_validation_never_launches(moe):
                                None, None, None, None, None, fake, 1 << 30, None, None) == moe.INVALID_ARG            # f <= 0
     assert L.moe_layer_forward(fake, fake, None, fake, None, fake, None, 8, 16, 16, 4, 1, 1.0, 0, 0, moe.F32, fake,
                                None, None, None, None, None, fake, 16, None, None) == moe.WORKSPACE_TOO_SMALL
+    dyn = lambda setting, C_max, ws_bytes, router=0, Me=None, bpr=0, C_out=None: L.moe_layer_forward_dynamic(   # noqa: E731
+        fake, fake, None, fake, None, fake, None, 64, 16, 16, 4, 2, setting, C_max, 1, 0, moe.F32, router, Me, 8, 0.07, bpr, fake,
+        None, None, None, None, None, C_out, fake, ws_bytes, None)
+    assert L.moe_layer_dynamic_workspace_bytes(64, 16, 16, 4, 2, 64, moe.F32, 0, 0, 0) > 0
+    assert L.moe_layer_dynamic_workspace_bytes(64, 16, 16, 4, 2, 64, moe.F32, 2, 0, 0) == 0                            # unknown router
+    assert L.moe_layer_dynamic_workspace_bytes(64, 16, 16, 4, 2, 64, moe.F32, 1, 8, 0) > L.moe_layer_dynamic_workspace_bytes(64, 16, 16, 4, 2, 64, moe.F32, 0, 0, 0)
+    assert dyn(0.0, 64, 16) == moe.WORKSPACE_TOO_SMALL
+    assert dyn(float("nan"), 64, 1 << 30) == moe.INVALID_ARG
+    assert dyn(2.0, 32, 1 << 30) == moe.INVALID_ARG                          # static capacity 64 does not fit buffers sized for 32
+    assert dyn(0.0, 0, 1 << 30) == moe.INVALID_ARG
+    assert dyn(0.0, 64, 1 << 30, router=1, Me=None) == moe.INVALID_ARG       # cosine router without expert embeddings
+    assert dyn(0.0, 64, 1 << 30, C_out=fake + 4) == moe.UNSUPPORTED          # C_out misaligned
     assert L.moe_layer_train_state_bytes(8, 16, 16, 4, 1, 2, moe.F32) > 0
     assert L.moe_layer_train_state_bytes(8, 12, 16, 4, 1, 2, moe.F32) == 0                                             # M % 8
     assert L.moe_layer_forward_train(fake, fake, None, fake, None, fake, None, 8, 16, 16, 4, 1, 1.0, 0, 0, moe.F32, fake,

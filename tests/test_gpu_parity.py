@@ -382,9 +382,9 @@ def run_layer(moe, cfg, inp):
     return layer, out
 
 
-def check_logits(got, ref):
+def check_logits(got, ref, floor=0.0):
     ulp = np.spacing(np.abs(ref).astype(np.float32))
-    assert (np.abs(got - ref) <= ulp).all() and (got != ref).mean() <= 1e-4
+    assert (np.abs(got - ref) <= ulp).all() and (got != ref).mean() <= max(1e-4, floor / got.size)
 
 
 SMALL_LAYERS = [
@@ -533,25 +533,133 @@ DYNAMIC_LAYERS = [
 ]
 
 
-@pytest.mark.parametrize("cfg", DYNAMIC_LAYERS, ids=lambda c: f"{c.name}-T{c.T}-E{c.E}")
-@pytest.mark.parametrize("setting", [0.0, -0.5, -1.0, -64.0, 1.25])
-def test_layer_dynamic_capacity(moe, cfg, setting):
-    inp = synth.make_inputs(cfg, seed=3, bias_std=0.25)
-    ref = O.moe_layer(inp["x"], inp["Wg"], inp["gate_bias"], inp["W1"], inp["b1"], inp["W2"], inp["b2"],
-                      cfg.k, cfg.f, cfg.normalize, cfg.act, tier="sparse", capacity_setting=setting)
+def oracle_dynamic_layer(inp, cfg, setting, C_max=None, bpr=False, cosine=None):
+    """The dynamic-capacity layer composed from the oracle's pinned pieces: logits (linear or cosine) -> arrivals ->
+    capacity (Sec. 4.1; never above C_max) -> routing at that capacity -> dispatch -> experts -> combine."""
+    T, E, k = cfg.T, cfg.E, cfg.k
+    if cosine is None:
+        logits = O.gate_logits(inp["x"], inp["Wg"], inp["gate_bias"])
+    else:
+        logits = O.cosine_gate_logits(inp["x"], cosine["Wp"], cosine["Me"], cosine["tau"])
+    arrivals = O.route(logits, k, 1, cfg.normalize, bpr=bpr)["counts"]
+    C = O.dynamic_capacity(arrivals, T, E, k, setting)
+    if C_max is not None:
+        C = min(C, C_max)
+    r = O.route(logits, k, C, cfg.normalize, bpr=bpr)
+    Z = O.encode_sparse(inp["x"], r["idx"], r["loc"], E, C)
+    Y = O.expert_ffn(Z, inp["W1"], inp["b1"], inp["W2"], inp["b2"], cfg.act, rows=r["counts"])
+    r.update(C=C, logits=logits, out=O.decode_sparse(Y, r["idx"], r["loc"], r["gate_w"], C))
+    return r
+
+
+def run_dynamic(moe, cfg, inp, setting, **kw):
     d = cfg.dtype
     gb = None if inp["gate_bias"] is None else torch.from_numpy(inp["gate_bias"]).cuda()
     got = moe.layer_forward_dynamic(dev(inp["x"], d), dev(inp["Wg"], d), gb, dev(inp["W1"], d), dev(inp["b1"], d),
-                                    dev(inp["W2"], d), dev(inp["b2"], d), cfg.k, setting, cfg.normalize, cfg.act)
+                                    dev(inp["W2"], d), dev(inp["b2"], d), cfg.k, setting, cfg.normalize, cfg.act, **kw)
     torch.cuda.synchronize()
+    return got
+
+
+@pytest.mark.parametrize("cfg", DYNAMIC_LAYERS, ids=lambda c: f"{c.name}-T{c.T}-E{c.E}")
+@pytest.mark.parametrize("setting", [0.0, -0.5, -1.0, -64.0, 1.25])
+def test_layer_dynamic_capacity(moe, cfg, setting):
+    """moe_layer_forward_dynamic (one C call, capacity chosen and used on the device) against the oracle's layer with
+    the same capacity setting; buffers sized for C_max = T."""
+    inp = synth.make_inputs(cfg, seed=3, bias_std=0.25)
+    ref = O.moe_layer(inp["x"], inp["Wg"], inp["gate_bias"], inp["W1"], inp["b1"], inp["W2"], inp["b2"],
+                      cfg.k, cfg.f, cfg.normalize, cfg.act, tier="sparse", capacity_setting=setting)
+    got = run_dynamic(moe, cfg, inp, setting)
     assert got["C"] == ref["C"]
-    if setting <= 0:
-        assert got["needed_capacity"] == int(ref["counts"].max())
+    assert got["needed_capacity"] == int(ref["counts"].max())
     if setting == 0:
         assert ref["kept"].all()
     assert_routing_equal(got, ref, ref["C"], cfg.name)
-    assert np.array_equal(got["slot_src"].cpu().numpy(), O.slot_source(ref["idx"], ref["loc"], cfg.E, ref["C"]))
     assert_close(host(got["out"]), ref["out"], cfg.dtype, f"dynamic-capacity layer output ({cfg.name}, setting {setting})")
+    dead = (~ref["kept"]).all(axis=1)
+    assert (host(got["out"])[dead].view(np.uint32) == 0).all()
+
+
+@pytest.mark.parametrize("cfg", DYNAMIC_LAYERS[1:], ids=lambda c: f"{c.name}-T{c.T}-E{c.E}")
+def test_layer_dynamic_capacity_bounded_buffers(moe, cfg):
+    """Buffers sized below the needed capacity: setting 0 then behaves like the negative setting with that bound; a
+    static factor that does not fit is refused."""
+    inp = synth.make_inputs(cfg, seed=4, bias_std=0.25)
+    C_max = O.capacity(cfg.T, cfg.E, cfg.k, 0.5)
+    ref = oracle_dynamic_layer(inp, cfg, 0.0, C_max=C_max)
+    assert ref["C"] == C_max and not ref["kept"].all()                         # the bound really cuts
+    same = O.moe_layer(inp["x"], inp["Wg"], inp["gate_bias"], inp["W1"], inp["b1"], inp["W2"], inp["b2"], cfg.k, cfg.f,
+                       cfg.normalize, cfg.act, tier="sparse", capacity_setting=-0.5)
+    assert same["C"] == C_max and np.array_equal(same["out"], ref["out"])
+    got = run_dynamic(moe, cfg, inp, 0.0, C_max=C_max)
+    assert got["C"] == C_max and got["needed_capacity"] == int(ref["counts"].max())
+    assert_routing_equal(got, ref, C_max, cfg.name)
+    assert_close(host(got["out"]), ref["out"], cfg.dtype, "bounded buffers")
+    with pytest.raises(moe.MoEError) as err:
+        run_dynamic(moe, cfg, inp, 1.0, C_max=C_max)
+    assert err.value.status == moe.INVALID_ARG
+
+
+@pytest.mark.parametrize("cfg", DYNAMIC_LAYERS[1:], ids=lambda c: f"{c.name}-T{c.T}-E{c.E}")
+@pytest.mark.parametrize("setting", [0.0, -0.75, 1.0])
+def test_layer_dynamic_batch_prioritized(moe, cfg, setting):
+    inp = synth.make_inputs(cfg, seed=6, bias_std=0.25)
+    ref = oracle_dynamic_layer(inp, cfg, setting, bpr=True)
+    got = run_dynamic(moe, cfg, inp, setting, bpr=True)
+    assert got["C"] == ref["C"]
+    assert_routing_equal(got, ref, ref["C"], f"{cfg.name} BPR")
+    assert_close(host(got["out"]), ref["out"], cfg.dtype, f"dynamic-capacity layer, batch prioritized routing, setting {setting}")
+    if setting < 0:                                                            # the order matters: token order drops other tokens
+        plain = oracle_dynamic_layer(inp, cfg, setting, bpr=False)
+        assert not np.array_equal(plain["kept"], ref["kept"])
+
+
+@pytest.mark.parametrize("cfg", DYNAMIC_LAYERS[1:], ids=lambda c: f"{c.name}-T{c.T}-E{c.E}")
+@pytest.mark.parametrize("setting,bpr", [(0.0, False), (-1.0, True), (1.25, False)])
+def test_layer_dynamic_cosine_router(moe, cfg, setting, bpr):
+    inp = synth.make_inputs(cfg, seed=7, bias_std=0.25)
+    rng = np.random.default_rng(cfg.T)
+    D = 64
+    Wp = synth.round_to_bf16((rng.standard_normal((cfg.M, D)) / np.sqrt(cfg.M)).astype(np.float32))
+    Me = rng.standard_normal((cfg.E, D)).astype(np.float32)
+    cos = dict(Wp=Wp, Me=Me, tau=0.07)
+    ref = oracle_dynamic_layer(inp, cfg, setting, bpr=bpr, cosine=cos)
+    inp2 = dict(inp, Wg=Wp, gate_bias=None)
+    got = run_dynamic(moe, cfg, inp2, setting, bpr=bpr, cosine_Me=torch.from_numpy(Me).cuda(), cosine_tau=0.07)
+    assert got["C"] == ref["C"]
+    check_logits(got["logits"].cpu().numpy(), ref["logits"], floor=1.5)
+    assert_routing_equal(got, ref, ref["C"], f"{cfg.name} cosine")
+    assert_close(host(got["out"]), ref["out"], cfg.dtype, f"dynamic-capacity layer, cosine router, setting {setting}")
+
+
+def test_layer_dynamic_in_hip_graph(moe):
+    """No host synchronisation, allocation or memset inside moe_layer_forward_dynamic: captured once, replayed on
+    different inputs (whose arrivals give different capacities), bit-identical to the eager call every time."""
+    cfg = synth.CONFIGS[3].scaled(T=4096, M=256, H=512, E=64)
+    inp = synth.make_inputs(cfg, seed=21, bias_std=0.25)
+    d = cfg.dtype
+    layer = moe.DynamicLayer(dev(inp["Wg"], d), torch.from_numpy(inp["gate_bias"]).cuda(), dev(inp["W1"], d), dev(inp["b1"], d),
+                             dev(inp["W2"], d), dev(inp["b2"], d), T=cfg.T, k=cfg.k, capacity_setting=0.0,
+                             normalize=cfg.normalize, act=cfg.act, C_max=cfg.T)
+    xs = [dev(inp["x"], d), dev(synth.make_inputs(cfg, seed=22)["x"], d), dev(synth.make_inputs(cfg, seed=23)["x"][::-1].copy(), d)]
+    eager = []
+    for x in xs:
+        out = layer.forward(x).clone()
+        torch.cuda.synchronize()
+        eager.append((out, layer.routing["C"].clone(), layer.routing["loc"].clone()))
+    assert len({int(c[0]) for _, c, _ in eager}) > 1, "the inputs should need different capacities"
+    static_x = xs[0].clone()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        static_out = layer.forward(static_x)
+    for rep in (0, 1, 2, 1, 0):                                     # replays with eager work and synchronisation in between
+        static_x.copy_(xs[rep])
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(static_out, eager[rep][0]), rep
+        assert torch.equal(layer.routing["C"], eager[rep][1]) and torch.equal(layer.routing["loc"], eager[rep][2])
+        layer.forward(xs[(rep + 1) % 3])
+        torch.cuda.synchronize()
 
 
 # ----------------------------------------------------------------------------------------------------------------
