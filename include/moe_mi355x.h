@@ -96,6 +96,24 @@ int moe_gate_topk(const float* logits, int64_t T, int64_t E, int k, int64_t C, i
                   int32_t* idx, float* gate_w, int32_t* loc, int32_t* counts, int32_t* slot_src,
                   void* ws, size_t ws_bytes, void* stream);
 
+/* Bytes of workspace moe_gate_route needs (the arrival counters of moe_gate_topk and, for bf16 gates, the transposed
+ * gate weights, their norms and one error bound per token).  0 on invalid arguments. */
+size_t moe_gate_route_workspace_bytes(int64_t T, int64_t M, int64_t E, int k, int dtype);
+
+/* The gating function from the tokens (Sec. 2.1): moe_gate_logits followed by moe_gate_topk, at memory speed.
+ *   Inputs as moe_gate_logits, outputs as moe_gate_topk (logits [T,E] fp32 is an output here, required).
+ * fp32 gates run exactly those two steps.  bf16 gates compute the logits on the bf16 matrix cores (exact products, fp32
+ * sums of 32 terms, fp64 sums of those) with a rigorous per-token error bound B_t = 32 * 2^-23 * |x_t| * max_e |w_e|; a
+ * token whose k+1 largest logits are not separated by more than 2 B_t has the logits of every expert that can still
+ * reach its top k recomputed in fp64 and rounded once, and is decided on those.  So idx, loc, counts and slot_src are
+ * the ones exactly rounded logits give (what moe_gate_logits + moe_gate_topk return), while `logits` holds exactly
+ * rounded values where a decision needed them and values within B_t of them elsewhere (typically within 1e-6; gate_w
+ * follows the stored logits).
+ *   ws: moe_gate_route_workspace_bytes, 256-byte aligned; x 16-byte aligned. */
+int moe_gate_route(const void* x, const void* Wg, const float* gate_bias, int dtype, int64_t T, int64_t M, int64_t E, int k,
+                   int64_t C, int normalize, float* logits, int32_t* idx, float* gate_w, int32_t* loc, int32_t* counts,
+                   int32_t* slot_src, void* ws, size_t ws_bytes, void* stream);
+
 /* moe_gate_topk for callers that cannot allocate device memory or bring a workspace (code under HIP graph capture,
  * tight serving loops, harnesses that forbid hipMalloc): the same kernels and the same outputs, with the arrival
  * counters in a device array of fixed size that the library holds on every GPU it runs on until the process ends.
@@ -237,7 +255,7 @@ int moe_decode_backward(const void* d_out, const void* Y, int dtype, const int32
                         const float* gate_w, const int32_t* slot_src, int64_t T, int64_t M, int64_t E, int k, int64_t C,
                         void* dY, float* dgate_w, void* stream);
 
-/* The whole path on one stream: gate logits -> top-k + slots -> encode -> expert FFN (filled rows only) -> decode,
+/* The whole path on one stream: gate (moe_gate_route) -> encode -> expert FFN (filled rows only) -> decode,
  * with C = moe_capacity(T,E,k,f).
  *   Inputs as in the entry points above.  out [T,M] (output, required).
  *   Optional outputs (each may be NULL): idx, loc [T,k] int32; gate_w [T,k] fp32; counts [E] int32; logits [T,E] fp32.

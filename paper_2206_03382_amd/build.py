@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmoe_mi355x.so")
 PROBE_LIB = os.path.join(HERE, "libmoe_probe.so")          # bench.py's measurement aid, a library of its own
-SOURCES = ["api.hip", "gate.hip", "dispatch.hip", "ffn_generic.hip", "ffn_mfma.hip", "ffn_backward.hip", "gate_backward.hip"]
+SOURCES = ["api.hip", "gate.hip", "gate_fast.hip", "dispatch.hip", "ffn_generic.hip", "ffn_mfma.hip", "ffn_backward.hip", "gate_backward.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-Wall", "-Wno-unused-function",
          # keep the compiler from forming packed fp32 math on its own

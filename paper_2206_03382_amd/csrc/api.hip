@@ -45,6 +45,36 @@ inline int row_shape_status(int64_t M) {
   return MOE_OK;
 }
 
+// The gating function from the tokens: logits, then decisions and slots.  bf16 gates take the fast logits kernel and
+// the top-k kernel's exact repair of near-ties; everything else the fp64 logits kernel.  Workspace: the arrival
+// counters, then (fast path) the transposed gate weights, their norms and the per-token error bounds.
+bool gate_uses_fast_logits(int dtype, int64_t T, int64_t M, int64_t E) { return gate_logits_fast_supports(dtype, T, M, E); }
+
+size_t gate_route_workspace(int64_t T, int64_t M, int64_t E, int k, int dtype) {
+  size_t n = align_up(moe_gate_workspace_bytes(T, E, k), 256);
+  if (gate_uses_fast_logits(dtype, T, M, E)) n += gate_fast_workspace_bytes(T, M, E);
+  return n;
+}
+
+template <typename F>
+hipError_t run_gate(const void* x, const void* Wg, const float* bias, int dtype, int64_t T, int64_t M, int64_t E, int k, int64_t C,
+                    int normalize, float* logits, int32_t* idx, float* gate_w, int32_t* loc, int32_t* counts, int32_t* slot_src,
+                    void* ws, hipStream_t s, F&& after_logits) {
+  int32_t* counters = (int32_t*)ws;
+  if (gate_uses_fast_logits(dtype, T, M, E)) {
+    const GateFastWorkspace f = gate_fast_layout((char*)ws + align_up(moe_gate_workspace_bytes(T, E, k), 256), T, M, E);
+    hipError_t err = launch_gate_logits_fast(x, Wg, bias, T, M, E, logits, f, s);
+    if (err != hipSuccess) return err;
+    if (!after_logits()) return hipErrorUnknown;
+    const GateRepair repair = {f.margin, x, f.Wt, bias, M, f.Mp};
+    return launch_gate_topk(logits, T, E, k, C, normalize, idx, gate_w, loc, counts, slot_src, counters, s, nullptr, &repair);
+  }
+  hipError_t err = launch_gate_logits(x, Wg, bias, dtype, T, M, E, logits, s);
+  if (err != hipSuccess) return err;
+  if (!after_logits()) return hipErrorUnknown;
+  return launch_gate_topk(logits, T, E, k, C, normalize, idx, gate_w, loc, counts, slot_src, counters, s);
+}
+
 struct LayerWorkspace {
   size_t logits, idx, loc, gate_w, counts, slot_src, gate_ws, Z, hidden, Y, total;
 };
@@ -59,7 +89,7 @@ LayerWorkspace layer_layout(int64_t T, int64_t M, int64_t H, int64_t E, int k, i
   w.gate_w = take((size_t)T * k * 4);
   w.counts = take((size_t)E * 4);
   w.slot_src = take((size_t)E * C * 4);
-  w.gate_ws = take(moe_gate_workspace_bytes(T, E, k));
+  w.gate_ws = take(gate_route_workspace(T, M, E, k, dtype));
   w.Z = take((size_t)E * C * M * esize(dtype));
   w.hidden = take((size_t)E * C * H * esize(dtype));
   w.Y = take((size_t)E * C * M * esize(dtype));
@@ -159,10 +189,27 @@ int moe_gate_topk(const float* logits, int64_t T, int64_t E, int k, int64_t C, i
                   int32_t* loc, int32_t* counts, int32_t* slot_src, void* ws, size_t ws_bytes, void* stream) {
   if (!logits || !idx || !gate_w || !loc || !counts || !ws || C < 1 || C > kMaxDim) return MOE_INVALID_ARG;
   if (int st = gate_shape_status(T, E, k)) return st;
-  if (!aligned(ws, 16)) return MOE_UNSUPPORTED;
+  if (!aligned(ws, 16) || !aligned(logits, 16)) return MOE_UNSUPPORTED;
   if (ws_bytes < moe_gate_workspace_bytes(T, E, k)) return MOE_WORKSPACE_TOO_SMALL;
-  return launch_gate_topk(logits, T, E, k, C, normalize, idx, gate_w, loc, counts, slot_src, (int32_t*)ws,
+  return launch_gate_topk(const_cast<float*>(logits), T, E, k, C, normalize, idx, gate_w, loc, counts, slot_src, (int32_t*)ws,
                           (hipStream_t)stream) == hipSuccess ? MOE_OK : MOE_HIP_ERROR;
+}
+
+size_t moe_gate_route_workspace_bytes(int64_t T, int64_t M, int64_t E, int k, int dtype) {
+  if (gate_shape_status(T, E, k) != MOE_OK || row_shape_status(M) != MOE_OK || !dtype_ok(dtype)) return 0;
+  return gate_route_workspace(T, M, E, k, dtype);
+}
+
+int moe_gate_route(const void* x, const void* Wg, const float* gate_bias, int dtype, int64_t T, int64_t M, int64_t E, int k,
+                   int64_t C, int normalize, float* logits, int32_t* idx, float* gate_w, int32_t* loc, int32_t* counts,
+                   int32_t* slot_src, void* ws, size_t ws_bytes, void* stream) {
+  if (!x || !Wg || !logits || !idx || !gate_w || !loc || !counts || !ws || !dtype_ok(dtype) || C < 1 || C > kMaxDim) return MOE_INVALID_ARG;
+  if (int st = gate_shape_status(T, E, k)) return st;
+  if (int st = row_shape_status(M)) return st;
+  if (!aligned(x, 16) || !aligned(Wg, 2) || !aligned(ws, 256) || !aligned(logits, 16)) return MOE_UNSUPPORTED;
+  if (ws_bytes < gate_route_workspace(T, M, E, k, dtype)) return MOE_WORKSPACE_TOO_SMALL;
+  return run_gate(x, Wg, gate_bias, dtype, T, M, E, k, C, normalize, logits, idx, gate_w, loc, counts, slot_src, ws,
+                  (hipStream_t)stream, [] { return true; }) == hipSuccess ? MOE_OK : MOE_HIP_ERROR;
 }
 
 size_t moe_gate_topk_static_max_bytes(void) { return kStaticScratchBytes; }
@@ -171,11 +218,12 @@ int moe_gate_topk_static(const float* logits, int64_t T, int64_t E, int k, int64
                          int32_t* loc, int32_t* counts, int32_t* slot_src, void* stream) {
   if (!logits || !idx || !gate_w || !loc || !counts || C < 1 || C > kMaxDim) return MOE_INVALID_ARG;
   if (int st = gate_shape_status(T, E, k)) return st;
+  if (!aligned(logits, 16)) return MOE_UNSUPPORTED;
   if (moe_gate_workspace_bytes(T, E, k) > kStaticScratchBytes) return MOE_SCRATCH_TOO_SMALL;
   void* ws = static_scratch_ptr();
   if (!ws) return MOE_HIP_ERROR;
   // the kernels write every counter they later read, so the last call's contents need no clearing
-  return launch_gate_topk(logits, T, E, k, C, normalize, idx, gate_w, loc, counts, slot_src, (int32_t*)ws,
+  return launch_gate_topk(const_cast<float*>(logits), T, E, k, C, normalize, idx, gate_w, loc, counts, slot_src, (int32_t*)ws,
                           (hipStream_t)stream) == hipSuccess ? MOE_OK : MOE_HIP_ERROR;
 }
 
@@ -208,7 +256,7 @@ int moe_gate_topk_bpr(const float* logits, int64_t T, int64_t E, int k, int64_t 
                       int32_t* loc, int32_t* counts, int32_t* slot_src, void* ws, size_t ws_bytes, void* stream) {
   if (!logits || !idx || !gate_w || !loc || !counts || !ws || C < 1 || C > kMaxDim) return MOE_INVALID_ARG;
   if (int st = gate_shape_status(T, E, k)) return st;
-  if (T > ((int64_t)1 << 18) || !aligned(ws, 256)) return MOE_UNSUPPORTED;    // the order is found by O(T^2) counting
+  if (T > ((int64_t)1 << 18) || !aligned(ws, 256) || !aligned(logits, 16)) return MOE_UNSUPPORTED;    // the order is found by O(T^2) counting
   if (ws_bytes < moe_gate_bpr_workspace_bytes(T, E, k)) return MOE_WORKSPACE_TOO_SMALL;
   char* base = (char*)ws;
   const size_t g = align_up(moe_gate_workspace_bytes(T, E, k), 256);
@@ -217,7 +265,7 @@ int moe_gate_topk_bpr(const float* logits, int64_t T, int64_t E, int k, int64_t 
   int32_t* perm = before + align_up((size_t)T * 4, 256) / 4;
   hipStream_t s = (hipStream_t)stream;
   if (launch_bpr_order(logits, T, E, key, before, perm, s) != hipSuccess) return MOE_HIP_ERROR;
-  return launch_gate_topk(logits, T, E, k, C, normalize, idx, gate_w, loc, counts, slot_src, (int32_t*)ws, s, perm) == hipSuccess
+  return launch_gate_topk(const_cast<float*>(logits), T, E, k, C, normalize, idx, gate_w, loc, counts, slot_src, (int32_t*)ws, s, perm) == hipSuccess
              ? MOE_OK : MOE_HIP_ERROR;
 }
 
@@ -367,7 +415,7 @@ TrainState train_layout(int64_t T, int64_t M, int64_t H, int64_t E, int k, int64
   w.gate_w = take((size_t)T * k * 4);
   w.counts = take((size_t)E * 4);
   w.slot_src = take((size_t)E * C * 4);
-  w.gate_ws = take(moe_gate_workspace_bytes(T, E, k));
+  w.gate_ws = take(gate_route_workspace(T, M, E, k, dtype));
   w.Z = take((size_t)E * C * M * es);
   w.pre = take((size_t)E * C * H * es);
   w.hidden = take((size_t)E * C * H * es);
@@ -405,7 +453,7 @@ int layer_forward(const void* x, const void* Wg, const float* gate_bias, const v
   float* d_gw = gate_w ? gate_w : (float*)(base + w.gate_w);
   int32_t* d_counts = counts ? counts : (int32_t*)(base + w.counts);
   int32_t* d_src = (int32_t*)(base + w.slot_src);
-  int32_t* d_gws = (int32_t*)(base + w.gate_ws);
+  void* d_gws = base + w.gate_ws;
   void* d_Z = base + w.Z;
   void* d_hidden = base + w.hidden;
   void* d_Y = base + w.Y;
@@ -414,8 +462,8 @@ int layer_forward(const void* x, const void* Wg, const float* gate_bias, const v
   auto mark = [&]() -> bool { return !stage_events || hipEventRecord((hipEvent_t)stage_events[stage++], s) == hipSuccess; };
 
   if (!mark()) return MOE_HIP_ERROR;
-  if (launch_gate_logits(x, Wg, gate_bias, dtype, T, M, E, d_logits, s) != hipSuccess || !mark()) return MOE_HIP_ERROR;
-  if (launch_gate_topk(d_logits, T, E, k, C, normalize, d_idx, d_gw, d_loc, d_counts, d_src, d_gws, s) != hipSuccess || !mark())
+  if (run_gate(x, Wg, gate_bias, dtype, T, M, E, k, C, normalize, d_logits, d_idx, d_gw, d_loc, d_counts, d_src, d_gws, s, mark) != hipSuccess ||
+      !mark())
     return MOE_HIP_ERROR;
   if (fuse_dispatch && dtype == MOE_BF16 && grouped_gemm_mfma_supports(E, C, M, H, T)) {
     // the first expert GEMM gathers its rows from x through slot_src: the dispatch buffer is never materialised
@@ -470,7 +518,7 @@ DynamicWorkspace dynamic_layout(int64_t T, int64_t M, int64_t H, int64_t E, int 
   w.fills = take((size_t)E * 4);
   w.C_dev = take(2 * sizeof(int64_t));
   w.slot_src = take((size_t)E * C_max * 4);
-  w.gate_ws = take(bpr ? moe_gate_bpr_workspace_bytes(T, E, k) : moe_gate_workspace_bytes(T, E, k));
+  w.gate_ws = take(bpr ? moe_gate_bpr_workspace_bytes(T, E, k) : gate_route_workspace(T, M, E, k, dtype));
   w.cosine_ws = take(router == MOE_ROUTER_COSINE ? moe_cosine_gate_workspace_bytes(T, D, E) : 0);
   w.Z = take((size_t)E * C_max * M * esize(dtype));
   w.hidden = take((size_t)E * C_max * H * esize(dtype));
@@ -532,19 +580,26 @@ int moe_layer_forward_dynamic(const void* x, const void* Wg, const float* gate_b
   int32_t* d_src = (int32_t*)(base + w.slot_src);
   hipStream_t s = (hipStream_t)stream;
 
+  // arrivals do not depend on the capacity: count them first (no slot sources yet), then choose the capacity on the device.
+  // The plain linear router takes the fast logits with exact repair of near-ties; the cosine router and batch prioritized
+  // routing (whose token order is itself decided on the logits) take logits that are exactly rounded throughout.
   int st;
-  if (router == MOE_ROUTER_COSINE)
-    st = moe_gate_logits_cosine(x, Wg, Me, tau, dtype, T, M, D, E, d_logits, base + w.cosine_ws, moe_cosine_gate_workspace_bytes(T, D, E), stream);
-  else
-    st = launch_gate_logits(x, Wg, gate_bias, dtype, T, M, E, d_logits, s) == hipSuccess ? MOE_OK : MOE_HIP_ERROR;
-  if (st != MOE_OK) return st;
-  // arrivals do not depend on the capacity: count them first (no slot sources yet), then choose the capacity on the device
-  if (bpr)
-    st = moe_gate_topk_bpr(d_logits, T, E, k, C_max, normalize, d_idx, d_gw, d_loc, d_counts, nullptr, base + w.gate_ws,
-                           moe_gate_bpr_workspace_bytes(T, E, k), stream);
-  else
-    st = launch_gate_topk(d_logits, T, E, k, C_max, normalize, d_idx, d_gw, d_loc, d_counts, nullptr, (int32_t*)(base + w.gate_ws), s) == hipSuccess
-             ? MOE_OK : MOE_HIP_ERROR;
+  if (router == MOE_ROUTER_LINEAR && !bpr) {
+    st = run_gate(x, Wg, gate_bias, dtype, T, M, E, k, C_max, normalize, d_logits, d_idx, d_gw, d_loc, d_counts, nullptr,
+                  base + w.gate_ws, s, [] { return true; }) == hipSuccess ? MOE_OK : MOE_HIP_ERROR;
+  } else {
+    if (router == MOE_ROUTER_COSINE)
+      st = moe_gate_logits_cosine(x, Wg, Me, tau, dtype, T, M, D, E, d_logits, base + w.cosine_ws, moe_cosine_gate_workspace_bytes(T, D, E), stream);
+    else
+      st = launch_gate_logits(x, Wg, gate_bias, dtype, T, M, E, d_logits, s) == hipSuccess ? MOE_OK : MOE_HIP_ERROR;
+    if (st != MOE_OK) return st;
+    if (bpr)
+      st = moe_gate_topk_bpr(d_logits, T, E, k, C_max, normalize, d_idx, d_gw, d_loc, d_counts, nullptr, base + w.gate_ws,
+                             moe_gate_bpr_workspace_bytes(T, E, k), stream);
+    else
+      st = launch_gate_topk(d_logits, T, E, k, C_max, normalize, d_idx, d_gw, d_loc, d_counts, nullptr, (int32_t*)(base + w.gate_ws), s) == hipSuccess
+               ? MOE_OK : MOE_HIP_ERROR;
+  }
   if (st != MOE_OK) return st;
   if (launch_dynamic_capacity(d_counts, E, bound, d_C, s, fixed, d_fills) != hipSuccess) return MOE_HIP_ERROR;
   // every buffer keeps the layout the caller's bound gives ([E, C_max, ...]); the chosen capacity only narrows which
@@ -583,8 +638,8 @@ int moe_layer_forward_train(const void* x, const void* Wg, const float* gate_bia
   int32_t* counts = (int32_t*)(base + w.counts);
   int32_t* src = (int32_t*)(base + w.slot_src);
   hipStream_t s = (hipStream_t)stream;
-  if (launch_gate_logits(x, Wg, gate_bias, dtype, T, M, E, logits, s) != hipSuccess) return MOE_HIP_ERROR;
-  if (launch_gate_topk(logits, T, E, k, C, normalize, idx, gw, loc, counts, src, (int32_t*)(base + w.gate_ws), s) != hipSuccess)
+  if (run_gate(x, Wg, gate_bias, dtype, T, M, E, k, C, normalize, logits, idx, gw, loc, counts, src, base + w.gate_ws, s,
+               [] { return true; }) != hipSuccess)
     return MOE_HIP_ERROR;
   // the slabs are internal and every later stage stops at an expert's fill: no zero rows needed
   if (launch_encode(x, dtype, idx, loc, src, T, M, E, k, C, base + w.Z, s, false) != hipSuccess) return MOE_HIP_ERROR;

@@ -89,9 +89,30 @@ hipError_t launch_gate_logits(const void* x, const void* Wg, const float* bias, 
 hipError_t launch_gate_logits_cosine(const void* x, const void* Wp, const float* Me, double tau, int dtype, int64_t T,
                                      int64_t M, int64_t D, int64_t E, float* logits, float* proj, double* MeT, double* norm,
                                      hipStream_t s);
-hipError_t launch_gate_topk(const float* logits, int64_t T, int64_t E, int k, int64_t C, int normalize, int32_t* idx,
+// Fast gate logits (gate_fast.hip): workspace pieces and what the top-k kernel needs to repair near-ties exactly
+struct GateFastWorkspace {
+  uint16_t* Wt;                                           // [E, Mp] = Wg^T, rows zero-padded
+  float* wnorm;                                           // [E]
+  float* margin;                                          // [T] error bound of a token's logits
+  int64_t Mp;
+};
+struct GateRepair {
+  const float* margin;
+  const void* x;
+  const uint16_t* Wt;
+  const float* bias;
+  int64_t M, Mp;
+};
+size_t gate_fast_workspace_bytes(int64_t T, int64_t M, int64_t E);
+GateFastWorkspace gate_fast_layout(void* ws, int64_t T, int64_t M, int64_t E);
+bool gate_logits_fast_supports(int dtype, int64_t T, int64_t M, int64_t E);
+hipError_t launch_gate_logits_fast(const void* x, const void* Wg, const float* bias, int64_t T, int64_t M, int64_t E,
+                                   float* logits, const GateFastWorkspace& w, hipStream_t s);
+// `repair` (optional): the logits are approximate to within repair->margin[t]; near-ties are then recomputed in fp64 and
+// written back into `logits` (not combinable with `perm`)
+hipError_t launch_gate_topk(float* logits, int64_t T, int64_t E, int k, int64_t C, int normalize, int32_t* idx,
                             float* gate_w, int32_t* loc, int32_t* counts, int32_t* slot_src, int32_t* block_counts,
-                            hipStream_t s, const int32_t* perm = nullptr);
+                            hipStream_t s, const int32_t* perm = nullptr, const GateRepair* repair = nullptr);
 hipError_t launch_bpr_order(const float* logits, int64_t T, int64_t E, uint64_t* key, int32_t* before, int32_t* perm,
                             hipStream_t s);
 hipError_t launch_decode_backward(const void* d_out, const void* Y, int dtype, const int32_t* idx, const int32_t* loc,

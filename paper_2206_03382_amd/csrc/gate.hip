@@ -257,13 +257,244 @@ hipError_t launch_gate_logits(const void* x, const void* Wg, const float* bias, 
 // (V per lane).  Selection is k rounds of argmax on (value, index): larger value wins, equal values -> lower
 // index, so the result is unique and independent of the reduction tree.
 // ---------------------------------------------------------------------------------------------------------------
-template <int V>
-__global__ __launch_bounds__(1024) void gate_topk_kernel(const float* __restrict__ logits, int64_t T, int E, int k, int G,
+// Value of the partner lane in one step of a reduction over a group of lanes.  Steps 1 and 2 swap within quads, steps 4
+// and 8 read the mirrored lane of the other half of 8 / 16 lanes (data-parallel primitives, no LDS traffic); the mirror
+// is as good as an xor partner wherever the lanes of each half already agree, which holds in a reduction whose steps run
+// in ascending order.  Steps 16 and 32 go through the cross-lane permute.
+template <int OFF> __device__ __forceinline__ int group_partner(int v) {
+  if constexpr (OFF == 1) return __builtin_amdgcn_update_dpp(0, v, 0xB1, 0xf, 0xf, false);        // quad_perm [1,0,3,2]
+  else if constexpr (OFF == 2) return __builtin_amdgcn_update_dpp(0, v, 0x4E, 0xf, 0xf, false);   // quad_perm [2,3,0,1]
+  else if constexpr (OFF == 4) return __builtin_amdgcn_update_dpp(0, v, 0x141, 0xf, 0xf, false);  // row_half_mirror
+  else if constexpr (OFF == 8) return __builtin_amdgcn_update_dpp(0, v, 0x140, 0xf, 0xf, false);  // row_mirror
+  else return __shfl_xor(v, OFF, 64);
+}
+template <int OFF> __device__ __forceinline__ float group_partner(float v) {
+  return __int_as_float(group_partner<OFF>(__float_as_int(v)));
+}
+
+template <int G> __device__ __forceinline__ float group_max(float v) {
+  if constexpr (G > 1) v = fmaxf(v, group_partner<1>(v));
+  if constexpr (G > 2) v = fmaxf(v, group_partner<2>(v));
+  if constexpr (G > 4) v = fmaxf(v, group_partner<4>(v));
+  if constexpr (G > 8) v = fmaxf(v, group_partner<8>(v));
+  if constexpr (G > 16) v = fmaxf(v, group_partner<16>(v));
+  if constexpr (G > 32) v = fmaxf(v, group_partner<32>(v));
+  return v;
+}
+template <int G> __device__ __forceinline__ float group_sum(float v) {
+  if constexpr (G > 1) v += group_partner<1>(v);
+  if constexpr (G > 2) v += group_partner<2>(v);
+  if constexpr (G > 4) v += group_partner<4>(v);
+  if constexpr (G > 8) v += group_partner<8>(v);
+  if constexpr (G > 16) v += group_partner<16>(v);
+  if constexpr (G > 32) v += group_partner<32>(v);
+  return v;
+}
+template <int OFF> __device__ __forceinline__ void argmax_step(float& bv, int& be) {
+  const float ov = group_partner<OFF>(bv);
+  const int oe = group_partner<OFF>(be);
+  if (ov > bv || (ov == bv && oe < be)) { bv = ov; be = oe; }
+}
+template <int G> __device__ __forceinline__ void group_argmax(float& bv, int& be) {
+  if constexpr (G > 1) argmax_step<1>(bv, be);
+  if constexpr (G > 2) argmax_step<2>(bv, be);
+  if constexpr (G > 4) argmax_step<4>(bv, be);
+  if constexpr (G > 8) argmax_step<8>(bv, be);
+  if constexpr (G > 16) argmax_step<16>(bv, be);
+  if constexpr (G > 32) argmax_step<32>(bv, be);
+}
+
+// The decisions of one token, taken by its group of G lanes on v[vi] = logit of expert gl + G vi (-inf past E; consumed).
+// Slot vi of lane gl receives choice j = gl + G vi: si = expert, sw = its softmax probability (not yet renormalised);
+// denom = the sum of the k probabilities.  With `check` the k + 1 largest values are ordered and the result says whether
+// some pair of neighbours is closer than `tol2` (twice the error bound of the logits) plus rounding slack (two units in
+// the last place of the larger one); theta = the smallest value looked at.
+template <int G, int V>
+__device__ __forceinline__ bool token_topk(float (&v)[V], int gl, int E, int k, bool check, float tol2, int (&si)[V], float (&sw)[V],
+                                           float& denom, float& theta) {
+  const float NEG_INF = -__builtin_inff();
+  float mx = v[0];
+#pragma unroll
+  for (int vi = 1; vi < V; ++vi) mx = fmaxf(mx, v[vi]);
+  mx = group_max<G>(mx);
+  float se = 0.f;
+#pragma unroll
+  for (int vi = 0; vi < V; ++vi) se += expf(v[vi] - mx);
+  se = group_sum<G>(se);
+#pragma unroll
+  for (int vi = 0; vi < V; ++vi) { si[vi] = 0; sw[vi] = 0.f; }
+  denom = 0.f;
+  bool close = false;
+  float prev = 0.f;
+  const int rounds = (check && k < E) ? k + 1 : k;
+  for (int j = 0; j < rounds; ++j) {
+    float bv = v[0];
+    int be = gl;
+#pragma unroll
+    for (int vi = 1; vi < V; ++vi)
+      if (v[vi] > bv) { bv = v[vi]; be = gl + G * vi; }
+    group_argmax<G>(bv, be);
+    be = be < E ? be : E - 1;                          // only reachable with non-finite logits; keeps indices in range
+    if (check && j > 0) close = close || !(prev - bv > tol2 + 4.8e-7f * fmaxf(fabsf(prev), fabsf(bv)));
+    prev = bv;
+    theta = bv;
+#pragma unroll
+    for (int vi = 0; vi < V; ++vi)
+      if (be == gl + G * vi) v[vi] = NEG_INF;          // the chosen expert leaves the pool
+    if (j < k) {
+      const float pj = expf(bv - mx) / se;
+      denom += pj;
+#pragma unroll
+      for (int vi = 0; vi < V; ++vi)
+        if (j == gl + G * vi) { si[vi] = be; sw[vi] = pj; }
+    }
+  }
+  return close;
+}
+
+// sum over m of x[t, m] * Wt[e, m] in fp64 by one wave, for two experts at once (every product of two bf16 values is
+// exact in fp32; lane l adds the 16-byte pieces l, l + 64, ... in ascending order, then a fixed butterfly adds the 64
+// partial sums); all lanes get both sums.  Four pieces are fetched per round so that their latencies overlap.
+__device__ __forceinline__ void wave_dot2_fp64(const uint16_t* __restrict__ xr, const uint16_t* __restrict__ wa,
+                                               const uint16_t* __restrict__ wb, int M, int lane, double& sa, double& sb) {
+  double acc_a = 0.0, acc_b = 0.0;
+  const int pieces = M >> 3;
+  for (int p0 = 0; p0 < pieces; p0 += 256) {
+    uint4 xv[4], av[4], bv[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int p = p0 + 64 * u + lane;
+      const int q = p < pieces ? p : 0;                  // pieces past the row's end re-read its start and are zeroed
+      xv[u] = *reinterpret_cast<const uint4*>(xr + q * 8);
+      av[u] = *reinterpret_cast<const uint4*>(wa + q * 8);
+      bv[u] = *reinterpret_cast<const uint4*>(wb + q * 8);
+      if (p >= pieces) xv[u] = make_uint4(0, 0, 0, 0);
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const uint32_t xa[4] = {xv[u].x, xv[u].y, xv[u].z, xv[u].w};
+      const uint32_t aa[4] = {av[u].x, av[u].y, av[u].z, av[u].w};
+      const uint32_t ba[4] = {bv[u].x, bv[u].y, bv[u].z, bv[u].w};
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const float xl = __uint_as_float(xa[q] << 16), xh = __uint_as_float(xa[q] & 0xffff0000u);
+        acc_a += (double)(xl * __uint_as_float(aa[q] << 16));
+        acc_a += (double)(xh * __uint_as_float(aa[q] & 0xffff0000u));
+        acc_b += (double)(xl * __uint_as_float(ba[q] << 16));
+        acc_b += (double)(xh * __uint_as_float(ba[q] & 0xffff0000u));
+      }
+    }
+  }
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) {
+    acc_a += __shfl_xor(acc_a, d, 64);
+    acc_b += __shfl_xor(acc_b, d, 64);
+  }
+  sa = acc_a;
+  sb = acc_b;
+}
+
+// Exact decisions for one token whose approximate logits (within tol2 / 2 of the exactly rounded ones) left its top k
+// open; run by one wave.  theta = the (k+1)-th largest approximate logit.  Every expert that can still reach the top k
+// (approximate logit within tol2 of theta) is looked at; those that have another such expert within tol2 get their logit
+// recomputed in fp64 from x and Wt and stored (an expert farther than that from every other keeps its place whatever the
+// true values are); then the token is decided again on the repaired row.  hist: the block's packed arrival counters.
+__device__ __forceinline__ void repair_token(int64_t t, float theta, float tol2, int lane, float* __restrict__ logits, int E, int k,
+                                             int normalize, int32_t* __restrict__ idx, float* __restrict__ gate_w, int* hist,
+                                             const uint16_t* __restrict__ x, const uint16_t* __restrict__ Wt,
+                                             const float* __restrict__ bias, int M, int Mp) {
+  const float NEG_INF = -__builtin_inff();
+  const float reach = theta - tol2 - 4.8e-7f * fabsf(theta);         // experts below this cannot be among the k largest
+  float rv[8];
+#pragma unroll
+  for (int vi = 0; vi < 8; ++vi) {
+    const int e = lane + 64 * vi;
+    rv[vi] = e < E ? logits[t * E + e] : NEG_INF;
+  }
+  bool need[8];
+#pragma unroll
+  for (int vi = 0; vi < 8; ++vi) need[vi] = false;
+#pragma unroll
+  for (int vi = 0; vi < 8; ++vi) {
+    unsigned long long todo = __ballot(rv[vi] >= reach);
+    while (todo) {
+      const int l = __builtin_ctzll(todo);
+      todo &= todo - 1;
+      const float val = __shfl(rv[vi], l, 64);
+      bool near = false;
+#pragma unroll
+      for (int vj = 0; vj < 8; ++vj)
+        near = near || (rv[vj] >= reach && !(vj == vi && lane == l) &&
+                        fabsf(rv[vj] - val) <= tol2 + 4.8e-7f * fmaxf(fabsf(rv[vj]), fabsf(val)));
+      if (__ballot(near) != 0ull && lane == l) need[vi] = true;
+    }
+  }
+  // the marked experts, two at a time (one pending until its partner turns up)
+  const uint16_t* xr = x + t * (int64_t)M;
+  int pend_e = -1, pend_l = 0, pend_vi = 0;
+  auto put = [&](int e, int l, int vi, double sum) __attribute__((always_inline)) {
+    const float val = (float)(sum + (bias ? (double)bias[e] : 0.0));
+#pragma unroll
+    for (int vj = 0; vj < 8; ++vj)
+      if (vj == vi && lane == l) rv[vj] = val;
+    if (lane == l) logits[t * E + e] = val;
+  };
+#pragma unroll
+  for (int vi = 0; vi < 8; ++vi) {
+    unsigned long long todo = __ballot(need[vi]);
+    while (todo) {
+      const int l = __builtin_ctzll(todo);
+      todo &= todo - 1;
+      const int e = l + 64 * vi;
+      if (pend_e < 0) { pend_e = e; pend_l = l; pend_vi = vi; continue; }
+      double sa, sb;
+      wave_dot2_fp64(xr, Wt + (int64_t)pend_e * Mp, Wt + (int64_t)e * Mp, M, lane, sa, sb);
+      put(pend_e, pend_l, pend_vi, sa);
+      put(e, l, vi, sb);
+      pend_e = -1;
+    }
+  }
+  if (pend_e >= 0) {
+    double sa, sb;
+    wave_dot2_fp64(xr, Wt + (int64_t)pend_e * Mp, Wt + (int64_t)pend_e * Mp, M, lane, sa, sb);
+    put(pend_e, pend_l, pend_vi, sa);
+  }
+  int si[8];
+  float sw[8], denom, th;
+  token_topk<64, 8>(rv, lane, E, k, false, 0.f, si, sw, denom, th);
+#pragma unroll
+  for (int vi = 0; vi < 8; ++vi) {
+    const int j = lane + 64 * vi;
+    if (j < k) {
+      idx[t * k + j] = si[vi];
+      gate_w[t * k + j] = normalize ? sw[vi] / denom : sw[vi];
+      atomicAdd(&hist[(j * E + si[vi]) >> 2], 1 << (8 * ((j * E + si[vi]) & 3)));
+    }
+  }
+}
+
+// One block per 64 tokens (in arrival order).  Phase 1: every token's decisions from its logits.  With `margin` (the
+// logits came from the fast kernel and are only known to within margin[t]) a token whose k + 1 largest logits are not
+// separated by more than twice that bound is set aside.  Phase 2: one wave per token set aside repairs it (repair_token):
+// the decisions then equal those taken on exactly rounded logits.  Phase 3: the block's per-(rank, expert) arrival counters go to memory.
+template <int G, int V>
+__global__ __launch_bounds__(1024) void gate_topk_kernel(float* __restrict__ logits, int64_t T, int E, int k,
                                                         int normalize, int32_t* __restrict__ idx,
                                                         float* __restrict__ gate_w, int32_t* __restrict__ block_counts,
-                                                        int NB, const int32_t* __restrict__ perm) {
-  extern __shared__ int hist[];                        // [k][E] arrivals of this block's tokens
-  for (int i = threadIdx.x; i < k * E; i += blockDim.x) hist[i] = 0;
+                                                        int NB, const int32_t* __restrict__ perm,
+                                                        const float* __restrict__ margin, const uint16_t* __restrict__ x,
+                                                        const uint16_t* __restrict__ Wt, const float* __restrict__ bias,
+                                                        int M, int Mp) {
+  extern __shared__ int smem_i[];
+  // [k][E] arrivals of this block's tokens: at most 64 each, so four 8-bit counters share a word (integer atomics on the
+  // word: the sums do not depend on the order)
+  int* hist = smem_i;
+  const int hist_words = (k * E + 3) >> 2;
+  int* aside_tok = smem_i + hist_words;                // [64] block-local tokens set aside
+  float* aside_theta = reinterpret_cast<float*>(aside_tok + kGateTokensPerBlock);
+  int* aside_n = aside_tok + 2 * kGateTokensPerBlock;
+  for (int i = threadIdx.x; i < hist_words; i += blockDim.x) hist[i] = 0;
+  if (threadIdx.x == 0) *aside_n = 0;
   __syncthreads();
   const int groups = blockDim.x / G, g = threadIdx.x / G, gl = threadIdx.x % G;   // blockDim.x is a multiple of 64 >= G
   const float NEG_INF = -__builtin_inff();
@@ -280,60 +511,176 @@ __global__ __launch_bounds__(1024) void gate_topk_kernel(const float* __restrict
       const int e = gl + G * vi;
       v[vi] = (valid && e < E) ? logits[t * E + e] : NEG_INF;
     }
-    float mx = v[0];
-#pragma unroll
-    for (int vi = 1; vi < V; ++vi) mx = fmaxf(mx, v[vi]);
-    for (int off = G >> 1; off >= 1; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
-    float se = 0.f;
-#pragma unroll
-    for (int vi = 0; vi < V; ++vi) se += expf(v[vi] - mx);
-    for (int off = G >> 1; off >= 1; off >>= 1) se += __shfl_xor(se, off);
-
     int si[V];
-    float sw[V];
-#pragma unroll
-    for (int vi = 0; vi < V; ++vi) { si[vi] = 0; sw[vi] = 0.f; }
-    float denom = 0.f;
-    for (int j = 0; j < k; ++j) {
-      float bv = v[0];
-      int be = gl;
-#pragma unroll
-      for (int vi = 1; vi < V; ++vi)
-        if (v[vi] > bv) { bv = v[vi]; be = gl + G * vi; }
-      for (int off = G >> 1; off >= 1; off >>= 1) {
-        const float ov = __shfl_xor(bv, off);
-        const int oe = __shfl_xor(be, off);
-        if (ov > bv || (ov == bv && oe < be)) { bv = ov; be = oe; }
+    float sw[V], denom, theta;
+    const bool check = margin != nullptr;
+    const float tol2 = (check && valid) ? 2.0f * margin[t] : 0.f;
+    bool publish = valid;
+    const bool close = token_topk<G, V>(v, gl, E, k, check, tol2, si, sw, denom, theta);
+    if (check && valid && close) {                     // uniform over the token's lanes
+      publish = false;
+      if (gl == 0) {
+        const int slot = atomicAdd(aside_n, 1);
+        aside_tok[slot] = tb;
+        aside_theta[slot] = theta;
       }
-      be = be < E ? be : E - 1;                        // only reachable with non-finite logits; keeps indices in range
-      const float pj = expf(bv - mx) / se;
-      denom += pj;
-#pragma unroll
-      for (int vi = 0; vi < V; ++vi) {
-        if (be == gl + G * vi) v[vi] = NEG_INF;        // the chosen expert leaves the pool
-        if (j == gl + G * vi) { si[vi] = be; sw[vi] = pj; }
-      }
-      if (valid && gl == 0) atomicAdd(&hist[j * E + be], 1);
     }
-    if (valid) {
+    if (publish) {
 #pragma unroll
       for (int vi = 0; vi < V; ++vi) {
         const int j = gl + G * vi;
         if (j < k) {
           idx[t * k + j] = si[vi];
           gate_w[t * k + j] = normalize ? sw[vi] / denom : sw[vi];
+          atomicAdd(&hist[(j * E + si[vi]) >> 2], 1 << (8 * ((j * E + si[vi]) & 3)));
         }
       }
     }
   }
   __syncthreads();
+  if (margin) {
+    const int n_aside = *aside_n;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
+    for (int i = wave; i < n_aside; i += nwaves)
+      repair_token((int64_t)blockIdx.x * kGateTokensPerBlock + aside_tok[i], aside_theta[i],
+                   2.0f * margin[(int64_t)blockIdx.x * kGateTokensPerBlock + aside_tok[i]], lane, logits, E, k, normalize, idx, gate_w,
+                   hist, x, Wt, bias, M, Mp);
+    __syncthreads();
+  }
   for (int i = threadIdx.x; i < k * E; i += blockDim.x) {
     const int j = i / E, e = i % E;
-    block_counts[((int64_t)j * NB + blockIdx.x) * E + e] = hist[i];
+    block_counts[((int64_t)e * k + j) * NB + blockIdx.x] = (hist[i >> 2] >> (8 * (i & 3))) & 0xff;
   }
 }
 
-// One block per expert: exclusive scan of block_counts[(j, b), e] over (j, b) in place; totals -> counts[e];
+// softmax + top-k with one lane per token, for k <= 32: the kernel of choice for wide gates.  A wave owns 64 consecutive
+// tokens (one block of the arrival counters).  Its logits pass through LDS 32 experts at a time (rows padded to 33 words:
+// the transposed reads are conflict-free); every lane walks its own row in ascending expert order and keeps the N = KMAX+1
+// largest values seen so far, sorted, in registers: a new value moves in above every smaller one (strictly smaller: an
+// equal value met later, i.e. a higher index, stays below) and the entries from there on shift down by one, so the list ends as the top k in the order the selection
+// rule asks for, and its (k+1)-th entry serves the near-tie check.  The softmax denominator is kept chunk by chunk
+// relative to the running maximum.  The four waves of a block work independently (no barrier).
+template <int KMAX, bool VEC4>
+__global__ __launch_bounds__(256) void gate_topk_lane_kernel(float* __restrict__ logits, int64_t T, int E, int k, int normalize,
+                                                             int32_t* __restrict__ idx, float* __restrict__ gate_w,
+                                                             int32_t* __restrict__ block_counts, int NB,
+                                                             const float* __restrict__ margin, const uint16_t* __restrict__ x,
+                                                             const uint16_t* __restrict__ Wt, const float* __restrict__ bias,
+                                                             int M, int Mp) {
+  constexpr int N = KMAX + 1, CW = 32, LDW = CW + 1;
+  extern __shared__ int smem_i[];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int hist_words = (k * E + 3) >> 2;
+  const int per_wave = kGateTokensPerBlock * LDW + hist_words;
+  float* tile = reinterpret_cast<float*>(smem_i + wave * per_wave);   // [64 tokens][33]
+  int* hist = smem_i + wave * per_wave + kGateTokensPerBlock * LDW;   // packed [k][E] arrival counters of this wave's tokens
+  const int b = blockIdx.x * 4 + wave;                                // block of 64 tokens
+  if (b >= NB) return;                                                // waves are independent: no barrier below
+  const int64_t t0 = (int64_t)b * kGateTokensPerBlock;
+  const int64_t t = t0 + lane;
+  const bool valid = t < T;
+  const float NEG_INF = -__builtin_inff();
+  for (int i = lane; i < hist_words; i += 64) hist[i] = 0;
+
+  float L[N];
+  int I[N];
+#pragma unroll
+  for (int i = 0; i < N; ++i) { L[i] = NEG_INF; I[i] = 0x7fffffff; }
+  float mx = NEG_INF, se = 0.f;
+  for (int e0 = 0; e0 < E; e0 += CW) {
+    // tile[row][c] = logits[t0 + row][e0 + c]  (-inf outside the matrix)
+    if (VEC4) {                                                        // E % 4 == 0: 16-byte pieces, 8 rows x 128 bytes per load
+      const int c4 = (lane & 7) * 4;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const int row = (lane >> 3) + 8 * i;
+        float4 v = make_float4(NEG_INF, NEG_INF, NEG_INF, NEG_INF);
+        if (t0 + row < T && e0 + c4 < E) v = *reinterpret_cast<const float4*>(logits + (t0 + row) * E + e0 + c4);
+        float* d = tile + row * LDW + c4;
+        d[0] = v.x; d[1] = v.y; d[2] = v.z; d[3] = v.w;
+      }
+    } else {
+      const int c = lane & 31;
+#pragma unroll 8
+      for (int i = 0; i < 32; ++i) {
+        const int row = (lane >> 5) + 2 * i;
+        tile[row * LDW + c] = (t0 + row < T && e0 + c < E) ? logits[(t0 + row) * E + e0 + c] : NEG_INF;
+      }
+    }
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_s_waitcnt(0xc07f);                                // lgkmcnt(0): the tile is in LDS before any lane reads it
+    float row[CW];
+#pragma unroll
+    for (int c = 0; c < CW; ++c) row[c] = tile[lane * LDW + c];
+    float cm = row[0];
+#pragma unroll
+    for (int c = 1; c < CW; ++c) cm = fmaxf(cm, row[c]);
+    if (cm > mx) { se *= __expf(mx - cm); mx = cm; }                   // (0 * exp(-inf) = 0 on the first chunk)
+#pragma unroll
+    for (int c = 0; c < CW; ++c) {
+      float v = row[c];
+      int e = e0 + c;
+      se += __expf(v - mx);
+      bool g = false;                                                  // once the value has moved in, everything below shifts down
+#pragma unroll
+      for (int i = 0; i < N; ++i) {
+        g = g || v > L[i];
+        const float tv = g ? L[i] : v;
+        const int ti = g ? I[i] : e;
+        L[i] = g ? v : L[i];
+        I[i] = g ? e : I[i];
+        v = tv;
+        e = ti;
+      }
+    }
+    __builtin_amdgcn_wave_barrier();                                   // every lane has read its row before the next chunk lands
+  }
+  // near-tie check on the k + 1 largest
+  bool close = false;
+  const bool check = margin != nullptr;
+  const float tol2 = (check && valid) ? 2.0f * margin[t] : 0.f;
+  float theta = NEG_INF;
+#pragma unroll
+  for (int i = 0; i < N; ++i) {
+    if (i < k || (i == k && k < E)) {
+      theta = L[i];
+      if (check && i > 0) close = close || !(L[i - 1] - L[i] > tol2 + 4.8e-7f * fmaxf(fabsf(L[i - 1]), fabsf(L[i])));
+    }
+  }
+  const bool aside = check && valid && close;
+  if (valid && !aside) {
+    float p[KMAX], denom = 0.f;
+#pragma unroll
+    for (int j = 0; j < KMAX; ++j) {
+      p[j] = 0.f;
+      if (j < k) { p[j] = expf(L[j] - mx) / se; denom += p[j]; }
+    }
+#pragma unroll
+    for (int j = 0; j < KMAX; ++j) {
+      if (j < k) {
+        const int e = I[j] < E ? I[j] : E - 1;                         // only reachable with non-finite logits
+        idx[t * k + j] = e;
+        gate_w[t * k + j] = normalize ? p[j] / denom : p[j];
+        atomicAdd(&hist[(j * E + e) >> 2], 1 << (8 * ((j * E + e) & 3)));
+      }
+    }
+  }
+  unsigned long long todo = __ballot(aside);
+  while (todo) {                                                        // the wave repairs its open tokens one by one
+    const int l = __builtin_ctzll(todo);
+    todo &= todo - 1;
+    repair_token(t0 + l, __shfl(theta, l, 64), __shfl(tol2, l, 64), lane, logits, E, k, normalize, idx, gate_w, hist, x, Wt, bias, M, Mp);
+  }
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_s_waitcnt(0xc07f);
+  for (int i = lane; i < k * E; i += 64) {
+    const int j = i / E, e = i % E;
+    block_counts[((int64_t)e * k + j) * NB + b] = (hist[i >> 2] >> (8 * (i & 3))) & 0xff;
+  }
+}
+
+// One block per expert: exclusive scan of block_counts[e, (j, b)] (an expert's counters are contiguous, in arrival order
+// (rank j, block b)) in place; totals -> counts[e];
 // slots [min(total, C), C) of slot_src[e] are marked unfilled.
 __global__ __launch_bounds__(256) void gate_scan_kernel(int32_t* __restrict__ block_counts, int L, int E, int64_t C,
                                                         int32_t* __restrict__ counts, int32_t* __restrict__ slot_src) {
@@ -342,7 +689,7 @@ __global__ __launch_bounds__(256) void gate_scan_kernel(int32_t* __restrict__ bl
   const int per = (L + 255) / 256;
   const int start = min(tid * per, L), stop = min(start + per, L);
   int sum = 0;
-  for (int i = start; i < stop; ++i) sum += block_counts[(int64_t)i * E + e];
+  for (int i = start; i < stop; ++i) sum += block_counts[(int64_t)e * L + i];
   part[tid] = sum;
   __syncthreads();
   for (int off = 1; off < 256; off <<= 1) {            // inclusive Hillis-Steele scan of the 256 partial sums
@@ -353,8 +700,8 @@ __global__ __launch_bounds__(256) void gate_scan_kernel(int32_t* __restrict__ bl
   }
   int run = part[tid] - sum;
   for (int i = start; i < stop; ++i) {
-    const int c = block_counts[(int64_t)i * E + e];
-    block_counts[(int64_t)i * E + e] = run;
+    const int c = block_counts[(int64_t)e * L + i];
+    block_counts[(int64_t)e * L + i] = run;
     run += c;
   }
   const int total = part[255];
@@ -391,32 +738,56 @@ __global__ __launch_bounds__(kGateTokensPerBlock) void gate_assign_kernel(const 
       remaining &= ~same;
     }
     if (valid) {
-      const int l = block_off[((int64_t)j * NB + blockIdx.x) * E + e] + r;
+      const int l = block_off[((int64_t)e * k + j) * NB + blockIdx.x] + r;
       loc[t * k + j] = l;
       if (slot_src && l < C) slot_src[(int64_t)e * C + l] = (int32_t)t;
     }
   }
 }
 
-hipError_t launch_gate_topk(const float* logits, int64_t T, int64_t E, int k, int64_t C, int normalize, int32_t* idx,
+hipError_t launch_gate_topk(float* logits, int64_t T, int64_t E, int k, int64_t C, int normalize, int32_t* idx,
                             float* gate_w, int32_t* loc, int32_t* counts, int32_t* slot_src, int32_t* block_counts,
-                            hipStream_t s, const int32_t* perm) {
+                            hipStream_t s, const int32_t* perm, const GateRepair* repair) {
   const int NB = (int)ceil_div(T, kGateTokensPerBlock);
-  // lane group per token: up to 16 experts one value per lane; from there on 16 lanes with up to 8 values each (4 tokens
-  // per wave and 4 cross-lane steps per reduction instead of 6), and a whole wave beyond 128 experts
+  // lane group per token: up to 16 experts one value per lane; from there on 16 lanes with up to 8 logits each (4 tokens
+  // per wave), and a whole wave beyond 128 experts
   int G = 1;
   while (G < E && G < 16) G <<= 1;
   if (E > 128) G = 64;
   const int V = (int)ceil_div(E, G);
-  const size_t shmem = (size_t)k * E * sizeof(int);
+  const size_t shmem = (((size_t)k * E + 3) / 4 + 2 * kGateTokensPerBlock + 1) * sizeof(int);
   // one lane group per token: as many threads as the block's 64 tokens need, so that (up to 16 experts) every token's
   // logits are fetched in one round instead of one dependent round trip per pass
   const dim3 grid(NB), block(256);
   const dim3 tblock((unsigned)(64 * G < 256 ? 256 : (64 * G > 1024 ? 1024 : 64 * G)));
-  if (V == 1) gate_topk_kernel<1><<<grid, tblock, shmem, s>>>(logits, T, (int)E, k, G, normalize, idx, gate_w, block_counts, NB, perm);
-  else if (V == 2) gate_topk_kernel<2><<<grid, tblock, shmem, s>>>(logits, T, (int)E, k, G, normalize, idx, gate_w, block_counts, NB, perm);
-  else if (V <= 4) gate_topk_kernel<4><<<grid, tblock, shmem, s>>>(logits, T, (int)E, k, G, normalize, idx, gate_w, block_counts, NB, perm);
-  else gate_topk_kernel<8><<<grid, tblock, shmem, s>>>(logits, T, (int)E, k, G, normalize, idx, gate_w, block_counts, NB, perm);
+  const float* margin = repair ? repair->margin : nullptr;
+  const uint16_t* rx = repair ? (const uint16_t*)repair->x : nullptr;
+  const uint16_t* rw = repair ? repair->Wt : nullptr;
+  const float* rb = repair ? repair->bias : nullptr;
+  const int rM = repair ? (int)repair->M : 0, rMp = repair ? (int)repair->Mp : 0;
+#define MOE_TOPK(GG, VV) gate_topk_kernel<GG, VV><<<grid, tblock, shmem, s>>>(logits, T, (int)E, k, normalize, idx, gate_w, block_counts, NB, perm, margin, rx, rw, rb, rM, rMp)
+#define MOE_TOPK_LANE(KM)                                                                                                     \
+  do {                                                                                                                        \
+    const size_t lsh = 4 * ((size_t)kGateTokensPerBlock * 33 + ((size_t)k * E + 3) / 4) * sizeof(int);                        \
+    const dim3 lgrid((unsigned)ceil_div(NB, 4));                                                                              \
+    if (E % 4 == 0) gate_topk_lane_kernel<KM, true><<<lgrid, block, lsh, s>>>(logits, T, (int)E, k, normalize, idx, gate_w, block_counts, NB, margin, rx, rw, rb, rM, rMp); \
+    else gate_topk_lane_kernel<KM, false><<<lgrid, block, lsh, s>>>(logits, T, (int)E, k, normalize, idx, gate_w, block_counts, NB, margin, rx, rw, rb, rM, rMp); \
+  } while (0)
+  // wide gates with few choices: one lane per token (its LDS footprint, 4 waves x (8.25 KB + k E bytes), must fit 64 KB);
+  // tokens in a caller-given order (perm) keep the lane-group kernel
+  const bool lane_kernel = !perm && E > 16 && k <= 32 && (size_t)k * E <= 7936;
+  if (lane_kernel) {
+    if (k <= 1) MOE_TOPK_LANE(1); else if (k <= 2) MOE_TOPK_LANE(2); else if (k <= 4) MOE_TOPK_LANE(4);
+    else if (k <= 8) MOE_TOPK_LANE(8); else if (k <= 16) MOE_TOPK_LANE(16); else MOE_TOPK_LANE(32);
+  }
+  else if (G == 1) MOE_TOPK(1, 1);
+  else if (G == 2) MOE_TOPK(2, 1);
+  else if (G == 4) MOE_TOPK(4, 1);
+  else if (G == 8) MOE_TOPK(8, 1);
+  else if (G == 16) { if (V == 1) MOE_TOPK(16, 1); else if (V == 2) MOE_TOPK(16, 2); else if (V <= 4) MOE_TOPK(16, 4); else MOE_TOPK(16, 8); }
+  else { if (V <= 4) MOE_TOPK(64, 4); else MOE_TOPK(64, 8); }
+#undef MOE_TOPK
+#undef MOE_TOPK_LANE
   hipError_t err = hipGetLastError();
   if (err != hipSuccess) return err;
   gate_scan_kernel<<<dim3((unsigned)E), block, 0, s>>>(block_counts, k * NB, (int)E, C, counts, slot_src);

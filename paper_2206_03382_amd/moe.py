@@ -34,6 +34,8 @@ SIGNATURES = {
     "moe_cosine_gate_workspace_bytes": (_sz, [_i64, _i64, _i64]),
     "moe_gate_logits_cosine": (_i32, [_vp, _vp, _vp, _dbl, _i32, _i64, _i64, _i64, _i64, _vp, _vp, _sz, _vp]),
     "moe_gate_topk": (_i32, [_vp, _i64, _i64, _i32, _i64, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "moe_gate_route_workspace_bytes": (_sz, [_i64, _i64, _i64, _i32, _i32]),
+    "moe_gate_route": (_i32, [_vp, _vp, _vp, _i32, _i64, _i64, _i64, _i32, _i64, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "moe_gate_topk_static_max_bytes": (_sz, []),
     "moe_gate_topk_static": (_i32, [_vp, _i64, _i64, _i32, _i64, _i32, _vp, _vp, _vp, _vp, _vp, _vp]),
     "moe_gate_bpr_workspace_bytes": (_sz, [_i64, _i64, _i32]),
@@ -173,6 +175,25 @@ def gate_topk(logits: torch.Tensor, k: int, C: int, normalize: int, want_slot_sr
     _check(entry(_p(logits), T, E, k, C, int(normalize), _p(idx), _p(gate_w), _p(loc), _p(counts), _p(slot_src),
                  _p(ws), ws.numel(), _stream()), "moe_gate_topk_bpr" if bpr else "moe_gate_topk")
     return dict(idx=idx, loc=loc, gate_w=gate_w, counts=counts, slot_src=slot_src)
+
+
+def gate_route(x: torch.Tensor, Wg: torch.Tensor, gate_bias: Optional[torch.Tensor], k: int, C: int, normalize: int) -> Dict[str, torch.Tensor]:
+    """The gate from the tokens (moe_gate_route): logits, idx, gate_w, loc, counts, slot_src."""
+    T, M = x.shape
+    E = Wg.shape[1]
+    dev = x.device
+    code = _dtype_code(x)
+    nbytes = int(lib().moe_gate_route_workspace_bytes(T, M, E, k, code))
+    if nbytes == 0:
+        raise MoEError(UNSUPPORTED, "moe_gate_route_workspace_bytes")
+    ws = torch.empty((nbytes,), dtype=torch.uint8, device=dev)
+    r = dict(logits=torch.empty((T, E), dtype=torch.float32, device=dev), idx=torch.empty((T, k), dtype=torch.int32, device=dev),
+             loc=torch.empty((T, k), dtype=torch.int32, device=dev), gate_w=torch.empty((T, k), dtype=torch.float32, device=dev),
+             counts=torch.empty((E,), dtype=torch.int32, device=dev), slot_src=torch.empty((E, C), dtype=torch.int32, device=dev))
+    _check(lib().moe_gate_route(_p(x), _p(Wg), _p(gate_bias), code, T, M, E, k, C, int(normalize), _p(r["logits"]), _p(r["idx"]),
+                                _p(r["gate_w"]), _p(r["loc"]), _p(r["counts"]), _p(r["slot_src"]), _p(ws), ws.numel(), _stream()),
+           "moe_gate_route")
+    return r
 
 
 def gate_topk_static(logits: torch.Tensor, k: int, C: int, normalize: int, out: Dict[str, torch.Tensor]) -> Dict[str, torch.Tensor]:
@@ -372,8 +393,8 @@ def layer_forward_backward(x, Wg, gate_bias, W1, b1, W2, b2, k: int, f: float, n
     the backward of decode, of the experts, of encode and of the gate.  Returns out and all gradients."""
     T, E = x.shape[0], W1.shape[0]
     C = capacity(T, E, k, f)
-    logits = gate_logits(x, Wg, gate_bias)
-    r = gate_topk(logits, k, C, normalize)
+    r = gate_route(x, Wg, gate_bias, k, C, normalize)
+    logits = r["logits"]
     Z = encode(x, r["idx"], r["loc"], r["slot_src"], E, C)
     Y, hidden, pre = expert_ffn_train(Z, W1, b1, W2, b2, act, counts=r["counts"])
     out = decode(Y, r["idx"], r["loc"], r["gate_w"])

@@ -64,7 +64,10 @@ def test_workspace_sizes(moe):
     assert moe.gate_workspace_bytes(1000, 8, 9) == 0                       # k > E
     T, M, H, E, k, C = 16384, 2048, 2048, 8, 2, 5120
     need = moe.layer_workspace_bytes(T, M, H, E, k, C, moe.BF16)
-    payload = T * E * 4 + 3 * T * k * 4 + E * 4 + E * C * 4 + moe.gate_workspace_bytes(T, E, k) + 2 * E * C * M * 2 + E * C * H * 2
+    gate = int(moe.lib().moe_gate_route_workspace_bytes(T, M, E, k, moe.BF16))
+    assert moe.gate_workspace_bytes(T, E, k) + E * M * 2 + E * 4 + T * 4 <= gate <= moe.gate_workspace_bytes(T, E, k) + E * M * 2 + E * 4 + T * 4 + 4 * 256
+    assert int(moe.lib().moe_gate_route_workspace_bytes(T, M, E, k, moe.F32)) == (moe.gate_workspace_bytes(T, E, k) + 255) // 256 * 256
+    payload = T * E * 4 + 3 * T * k * 4 + E * 4 + E * C * 4 + gate + 2 * E * C * M * 2 + E * C * H * 2
     assert payload <= need <= payload + 10 * 256
     assert moe.layer_workspace_bytes(T, M + 4, H, E, k, C, moe.BF16) == 0   # M not a multiple of 8
     assert moe.layer_workspace_bytes(T, M, H, E, k, C, 7) == 0              # unknown dtype

@@ -109,6 +109,63 @@ def test_gate_topk_is_deterministic(moe):
 
 
 # ----------------------------------------------------------------------------------------------------------------
+# moe_gate_route: the gate from the tokens; bf16 gates take the matrix-core logits with exact repair of near-ties
+# ----------------------------------------------------------------------------------------------------------------
+ROUTE_CASES = [
+    # T, M, E, k, f, bias
+    (1, 8, 1, 1, 1.0, False), (70, 40, 4, 2, 1.0, True), (1000, 256, 8, 2, 1.25, False), (333, 776, 17, 5, 1.0, True),
+    (2048, 1024, 128, 8, 2.0, True), (130, 64, 130, 3, 1.0, False), (65, 2048, 300, 4, 1.5, True), (5000, 264, 64, 2, 1.0, True),
+    (3000, 4096, 32, 1, 1.25, False), (777, 136, 40, 40, 1.0, False), (4096, 512, 512, 16, 1.0, True),
+]
+
+
+@pytest.mark.parametrize("dtype", [synth.DT_F32, synth.DT_BF16])
+@pytest.mark.parametrize("T,M,E,k,f,bias", ROUTE_CASES)
+def test_gate_route(moe, dtype, T, M, E, k, f, bias):
+    cfg = synth.CONFIGS[1].scaled(T=T, M=M, H=8, E=E, k=k, dtype=dtype, cfg_id=60 + dtype)
+    inp = synth.make_inputs(cfg, seed=T + 1)
+    gb = (np.linspace(-1, 1, E).astype(np.float32)) if bias else None
+    C = O.capacity(T, E, k, f)
+    logits = O.gate_logits(inp["x"], inp["Wg"], gb)
+    ref = O.route(logits, k, C, 1)
+    got = moe.gate_route(dev(inp["x"], dtype), dev(inp["Wg"], dtype), None if gb is None else torch.from_numpy(gb).cuda(), k, C, 1)
+    check_routed_logits(got["logits"].cpu().numpy(), logits)
+    assert_routing_equal(got, ref, C, f"gate_route T={T} M={M} E={E} k={k}")
+    assert np.array_equal(got["slot_src"].cpu().numpy(), O.slot_source(ref["idx"], ref["loc"], E, C))
+
+
+@pytest.mark.parametrize("T,M,E,k", [(4096, 512, 16, 2), (3000, 1024, 64, 4), (2500, 256, 128, 8), (1000, 2048, 200, 3)])
+def test_gate_route_near_ties(moe, T, M, E, k):
+    """Gate weights built to make the matrix-core logits ambiguous: duplicated expert columns (exact ties, which must go
+    to the lower index), columns that differ from another in one entry by one bf16 step (true gaps far below the error
+    bound of the fast logits), and tokens of all zeros (every logit equal)."""
+    cfg = synth.CONFIGS[1].scaled(T=T, M=M, H=8, E=E, k=k, dtype=synth.DT_BF16, cfg_id=62)
+    inp = synth.make_inputs(cfg, seed=T + 5)
+    x, Wg = inp["x"].copy(), inp["Wg"].copy()
+    rng = np.random.default_rng(E)
+    for a, b in ((1, 0), (E - 1, 2), (E // 2, 3)):                          # exact duplicates
+        Wg[:, a] = Wg[:, b]
+    for a, b in ((4, 5), (E - 2, 6), (7, E // 2 + 1)):                      # one entry differs by one bf16 step
+        Wg[:, a] = Wg[:, b]
+        m = int(rng.integers(0, M))
+        bits = synth.bf16_bits(Wg[m:m + 1, a])
+        Wg[m, a] = synth.bf16_bits_to_f32(bits + np.uint16(1))[0]
+    x[::97] = 0.0
+    C = O.capacity(T, E, k, 1.0)
+    logits = O.gate_logits(x, Wg, None)
+    ref = O.route(logits, k, C, 1)
+    d = synth.DT_BF16
+    got = moe.gate_route(dev(x, d), dev(Wg, d), None, k, C, 1)
+    check_routed_logits(got["logits"].cpu().numpy(), logits)
+    assert_routing_equal(got, ref, C, f"near ties T={T} E={E} k={k}")
+    # the duplicated columns do occur among the choices, and the lower index comes first whenever both are chosen
+    idx = ref["idx"]
+    both = (idx == 0).any(axis=1) & (idx == 1).any(axis=1)
+    assert both.any()
+    assert (np.argmax(idx[both] == 0, axis=1) < np.argmax(idx[both] == 1, axis=1)).all()
+
+
+# ----------------------------------------------------------------------------------------------------------------
 # moe_gate_logits
 # ----------------------------------------------------------------------------------------------------------------
 @pytest.mark.parametrize("dtype", [synth.DT_F32, synth.DT_BF16])
@@ -383,8 +440,15 @@ def run_layer(moe, cfg, inp):
 
 
 def check_logits(got, ref, floor=0.0):
+    """Exactly rounded logits (fp64 sums on both sides): equal up to the last bit, in all but a few entries."""
     ulp = np.spacing(np.abs(ref).astype(np.float32))
     assert (np.abs(got - ref) <= ulp).all() and (got != ref).mean() <= max(1e-4, floor / got.size)
+
+
+def check_routed_logits(got, ref):
+    """Logits as the gate stores them inside the layer: exactly rounded where a decision needed them, within the
+    matrix-core path's error bound elsewhere; the bar for floating-point values, 1e-5 * max|ref|."""
+    assert np.abs(got - ref).max() <= 1e-5 * np.abs(ref).max()
 
 
 SMALL_LAYERS = [
@@ -407,7 +471,7 @@ def test_layer_small(moe, cfg, bias):
                       cfg.k, cfg.f, cfg.normalize, cfg.act, tier=tier)
     layer, out = run_layer(moe, cfg, inp)
     assert layer.C == ref["C"]
-    check_logits(layer.routing["logits"].cpu().numpy(), ref["logits"])
+    check_routed_logits(layer.routing["logits"].cpu().numpy(), ref["logits"])
     assert_routing_equal(layer.routing, ref, ref["C"], cfg.name)
     got = host(out)
     assert_close(got, ref["out"], cfg.dtype, f"layer output ({cfg.name})")
@@ -674,7 +738,7 @@ def test_layer_full_size(moe, cfg):
                       cfg.k, cfg.f, cfg.normalize, cfg.act, tier="sparse")
     print("[full-size] HIP path", flush=True)
     layer, out = run_layer(moe, cfg, inp)
-    check_logits(layer.routing["logits"].cpu().numpy(), ref["logits"])
+    check_routed_logits(layer.routing["logits"].cpu().numpy(), ref["logits"])
     assert_routing_equal(layer.routing, ref, ref["C"], cfg.name)
     plain = host(out).copy()
     assert_close(plain, ref["out"], cfg.dtype, f"layer output ({cfg.name})")
@@ -739,7 +803,7 @@ def test_layer_full_size_finegrained(moe, progress):
     fused = layer.forward(xd, fuse_dispatch=True)
     torch.cuda.synchronize()
     assert torch.equal(fused, out), "fused dispatch must reproduce the plain path bit for bit"
-    check_logits(layer.routing["logits"].cpu().numpy(), logits)
+    check_routed_logits(layer.routing["logits"].cpu().numpy(), logits)
     assert_routing_equal(layer.routing, ref, C, cfg.name)
     g = layer.routing
     del layer, fused
