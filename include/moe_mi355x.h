@@ -126,7 +126,7 @@ size_t moe_gate_topk_static_max_bytes(void);
 int moe_gate_topk_static(const float* logits, int64_t T, int64_t E, int k, int64_t C, int normalize,
                          int32_t* idx, float* gate_w, int32_t* loc, int32_t* counts, int32_t* slot_src, void* stream);
 
-/* Bytes of workspace moe_gate_topk_bpr needs.  0 on invalid arguments or T > 2^18. */
+/* Bytes of workspace moe_gate_topk_bpr needs.  0 on invalid arguments. */
 size_t moe_gate_bpr_workspace_bytes(int64_t T, int64_t E, int k);
 
 /* moe_gate_topk with batch prioritized routing (named in Sec. 3.2 and in the Appendix's comparison of routing
@@ -134,8 +134,8 @@ size_t moe_gate_bpr_workspace_bytes(int64_t T, int64_t E, int k);
  * order, so that under a tight capacity the least confident tokens are the ones dropped.  Priority = the token's
  * largest routing probability, computed in fp64 and rounded to fp32; equal priorities -> lower token index.
  * Arguments and outputs as moe_gate_topk (loc is the arrival position in the prioritized order).
- * ws: moe_gate_bpr_workspace_bytes, 256-byte aligned.  T <= 2^18 (the order is found by exact O(T^2) counting), else
- * MOE_UNSUPPORTED. */
+ * The order is found by a stable radix sort of the priorities' bit patterns (integer work: deterministic).
+ * ws: moe_gate_bpr_workspace_bytes, 256-byte aligned. */
 int moe_gate_topk_bpr(const float* logits, int64_t T, int64_t E, int k, int64_t C, int normalize, int32_t* idx, float* gate_w,
                       int32_t* loc, int32_t* counts, int32_t* slot_src, void* ws, size_t ws_bytes, void* stream);
 

@@ -248,23 +248,19 @@ int moe_slot_sources(const int32_t* idx, const int32_t* loc, int64_t T, int64_t 
 
 size_t moe_gate_bpr_workspace_bytes(int64_t T, int64_t E, int k) {
   const size_t g = moe_gate_workspace_bytes(T, E, k);
-  if (g == 0 || T > ((int64_t)1 << 18)) return 0;
-  return align_up(g, 256) + align_up((size_t)T * 8, 256) + 2 * align_up((size_t)T * 4, 256);
+  if (g == 0) return 0;
+  return align_up(g, 256) + bpr_order_workspace_bytes(T);
 }
 
 int moe_gate_topk_bpr(const float* logits, int64_t T, int64_t E, int k, int64_t C, int normalize, int32_t* idx, float* gate_w,
                       int32_t* loc, int32_t* counts, int32_t* slot_src, void* ws, size_t ws_bytes, void* stream) {
   if (!logits || !idx || !gate_w || !loc || !counts || !ws || C < 1 || C > kMaxDim) return MOE_INVALID_ARG;
   if (int st = gate_shape_status(T, E, k)) return st;
-  if (T > ((int64_t)1 << 18) || !aligned(ws, 256) || !aligned(logits, 16)) return MOE_UNSUPPORTED;    // the order is found by O(T^2) counting
+  if (!aligned(ws, 256) || !aligned(logits, 16)) return MOE_UNSUPPORTED;
   if (ws_bytes < moe_gate_bpr_workspace_bytes(T, E, k)) return MOE_WORKSPACE_TOO_SMALL;
-  char* base = (char*)ws;
-  const size_t g = align_up(moe_gate_workspace_bytes(T, E, k), 256);
-  uint64_t* key = (uint64_t*)(base + g);
-  int32_t* before = (int32_t*)(base + g + align_up((size_t)T * 8, 256));
-  int32_t* perm = before + align_up((size_t)T * 4, 256) / 4;
   hipStream_t s = (hipStream_t)stream;
-  if (launch_bpr_order(logits, T, E, key, before, perm, s) != hipSuccess) return MOE_HIP_ERROR;
+  const int32_t* perm = nullptr;
+  if (launch_bpr_order(logits, T, E, (char*)ws + align_up(moe_gate_workspace_bytes(T, E, k), 256), &perm, s) != hipSuccess) return MOE_HIP_ERROR;
   return launch_gate_topk(const_cast<float*>(logits), T, E, k, C, normalize, idx, gate_w, loc, counts, slot_src, (int32_t*)ws, s, perm) == hipSuccess
              ? MOE_OK : MOE_HIP_ERROR;
 }

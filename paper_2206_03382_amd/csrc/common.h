@@ -113,8 +113,8 @@ hipError_t launch_gate_logits_fast(const void* x, const void* Wg, const float* b
 hipError_t launch_gate_topk(float* logits, int64_t T, int64_t E, int k, int64_t C, int normalize, int32_t* idx,
                             float* gate_w, int32_t* loc, int32_t* counts, int32_t* slot_src, int32_t* block_counts,
                             hipStream_t s, const int32_t* perm = nullptr, const GateRepair* repair = nullptr);
-hipError_t launch_bpr_order(const float* logits, int64_t T, int64_t E, uint64_t* key, int32_t* before, int32_t* perm,
-                            hipStream_t s);
+size_t bpr_order_workspace_bytes(int64_t T);
+hipError_t launch_bpr_order(const float* logits, int64_t T, int64_t E, void* ws, const int32_t** perm, hipStream_t s);
 hipError_t launch_decode_backward(const void* d_out, const void* Y, int dtype, const int32_t* idx, const int32_t* loc,
                                   const float* gate_w, const int32_t* slot_src, int64_t T, int64_t M, int64_t E, int k,
                                   int64_t C, void* dY, float* dgate_w, hipStream_t s, bool fill_unfilled = true);

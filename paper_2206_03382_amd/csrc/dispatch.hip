@@ -14,10 +14,16 @@ __global__ __launch_bounds__(256) void encode_gather_kernel(const uint4* __restr
   const int lane = threadIdx.x & 63;
   const int64_t wave = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * 4 + (threadIdx.x >> 6)));
   const int64_t nwaves = (int64_t)gridDim.x * 4;
+  int nxt[ROWS];                                                      // slot sources of the next iteration, fetched one ahead
+#pragma unroll
+  for (int i = 0; i < ROWS; ++i) nxt[i] = (wave * ROWS + i < nrows) ? slot_src[wave * ROWS + i] : -2;
   for (int64_t r0 = wave * ROWS; r0 < nrows; r0 += nwaves * ROWS) {
     int src[ROWS];
 #pragma unroll
-    for (int i = 0; i < ROWS; ++i) src[i] = (r0 + i < nrows) ? slot_src[r0 + i] : -2;
+    for (int i = 0; i < ROWS; ++i) src[i] = nxt[i];
+    const int64_t r1 = r0 + nwaves * ROWS;
+#pragma unroll
+    for (int i = 0; i < ROWS; ++i) nxt[i] = (r1 + i < nrows) ? slot_src[r1 + i] : -2;
     if (!FILL) {
       bool any = false;
 #pragma unroll

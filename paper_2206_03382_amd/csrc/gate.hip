@@ -939,10 +939,10 @@ hipError_t launch_gate_logits_cosine(const void* x, const void* Wp, const float*
 // of decreasing priority, priority = the token's largest routing probability 1 / sum_e exp(l_e - l_max), computed in
 // fp64 and rounded to fp32 so that the order is a decision on an exactly comparable key; ties -> lower token.
 // ---------------------------------------------------------------------------------------------------------------
-// The sort key is one 64-bit integer per token: the fp32 priority's bit pattern (priorities are positive, so the
-// pattern orders like the value) above the complemented token index, so that "goes before" is a single comparison.
+// The sort key is the complement of the fp32 priority's bit pattern (priorities are positive, so the pattern orders like
+// the value): ascending keys = descending priority.  A stable sort keeps equal priorities in token order.
 __global__ __launch_bounds__(256) void bpr_key_kernel(const float* __restrict__ logits, int64_t T, int E,
-                                                      uint64_t* __restrict__ key) {
+                                                      uint32_t* __restrict__ key, int32_t* __restrict__ val) {
   const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (t >= T) return;
   const float* row = logits + t * E;
@@ -951,45 +951,140 @@ __global__ __launch_bounds__(256) void bpr_key_kernel(const float* __restrict__ 
   double se = 0.0;
   for (int e = 0; e < E; ++e) se += exp((double)row[e] - (double)mx);
   const float prio = (float)(1.0 / se);
-  key[t] = ((uint64_t)__float_as_uint(prio) << 32) | (uint64_t)(0xffffffffu - (uint32_t)t);
+  key[t] = ~__float_as_uint(prio);
+  val[t] = (int32_t)t;
 }
 
-// Position of every token in the order by counting the tokens that go before it: O(T^2) comparisons, exact and
-// deterministic (integer atomics).  Block (x, y) counts, for 256 tokens, the keys of slice y that are larger.
-constexpr int kBprSlice = 2048;
-__global__ __launch_bounds__(256) void bpr_count_kernel(const uint64_t* __restrict__ key, int64_t T, int32_t* __restrict__ before) {
-  __shared__ uint64_t tile[kBprSlice];
-  const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  const int64_t base = (int64_t)blockIdx.y * kBprSlice;
-  for (int i = threadIdx.x; i < kBprSlice; i += 256) tile[i] = base + i < T ? key[base + i] : 0ull;   // 0 is below every key
+// Stable least-significant-digit radix sort of (key, token) pairs, three passes of 11, 11 and 10 bits.  A block owns a
+// tile of 2048 consecutive pairs.  Pass: per-tile digit histograms -> one exclusive scan over (digit, tile) -> stable
+// scatter (a pair's place = start of its (digit, tile) run + the number of pairs of that digit before it in the tile).
+// Integer arithmetic only; every result is a pure function of the keys.
+constexpr int kSortTile = 2048, kSortBins = 2048;
+
+__global__ __launch_bounds__(256) void radix_hist_kernel(const uint32_t* __restrict__ key, int64_t n, int shift, int bins, int tiles,
+                                                         uint32_t* __restrict__ hist) {
+  __shared__ uint32_t h[kSortBins];
+  for (int i = threadIdx.x; i < bins; i += 256) h[i] = 0;
   __syncthreads();
-  if (t >= T) return;
-  const uint64_t mine = key[t];
-  int n = 0;
-#pragma unroll 16
-  for (int i = 0; i < kBprSlice; ++i) n += tile[i] > mine ? 1 : 0;
-  if (n) atomicAdd(&before[t], n);
+  const int64_t base = (int64_t)blockIdx.x * kSortTile;
+  for (int i = threadIdx.x; i < kSortTile; i += 256)
+    if (base + i < n) atomicAdd(&h[(key[base + i] >> shift) & (bins - 1)], 1u);
+  __syncthreads();
+  for (int i = threadIdx.x; i < bins; i += 256) hist[(int64_t)i * tiles + blockIdx.x] = h[i];
 }
 
-__global__ __launch_bounds__(256) void bpr_scatter_kernel(const int32_t* __restrict__ before, int64_t T, int32_t* __restrict__ perm) {
-  const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (t < T && (uint32_t)before[t] < (uint64_t)T) perm[before[t]] = (int32_t)t;
+// exclusive scan of hist[0 .. m) in place, one block (the array holds bins x tiles counters: small next to the keys), 8192
+// counters per round: eight consecutive ones per thread, a shuffle scan inside each wave, the 16 wave totals through LDS
+__global__ __launch_bounds__(1024) void radix_scan_kernel(uint32_t* __restrict__ hist, int64_t m) {
+  __shared__ uint32_t wave_tot[16];
+  __shared__ uint32_t carry_s;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  if (threadIdx.x == 0) carry_s = 0;
+  __syncthreads();
+  for (int64_t r0 = 0; r0 < m; r0 += 8192) {
+    const int64_t start = r0 + (int64_t)threadIdx.x * 8;
+    uint32_t v[8], sum = 0;
+    if (start + 8 <= m) {                                // the array is 256-byte aligned and start a multiple of 8
+      const uint4 a = *reinterpret_cast<const uint4*>(hist + start), b = *reinterpret_cast<const uint4*>(hist + start + 4);
+      v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+    } else {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) v[i] = start + i < m ? hist[start + i] : 0u;
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) sum += v[i];
+    uint32_t inc = sum;                                  // inclusive scan of the sums over the wave
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+      const uint32_t t = __shfl_up(inc, d, 64);
+      if (lane >= d) inc += t;
+    }
+    if (lane == 63) wave_tot[wave] = inc;
+    __syncthreads();
+    uint32_t run = carry_s + inc - sum;
+    for (int w = 0; w < wave; ++w) run += wave_tot[w];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      if (start + i < m) hist[start + i] = run;
+      run += v[i];
+    }
+    __syncthreads();
+    if (threadIdx.x == 1023) carry_s = run;               // the last thread's running sum = everything so far
+    __syncthreads();
+  }
 }
 
-hipError_t launch_bpr_order(const float* logits, int64_t T, int64_t E, uint64_t* key, int32_t* before, int32_t* perm,
-                            hipStream_t s) {
-  const dim3 grid((unsigned)ceil_div(T, 256)), block(256);
-  bpr_key_kernel<<<grid, block, 0, s>>>(logits, T, (int)E, key);
+__global__ __launch_bounds__(256) void radix_scatter_kernel(const uint32_t* __restrict__ key_in, const int32_t* __restrict__ val_in,
+                                                            int64_t n, int shift, int bins, int tiles,
+                                                            const uint32_t* __restrict__ offsets, uint32_t* __restrict__ key_out,
+                                                            int32_t* __restrict__ val_out) {
+  __shared__ uint32_t before[kSortBins];                  // pairs of each digit in the tile's earlier sub-tiles
+  __shared__ uint16_t cnt[4][kSortBins];                  // pairs of each digit in each wave of the current sub-tile
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  for (int i = threadIdx.x; i < bins; i += 256) { before[i] = 0; cnt[0][i] = 0; cnt[1][i] = 0; cnt[2][i] = 0; cnt[3][i] = 0; }
+  __syncthreads();
+  const int64_t base = (int64_t)blockIdx.x * kSortTile;
+  const int nbits = bins == 2048 ? 11 : 10;
+  for (int sub = 0; sub < kSortTile / 256; ++sub) {      // sub-tiles in order; within one: wave by wave, lane by lane
+    const int64_t i = base + sub * 256 + threadIdx.x;
+    const bool live = i < n;
+    const uint32_t k = live ? key_in[i] : 0u;
+    const int32_t v = live ? val_in[i] : 0;
+    const int d = (int)((k >> shift) & (uint32_t)(bins - 1));
+    // lanes of this wave with the same digit: intersect, bit by bit, the ballots that agree with this lane's bit
+    unsigned long long peers = __ballot(live);
+    for (int bit = 0; bit < nbits; ++bit) {
+      const unsigned long long set = __ballot((d >> bit) & 1);
+      peers &= ((d >> bit) & 1) ? set : ~set;
+    }
+    const int rank_in_wave = __popcll(peers & ((1ull << lane) - 1ull));
+    if (live && rank_in_wave == 0) cnt[wave][d] = (uint16_t)__popcll(peers);   // the group's first lane reports its size
+    __syncthreads();
+    if (live) {
+      uint32_t r = before[d] + rank_in_wave;
+      for (int w = 0; w < wave; ++w) r += cnt[w][d];
+      const int64_t dst = (int64_t)offsets[(int64_t)d * tiles + blockIdx.x] + r;
+      key_out[dst] = k;
+      val_out[dst] = v;
+    }
+    __syncthreads();
+    for (int q = threadIdx.x; q < bins; q += 256) {
+      before[q] += (uint32_t)cnt[0][q] + cnt[1][q] + cnt[2][q] + cnt[3][q];
+      cnt[0][q] = 0; cnt[1][q] = 0; cnt[2][q] = 0; cnt[3][q] = 0;
+    }
+    __syncthreads();
+  }
+}
+
+size_t bpr_order_workspace_bytes(int64_t T) {
+  const int64_t tiles = ceil_div(T, kSortTile);
+  return 4 * align_up((size_t)T * 4, 256) + align_up((size_t)kSortBins * tiles * 4, 256);
+}
+
+// perm[i] = the token that arrives i-th under batch prioritized routing; returns it through *perm (a piece of ws)
+hipError_t launch_bpr_order(const float* logits, int64_t T, int64_t E, void* ws, const int32_t** perm, hipStream_t s) {
+  const int64_t tiles = ceil_div(T, kSortTile);
+  const size_t piece = align_up((size_t)T * 4, 256);
+  char* base = (char*)ws;
+  uint32_t* key[2] = {(uint32_t*)base, (uint32_t*)(base + piece)};
+  int32_t* val[2] = {(int32_t*)(base + 2 * piece), (int32_t*)(base + 3 * piece)};
+  uint32_t* hist = (uint32_t*)(base + 4 * piece);
+  bpr_key_kernel<<<dim3((unsigned)ceil_div(T, 256)), dim3(256), 0, s>>>(logits, T, (int)E, key[0], val[0]);
   hipError_t err = hipGetLastError();
   if (err != hipSuccess) return err;
-  fill_i32_kernel<<<dim3((unsigned)ceil_div(T, 1024)), block, 0, s>>>(before, T, 0);
-  err = hipGetLastError();
-  if (err != hipSuccess) return err;
-  bpr_count_kernel<<<dim3((unsigned)ceil_div(T, 256), (unsigned)ceil_div(T, kBprSlice)), block, 0, s>>>(key, T, before);
-  err = hipGetLastError();
-  if (err != hipSuccess) return err;
-  bpr_scatter_kernel<<<grid, block, 0, s>>>(before, T, perm);
-  return hipGetLastError();
+  const int shifts[3] = {0, 11, 22}, binsv[3] = {2048, 2048, 1024};
+  int cur = 0;
+  for (int p = 0; p < 3; ++p) {
+    radix_hist_kernel<<<dim3((unsigned)tiles), dim3(256), 0, s>>>(key[cur], T, shifts[p], binsv[p], (int)tiles, hist);
+    radix_scan_kernel<<<dim3(1), dim3(1024), 0, s>>>(hist, (int64_t)binsv[p] * tiles);
+    radix_scatter_kernel<<<dim3((unsigned)tiles), dim3(256), 0, s>>>(key[cur], val[cur], T, shifts[p], binsv[p], (int)tiles, hist,
+                                                                     key[cur ^ 1], val[cur ^ 1]);
+    err = hipGetLastError();
+    if (err != hipSuccess) return err;
+    cur ^= 1;
+  }
+  *perm = val[cur];
+  return hipSuccess;
 }
 
 }  // namespace moe

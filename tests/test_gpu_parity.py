@@ -99,6 +99,18 @@ def test_gate_topk_batch_prioritized(moe, T, E, k, f, normalize, quantum):
     assert np.array_equal(got["slot_src"].cpu().numpy(), O.slot_source(ref["idx"], ref["loc"], E, C))
 
 
+def test_gate_topk_batch_prioritized_many_tokens(moe):
+    """More tokens than one sort tile many times over (and past 2^18): the prioritized order comes from a radix sort, whose
+    place computations span several tiles and all three digit passes; quantised logits give long runs of equal priorities."""
+    T, E, k = 300001, 16, 2
+    logits = synth.make_logits(T, E, seed=77, quantum=0.5)
+    C = O.capacity(T, E, k, 0.6)
+    ref = O.route(logits, k, C, 1, bpr=True)
+    got = moe.gate_topk(torch.from_numpy(logits).cuda(), k, C, 1, bpr=True)
+    assert_routing_equal(got, ref, C, "BPR, 300001 tokens")
+    assert not np.array_equal(ref["kept"], O.route(logits, k, C, 1)["kept"])       # the order matters at this capacity
+
+
 def test_gate_topk_is_deterministic(moe):
     logits = torch.from_numpy(synth.make_logits(5000, 64, seed=3, quantum=0.25)).cuda()
     a = moe.gate_topk(logits, 4, 300, 1)
