@@ -108,7 +108,10 @@ def measure(cfg, inp, steps: int, warmup: int, cold: bool = True):
     bf16 = d == synth.DT_BF16
     peak = MFMA_BF16_PEAK_TFLOPS if bf16 else FP32_VECTOR_PEAK_TFLOPS
     achieved = flop_per_gemm / (gemm_ms * 1e-3) / 1e12
-    enc_bytes = 2 * R * M * es + 4 * E * C                       # read each kept row once, write it once (the layer leaves unfilled slots alone)
+    # encode inside the layer: a token feeding several slots is read once and written to each (k >= 2); with one choice per
+    # token the slots gather their rows (one read per slot); unfilled slots are left alone either way
+    live_tokens = int((layer.routing["loc"] < C).any(dim=1).sum().item())
+    enc_bytes = ((live_tokens if k >= 2 else R) + R) * M * es + 8 * T * k
     dec_bytes = (R + T) * M * es + 12 * T * k                    # read each kept expert-output row once, write [T,M]
     logit_bytes = T * M * es + M * E * es + 4 * T * E            # read every token row once, write the logits
     topk_bytes = 4 * T * E + 12 * T * k + 4 * E + 4 * E * C

@@ -49,6 +49,9 @@ __global__ __launch_bounds__(256) void zero_fill_kernel(uint4* __restrict__ p, i
   for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (int64_t)gridDim.x * 256) p[i] = make_uint4(0, 0, 0, 0);
 }
 
+// One wave per token: the row is read once and written to each of its kept slots (every slot row is written whole, so the
+// stores are as coalesced as the gather form's).  With k choices per token this moves (1 + k) rows per token where the
+// gather form moves 2 k (it re-reads the token once per slot, far apart in time).
 __global__ __launch_bounds__(256) void encode_scatter_kernel(const uint4* __restrict__ x, const int32_t* __restrict__ idx,
                                                              const int32_t* __restrict__ loc, int64_t T, int E, int k,
                                                              int64_t C, int cpr, uint4* __restrict__ Z) {
@@ -56,11 +59,24 @@ __global__ __launch_bounds__(256) void encode_scatter_kernel(const uint4* __rest
   const int64_t wave = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * 4 + (threadIdx.x >> 6)));
   const int64_t nwaves = (int64_t)gridDim.x * 4;
   for (int64_t t = wave; t < T; t += nwaves) {
-    for (int j = 0; j < k; ++j) {
-      const int e = idx[t * k + j], l = loc[t * k + j];
-      if (l < 0 || l >= C || (unsigned)e >= (unsigned)E) continue;   // dropped (or invalid) choice
-      const int64_t row = (int64_t)e * C + l;
-      for (int c = lane; c < cpr; c += 64) Z[row * cpr + c] = x[t * cpr + c];
+    for (int j0 = 0; j0 < k; j0 += 8) {                              // eight choices at a time share one read of the row
+      int64_t row[8];
+      bool any = false;
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        row[u] = -1;
+        if (j0 + u < k) {
+          const int e = idx[t * k + j0 + u], l = loc[t * k + j0 + u];
+          if (l >= 0 && l < C && (unsigned)e < (unsigned)E) { row[u] = (int64_t)e * C + l; any = true; }   // kept choice
+        }
+      }
+      if (!any) continue;
+      for (int c = lane; c < cpr; c += 64) {
+        const uint4 v = x[t * cpr + c];
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+          if (row[u] >= 0) Z[row[u] * cpr + c] = v;
+      }
     }
   }
 }
@@ -70,6 +86,12 @@ hipError_t launch_encode(const void* x, int dtype, const int32_t* idx, const int
   const int es = (dtype == MOE_F32) ? 4 : 2;
   const int cpr = (int)(M * es / 16);
   const int64_t nrows = E * C;
+  const int64_t sb = ceil_div(T, 4);
+  if (slot_src && !fill_unfilled && k >= 2) {
+    // unfilled slots stay untouched and a token feeds several slots: read every token once, write its kept slots
+    encode_scatter_kernel<<<dim3((unsigned)(sb < 16384 ? sb : 16384)), dim3(256), 0, s>>>((const uint4*)x, idx, loc, T, (int)E, k, C, cpr, (uint4*)Z);
+    return hipGetLastError();
+  }
   if (slot_src) {
     constexpr int ROWS = 4;
     const int64_t blocks = ceil_div(nrows, 4 * ROWS);
@@ -83,8 +105,7 @@ hipError_t launch_encode(const void* x, int dtype, const int32_t* idx, const int
   zero_fill_kernel<<<dim3((unsigned)(zb < 16384 ? (zb > 0 ? zb : 1) : 16384)), dim3(256), 0, s>>>((uint4*)Z, n16);
   hipError_t err = hipGetLastError();
   if (err != hipSuccess) return err;
-  const int64_t sb = ceil_div(T, 4);
-  encode_scatter_kernel<<<dim3((unsigned)(sb < 8192 ? sb : 8192)), dim3(256), 0, s>>>((const uint4*)x, idx, loc, T, (int)E, k, C, cpr, (uint4*)Z);
+  encode_scatter_kernel<<<dim3((unsigned)(sb < 16384 ? sb : 16384)), dim3(256), 0, s>>>((const uint4*)x, idx, loc, T, (int)E, k, C, cpr, (uint4*)Z);
   return hipGetLastError();
 }
 
