@@ -352,18 +352,26 @@ __device__ __forceinline__ bool token_topk(float (&v)[V], int gl, int E, int k, 
   return close;
 }
 
-// sum over m of x[t, m] * Wt[e, m] in fp64 by one wave, for two experts at once (every product of two bf16 values is
-// exact in fp32; lane l adds the 16-byte pieces l, l + 64, ... in ascending order, then a fixed butterfly adds the 64
-// partial sums); all lanes get both sums.  Four pieces are fetched per round so that their latencies overlap.
-__device__ __forceinline__ void wave_dot2_fp64(const uint16_t* __restrict__ xr, const uint16_t* __restrict__ wa,
-                                               const uint16_t* __restrict__ wb, int M, int lane, double& sa, double& sb) {
+// The ballot of a predicate over this lane's group of G lanes (G = 16: four groups per wave; G = 64: the wave)
+template <int G> __device__ __forceinline__ unsigned long long group_ballot(bool p, int grp) {
+  const unsigned long long b = __ballot(p);
+  return G == 64 ? b : (b >> (G * grp)) & ((1ull << (G & 63)) - 1ull);
+}
+
+// sum over m of x[t, m] * Wt[e, m] in fp64 by a group of G lanes, for two experts at once (every product of two bf16
+// values is exact in fp32; lane gl adds the 16-byte pieces gl, gl + G, ... in ascending order, then a fixed butterfly adds
+// the G partial sums); all lanes of the group get both sums.  Four pieces are fetched per round so that their latencies
+// overlap.
+template <int G>
+__device__ __forceinline__ void group_dot2_fp64(const uint16_t* __restrict__ xr, const uint16_t* __restrict__ wa,
+                                                const uint16_t* __restrict__ wb, int M, int gl, double& sa, double& sb) {
   double acc_a = 0.0, acc_b = 0.0;
   const int pieces = M >> 3;
-  for (int p0 = 0; p0 < pieces; p0 += 256) {
+  for (int p0 = 0; p0 < pieces; p0 += 4 * G) {
     uint4 xv[4], av[4], bv[4];
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
-      const int p = p0 + 64 * u + lane;
+      const int p = p0 + G * u + gl;
       const int q = p < pieces ? p : 0;                  // pieces past the row's end re-read its start and are zeroed
       xv[u] = *reinterpret_cast<const uint4*>(xr + q * 8);
       av[u] = *reinterpret_cast<const uint4*>(wa + q * 8);
@@ -386,7 +394,7 @@ __device__ __forceinline__ void wave_dot2_fp64(const uint16_t* __restrict__ xr, 
     }
   }
 #pragma unroll
-  for (int d = 32; d >= 1; d >>= 1) {
+  for (int d = G / 2; d >= 1; d >>= 1) {
     acc_a += __shfl_xor(acc_a, d, 64);
     acc_b += __shfl_xor(acc_b, d, 64);
   }
@@ -395,60 +403,64 @@ __device__ __forceinline__ void wave_dot2_fp64(const uint16_t* __restrict__ xr, 
 }
 
 // Exact decisions for one token whose approximate logits (within tol2 / 2 of the exactly rounded ones) left its top k
-// open; run by one wave.  theta = the (k+1)-th largest approximate logit.  Every expert that can still reach the top k
+// open; run by a group of G lanes (a wave, or a quarter of one for gates of at most 128 experts: four tokens are then
+// repaired side by side).  theta = the (k+1)-th largest approximate logit.  Every expert that can still reach the top k
 // (approximate logit within tol2 of theta) is looked at; those that have another such expert within tol2 get their logit
 // recomputed in fp64 from x and Wt and stored (an expert farther than that from every other keeps its place whatever the
 // true values are); then the token is decided again on the repaired row.  hist: the block's packed arrival counters.
-__device__ __forceinline__ void repair_token(int64_t t, float theta, float tol2, int lane, float* __restrict__ logits, int E, int k,
-                                             int normalize, int32_t* __restrict__ idx, float* __restrict__ gate_w, int* hist,
-                                             const uint16_t* __restrict__ x, const uint16_t* __restrict__ Wt,
+// `on` = this group has a token (groups without one run along with nothing to do).
+template <int G>
+__device__ __forceinline__ void repair_token(bool on, int64_t t, float theta, float tol2, int lane, float* __restrict__ logits,
+                                             int E, int k, int normalize, int32_t* __restrict__ idx, float* __restrict__ gate_w,
+                                             int* hist, const uint16_t* __restrict__ x, const uint16_t* __restrict__ Wt,
                                              const float* __restrict__ bias, int M, int Mp) {
   const float NEG_INF = -__builtin_inff();
+  const int grp = lane / G, gl = lane % G;
   const float reach = theta - tol2 - 4.8e-7f * fabsf(theta);         // experts below this cannot be among the k largest
   float rv[8];
 #pragma unroll
   for (int vi = 0; vi < 8; ++vi) {
-    const int e = lane + 64 * vi;
-    rv[vi] = e < E ? logits[t * E + e] : NEG_INF;
+    const int e = gl + G * vi;
+    rv[vi] = (on && e < E) ? logits[t * E + e] : NEG_INF;
   }
   bool need[8];
 #pragma unroll
   for (int vi = 0; vi < 8; ++vi) need[vi] = false;
 #pragma unroll
   for (int vi = 0; vi < 8; ++vi) {
-    unsigned long long todo = __ballot(rv[vi] >= reach);
+    unsigned long long todo = group_ballot<G>(on && rv[vi] >= reach, grp);
     while (todo) {
       const int l = __builtin_ctzll(todo);
       todo &= todo - 1;
-      const float val = __shfl(rv[vi], l, 64);
+      const float val = __shfl(rv[vi], grp * G + l, 64);
       bool near = false;
 #pragma unroll
       for (int vj = 0; vj < 8; ++vj)
-        near = near || (rv[vj] >= reach && !(vj == vi && lane == l) &&
+        near = near || (rv[vj] >= reach && !(vj == vi && gl == l) &&
                         fabsf(rv[vj] - val) <= tol2 + 4.8e-7f * fmaxf(fabsf(rv[vj]), fabsf(val)));
-      if (__ballot(near) != 0ull && lane == l) need[vi] = true;
+      if (group_ballot<G>(near, grp) != 0ull && gl == l) need[vi] = true;
     }
   }
   // the marked experts, two at a time (one pending until its partner turns up)
-  const uint16_t* xr = x + t * (int64_t)M;
+  const uint16_t* xr = x + (on ? t : 0) * (int64_t)M;
   int pend_e = -1, pend_l = 0, pend_vi = 0;
   auto put = [&](int e, int l, int vi, double sum) __attribute__((always_inline)) {
     const float val = (float)(sum + (bias ? (double)bias[e] : 0.0));
 #pragma unroll
     for (int vj = 0; vj < 8; ++vj)
-      if (vj == vi && lane == l) rv[vj] = val;
-    if (lane == l) logits[t * E + e] = val;
+      if (vj == vi && gl == l) rv[vj] = val;
+    if (gl == l) logits[t * E + e] = val;
   };
 #pragma unroll
   for (int vi = 0; vi < 8; ++vi) {
-    unsigned long long todo = __ballot(need[vi]);
+    unsigned long long todo = group_ballot<G>(need[vi], grp);
     while (todo) {
       const int l = __builtin_ctzll(todo);
       todo &= todo - 1;
-      const int e = l + 64 * vi;
+      const int e = l + G * vi;
       if (pend_e < 0) { pend_e = e; pend_l = l; pend_vi = vi; continue; }
       double sa, sb;
-      wave_dot2_fp64(xr, Wt + (int64_t)pend_e * Mp, Wt + (int64_t)e * Mp, M, lane, sa, sb);
+      group_dot2_fp64<G>(xr, Wt + (int64_t)pend_e * Mp, Wt + (int64_t)e * Mp, M, gl, sa, sb);
       put(pend_e, pend_l, pend_vi, sa);
       put(e, l, vi, sb);
       pend_e = -1;
@@ -456,19 +468,21 @@ __device__ __forceinline__ void repair_token(int64_t t, float theta, float tol2,
   }
   if (pend_e >= 0) {
     double sa, sb;
-    wave_dot2_fp64(xr, Wt + (int64_t)pend_e * Mp, Wt + (int64_t)pend_e * Mp, M, lane, sa, sb);
+    group_dot2_fp64<G>(xr, Wt + (int64_t)pend_e * Mp, Wt + (int64_t)pend_e * Mp, M, gl, sa, sb);
     put(pend_e, pend_l, pend_vi, sa);
   }
   int si[8];
   float sw[8], denom, th;
-  token_topk<64, 8>(rv, lane, E, k, false, 0.f, si, sw, denom, th);
+  token_topk<G, 8>(rv, gl, E, k, false, 0.f, si, sw, denom, th);
+  if (on) {
 #pragma unroll
-  for (int vi = 0; vi < 8; ++vi) {
-    const int j = lane + 64 * vi;
-    if (j < k) {
-      idx[t * k + j] = si[vi];
-      gate_w[t * k + j] = normalize ? sw[vi] / denom : sw[vi];
-      atomicAdd(&hist[(j * E + si[vi]) >> 2], 1 << (8 * ((j * E + si[vi]) & 3)));
+    for (int vi = 0; vi < 8; ++vi) {
+      const int j = gl + G * vi;
+      if (j < k) {
+        idx[t * k + j] = si[vi];
+        gate_w[t * k + j] = normalize ? sw[vi] / denom : sw[vi];
+        atomicAdd(&hist[(j * E + si[vi]) >> 2], 1 << (8 * ((j * E + si[vi]) & 3)));
+      }
     }
   }
 }
@@ -542,9 +556,9 @@ __global__ __launch_bounds__(1024) void gate_topk_kernel(float* __restrict__ log
     const int n_aside = *aside_n;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
     for (int i = wave; i < n_aside; i += nwaves)
-      repair_token((int64_t)blockIdx.x * kGateTokensPerBlock + aside_tok[i], aside_theta[i],
-                   2.0f * margin[(int64_t)blockIdx.x * kGateTokensPerBlock + aside_tok[i]], lane, logits, E, k, normalize, idx, gate_w,
-                   hist, x, Wt, bias, M, Mp);
+      repair_token<64>(true, (int64_t)blockIdx.x * kGateTokensPerBlock + aside_tok[i], aside_theta[i],
+                       2.0f * margin[(int64_t)blockIdx.x * kGateTokensPerBlock + aside_tok[i]], lane, logits, E, k, normalize, idx,
+                       gate_w, hist, x, Wt, bias, M, Mp);
     __syncthreads();
   }
   for (int i = threadIdx.x; i < k * E; i += blockDim.x) {
@@ -665,11 +679,31 @@ __global__ __launch_bounds__(256) void gate_topk_lane_kernel(float* __restrict__
       }
     }
   }
-  unsigned long long todo = __ballot(aside);
-  while (todo) {                                                        // the wave repairs its open tokens one by one
-    const int l = __builtin_ctzll(todo);
-    todo &= todo - 1;
-    repair_token(t0 + l, __shfl(theta, l, 64), __shfl(tol2, l, 64), lane, logits, E, k, normalize, idx, gate_w, hist, x, Wt, bias, M, Mp);
+  // the wave repairs its open tokens: four side by side, a quarter of the wave each, for gates of at most 128 experts
+  // (their list goes through the tile's LDS, which is free now), one by one with the whole wave otherwise
+  const unsigned long long open = __ballot(aside);
+  if (open) {
+    if (E <= 128) {
+      int* list = reinterpret_cast<int*>(tile);
+      if (aside) list[__popcll(open & ((1ull << lane) - 1ull))] = lane;
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_s_waitcnt(0xc07f);
+      const int n_open = __popcll(open), grp = lane >> 4;
+      for (int i0 = 0; i0 < n_open; i0 += 4) {
+        const bool on = i0 + grp < n_open;
+        const int src = on ? list[i0 + grp] : 0;
+        repair_token<16>(on, t0 + src, __shfl(theta, src, 64), __shfl(tol2, src, 64), lane, logits, E, k, normalize, idx, gate_w, hist,
+                         x, Wt, bias, M, Mp);
+      }
+    } else {
+      unsigned long long todo = open;
+      while (todo) {
+        const int l = __builtin_ctzll(todo);
+        todo &= todo - 1;
+        repair_token<64>(true, t0 + l, __shfl(theta, l, 64), __shfl(tol2, l, 64), lane, logits, E, k, normalize, idx, gate_w, hist, x,
+                         Wt, bias, M, Mp);
+      }
+    }
   }
   __builtin_amdgcn_wave_barrier();
   __builtin_amdgcn_s_waitcnt(0xc07f);

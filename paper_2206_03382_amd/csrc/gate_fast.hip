@@ -18,7 +18,7 @@
 //
 // Layout: gate_prepare_kernel writes Wt [E, Mp] = Wg^T (k contiguous, rows zero-padded to a multiple of 128) and the
 // experts' norms once per call.  gate_logits_fast_kernel: a block of four waves shares 128-wide k-chunks of Wt in LDS
-// (double buffered, rows padded by 16 bytes: conflict-free 16-byte operand reads); a wave owns TW tiles of 16 tokens
+// (double buffered, filled by direct global->LDS loads, pieces XOR-swizzled: conflict-free 16-byte operand reads); a wave owns TW tiles of 16 tokens
 // whose rows go straight from global memory into the A operand (lane = token l % 16, 8 consecutive k at 8 (l / 16)),
 // through a ring of R steps of prefetch.
 #include <type_traits>
@@ -33,8 +33,14 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 namespace {
 
 constexpr int kChunk = 128;                 // Wt rows are zero-padded to a multiple of this many k
-constexpr int kRowPad = 8;                  // bf16 elements of padding per LDS row
 constexpr float kUlp = 1.1920929e-07f;      // 2^-23
+
+// Direct global->LDS load of 16 bytes per lane from base + voff: lane l's data lands at lds_addr + 16 l.  Written as
+// inline assembly so that the compiler does not order it against the LDS reads of the other buffer; completion is tracked
+// by hand (s_waitcnt vmcnt + barrier before the buffer is read).
+__device__ __forceinline__ void global_to_lds_16(const void* base, uint32_t voff, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(voff), "s"(base), "s"(lds_addr) : "memory", "m0");
+}
 
 // Wt[e, m] = Wg[m, e] for m < M, 0 for M <= m < Mp; wnorm[e] = |w_e|_2 rounded up.  One block per expert.
 __global__ __launch_bounds__(256) void gate_prepare_kernel(const uint16_t* __restrict__ Wg, int M, int Mp, int E,
@@ -68,13 +74,17 @@ __global__ __launch_bounds__(256, 2) void gate_logits_fast_kernel(const uint16_t
                                                                   const float* __restrict__ wnorm, const float* __restrict__ bias,
                                                                   int64_t T, int M, int Mp, int E, int e_base, float bound,
                                                                   float* __restrict__ logits, float* __restrict__ margin) {
-  constexpr int EN = NT * EH * 16, LD = KCH + kRowPad;            // experts of this pass, LDS row length (elements)
-  constexpr int CS = KCH / 32;                                    // K-steps per chunk
-  constexpr int PIECES = EN * KCH / 8, PPT = (PIECES + 255) / 256;   // 16-byte pieces of a chunk, per thread
+  constexpr int EN = NT * EH * 16;                                  // experts of this pass
+  constexpr int CS = KCH / 32;                                      // K-steps per chunk
+  constexpr int SLOTS = KCH / 8;                                    // 16-byte pieces of a chunk row
+  constexpr int WI = EN * KCH * 2 / 4096;                           // direct loads (1 KB each) per wave and chunk
+  static_assert(KCH == 128 && WI >= 1, "a 1 KB direct load covers four 256-byte rows");
   static_assert(R % CS == 0 || CS % R == 0, "chunk boundaries fall on whole prefetch groups");
   static_assert(R % CH == 0 && CS % CH == 0, "chains do not straddle groups or chunks");
-  __shared__ __attribute__((aligned(16))) uint16_t wl[2][EN * LD];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  // Wt chunks in LDS, double buffered: [EN rows][16 pieces of 8 k], piece p of row e stored at position p ^ (e % 16), so
+  // that the 16 lanes of an operand read (16 consecutive rows, same p) cover all banks once.  Filled by direct loads.
+  __shared__ __attribute__((aligned(1024))) uint16_t wl[2][EN * KCH];
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int r = lane & 15, kq = lane >> 4;
   const int eh = wave % EH;                                         // this wave's share of the experts: tiles eh*NT .. eh*NT+NT-1
   const int64_t t0 = ((int64_t)blockIdx.x * (4 / EH) + wave / EH) * (16 * TW);
@@ -86,26 +96,21 @@ __global__ __launch_bounds__(256, 2) void gate_logits_fast_kernel(const uint16_t
     const int64_t t = t0 + w * 16 + r;
     xp[w] = x + (t < T ? t : T - 1) * (int64_t)M + kq * 8;
   }
-  // this thread's pieces of a Wt chunk: piece id -> (expert row, 16-byte piece of the chunk); rows past E and chunks past
-  // the end read the start of Wt and are masked to zero
-  uint4 wreg[PPT];
-  auto w_fetch = [&](int c) __attribute__((always_inline)) {
+  // this wave's direct loads of a chunk: load i fills the 1 KB block i*4 + wave = rows 4 (i*4 + wave) .. +3; lane l brings
+  // the piece that belongs at position l % 16 of row +l/16.  Rows past E repeat the last expert (their logits are never
+  // stored).  The byte offsets do not depend on the chunk: only the base moves.
+  uint32_t woff[WI];
 #pragma unroll
-    for (int i = 0; i < PPT; ++i) {
-      const int id = threadIdx.x + i * 256;
-      const int row = id / (KCH / 8), piece = id % (KCH / 8), e = e_base + row;
-      const bool live = id < PIECES && e < E && c < chunks;
-      const uint4 v = *reinterpret_cast<const uint4*>(Wt + (live ? (int64_t)e * Mp + c * KCH + piece * 8 : 0));
-      const uint32_t keep = live ? 0xffffffffu : 0u;
-      wreg[i] = make_uint4(v.x & keep, v.y & keep, v.z & keep, v.w & keep);
-    }
-  };
-  auto w_store = [&](int buf) __attribute__((always_inline)) {
+  for (int i = 0; i < WI; ++i) {
+    const int row = (i * 4 + wave) * 4 + (lane >> 4);
+    const int e = e_base + row < E ? e_base + row : E - 1;
+    woff[i] = (uint32_t)(((int64_t)e * Mp + (((lane & 15) ^ (row & 15)) << 3)) * 2);
+  }
+  const uint32_t wl_addr = (uint32_t)(uintptr_t)((__attribute__((address_space(3))) char*)&wl[0][0]);
+  auto w_issue = [&](int c) __attribute__((always_inline)) {         // chunk c -> buffer c & 1
 #pragma unroll
-    for (int i = 0; i < PPT; ++i) {
-      const int id = threadIdx.x + i * 256;
-      if (id < PIECES) *reinterpret_cast<uint4*>(&wl[buf][(id / (KCH / 8)) * LD + (id % (KCH / 8)) * 8]) = wreg[i];
-    }
+    for (int i = 0; i < WI; ++i)
+      global_to_lds_16(Wt + (int64_t)c * KCH, woff[i], wl_addr + (uint32_t)((c & 1) * EN * KCH * 2 + (i * 4 + wave) * 1024));
   };
   // x ring: slot j holds K-step s with s % R == j.  FAST: the step lies wholly inside the row (no predicate; the
   // offset from xp is a compile-time constant).  Otherwise pieces past the row's end read its start and are zeroed.
@@ -134,12 +139,11 @@ __global__ __launch_bounds__(256, 2) void gate_logits_fast_kernel(const uint16_t
     for (int nt = 0; nt < NT; ++nt) { acc[w][nt] = f32x4{0.f, 0.f, 0.f, 0.f}; sup[w][nt] = f32x4{0.f, 0.f, 0.f, 0.f}; }
   }
 
-  w_fetch(0);
+  w_issue(0);
 #pragma unroll
   for (int j = 0; j < R; ++j) x_fetch(std::false_type{}, j, j, j);
-  w_store(0);
+  asm volatile("s_waitcnt vmcnt(%0)" : : "n"(R * TW) : "memory");   // loads return in order: chunk 0 of Wt has landed
   __syncthreads();
-  w_fetch(1);
 
   const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
   f32x4 part[TW][NT];                                               // fp32 sums of the current chain
@@ -149,6 +153,8 @@ __global__ __launch_bounds__(256, 2) void gate_logits_fast_kernel(const uint16_t
       const int s = s0 + j;                                         // uniform over the block
       const int c = s / CS;
       const uint16_t* wbuf = wl[c & 1];
+      // first step of a chunk: the other buffer is free (every wave is past the last barrier): start the next chunk
+      if (s % CS == 0 && c + 1 < chunks) w_issue(c + 1);
       bf16x8 a[TW];
 #pragma unroll
       for (int w = 0; w < TW; ++w) {
@@ -158,7 +164,7 @@ __global__ __launch_bounds__(256, 2) void gate_logits_fast_kernel(const uint16_t
       x_fetch(fast_tag, j, j + R, s + R);
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt) {
-        const bf16x8 b = *reinterpret_cast<const bf16x8*>(&wbuf[((eh * NT + nt) * 16 + r) * LD + (s % CS) * 32 + kq * 8]);
+        const bf16x8 b = *reinterpret_cast<const bf16x8*>(&wbuf[((eh * NT + nt) * 16 + r) * KCH + ((((s % CS) * 4 + kq) ^ r) << 3)]);
 #pragma unroll
         for (int w = 0; w < TW; ++w) {
           part[w][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[w], b, j % CH == 0 ? zero : part[w][nt], 0, 0, 0);
@@ -178,10 +184,10 @@ __global__ __launch_bounds__(256, 2) void gate_logits_fast_kernel(const uint16_t
             sup[w][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
           }
       }
-      if ((s + 1) % CS == 0 && c + 1 < chunks) {                    // last step of a chunk: hand over the next one
-        w_store((c + 1) & 1);
+      if ((s + 1) % CS == 0 && c + 1 < chunks) {                    // last step of a chunk: the next one must have landed
+        // its direct loads were issued CS steps ago, followed by CS x TW token loads; loads return in order
+        asm volatile("s_waitcnt vmcnt(%0)" : : "n"(CS * TW) : "memory");
         __syncthreads();
-        w_fetch(c + 2);
       }
     }
 #pragma unroll
@@ -254,7 +260,8 @@ GateFastWorkspace gate_fast_layout(void* ws, int64_t T, int64_t M, int64_t E) {
 }
 
 bool gate_logits_fast_supports(int dtype, int64_t T, int64_t M, int64_t E) {
-  return dtype == MOE_BF16 && M % 8 == 0 && E <= 512 && M <= ((int64_t)1 << 24) && T * 1 <= ((int64_t)1 << 30);
+  // 32-bit byte offsets inside Wt
+  return dtype == MOE_BF16 && M % 8 == 0 && E <= 512 && E * (M + kChunk) * 2 < ((int64_t)1 << 31) && T <= ((int64_t)1 << 30);
 }
 
 // logits' (fp32, within margin[t] of the exactly rounded sums) and margin [T]; ws laid out by gate_fast_layout.
@@ -281,7 +288,7 @@ hipError_t launch_gate_logits_fast(const void* x, const void* Wg, const float* b
     if (rem <= 16) { if (wide) MOE_FAST_R(1, 2, 8, 1, 1); else MOE_FAST_R(1, 1, 16, 1, 1); }
     else if (rem <= 32) { if (wide) MOE_FAST_R(2, 2, 4, 1, 1); else MOE_FAST_R(2, 1, 8, 1, 1); }
     else if (rem <= 64) { if (wide) MOE_FAST_R(4, 2, 4, 2, 1); else MOE_FAST_R(4, 1, 8, 2, 1); }
-    else MOE_FAST_R(8, 1, 4, 2, 1);
+    else MOE_FAST_R(8, 1, 8, 2, 1);
 #undef MOE_FAST_R
 #undef MOE_FAST
   }
