@@ -119,6 +119,18 @@ struct Frags {
   bf16x8 a[4], b[4];
 };
 
+// Inclusive prefix sum over the 64 lanes with data-parallel primitives (shifts inside rows of 16 lanes, then the rows'
+// totals broadcast forward): no trip through the LDS crossbar, a few cycles per step.
+__device__ __forceinline__ int wave_inclusive_scan(int v) {
+  v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, true);    // row_shr:1
+  v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, true);    // row_shr:2
+  v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, true);    // row_shr:4
+  v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, true);    // row_shr:8
+  v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false);   // row_bcast:15 into rows 1 and 3
+  v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, false);   // row_bcast:31 into rows 2 and 3
+  return v;
+}
+
 }  // namespace
 
 // ---- main loop -------------------------------------------------------------------------------------------------
@@ -312,47 +324,42 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_mfma_kernel(const uint1
   const int lane = threadIdx.x & 63;
   const int b = blockIdx.x;
   const int group = ((b / 8) / 32) * 8 + b % 8, slot = (b / 8) % 32;
-  auto live_row_tiles = [&](int el) -> int {                        // row tiles of expert el that hold real rows
+  auto live_rows = [&](int el) -> int {                             // rows of expert el that exist (its fill, at most C)
     if (el >= E) return 0;
     int64_t r = C;
     if (counts) { const int64_t c = counts[el]; r = c < C ? (c > 0 ? c : 0) : C; }
-    return (int)((r + BM - 1) / BM);
+    return (int)r;
   };
   constexpr int kChunks = kMaxExperts / 64;
-  int mtv[kChunks];                                                 // lane l of chunk c: live row tiles of expert 64 c + l
+  int rowsv[kChunks], mtv[kChunks];                                 // lane l of chunk c: rows / live row tiles of expert 64 c + l
 #pragma unroll
-  for (int c = 0; c < kChunks; ++c) mtv[c] = c * 64 < E ? live_row_tiles(c * 64 + lane) : 0;   // all loads in flight at once
+  for (int c = 0; c < kChunks; ++c) rowsv[c] = c * 64 < E ? live_rows(c * 64 + lane) : 0;      // all loads in flight at once
+#pragma unroll
+  for (int c = 0; c < kChunks; ++c) mtv[c] = (rowsv[c] + BM - 1) / BM;
   int total_full = 0;                                               // full groups of all experts
 #pragma unroll
   for (int c = 0; c < kChunks; ++c) {
     if (c * 64 >= E) break;
-    int v = mtv[c] * NT / 32;
-#pragma unroll
-    for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, 64);
-    total_full += __builtin_amdgcn_readfirstlane(v);
+    total_full += __builtin_amdgcn_readlane(wave_inclusive_scan(mtv[c] * NT / 32), 63);
   }
   const bool short_group = group >= total_full;
   const int target = short_group ? group - total_full : group;
-  int e = -1, mte = 0, rank = 0;                                    // expert, its live row tiles, group's rank among its own
+  int e = -1, mte = 0, rank = 0, rows_e = 0;                        // expert, its live row tiles, group's rank among its own, its rows
   int base = 0;
 #pragma unroll
   for (int c = 0; c < kChunks; ++c) {
     if (c * 64 >= E || e >= 0) break;
     const int mt_l = mtv[c];
     const int ng_l = short_group ? ((mt_l * NT) % 32 != 0 ? 1 : 0) : mt_l * NT / 32;
-    int inc = ng_l;                                                 // inclusive prefix sum over the wave
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-      const int t = __shfl_up(inc, d, 64);
-      if (lane >= d) inc += t;
-    }
-    const int tot = __builtin_amdgcn_readfirstlane(__shfl(inc, 63, 64));
+    const int inc = wave_inclusive_scan(ng_l);                      // inclusive prefix sum over the wave
+    const int tot = __builtin_amdgcn_readlane(inc, 63);
     if (target < base + tot) {
       const unsigned long long hit = __ballot(base + inc > target);
       const int l = __builtin_amdgcn_readfirstlane(__builtin_ctzll(hit));
       e = c * 64 + l;                                               // the same in every lane: keep them in scalar registers
-      mte = __builtin_amdgcn_readfirstlane(__shfl(mt_l, l, 64));
-      rank = __builtin_amdgcn_readfirstlane(target - (base + __shfl(inc - ng_l, l, 64)));
+      mte = __builtin_amdgcn_readlane(mt_l, l);
+      rows_e = __builtin_amdgcn_readlane(rowsv[c], l);
+      rank = target - (base + __builtin_amdgcn_readlane(inc - ng_l, l));
     }
     base += tot;
   }
@@ -363,8 +370,7 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_mfma_kernel(const uint1
   int mt, nt;
   if (q < full) { mt = (q % (mte * 8)) / 8; nt = (q / (mte * 8)) * 8 + q % 8; }
   else { const int w = NT % 8, r = q - full; mt = r / w; nt = (NT / 8) * 8 + r % w; }
-  int64_t rows = C;
-  if (counts) { const int64_t c = counts[e]; rows = c < C ? (c > 0 ? c : 0) : C; }
+  const int64_t rows = rows_e;                                      // already here from the search: no second trip to memory
   const int64_t m0 = (int64_t)mt * BM;
   if (m0 >= rows) return;                                           // cannot happen (mt < mte); keeps every access in the slab
   const int n0 = nt * BN;
