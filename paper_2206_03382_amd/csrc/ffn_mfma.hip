@@ -293,36 +293,12 @@ __device__ __forceinline__ void tile_main_loop(char* smem, const char* a_base, c
 // from the side buffers, which also covers an expert without any slot (one K-step of zeros).
 __host__ __device__ inline int slot_ksteps(int64_t fill) { return fill > 0 ? (int)((fill + BK - 1) / BK) : 1; }
 
-// GRAD (kNT only): the epilogue multiplies by act'(pre) read from `pre` [E,C,N], i.e. the product is the gradient with
-// respect to the pre-activations of a layer whose activation is ACT; with ACT < 0 it adds `pre` instead (a product
-// accumulated onto an existing matrix; `pre` may then be `out` itself, every element being read before it is written
-// by the same lane).
-// DUAL (kNN with an activation only): the values before the activation are written to `pre_out` as well.
-template <int ACT, int MODE, bool GRAD, bool DUAL = false>
-__global__ __launch_bounds__(kThreads) void grouped_gemm_mfma_kernel(const uint16_t* __restrict__ A,
-                                                                     const uint16_t* __restrict__ B,
-                                                                     const uint16_t* __restrict__ bias,
-                                                                     const int32_t* __restrict__ counts,
-                                                                     const int32_t* __restrict__ gather, int gather_rows,
-                                                                     int E, int64_t C, int K, int N, int MT, int NT,
-                                                                     uint16_t* out,                 // may alias `pre`
-                                                                     const int32_t* __restrict__ kfill,
-                                                                     const uint16_t* __restrict__ a_tail,
-                                                                     const uint16_t* __restrict__ b_tail,
-                                                                     const uint16_t* pre,
-                                                                     uint16_t* __restrict__ pre_out) {
-  __shared__ __attribute__((aligned(1024))) char smem[2 * kStageBytes];
-
-  // ---- which tile -------------------------------------------------------------------------------------------------
-  // An expert's live tiles (row tiles below its fill x all column tiles) are numbered by blocks of 8 tile columns and,
-  // inside a block, row by row: 32 consecutive numbers are 4 row tiles x 8 column tiles that share A rows and B
-  // columns.  Each expert's numbering is cut into groups of 32; the full groups of all experts are numbered first,
-  // then the short last groups (ragged tails), and this sequence is dealt round-robin to the 8 XCDs: hardware deals
-  // blocks round-robin, so block b runs on XCD b % 8, whose 32 CUs hold one group at a time in their own L2.  Counting
-  // only live groups, full ones first, keeps the XCDs evenly loaded whatever the experts' fills are.  Every wave finds
-  // its group by prefix sums over the experts' group counts, 64 experts per step.
-  const int lane = threadIdx.x & 63;
-  const int b = blockIdx.x;
+// Which tile block number b works on (see the numbering described in the kernel below).  Returns kTileNone past the last
+// live group, kTileIdle for an idle slot of a short group, kTileLive otherwise with the expert, its row and column tile and
+// the expert's number of real rows.
+constexpr int kTileLive = 0, kTileIdle = 1, kTileNone = 2;
+__device__ __forceinline__ int find_tile(int b, int lane, int E, int64_t C, const int32_t* __restrict__ counts, int NT,
+                                         int& e_out, int& mt_out, int& nt_out, int& rows_out) {
   const int group = ((b / 8) / 32) * 8 + b % 8, slot = (b / 8) % 32;
   auto live_rows = [&](int el) -> int {                             // rows of expert el that exist (its fill, at most C)
     if (el >= E) return 0;
@@ -363,13 +339,48 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_mfma_kernel(const uint1
     }
     base += tot;
   }
-  if (e < 0) return;                                                // past the last live group
+  if (e < 0) return kTileNone;                                      // past the last live group
   const int q = (short_group ? mte * NT / 32 : rank) * 32 + slot;
-  if (q >= mte * NT) return;                                        // idle slot of a short group
+  if (q >= mte * NT) return kTileIdle;                              // idle slot of a short group
   const int full = (NT / 8) * mte * 8;                              // live tiles of this expert in full 8-column blocks
   int mt, nt;
   if (q < full) { mt = (q % (mte * 8)) / 8; nt = (q / (mte * 8)) * 8 + q % 8; }
   else { const int w = NT % 8, r = q - full; mt = r / w; nt = (NT / 8) * 8 + r % w; }
+  e_out = e; mt_out = mt; nt_out = nt; rows_out = rows_e;
+  return kTileLive;
+}
+
+// GRAD (kNT only): the epilogue multiplies by act'(pre) read from `pre` [E,C,N], i.e. the product is the gradient with
+// respect to the pre-activations of a layer whose activation is ACT; with ACT < 0 it adds `pre` instead (a product
+// accumulated onto an existing matrix; `pre` may then be `out` itself, every element being read before it is written
+// by the same lane).
+// DUAL (kNN with an activation only): the values before the activation are written to `pre_out` as well.
+template <int ACT, int MODE, bool GRAD, bool DUAL = false>
+__global__ __launch_bounds__(kThreads) void grouped_gemm_mfma_kernel(const uint16_t* __restrict__ A,
+                                                                     const uint16_t* __restrict__ B,
+                                                                     const uint16_t* __restrict__ bias,
+                                                                     const int32_t* __restrict__ counts,
+                                                                     const int32_t* __restrict__ gather, int gather_rows,
+                                                                     int E, int64_t C, int K, int N, int MT, int NT,
+                                                                     uint16_t* out,                 // may alias `pre`
+                                                                     const int32_t* __restrict__ kfill,
+                                                                     const uint16_t* __restrict__ a_tail,
+                                                                     const uint16_t* __restrict__ b_tail,
+                                                                     const uint16_t* pre,
+                                                                     uint16_t* __restrict__ pre_out) {
+  __shared__ __attribute__((aligned(1024))) char smem[2 * kStageBytes];
+
+  // ---- which tile -------------------------------------------------------------------------------------------------
+  // An expert's live tiles (row tiles below its fill x all column tiles) are numbered by blocks of 8 tile columns and,
+  // inside a block, row by row: 32 consecutive numbers are 4 row tiles x 8 column tiles that share A rows and B
+  // columns.  Each expert's numbering is cut into groups of 32; the full groups of all experts are numbered first,
+  // then the short last groups (ragged tails), and this sequence is dealt round-robin to the 8 XCDs: hardware deals
+  // blocks round-robin, so block b runs on XCD b % 8, whose 32 CUs hold one group at a time in their own L2.  Counting
+  // only live groups, full ones first, keeps the XCDs evenly loaded whatever the experts' fills are.  Every wave finds
+  // its group by prefix sums over the experts' group counts, 64 experts per step.
+  const int lane = threadIdx.x & 63;
+  int e, mt, nt, rows_e;
+  if (find_tile(blockIdx.x, lane, E, C, counts, NT, e, mt, nt, rows_e) != kTileLive) return;
   const int64_t rows = rows_e;                                      // already here from the search: no second trip to memory
   const int64_t m0 = (int64_t)mt * BM;
   if (m0 >= rows) return;                                           // cannot happen (mt < mte); keeps every access in the slab
