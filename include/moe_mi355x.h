@@ -310,6 +310,9 @@ int moe_layer_forward_dynamic(const void* x, const void* Wg, const float* gate_b
  *   dW2 [E,H,M], db2 [E,M]   (any of dWg ... db2 may be NULL; dx is required),
  * running moe_decode_backward, moe_expert_ffn_backward, moe_encode_backward and moe_gate_backward on the state's
  * buffers.  The choice of experts, the slot assignment and dropped choices carry no gradient.
+ * Where the matrix-core kernels take the shape (bf16, M and H multiples of 256, T * M * 2 < 2^32) the step never writes
+ * the dispatch buffer: the forward's first product and the backward's dW1 = Z^T dP read the rows of Z from x through the
+ * slot -> token map, as moe_layer_forward_fused does; results are bit-identical to the buffered route.
  *   state: device memory of at least moe_layer_train_state_bytes(T, M, H, E, k, moe_capacity(T, E, k, f), dtype)
  *   bytes, 256-byte aligned, owned by the caller; its layout is private; it must not change between the two calls.
  *   One state serves one step at a time: two steps that overlap on different streams need two states. */

@@ -398,7 +398,14 @@ namespace {
 struct TrainState {
   size_t logits, idx, loc, gate_w, counts, slot_src, gate_ws, Z, pre, hidden, Y;     // written by the forward
   size_t dgate_w, dY, dZ, ffn_ws, gate_bwd_ws, total;                                // scratch of the backward
+  bool fused;                                                                        // no Z: rows are read through slot_src
 };
+
+// The training step reads the experts' input rows straight from the token matrix through the slot -> token map (first
+// GEMM of the forward, first layer's weight gradient of the backward) wherever the matrix-core kernels take the shape.
+bool train_fuses_dispatch(int64_t T, int64_t M, int64_t H, int64_t E, int64_t C, int dtype) {
+  return dtype == MOE_BF16 && grouped_gemm_mfma_supports(E, C, M, H, T) && ffn_backward_gather_supports(E, C, M, H, T, dtype);
+}
 
 TrainState train_layout(int64_t T, int64_t M, int64_t H, int64_t E, int k, int64_t C, int dtype) {
   TrainState w;
@@ -412,7 +419,8 @@ TrainState train_layout(int64_t T, int64_t M, int64_t H, int64_t E, int k, int64
   w.counts = take((size_t)E * 4);
   w.slot_src = take((size_t)E * C * 4);
   w.gate_ws = take(gate_route_workspace(T, M, E, k, dtype));
-  w.Z = take((size_t)E * C * M * es);
+  w.fused = train_fuses_dispatch(T, M, H, E, C, dtype);
+  w.Z = take(w.fused ? 0 : (size_t)E * C * M * es);                 // fused dispatch: the slabs of dispatched rows never exist
   w.pre = take((size_t)E * C * H * es);
   w.hidden = take((size_t)E * C * H * es);
   w.Y = take((size_t)E * C * M * es);
@@ -601,7 +609,7 @@ int moe_layer_forward_dynamic(const void* x, const void* Wg, const float* gate_b
   // every buffer keeps the layout the caller's bound gives ([E, C_max, ...]); the chosen capacity only narrows which
   // choices are kept (loc < C, read from device memory) and how many rows of a slab are filled
   if (launch_slot_sources(d_idx, d_loc, T, E, k, C_max, d_src, s, d_C) != hipSuccess) return MOE_HIP_ERROR;
-  if (launch_encode(x, dtype, d_idx, d_loc, d_src, T, M, E, k, C_max, base + w.Z, s, false) != hipSuccess) return MOE_HIP_ERROR;
+  if (launch_encode(x, dtype, d_idx, d_loc, d_src, T, M, E, k, C_max, base + w.Z, s, false, d_C) != hipSuccess) return MOE_HIP_ERROR;
   if (launch_grouped_gemm(base + w.Z, W1, b1, act, dtype, d_fills, E, C_max, M, H, base + w.hidden, s) != hipSuccess) return MOE_HIP_ERROR;
   if (launch_grouped_gemm(base + w.hidden, W2, b2, -1, dtype, d_fills, E, C_max, H, M, base + w.Y, s) != hipSuccess) return MOE_HIP_ERROR;
   if (launch_decode(base + w.Y, dtype, d_idx, d_loc, d_gw, T, M, E, k, C_max, out, s, d_C) != hipSuccess) return MOE_HIP_ERROR;
@@ -637,10 +645,15 @@ int moe_layer_forward_train(const void* x, const void* Wg, const float* gate_bia
   if (run_gate(x, Wg, gate_bias, dtype, T, M, E, k, C, normalize, logits, idx, gw, loc, counts, src, base + w.gate_ws, s,
                [] { return true; }) != hipSuccess)
     return MOE_HIP_ERROR;
-  // the slabs are internal and every later stage stops at an expert's fill: no zero rows needed
-  if (launch_encode(x, dtype, idx, loc, src, T, M, E, k, C, base + w.Z, s, false) != hipSuccess) return MOE_HIP_ERROR;
-  if (launch_grouped_gemm(base + w.Z, W1, b1, act, dtype, counts, E, C, M, H, base + w.hidden, s, base + w.pre) != hipSuccess)
-    return MOE_HIP_ERROR;
+  if (w.fused) {
+    if (launch_grouped_gemm_mfma(x, W1, b1, act, counts, E, C, M, H, base + w.hidden, s, src, T, base + w.pre) != hipSuccess)
+      return MOE_HIP_ERROR;
+  } else {
+    // the slabs are internal and every later stage stops at an expert's fill: no zero rows needed
+    if (launch_encode(x, dtype, idx, loc, src, T, M, E, k, C, base + w.Z, s, false) != hipSuccess) return MOE_HIP_ERROR;
+    if (launch_grouped_gemm(base + w.Z, W1, b1, act, dtype, counts, E, C, M, H, base + w.hidden, s, base + w.pre) != hipSuccess)
+      return MOE_HIP_ERROR;
+  }
   if (launch_grouped_gemm(base + w.hidden, W2, b2, -1, dtype, counts, E, C, H, M, base + w.Y, s) != hipSuccess) return MOE_HIP_ERROR;
   if (launch_decode(base + w.Y, dtype, idx, loc, gw, T, M, E, k, C, out, s) != hipSuccess) return MOE_HIP_ERROR;
   return MOE_OK;
@@ -674,8 +687,9 @@ int moe_layer_backward(const void* x, const void* Wg, const void* W1, const void
   if (launch_decode_backward(d_out, base + w.Y, dtype, idx, loc, gw, src, T, M, E, k, C, base + w.dY, dgw, s, false) != hipSuccess)
     return MOE_HIP_ERROR;
   // experts: dZ over the filled slots, parameter gradients
-  if (launch_expert_ffn_backward(base + w.Z, W1, b1, W2, base + w.pre, base + w.hidden, base + w.dY, act, dtype, counts, E, C, M,
-                                 H, base + w.ffn_ws, base + w.dZ, dW1, db1, dW2, db2, s) != hipSuccess)
+  if (launch_expert_ffn_backward(w.fused ? x : base + w.Z, W1, b1, W2, base + w.pre, base + w.hidden, base + w.dY, act, dtype,
+                                 counts, E, C, M, H, base + w.ffn_ws, base + w.dZ, dW1, db1, dW2, db2, s, w.fused ? src : nullptr,
+                                 w.fused ? T : 0) != hipSuccess)
     return MOE_HIP_ERROR;
   // encode: dx = sum of a token's kept slot rows of dZ (decode with unit weights)
   if (launch_decode(base + w.dZ, dtype, idx, loc, nullptr, T, M, E, k, C, dx, s) != hipSuccess) return MOE_HIP_ERROR;

@@ -125,9 +125,10 @@ hipError_t launch_dynamic_capacity(const int32_t* counts, int64_t E, int64_t bou
 // C_dev (optional, device): only choices with loc < min(*C_dev, C) are kept; slot_src keeps its [E, C] layout
 hipError_t launch_slot_sources(const int32_t* idx, const int32_t* loc, int64_t T, int64_t E, int k, int64_t C,
                                int32_t* slot_src, hipStream_t s, const int64_t* C_dev = nullptr);
+// C_dev (optional, device): as for launch_slot_sources (slot_src must have been built with the same C_dev)
 hipError_t launch_encode(const void* x, int dtype, const int32_t* idx, const int32_t* loc, const int32_t* slot_src,
                          int64_t T, int64_t M, int64_t E, int k, int64_t C, void* Z, hipStream_t s,
-                         bool fill_unfilled = true);
+                         bool fill_unfilled = true, const int64_t* C_dev = nullptr);
 // C_dev (optional, device): only choices with loc < min(*C_dev, C) are kept; Y keeps its [E, C, M] layout
 hipError_t launch_decode(const void* Y, int dtype, const int32_t* idx, const int32_t* loc, const float* gate_w,
                          int64_t T, int64_t M, int64_t E, int k, int64_t C, void* out, hipStream_t s,
@@ -143,7 +144,8 @@ bool grouped_gemm_mfma_supports_nt(int64_t rows, int64_t K, int64_t N);
 hipError_t launch_grouped_gemm_mfma_nt(const void* A, const void* Bt, const int32_t* counts, int64_t E, int64_t C,
                                        int64_t K, int64_t N, void* out, const void* pre, int act, hipStream_t s);
 hipError_t launch_grouped_gemm_mfma_tn(const void* At, const void* B, const int32_t* kfill, int64_t E, int64_t C, int64_t R,
-                                       int64_t N, void* a_tail, void* b_tail, void* out, hipStream_t s);
+                                       int64_t N, void* a_tail, void* b_tail, void* out, hipStream_t s,
+                                       const int32_t* gather = nullptr, int64_t gather_rows = 0);
 
 size_t gate_backward_workspace_bytes(int64_t T, int64_t M, int64_t E);
 hipError_t launch_gate_backward(const void* x, const void* Wg, const float* logits, const int32_t* idx, const float* dgate_w,
@@ -159,6 +161,9 @@ FfnBackwardWorkspace ffn_backward_layout(int64_t E, int64_t C, int64_t M, int64_
 hipError_t launch_expert_ffn_backward(const void* Z, const void* W1, const void* b1, const void* W2, const void* pre,
                                       const void* hidden, const void* dY, int act, int dtype, const int32_t* counts, int64_t E,
                                       int64_t C, int64_t M, int64_t H, void* ws, void* dZ, void* dW1, void* db1, void* dW2,
-                                      void* db2, hipStream_t s);
+                                      void* db2, hipStream_t s, const int32_t* gather = nullptr, int64_t gather_rows = 0);
+// With `gather` [E, C] (slot -> token) `Z` is the token matrix [gather_rows, M] itself (fused dispatch: the slabs of
+// dispatched rows were never written); needs saved pre-activations and shapes the matrix-core backward takes.
+bool ffn_backward_gather_supports(int64_t E, int64_t C, int64_t M, int64_t H, int64_t gather_rows, int dtype);
 
 }  // namespace moe

@@ -54,10 +54,13 @@ __global__ __launch_bounds__(256) void zero_fill_kernel(uint4* __restrict__ p, i
 // gather form moves 2 k (it re-reads the token once per slot, far apart in time).
 __global__ __launch_bounds__(256) void encode_scatter_kernel(const uint4* __restrict__ x, const int32_t* __restrict__ idx,
                                                              const int32_t* __restrict__ loc, int64_t T, int E, int k,
-                                                             int64_t C, int cpr, uint4* __restrict__ Z) {
+                                                             int64_t C, int cpr, uint4* __restrict__ Z,
+                                                             const int64_t* __restrict__ C_dev) {
   const int lane = threadIdx.x & 63;
   const int64_t wave = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * 4 + (threadIdx.x >> 6)));
   const int64_t nwaves = (int64_t)gridDim.x * 4;
+  int64_t Ck = C;                                                    // kept <=> loc < Ck; the slabs keep their stride C
+  if (C_dev) { const int64_t c = *C_dev; Ck = c < C ? c : C; }
   for (int64_t t = wave; t < T; t += nwaves) {
     for (int j0 = 0; j0 < k; j0 += 8) {                              // eight choices at a time share one read of the row
       int64_t row[8];
@@ -67,7 +70,7 @@ __global__ __launch_bounds__(256) void encode_scatter_kernel(const uint4* __rest
         row[u] = -1;
         if (j0 + u < k) {
           const int e = idx[t * k + j0 + u], l = loc[t * k + j0 + u];
-          if (l >= 0 && l < C && (unsigned)e < (unsigned)E) { row[u] = (int64_t)e * C + l; any = true; }   // kept choice
+          if (l >= 0 && l < Ck && (unsigned)e < (unsigned)E) { row[u] = (int64_t)e * C + l; any = true; }  // kept choice
         }
       }
       if (!any) continue;
@@ -82,14 +85,19 @@ __global__ __launch_bounds__(256) void encode_scatter_kernel(const uint4* __rest
 }
 
 hipError_t launch_encode(const void* x, int dtype, const int32_t* idx, const int32_t* loc, const int32_t* slot_src,
-                         int64_t T, int64_t M, int64_t E, int k, int64_t C, void* Z, hipStream_t s, bool fill_unfilled) {
+                         int64_t T, int64_t M, int64_t E, int k, int64_t C, void* Z, hipStream_t s, bool fill_unfilled,
+                         const int64_t* C_dev) {
   const int es = (dtype == MOE_F32) ? 4 : 2;
   const int cpr = (int)(M * es / 16);
   const int64_t nrows = E * C;
   const int64_t sb = ceil_div(T, 4);
-  if (slot_src && !fill_unfilled && k >= 2) {
-    // unfilled slots stay untouched and a token feeds several slots: read every token once, write its kept slots
-    encode_scatter_kernel<<<dim3((unsigned)(sb < 16384 ? sb : 16384)), dim3(256), 0, s>>>((const uint4*)x, idx, loc, T, (int)E, k, C, cpr, (uint4*)Z);
+  // Unfilled slots may stay untouched and a token feeds several slots: reading every token once and writing its kept slots
+  // moves 1 + k rows per token where the slot-major form moves 2 k.  That pays when most choices are kept (many choices
+  // per token, or slots to spare); where capacity is tight and many choices are dropped the slot-major form wins, because
+  // it never looks at a dropped token.
+  const bool token_major = k >= 4 || (k >= 2 && 4 * E * C >= 5 * T * k);
+  if (slot_src && !fill_unfilled && token_major) {
+    encode_scatter_kernel<<<dim3((unsigned)(sb < 16384 ? sb : 16384)), dim3(256), 0, s>>>((const uint4*)x, idx, loc, T, (int)E, k, C, cpr, (uint4*)Z, C_dev);
     return hipGetLastError();
   }
   if (slot_src) {
@@ -105,7 +113,7 @@ hipError_t launch_encode(const void* x, int dtype, const int32_t* idx, const int
   zero_fill_kernel<<<dim3((unsigned)(zb < 16384 ? (zb > 0 ? zb : 1) : 16384)), dim3(256), 0, s>>>((uint4*)Z, n16);
   hipError_t err = hipGetLastError();
   if (err != hipSuccess) return err;
-  encode_scatter_kernel<<<dim3((unsigned)(sb < 16384 ? sb : 16384)), dim3(256), 0, s>>>((const uint4*)x, idx, loc, T, (int)E, k, C, cpr, (uint4*)Z);
+  encode_scatter_kernel<<<dim3((unsigned)(sb < 16384 ? sb : 16384)), dim3(256), 0, s>>>((const uint4*)x, idx, loc, T, (int)E, k, C, cpr, (uint4*)Z, nullptr);
   return hipGetLastError();
 }
 

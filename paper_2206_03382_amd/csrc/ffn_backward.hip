@@ -143,7 +143,8 @@ FfnBackwardWorkspace ffn_backward_layout(int64_t E, int64_t C, int64_t M, int64_
 template <typename ET>
 static hipError_t ffn_backward_t(const void* Z, const void* W1, const void* b1, const void* W2, const void* saved_pre,
                                  const void* hidden, const void* dY, int act, int dtype, const int32_t* counts, int64_t E, int64_t C, int64_t M,
-                                 int64_t H, char* ws, void* dZ, void* dW1, void* db1, void* dW2, void* db2, hipStream_t s) {
+                                 int64_t H, char* ws, void* dZ, void* dW1, void* db1, void* dW2, void* db2, hipStream_t s,
+                                 const int32_t* gather, int64_t gather_rows) {
   const FfnBackwardWorkspace w = ffn_backward_layout(E, C, M, H, dtype);
   const int64_t Cp = w.Cp;
   const int es = (int)sizeof(ET);
@@ -152,7 +153,10 @@ static hipError_t ffn_backward_t(const void* Z, const void* W1, const void* b1, 
   hipError_t err;
 #define MOE_TRY(x) do { err = (x); if (err != hipSuccess) return err; } while (0)
   // pre-activations: the caller's (kept by the training forward), else recomputed
-  if (!saved_pre) MOE_TRY(launch_grouped_gemm(Z, W1, b1, -1, dtype, counts, E, C, M, H, ws + w.pre, s));
+  if (!saved_pre) {
+    if (gather) return hipErrorInvalidValue;                       // a fused-dispatch training forward always keeps them
+    MOE_TRY(launch_grouped_gemm(Z, W1, b1, -1, dtype, counts, E, C, M, H, ws + w.pre, s));
+  }
   auto colsums = [&]() -> hipError_t {
     if (db1) {
       const int cprH = (int)(H * es / 16);
@@ -169,9 +173,10 @@ static hipError_t ffn_backward_t(const void* Z, const void* W1, const void* b1, 
     MOE_TRY(launch_grouped_gemm_mfma_nt(dY, W2, counts, E, C, M, H, dP, pre, act, s));
     if (dZ) MOE_TRY(launch_grouped_gemm_mfma_nt(dP, W1, counts, E, C, H, M, dZ, nullptr, -1, s));
     if (dW2) MOE_TRY(launch_grouped_gemm_mfma_tn(hidden, dY, counts, E, C, H, M, At, Bp, dW2, s));
-    if (dW1) MOE_TRY(launch_grouped_gemm_mfma_tn(Z, dP, counts, E, C, M, H, At, Bp, dW1, s));
+    if (dW1) MOE_TRY(launch_grouped_gemm_mfma_tn(Z, dP, counts, E, C, M, H, At, Bp, dW1, s, gather, gather_rows));
     return colsums();
   }
+  if (gather) return hipErrorInvalidValue;                         // the plain products below need the dispatched rows
   // dH = dY W2^T, then dP = dH * act'(pre)
   MOE_TRY(transpose_pad<ET>(W2, nullptr, E, H, M, H, Wt, s));                          // [E,H,M] -> [E,M,H]
   MOE_TRY(launch_grouped_gemm(dY, Wt, nullptr, -1, dtype, counts, E, C, M, H, dP, s));
@@ -209,13 +214,20 @@ static hipError_t ffn_backward_t(const void* Z, const void* W1, const void* b1, 
   return hipSuccess;
 }
 
+bool ffn_backward_gather_supports(int64_t E, int64_t C, int64_t M, int64_t H, int64_t gather_rows, int dtype) {
+  return dtype == MOE_BF16 && grouped_gemm_mfma_supports_backward(E, C, M, H) && gather_rows > 0 &&
+         gather_rows * M * 2 < ((int64_t)1 << 32);
+}
+
 hipError_t launch_expert_ffn_backward(const void* Z, const void* W1, const void* b1, const void* W2, const void* pre,
                                       const void* hidden, const void* dY, int act, int dtype, const int32_t* counts, int64_t E,
                                       int64_t C, int64_t M, int64_t H, void* ws, void* dZ, void* dW1, void* db1, void* dW2,
-                                      void* db2, hipStream_t s) {
+                                      void* db2, hipStream_t s, const int32_t* gather, int64_t gather_rows) {
   if (dtype == MOE_F32)
-    return ffn_backward_t<float>(Z, W1, b1, W2, pre, hidden, dY, act, dtype, counts, E, C, M, H, (char*)ws, dZ, dW1, db1, dW2, db2, s);
-  return ffn_backward_t<uint16_t>(Z, W1, b1, W2, pre, hidden, dY, act, dtype, counts, E, C, M, H, (char*)ws, dZ, dW1, db1, dW2, db2, s);
+    return ffn_backward_t<float>(Z, W1, b1, W2, pre, hidden, dY, act, dtype, counts, E, C, M, H, (char*)ws, dZ, dW1, db1, dW2, db2, s,
+                                 gather, gather_rows);
+  return ffn_backward_t<uint16_t>(Z, W1, b1, W2, pre, hidden, dY, act, dtype, counts, E, C, M, H, (char*)ws, dZ, dW1, db1, dW2, db2, s,
+                                  gather, gather_rows);
 }
 
 }  // namespace moe

@@ -139,13 +139,22 @@ __device__ __forceinline__ int wave_inclusive_scan(int v) {
 // they may start only after the barrier that follows the last read of that stage (issued during sub-step 2): 8 of a
 // wave's 16 loads are issued in sub-step 3 of K-step kt, the other 8 in sub-step 0 of K-step kt+1, and they are
 // waited for before the barrier of K-step kt+1, two sub-steps later.
-template <int NI, int MODE>
+// GK (kTN only): the k-rows of A are gathered.  K-step t's row 2 (4 q + wave) + kg is row gk.rows[64 t + ...] of the
+// matrix at a_base (row length gk.row_bytes); a_voff[0] then holds the lane's offset into the side buffer for q = 0.
+struct GatherK {
+  const int32_t* rows;          // this expert's slot -> row map (uniform)
+  uint32_t row_bytes;           // bytes per row of the gathered matrix
+  uint32_t nrows;               // rows of the gathered matrix (indices outside read row 0)
+  uint32_t col;                 // per lane: byte offset of its 16-byte piece inside a row
+  uint32_t tail_step;           // bytes between the side buffer's k-rows of consecutive q
+};
+template <int NI, int MODE, bool GK = false>
 __device__ __forceinline__ void tile_main_loop(char* smem, const char* a_base, const char* b_base, const char* a_last,
                                                const char* b_last, const uint32_t (&a_voff)[8],
                                                const uint32_t (&b_voff)[8], int64_t a_step, int64_t b_step,
                                                const int (&a_off)[4], const int (&b_off)[4], int a_swz, int kg,
                                                int a_mask, int wave, int KT, const uint16_t* bias_w,
-                                               f32x16 (&acc)[4][4]) {
+                                               f32x16 (&acc)[4][4], const GatherK& gk = GatherK{}) {
   constexpr bool FULL = NI == 4;
   constexpr bool TRA = MODE == kTN;          // A through transposing reads (two per fragment)
   constexpr bool TRB = MODE != kNT;          // B through transposing reads
@@ -186,13 +195,37 @@ __device__ __forceinline__ void tile_main_loop(char* smem, const char* a_base, c
   };
   // direct load number idx (0..15: A0..A7, B0..B7) of K-step `tile` (the caller guarantees tile < KT).  With a
   // transposed A the last K-step comes from the zero-padded side buffers.
+  // gathered A: the eight row indices of one K-step are fetched a K-step before they are needed (plain loads, so the
+  // wait the compiler puts before their use falls behind the barrier's own wait) and turned into offsets in place.
+  // The last K-step comes from the zero-padded side buffer instead (tail).
+  auto gather_fetch = [&](int tile, uint32_t (&g)[8]) {
+    const int32_t* p = gk.rows + (int64_t)tile * BK + wave * 2 + kg;
+#pragma unroll
+    for (int q = 0; q < 8; ++q) g[q] = (uint32_t)p[8 * q];
+  };
+  auto gather_offsets = [&](bool tail, uint32_t (&g)[8]) {
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      if (tail) {
+        g[q] = a_voff[0] + q * gk.tail_step;
+      } else {
+        const uint32_t r = g[q] < gk.nrows ? g[q] : 0u;
+        g[q] = r * gk.row_bytes + gk.col;
+      }
+    }
+  };
+  uint32_t gv[8];
   auto dma = [&](int idx, int tile) {
     const int q = idx & 7;
     const uint32_t dst = smem_addr + (tile & 1) * kStageBytes + (q * 4 + wave) * 1024;
     const bool last = MODE == kTN && tile == KT - 1;
     if (idx < 8) {
-      const char* src = last ? a_last : a_base + tile * a_step;
-      if (FULL || ((a_mask >> q) & 1)) global_to_lds_16(src, a_voff[q], dst);   // skip rows past the slab's fill
+      if (GK) {
+        global_to_lds_16(last ? a_last : a_base, gv[q], dst);
+      } else {
+        const char* src = last ? a_last : a_base + tile * a_step;
+        if (FULL || ((a_mask >> q) & 1)) global_to_lds_16(src, a_voff[q], dst);   // skip rows past the slab's fill
+      }
     } else {
       const char* src = last ? b_last : b_base + tile * b_step;
       global_to_lds_16(src, b_voff[q], dst + kATileBytes);
@@ -222,9 +255,12 @@ __device__ __forceinline__ void tile_main_loop(char* smem, const char* a_base, c
   using F_ = std::false_type;
   // one K-step; DMA0: second half of the loads of K-step kt+1 (sub-step 0), DMA3: first half of K-step kt+2
   // (sub-step 3), NEXT: a K-step kt+1 exists
-  auto kstep = [&](auto dma0_tag, auto dma3_tag, auto next_tag, int kt) {
+  // TAIL (gathered A only): K-step kt+2 is the last one
+  auto kstep = [&](auto dma0_tag, auto dma3_tag, auto next_tag, int kt, auto tail_tag) {
+    constexpr bool TAIL = decltype(tail_tag)::value;
     const char* cur = smem + (kt & 1) * kStageBytes;
     const char* nxt = smem + ((kt + 1) & 1) * kStageBytes;
+    if (GK && decltype(dma3_tag)::value && !TAIL) { gather_fetch(kt + 2, gv); PIN(); }
     substep(T_{}, dma0_tag, f[0], f[1], cur, 1, 8, kt + 1);
     substep(T_{}, F_{}, f[1], f[0], cur, 2, 0, 0);
     substep(T_{}, F_{}, f[0], f[1], cur, 3, 0, 0);
@@ -232,12 +268,24 @@ __device__ __forceinline__ void tile_main_loop(char* smem, const char* a_base, c
     PIN();
     asm volatile("s_barrier" ::: "memory");
     PIN();
+    if (GK && decltype(dma3_tag)::value) { gather_offsets(TAIL, gv); PIN(); }   // nothing else is in flight here
     substep(next_tag, dma3_tag, f[1], f[0], nxt, 0, 0, kt + 2);
   };
 
+  uint32_t gv1[8];
+  if (GK) {                                                         // both K-steps' indices before any direct load is in flight
+    if (KT > 1) gather_fetch(0, gv);
+    if (KT > 2) gather_fetch(1, gv1);
+    gather_offsets(KT == 1, gv);
+  }
 #pragma unroll
   for (int idx = 0; idx < kLoadsPerWave; ++idx) dma(idx, 0);
   if (KT > 1) {
+    if (GK) {
+      gather_offsets(KT == 2, gv1);
+#pragma unroll
+      for (int q = 0; q < 8; ++q) gv[q] = gv1[q];
+    }
 #pragma unroll
     for (int idx = 0; idx < kLoadsPerWave; ++idx) dma(idx, 1);
   }
@@ -277,15 +325,22 @@ __device__ __forceinline__ void tile_main_loop(char* smem, const char* a_base, c
   PIN();
 
   if (KT >= 3) {
-    kstep(F_{}, T_{}, T_{}, 0);                                      // K-step 1 was loaded whole in the prologue
-    for (int kt = 1; kt < KT - 2; ++kt) kstep(T_{}, T_{}, T_{}, kt);
-    kstep(T_{}, F_{}, T_{}, KT - 2);                                 // no K-step KT to load
-    kstep(F_{}, F_{}, F_{}, KT - 1);
+    if (GK) {                                                        // the K-step that loads the last one is peeled as well
+      if (KT == 3) kstep(F_{}, T_{}, T_{}, 0, T_{});
+      else kstep(F_{}, T_{}, T_{}, 0, F_{});
+      for (int kt = 1; kt < KT - 3; ++kt) kstep(T_{}, T_{}, T_{}, kt, F_{});
+      if (KT > 3) kstep(T_{}, T_{}, T_{}, KT - 3, T_{});
+    } else {
+      kstep(F_{}, T_{}, T_{}, 0, F_{});                              // K-step 1 was loaded whole in the prologue
+      for (int kt = 1; kt < KT - 2; ++kt) kstep(T_{}, T_{}, T_{}, kt, F_{});
+    }
+    kstep(T_{}, F_{}, T_{}, KT - 2, F_{});                           // no K-step KT to load
+    kstep(F_{}, F_{}, F_{}, KT - 1, F_{});
   } else if (KT == 2) {
-    kstep(F_{}, F_{}, T_{}, 0);
-    kstep(F_{}, F_{}, F_{}, 1);
+    kstep(F_{}, F_{}, T_{}, 0, F_{});
+    kstep(F_{}, F_{}, F_{}, 1, F_{});
   } else {
-    kstep(F_{}, F_{}, F_{}, 0);
+    kstep(F_{}, F_{}, F_{}, 0, F_{});
   }
 }
 
@@ -355,7 +410,9 @@ __device__ __forceinline__ int find_tile(int b, int lane, int E, int64_t C, cons
 // accumulated onto an existing matrix; `pre` may then be `out` itself, every element being read before it is written
 // by the same lane).
 // DUAL (kNN with an activation only): the values before the activation are written to `pre_out` as well.
-template <int ACT, int MODE, bool GRAD, bool DUAL = false>
+// GK (kTN only): A's k-rows (slots) are gathered through `gather` [E, K] from the matrix A [gather_rows, C] (the token
+// matrix, for the first layer's weight gradient when the dispatch buffer was never written).
+template <int ACT, int MODE, bool GRAD, bool DUAL = false, bool GK = false>
 __global__ __launch_bounds__(kThreads) void grouped_gemm_mfma_kernel(const uint16_t* __restrict__ A,
                                                                      const uint16_t* __restrict__ B,
                                                                      const uint16_t* __restrict__ bias,
@@ -403,7 +460,7 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_mfma_kernel(const uint1
   const char* b_last = nullptr;
   int KT = K / BK;
   if (MODE == kTN) {                                                // A [E, K slots, C], B [E, K slots, N]
-    a_base = (const char*)(A + (int64_t)e * K * C);
+    a_base = GK ? (const char*)A : (const char*)(A + (int64_t)e * K * C);
     b_base = (const char*)(B + (int64_t)e * K * N);
     int64_t fill = K;
     if (kfill) { const int64_t c = kfill[e]; fill = c < K ? (c > 0 ? c : 0) : K; }
@@ -468,7 +525,16 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_mfma_kernel(const uint1
   // the number of live sub-tiles is a template argument, so that the loop body of a ragged tile is as branch-free as a
   // full one's (a wave with no rows still loads its share of B and joins the barriers)
 #define MOE_TILE_LOOP(NI) tile_main_loop<NI, MODE>(smem, a_base, b_base, a_last, b_last, a_voff, b_voff, a_step, b_step, a_off, b_off, a_swz, kg, a_mask, wave, KT, bias_w, acc)
-  if (MODE == kTN) {                                                // output rows are a weight dimension: never ragged
+  if (MODE == kTN && GK) {
+    GatherK gk;
+    gk.rows = gather + (int64_t)e * K;
+    gk.row_bytes = (uint32_t)(C * 2);
+    gk.nrows = (uint32_t)gather_rows;
+    gk.col = a_voff[0] - (uint32_t)((wave * 2 + kg) * C * 2);       // (m0 + 8 c) * 2: the k-row term taken out again
+    gk.tail_step = (uint32_t)(8 * C * 2);
+    tile_main_loop<4, MODE, true>(smem, a_base, b_base, a_last, b_last, a_voff, b_voff, a_step, b_step, a_off, b_off, a_swz, kg,
+                                  a_mask, wave, KT, bias_w, acc, gk);
+  } else if (MODE == kTN) {                                         // output rows are a weight dimension: never ragged
     MOE_TILE_LOOP(4);
   } else {
     switch (ni) {
@@ -551,15 +617,21 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_mfma_kernel(const uint1
 // dst[e, j, :] = src[e, 64 (KT_e - 1) + j, :] if that slot is below the expert's fill, else 0, for j < 64: the last
 // K-step of a kTN product.   src [E, C, W], dst [E, 64, W]; 16-byte pieces, one block per (expert, 4 slots).
 __global__ __launch_bounds__(256) void tail_rows_kernel(const uint4* __restrict__ src, const int32_t* __restrict__ kfill,
-                                                        int64_t C, int cpr, uint4* __restrict__ dst) {
+                                                        int64_t C, int cpr, uint4* __restrict__ dst,
+                                                        const int32_t* __restrict__ gather, int64_t gather_rows) {
   const int e = blockIdx.y;
   int64_t fill = C;
   if (kfill) { const int64_t c = kfill[e]; fill = c < C ? (c > 0 ? c : 0) : C; }
   const int64_t first = (int64_t)(slot_ksteps(fill) - 1) * BK;
   const int j = blockIdx.x * 4 + (threadIdx.x >> 6);
   const int64_t slot = first + j;
+  int64_t row = (int64_t)e * C + slot;
+  if (gather && slot < fill) {                                      // the slot's row of the gathered matrix
+    const int64_t t = gather[row];
+    row = t >= 0 && t < gather_rows ? t : 0;
+  }
   for (int ch = threadIdx.x & 63; ch < cpr; ch += 64)
-    dst[((int64_t)e * BK + j) * cpr + ch] = slot < fill ? src[((int64_t)e * C + slot) * cpr + ch] : make_uint4(0, 0, 0, 0);
+    dst[((int64_t)e * BK + j) * cpr + ch] = slot < fill ? src[row * cpr + ch] : make_uint4(0, 0, 0, 0);
 }
 
 bool grouped_gemm_mfma_supports(int64_t E, int64_t C, int64_t K, int64_t N, int64_t gather_rows) {
@@ -624,19 +696,27 @@ hipError_t launch_grouped_gemm_mfma_nt(const void* A, const void* Bt, const int3
 
 // out[e] (R x N) = At[e]^T * B[e] over the first min(kfill[e], C) of the C slots; At [E, C, R], B [E, C, N], R and N
 // multiples of 256.  a_tail [E, 64, R] and b_tail [E, 64, N] are scratch for the zero-padded last K-step.
+// With `gather` [E, C] (slot -> row, as the dispatch builds it) At is one matrix [gather_rows, R] and slot c of expert e
+// is its row gather[e, c]; gather_rows * R * 2 must stay below 2^32.
 hipError_t launch_grouped_gemm_mfma_tn(const void* At, const void* B, const int32_t* kfill, int64_t E, int64_t C, int64_t R,
-                                       int64_t N, void* a_tail, void* b_tail, void* out, hipStream_t s) {
+                                       int64_t N, void* a_tail, void* b_tail, void* out, hipStream_t s,
+                                       const int32_t* gather, int64_t gather_rows) {
   const int cprR = (int)(R / 8), cprN = (int)(N / 8);
-  tail_rows_kernel<<<dim3(BK / 4, (unsigned)E), dim3(256), 0, s>>>((const uint4*)At, kfill, C, cprR, (uint4*)a_tail);
-  tail_rows_kernel<<<dim3(BK / 4, (unsigned)E), dim3(256), 0, s>>>((const uint4*)B, kfill, C, cprN, (uint4*)b_tail);
+  tail_rows_kernel<<<dim3(BK / 4, (unsigned)E), dim3(256), 0, s>>>((const uint4*)At, kfill, C, cprR, (uint4*)a_tail, gather, gather_rows);
+  tail_rows_kernel<<<dim3(BK / 4, (unsigned)E), dim3(256), 0, s>>>((const uint4*)B, kfill, C, cprN, (uint4*)b_tail, nullptr, 0);
   hipError_t err = hipGetLastError();
   if (err != hipSuccess) return err;
   const int MT = (int)(R / BM), NT = (int)(N / BN);
   const int64_t groups = E * ceil_div((int64_t)MT * NT, 32);
   const dim3 grid((unsigned)(ceil_div(groups, 8) * 256)), block(kThreads);
-  grouped_gemm_mfma_kernel<-1, kTN, false><<<grid, block, 0, s>>>(
-      (const uint16_t*)At, (const uint16_t*)B, nullptr, nullptr, nullptr, 0, (int)E, R, (int)C, (int)N, MT, NT,
-      (uint16_t*)out, kfill, (const uint16_t*)a_tail, (const uint16_t*)b_tail, nullptr, nullptr);
+  if (gather)
+    grouped_gemm_mfma_kernel<-1, kTN, false, false, true><<<grid, block, 0, s>>>(
+        (const uint16_t*)At, (const uint16_t*)B, nullptr, nullptr, gather, (int)gather_rows, (int)E, R, (int)C, (int)N, MT, NT,
+        (uint16_t*)out, kfill, (const uint16_t*)a_tail, (const uint16_t*)b_tail, nullptr, nullptr);
+  else
+    grouped_gemm_mfma_kernel<-1, kTN, false><<<grid, block, 0, s>>>(
+        (const uint16_t*)At, (const uint16_t*)B, nullptr, nullptr, nullptr, 0, (int)E, R, (int)C, (int)N, MT, NT,
+        (uint16_t*)out, kfill, (const uint16_t*)a_tail, (const uint16_t*)b_tail, nullptr, nullptr);
   return hipGetLastError();
 }
 

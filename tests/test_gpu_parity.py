@@ -526,6 +526,34 @@ def test_layer_forward_backward(moe, cfg):
             assert torch.equal(g2[name], got[name]), name
 
 
+# The training step reads the experts' input rows through the slot -> token map (no dispatch buffer).  Its weight
+# gradient walks an expert's slots 64 at a time with the last step from a zero-padded side buffer: fills of exactly
+# 0, 64, 128, ... and one past them are the corner cases.  A zero gate matrix with a fixed bias sends every token to the
+# same two experts (in bias order), so the fills are T, T, 0, 0.
+@pytest.mark.parametrize("T", [1, 63, 64, 65, 128, 129, 192, 256, 257])
+def test_layer_train_step_fills_at_reduction_step_boundaries(moe, T):
+    cfg = synth.CONFIGS[1].scaled(T=T, M=256, H=512, E=4, k=2, f=2.0)
+    inp = synth.make_inputs(cfg, seed=31, bias_std=0.25)
+    inp["Wg"] = np.zeros_like(inp["Wg"])
+    inp["gate_bias"] = np.array([0.5, -1.0, 1.5, -2.0], dtype=np.float32)
+    d_out = synth.make_inputs(cfg.scaled(cfg_id=53), seed=32)["x"]
+    ref = O.moe_layer_backward(inp["x"], inp["Wg"], inp["gate_bias"], inp["W1"], inp["b1"], inp["W2"], inp["b2"],
+                               cfg.k, cfg.f, cfg.normalize, cfg.act, d_out)
+    assert ref["forward"]["counts"].tolist() == [T, 0, T, 0]
+    d = cfg.dtype
+    tl = moe.TrainLayer(dev(inp["Wg"], d), torch.from_numpy(inp["gate_bias"]).cuda(), dev(inp["W1"], d), dev(inp["b1"], d),
+                        dev(inp["W2"], d), dev(inp["b2"], d), T=cfg.T, k=cfg.k, f=cfg.f, normalize=cfg.normalize, act=cfg.act)
+    xd, dod = dev(inp["x"], d), dev(d_out, d)
+    out = tl.forward(xd)
+    g = tl.backward(xd, dod)
+    torch.cuda.synchronize()
+    assert_close(host(out), ref["forward"]["out"], d, "out")
+    for name in ("dx", "dW1", "db1", "dW2", "db2"):
+        assert_close(host(g[name]), ref[name], d, name)
+    for e in (1, 3):                                                # experts without a token: exactly zero gradients
+        assert (host(g["dW1"])[e].view(np.uint32) << 1 == 0).all() and (host(g["dW2"])[e].view(np.uint32) << 1 == 0).all()
+
+
 # ----------------------------------------------------------------------------------------------------------------
 # the layer call allocates nothing, clears nothing by memset and never synchronises: it can be captured in a HIP graph
 # ----------------------------------------------------------------------------------------------------------------
