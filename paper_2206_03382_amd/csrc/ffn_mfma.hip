@@ -348,13 +348,27 @@ __device__ __forceinline__ void tile_main_loop(char* smem, const char* a_base, c
 // from the side buffers, which also covers an expert without any slot (one K-step of zeros).
 __host__ __device__ inline int slot_ksteps(int64_t fill) { return fill > 0 ? (int)((fill + BK - 1) / BK) : 1; }
 
+// Tiles per group of the block numbering (log2): 32 when the launch has several rounds of tiles for every compute unit;
+// fewer when it has not, so that the groups, which are dealt whole to the XCDs, still spread evenly over them.
+__host__ __device__ inline int group_size_log2(int64_t live_tiles) { return live_tiles >= 1024 ? 5 : (live_tiles >= 512 ? 4 : 3); }
+
+// Blocks to launch so that every tile is reached whatever the fills turn out to be and whichever group size they select.
+static inline unsigned tile_grid(int64_t E, int64_t MT, int64_t NT) {
+  int64_t blocks = 0;
+  for (int gs = 3; gs <= 5; ++gs) {
+    const int64_t G = (int64_t)1 << gs, groups = E * ceil_div(MT * NT, G);      // upper bound: every expert full
+    const int64_t b = ceil_div(groups, 8) * 8 * G;                              // G blocks per group, groups dealt to 8 XCDs
+    blocks = b > blocks ? b : blocks;
+  }
+  return (unsigned)blocks;
+}
+
 // Which tile block number b works on (see the numbering described in the kernel below).  Returns kTileNone past the last
 // live group, kTileIdle for an idle slot of a short group, kTileLive otherwise with the expert, its row and column tile and
 // the expert's number of real rows.
 constexpr int kTileLive = 0, kTileIdle = 1, kTileNone = 2;
 __device__ __forceinline__ int find_tile(int b, int lane, int E, int64_t C, const int32_t* __restrict__ counts, int NT,
                                          int& e_out, int& mt_out, int& nt_out, int& rows_out) {
-  const int group = ((b / 8) / 32) * 8 + b % 8, slot = (b / 8) % 32;
   auto live_rows = [&](int el) -> int {                             // rows of expert el that exist (its fill, at most C)
     if (el >= E) return 0;
     int64_t r = C;
@@ -367,11 +381,19 @@ __device__ __forceinline__ int find_tile(int b, int lane, int E, int64_t C, cons
   for (int c = 0; c < kChunks; ++c) rowsv[c] = c * 64 < E ? live_rows(c * 64 + lane) : 0;      // all loads in flight at once
 #pragma unroll
   for (int c = 0; c < kChunks; ++c) mtv[c] = (rowsv[c] + BM - 1) / BM;
+  int live_tiles = 0;                                               // live tiles of all experts
+#pragma unroll
+  for (int c = 0; c < kChunks; ++c) {
+    if (c * 64 >= E) break;
+    live_tiles += __builtin_amdgcn_readlane(wave_inclusive_scan(mtv[c] * NT), 63);
+  }
+  const int gs = group_size_log2(live_tiles), G = 1 << gs;          // tiles per group
+  const int group = ((b / 8) >> gs) * 8 + b % 8, slot = (b / 8) & (G - 1);
   int total_full = 0;                                               // full groups of all experts
 #pragma unroll
   for (int c = 0; c < kChunks; ++c) {
     if (c * 64 >= E) break;
-    total_full += __builtin_amdgcn_readlane(wave_inclusive_scan(mtv[c] * NT / 32), 63);
+    total_full += __builtin_amdgcn_readlane(wave_inclusive_scan((mtv[c] * NT) >> gs), 63);
   }
   const bool short_group = group >= total_full;
   const int target = short_group ? group - total_full : group;
@@ -381,7 +403,7 @@ __device__ __forceinline__ int find_tile(int b, int lane, int E, int64_t C, cons
   for (int c = 0; c < kChunks; ++c) {
     if (c * 64 >= E || e >= 0) break;
     const int mt_l = mtv[c];
-    const int ng_l = short_group ? ((mt_l * NT) % 32 != 0 ? 1 : 0) : mt_l * NT / 32;
+    const int ng_l = short_group ? (((mt_l * NT) & (G - 1)) != 0 ? 1 : 0) : (mt_l * NT) >> gs;
     const int inc = wave_inclusive_scan(ng_l);                      // inclusive prefix sum over the wave
     const int tot = __builtin_amdgcn_readlane(inc, 63);
     if (target < base + tot) {
@@ -395,7 +417,7 @@ __device__ __forceinline__ int find_tile(int b, int lane, int E, int64_t C, cons
     base += tot;
   }
   if (e < 0) return kTileNone;                                      // past the last live group
-  const int q = (short_group ? mte * NT / 32 : rank) * 32 + slot;
+  const int q = ((short_group ? (mte * NT) >> gs : rank) << gs) + slot;
   if (q >= mte * NT) return kTileIdle;                              // idle slot of a short group
   const int full = (NT / 8) * mte * 8;                              // live tiles of this expert in full 8-column blocks
   int mt, nt;
@@ -434,7 +456,9 @@ __global__ __launch_bounds__(kThreads) void grouped_gemm_mfma_kernel(const uint1
   // then the short last groups (ragged tails), and this sequence is dealt round-robin to the 8 XCDs: hardware deals
   // blocks round-robin, so block b runs on XCD b % 8, whose 32 CUs hold one group at a time in their own L2.  Counting
   // only live groups, full ones first, keeps the XCDs evenly loaded whatever the experts' fills are.  Every wave finds
-  // its group by prefix sums over the experts' group counts, 64 experts per step.
+  // its group by prefix sums over the experts' group counts, 64 experts per step.  A launch with few live tiles (a
+  // couple of rounds per compute unit or less) cuts groups of 16 or 8 instead: whole groups go to one XCD, and with 32
+  // per group a handful of them would leave some XCDs with twice the work of others.
   const int lane = threadIdx.x & 63;
   int e, mt, nt, rows_e;
   if (find_tile(blockIdx.x, lane, E, C, counts, NT, e, mt, nt, rows_e) != kTileLive) return;
@@ -647,8 +671,7 @@ hipError_t launch_grouped_gemm_mfma(const void* A, const void* B, const void* bi
                                     int64_t E, int64_t C, int64_t K, int64_t N, void* out, hipStream_t s,
                                     const int32_t* gather, int64_t gather_rows, void* pre_out) {
   const int MT = (int)ceil_div(C, BM), NT = (int)(N / BN);
-  const int64_t groups = E * ceil_div((int64_t)MT * NT, 32);                  // upper bound: every expert full
-  const dim3 grid((unsigned)(ceil_div(groups, 8) * 256)), block(kThreads);    // 32 blocks per group, groups dealt to 8 XCDs
+  const dim3 grid(tile_grid(E, MT, NT)), block(kThreads);
 #define MOE_LAUNCH_GEMM(ACT, DUAL)                                                                                    \
   grouped_gemm_mfma_kernel<ACT, kNN, false, DUAL><<<grid, block, 0, s>>>(                                             \
       (const uint16_t*)A, (const uint16_t*)B, (const uint16_t*)bias, counts, gather, (int)gather_rows, (int)E, C,     \
@@ -677,8 +700,7 @@ hipError_t launch_grouped_gemm_mfma(const void* A, const void* B, const void* bi
 hipError_t launch_grouped_gemm_mfma_nt(const void* A, const void* Bt, const int32_t* counts, int64_t E, int64_t C,
                                        int64_t K, int64_t N, void* out, const void* pre, int act, hipStream_t s) {
   const int MT = (int)ceil_div(C, BM), NT = (int)(N / BN);
-  const int64_t groups = E * ceil_div((int64_t)MT * NT, 32);
-  const dim3 grid((unsigned)(ceil_div(groups, 8) * 256)), block(kThreads);
+  const dim3 grid(tile_grid(E, MT, NT)), block(kThreads);
 #define MOE_LAUNCH_GEMM(ACT, GRAD)                                                                                    \
   grouped_gemm_mfma_kernel<ACT, kNT, GRAD><<<grid, block, 0, s>>>(                                                    \
       (const uint16_t*)A, (const uint16_t*)Bt, nullptr, counts, nullptr, 0, (int)E, C, (int)K, (int)N, MT, NT,        \
@@ -707,8 +729,7 @@ hipError_t launch_grouped_gemm_mfma_tn(const void* At, const void* B, const int3
   hipError_t err = hipGetLastError();
   if (err != hipSuccess) return err;
   const int MT = (int)(R / BM), NT = (int)(N / BN);
-  const int64_t groups = E * ceil_div((int64_t)MT * NT, 32);
-  const dim3 grid((unsigned)(ceil_div(groups, 8) * 256)), block(kThreads);
+  const dim3 grid(tile_grid(E, MT, NT)), block(kThreads);
   if (gather)
     grouped_gemm_mfma_kernel<-1, kTN, false, false, true><<<grid, block, 0, s>>>(
         (const uint16_t*)At, (const uint16_t*)B, nullptr, nullptr, gather, (int)gather_rows, (int)E, R, (int)C, (int)N, MT, NT,
