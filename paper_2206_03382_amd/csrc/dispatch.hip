@@ -284,12 +284,92 @@ __global__ __launch_bounds__(256) void gate_weight_grad_kernel(const uint4* __re
   }
 }
 
+// Both results in one pass over the tokens, for callers that leave unfilled slots alone (the layer's backward): a wave
+// reads its token's d_out row once and, for up to eight kept choices at a time, reads the choice's row of Y (for the
+// dot product) and writes its row of dY.  d_out [T,M] is read once instead of once per slot and once per choice.  The
+// arithmetic and its order are those of the two kernels above, so the results are bit-identical to theirs.
+template <typename ET>
+__global__ __launch_bounds__(256) void decode_backward_token_kernel(const uint4* __restrict__ d_out, const uint4* __restrict__ Y,
+                                                                    const int32_t* __restrict__ idx,
+                                                                    const int32_t* __restrict__ loc,
+                                                                    const float* __restrict__ gate_w, int64_t T, int E, int k,
+                                                                    int64_t C, int cpr, uint4* __restrict__ dY,
+                                                                    float* __restrict__ dgate_w) {
+  constexpr int N = Pack16<ET>::N;
+  const int lane = threadIdx.x & 63;
+  const int64_t wave = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * 4 + (threadIdx.x >> 6)));
+  const int64_t nwaves = (int64_t)gridDim.x * 4;
+  for (int64_t t = wave; t < T; t += nwaves) {
+    for (int j0 = 0; j0 < k; j0 += 8) {
+      int64_t row[8];
+      float w[8], acc[8];
+      bool any = false;
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        row[u] = -1;
+        w[u] = 0.f;
+        acc[u] = 0.f;
+        if (j0 + u < k) {
+          const int e = idx[t * k + j0 + u], l = loc[t * k + j0 + u];
+          if (l >= 0 && l < C && (unsigned)e < (unsigned)E) {       // kept choice (wave-uniform)
+            row[u] = (int64_t)e * C + l;
+            w[u] = gate_w[t * k + j0 + u];
+            any = true;
+          }
+        }
+      }
+      if (any) {
+        for (int ch = lane; ch < cpr; ch += 64) {
+          float a[N];
+          Pack16<ET>::unpack(d_out[t * cpr + ch], a);
+          uint4 yv[8];
+#pragma unroll
+          for (int u = 0; u < 8; ++u)
+            if (row[u] >= 0) yv[u] = Y[row[u] * cpr + ch];
+#pragma unroll
+          for (int u = 0; u < 8; ++u) {
+            if (row[u] < 0) continue;
+            float b[N], f[N];
+            Pack16<ET>::unpack(yv[u], b);
+#pragma unroll
+            for (int v = 0; v < N; ++v) acc[u] = fmaf(a[v], b[v], acc[u]);
+#pragma unroll
+            for (int v = 0; v < N; ++v) f[v] = w[u] * a[v];
+            dY[row[u] * cpr + ch] = Pack16<ET>::pack(f);
+          }
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        if (j0 + u >= k) break;
+        float sum = acc[u];
+        if (row[u] >= 0) {
+#pragma unroll
+          for (int d = 32; d >= 1; d >>= 1) sum += __shfl_xor(sum, d, 64);
+        }
+        if (lane == 0) dgate_w[t * k + j0 + u] = sum;
+      }
+    }
+  }
+}
+
 hipError_t launch_decode_backward(const void* d_out, const void* Y, int dtype, const int32_t* idx, const int32_t* loc,
                                   const float* gate_w, const int32_t* slot_src, int64_t T, int64_t M, int64_t E, int k,
                                   int64_t C, void* dY, float* dgate_w, hipStream_t s, bool fill_unfilled) {
   const int es = (dtype == MOE_F32) ? 4 : 2;
   const int cpr = (int)(M * es / 16);
   const dim3 block(256);
+  if (dY && dgate_w && !fill_unfilled) {
+    const int64_t blocks = ceil_div(T, 4);
+    const dim3 grid((unsigned)(blocks < 16384 ? blocks : 16384));
+    if (dtype == MOE_F32)
+      decode_backward_token_kernel<float><<<grid, block, 0, s>>>((const uint4*)d_out, (const uint4*)Y, idx, loc, gate_w, T, (int)E, k, C,
+                                                                   cpr, (uint4*)dY, dgate_w);
+    else
+      decode_backward_token_kernel<uint16_t><<<grid, block, 0, s>>>((const uint4*)d_out, (const uint4*)Y, idx, loc, gate_w, T, (int)E, k,
+                                                                      C, cpr, (uint4*)dY, dgate_w);
+    return hipGetLastError();
+  }
   if (dY) {
     constexpr int ROWS = 4;
     const int64_t nrows = E * C, blocks = ceil_div(nrows, 4 * ROWS);
