@@ -52,6 +52,7 @@ __global__ __launch_bounds__(256) void zero_fill_kernel(uint4* __restrict__ p, i
 // One wave per token: the row is read once and written to each of its kept slots (every slot row is written whole, so the
 // stores are as coalesced as the gather form's).  With k choices per token this moves (1 + k) rows per token where the
 // gather form moves 2 k (it re-reads the token once per slot, far apart in time).
+template <bool STREAM>
 __global__ __launch_bounds__(256) void encode_scatter_kernel(const uint4* __restrict__ x, const int32_t* __restrict__ idx,
                                                              const int32_t* __restrict__ loc, int64_t T, int E, int k,
                                                              int64_t C, int cpr, uint4* __restrict__ Z,
@@ -75,7 +76,7 @@ __global__ __launch_bounds__(256) void encode_scatter_kernel(const uint4* __rest
       }
       if (!any) continue;
       for (int c = lane; c < cpr; c += 64) {
-        const uint4 v = x[t * cpr + c];
+        const uint4 v = STREAM ? load_stream(x + t * cpr + c) : x[t * cpr + c];
 #pragma unroll
         for (int u = 0; u < 8; ++u)
           if (row[u] >= 0) Z[row[u] * cpr + c] = v;
@@ -97,7 +98,10 @@ hipError_t launch_encode(const void* x, int dtype, const int32_t* idx, const int
   // it never looks at a dropped token.
   const bool token_major = k >= 4 || (k >= 2 && 4 * E * C >= 5 * T * k);
   if (slot_src && !fill_unfilled && token_major) {
-    encode_scatter_kernel<<<dim3((unsigned)(sb < 16384 ? sb : 16384)), dim3(256), 0, s>>>((const uint4*)x, idx, loc, T, (int)E, k, C, cpr, (uint4*)Z, C_dev);
+    if ((double)T * M * es >= 536870912.0)                           // token matrix beyond the caches: rows are streamed
+      encode_scatter_kernel<true><<<dim3((unsigned)(sb < 16384 ? sb : 16384)), dim3(256), 0, s>>>((const uint4*)x, idx, loc, T, (int)E, k, C, cpr, (uint4*)Z, C_dev);
+    else
+      encode_scatter_kernel<false><<<dim3((unsigned)(sb < 16384 ? sb : 16384)), dim3(256), 0, s>>>((const uint4*)x, idx, loc, T, (int)E, k, C, cpr, (uint4*)Z, C_dev);
     return hipGetLastError();
   }
   if (slot_src) {
@@ -113,7 +117,7 @@ hipError_t launch_encode(const void* x, int dtype, const int32_t* idx, const int
   zero_fill_kernel<<<dim3((unsigned)(zb < 16384 ? (zb > 0 ? zb : 1) : 16384)), dim3(256), 0, s>>>((uint4*)Z, n16);
   hipError_t err = hipGetLastError();
   if (err != hipSuccess) return err;
-  encode_scatter_kernel<<<dim3((unsigned)(sb < 16384 ? sb : 16384)), dim3(256), 0, s>>>((const uint4*)x, idx, loc, T, (int)E, k, C, cpr, (uint4*)Z, nullptr);
+  encode_scatter_kernel<false><<<dim3((unsigned)(sb < 16384 ? sb : 16384)), dim3(256), 0, s>>>((const uint4*)x, idx, loc, T, (int)E, k, C, cpr, (uint4*)Z, nullptr);
   return hipGetLastError();
 }
 
@@ -146,7 +150,8 @@ template <> struct Pack16<uint16_t> {
   }
 };
 
-template <typename ET>
+// STREAM: the slabs are far larger than the caches, so their rows are loaded as streamed data (each is read exactly once).
+template <typename ET, bool STREAM>
 __global__ __launch_bounds__(256) void decode_kernel(const uint4* __restrict__ Y, const int32_t* __restrict__ idx,
                                                      const int32_t* __restrict__ loc, const float* __restrict__ gate_w,
                                                      int64_t T, int E, int k, int64_t C, int cpr, uint4* __restrict__ out,
@@ -174,7 +179,8 @@ __global__ __launch_bounds__(256) void decode_kernel(const uint4* __restrict__ Y
             const int l = loc[t * k + j], e = idx[t * k + j];
             if (l >= 0 && l < C && (unsigned)e < (unsigned)E) {           // kept choice
               w[u] = gate_w ? gate_w[t * k + j] : 1.0f;               // no weights: backward of encode
-              v[u] = Y[((int64_t)e * stride + l) * cpr + c];
+              const uint4* src = Y + ((int64_t)e * stride + l) * cpr + c;
+              v[u] = STREAM ? load_stream(src) : *src;
             }
           }
         }
@@ -191,6 +197,54 @@ __global__ __launch_bounds__(256) void decode_kernel(const uint4* __restrict__ Y
   }
 }
 
+// Up to eight choices per token (the usual case): a token's slots and weights are looked up once, then every 16-byte
+// piece of the output row has all its source rows in flight at the same time.  Missing and dropped choices enter the sum
+// as 0 * 0 in their rank's place.
+template <typename ET, bool STREAM>
+__global__ __launch_bounds__(256) void decode_k8_kernel(const uint4* __restrict__ Y, const int32_t* __restrict__ idx,
+                                                        const int32_t* __restrict__ loc, const float* __restrict__ gate_w,
+                                                        int64_t T, int E, int k, int64_t C, int cpr, uint4* __restrict__ out,
+                                                        const int64_t* __restrict__ C_dev) {
+  constexpr int N = Pack16<ET>::N;
+  const int lane = threadIdx.x & 63;
+  const int64_t wave = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * 4 + (threadIdx.x >> 6)));
+  const int64_t nwaves = (int64_t)gridDim.x * 4;
+  const int64_t stride = C;
+  if (C_dev) { const int64_t c = *C_dev; C = c < C ? c : C; }
+  for (int64_t t = wave; t < T; t += nwaves) {
+    int64_t row[8];
+    float w[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      row[u] = -1;
+      w[u] = 0.f;
+      if (u < k) {
+        const int l = loc[t * k + u], e = idx[t * k + u];
+        if (l >= 0 && l < C && (unsigned)e < (unsigned)E) {           // kept choice
+          w[u] = gate_w ? gate_w[t * k + u] : 1.0f;
+          row[u] = ((int64_t)e * stride + l) * cpr;
+        }
+      }
+    }
+    for (int c = lane; c < cpr; c += 64) {
+      uint4 v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = row[u] >= 0 ? (STREAM ? load_stream(Y + row[u] + c) : Y[row[u] + c]) : make_uint4(0, 0, 0, 0);
+      float acc[N];
+#pragma unroll
+      for (int i = 0; i < N; ++i) acc[i] = 0.f;
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        float f[N];
+        Pack16<ET>::unpack(v[u], f);
+#pragma unroll
+        for (int i = 0; i < N; ++i) acc[i] = fmaf(w[u], f[i], acc[i]);
+      }
+      out[t * cpr + c] = Pack16<ET>::pack(acc);
+    }
+  }
+}
+
 hipError_t launch_decode(const void* Y, int dtype, const int32_t* idx, const int32_t* loc, const float* gate_w,
                          int64_t T, int64_t M, int64_t E, int k, int64_t C, void* out, hipStream_t s,
                          const int64_t* C_dev) {
@@ -198,8 +252,16 @@ hipError_t launch_decode(const void* Y, int dtype, const int32_t* idx, const int
   const int cpr = (int)(M * es / 16);
   const int64_t blocks = ceil_div(T, 4);
   const dim3 grid((unsigned)(blocks < 16384 ? blocks : 16384)), block(256);
-  if (dtype == MOE_F32) decode_kernel<float><<<grid, block, 0, s>>>((const uint4*)Y, idx, loc, gate_w, T, (int)E, k, C, cpr, (uint4*)out, C_dev);
-  else decode_kernel<uint16_t><<<grid, block, 0, s>>>((const uint4*)Y, idx, loc, gate_w, T, (int)E, k, C, cpr, (uint4*)out, C_dev);
+  // wide choice lists with slabs beyond the caches: all of a token's rows in flight, loaded as streamed data
+  const bool wide = k >= 3 && k <= 8, stream = (double)E * C * M * es >= 1073741824.0;
+#define MOE_LAUNCH_DECODE(KERNEL, ET, STREAM) KERNEL<ET, STREAM><<<grid, block, 0, s>>>((const uint4*)Y, idx, loc, gate_w, T, (int)E, k, C, cpr, (uint4*)out, C_dev)
+#define MOE_LAUNCH_DECODE_ET(KERNEL, STREAM) do { if (dtype == MOE_F32) MOE_LAUNCH_DECODE(KERNEL, float, STREAM); else MOE_LAUNCH_DECODE(KERNEL, uint16_t, STREAM); } while (0)
+  if (wide && stream) MOE_LAUNCH_DECODE_ET(decode_k8_kernel, true);
+  else if (wide) MOE_LAUNCH_DECODE_ET(decode_k8_kernel, false);
+  else if (stream) MOE_LAUNCH_DECODE_ET(decode_kernel, true);
+  else MOE_LAUNCH_DECODE_ET(decode_kernel, false);
+#undef MOE_LAUNCH_DECODE_ET
+#undef MOE_LAUNCH_DECODE
   return hipGetLastError();
 }
 
@@ -288,7 +350,7 @@ __global__ __launch_bounds__(256) void gate_weight_grad_kernel(const uint4* __re
 // reads its token's d_out row once and, for up to eight kept choices at a time, reads the choice's row of Y (for the
 // dot product) and writes its row of dY.  d_out [T,M] is read once instead of once per slot and once per choice.  The
 // arithmetic and its order are those of the two kernels above, so the results are bit-identical to theirs.
-template <typename ET>
+template <typename ET, bool STREAM>
 __global__ __launch_bounds__(256) void decode_backward_token_kernel(const uint4* __restrict__ d_out, const uint4* __restrict__ Y,
                                                                     const int32_t* __restrict__ idx,
                                                                     const int32_t* __restrict__ loc,
@@ -325,7 +387,7 @@ __global__ __launch_bounds__(256) void decode_backward_token_kernel(const uint4*
           uint4 yv[8];
 #pragma unroll
           for (int u = 0; u < 8; ++u)
-            if (row[u] >= 0) yv[u] = Y[row[u] * cpr + ch];
+            if (row[u] >= 0) yv[u] = STREAM ? load_stream(Y + row[u] * cpr + ch) : Y[row[u] * cpr + ch];
 #pragma unroll
           for (int u = 0; u < 8; ++u) {
             if (row[u] < 0) continue;
@@ -362,12 +424,11 @@ hipError_t launch_decode_backward(const void* d_out, const void* Y, int dtype, c
   if (dY && dgate_w && !fill_unfilled) {
     const int64_t blocks = ceil_div(T, 4);
     const dim3 grid((unsigned)(blocks < 16384 ? blocks : 16384));
-    if (dtype == MOE_F32)
-      decode_backward_token_kernel<float><<<grid, block, 0, s>>>((const uint4*)d_out, (const uint4*)Y, idx, loc, gate_w, T, (int)E, k, C,
-                                                                   cpr, (uint4*)dY, dgate_w);
-    else
-      decode_backward_token_kernel<uint16_t><<<grid, block, 0, s>>>((const uint4*)d_out, (const uint4*)Y, idx, loc, gate_w, T, (int)E, k,
-                                                                      C, cpr, (uint4*)dY, dgate_w);
+    const bool stream = (double)E * C * M * es >= 1073741824.0;
+#define MOE_LAUNCH_DBT(ET, STREAM) decode_backward_token_kernel<ET, STREAM><<<grid, block, 0, s>>>((const uint4*)d_out, (const uint4*)Y, idx, loc, gate_w, T, (int)E, k, C, cpr, (uint4*)dY, dgate_w)
+    if (dtype == MOE_F32) { if (stream) MOE_LAUNCH_DBT(float, true); else MOE_LAUNCH_DBT(float, false); }
+    else { if (stream) MOE_LAUNCH_DBT(uint16_t, true); else MOE_LAUNCH_DBT(uint16_t, false); }
+#undef MOE_LAUNCH_DBT
     return hipGetLastError();
   }
   if (dY) {
