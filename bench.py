@@ -214,7 +214,7 @@ def cpu_baseline(cfg, inp, budget_s: float = 12.0):
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=HEADLINE_CONFIG,
                     help="index into the five workloads (default 4: T=131072, M=4096, H=1024, E=128, top-8, the largest)")
