@@ -9,7 +9,7 @@
 //     of a partial sum bounded by sum |x w| give  |error| <= 32 CH 2^-23 sum_{chunk} |x_m w_me|;
 //   * eight chunk results are added in fp32 by the vector unit (round to nearest: 2^-24 each), and those sums are added
 //     in fp32 again (ceil(chunks / 8) additions), then the bias: every partial sum is bounded by sum_m |x_m w_me| + |b_e|.
-// So  |logit' - exact sum| <= B_t = (32 CH 2^-23 + (9 + ceil(chunks / 8)) 2^-24) (|x_t| max_e |w_e| + max_e |b_e|)
+// So  |logit' - exact sum| <= B_t = (32 CH 2^-23 + (10 + ceil(chunks / 8)) 2^-24) (|x_t| max_e |w_e| + max_e |b_e|)
 // by Cauchy-Schwarz over the whole row.  B_t is written per token (`margin`); |x_t|^2 comes from the matrix cores too
 // (the diagonal of X X^T, accumulated beside the logits).  The top-k kernel orders a token's k+1 largest logits and accepts
 // them only if every gap between neighbours exceeds 2 B_t (plus the rounding of the exactly rounded value itself); the few
@@ -146,7 +146,16 @@ __global__ __launch_bounds__(256, 2) void gate_logits_fast_kernel(const uint16_t
   __syncthreads();
 
   const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
-  f32x4 part[TW][NT];                                               // fp32 sums of the current chain
+  // fp32 sums of the current chain and of the one before it.  A chain's sum is added to its super-chunk one chain late,
+  // behind the first matrix-core instruction of the next chain (by then it has long left the pipeline), and the addition
+  // is pinned there: left to itself the compiler keeps every chain's sum of a whole prefetch group alive and adds them
+  // all at the group's end, which costs 32 registers per chain.
+  static_assert((R / CH) % 2 == 0, "chains alternate between two accumulators across prefetch groups");
+  f32x4 part[2][TW][NT];
+#pragma unroll
+  for (int w = 0; w < TW; ++w)
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) part[1][w][nt] = zero;
   auto group = [&](auto fast_tag, int s0) __attribute__((always_inline)) {
 #pragma unroll
     for (int j = 0; j < R; ++j) {
@@ -167,14 +176,16 @@ __global__ __launch_bounds__(256, 2) void gate_logits_fast_kernel(const uint16_t
         const bf16x8 b = *reinterpret_cast<const bf16x8*>(&wbuf[((eh * NT + nt) * 16 + r) * KCH + ((((s % CS) * 4 + kq) ^ r) << 3)]);
 #pragma unroll
         for (int w = 0; w < TW; ++w) {
-          part[w][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[w], b, j % CH == 0 ? zero : part[w][nt], 0, 0, 0);
-          if (j % CH == CH - 1) {
+          const int p = (j / CH) & 1;                               // compile-time: j is an unrolled index
+          part[p][w][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[w], b, j % CH == 0 ? zero : part[p][w][nt], 0, 0, 0);
+          if (j % CH == 0) {                                        // the chain before this one (zeros before the very first)
 #pragma unroll
-            for (int v = 0; v < 4; ++v) sup[w][nt][v] += part[w][nt][v];
+            for (int v = 0; v < 4; ++v) sup[w][nt][v] += part[p ^ 1][w][nt][v];
+            asm volatile("" : "+v"(sup[w][nt]));
           }
         }
       }
-      if ((s + 1) % (8 * CH) == 0) {                                // eight chunks make a super-chunk
+      if ((s + 1) % (8 * CH) == 0) {                                // eight chains make a super-chunk (the latest one joins the next)
 #pragma unroll
         for (int w = 0; w < TW; ++w)
 #pragma unroll
@@ -197,6 +208,13 @@ __global__ __launch_bounds__(256, 2) void gate_logits_fast_kernel(const uint16_t
   for (; s0 + 2 * R <= full_steps; s0 += R) group(std::true_type{}, s0);      // this group and the one it prefetches are full
   for (; s0 < steps; s0 += R) group(std::false_type{}, s0);                  // steps is a multiple of R (the launcher sees to it)
 
+  // the last chain's sum (R / CH is even: it sits in the second accumulator)
+#pragma unroll
+  for (int w = 0; w < TW; ++w)
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) sup[w][nt][v] += part[1][w][nt][v];
   // logits: lane holds expert column nt*16 + r of token rows 4 kq + v
 #pragma unroll
   for (int w = 0; w < TW; ++w)
@@ -238,7 +256,7 @@ void launch_fast_one(const uint16_t* x, const uint16_t* Wt, const float* wnorm, 
   // error bound of a logit per unit of |x| |w| + |b|: the chunk's matrix-core sum (one unit in the last place per term),
   // eight chunk results, the super-chunks, the bias (round to nearest each), with slack for the norms' own rounding
   const int chunks = Mp / (32 * CH);
-  const float bound = (float)((32.0 * CH * (double)kUlp + (9.0 + (chunks + 7) / 8) * 0.5 * (double)kUlp) * 1.01);
+  const float bound = (float)((32.0 * CH * (double)kUlp + (10.0 + (chunks + 7) / 8) * 0.5 * (double)kUlp) * 1.01);
   gate_logits_fast_kernel<NT, TW, R, KCH, CH, EH><<<grid, block, 0, s>>>(x, Wt, wnorm, bias, T, M, Mp, E, e_base, bound, logits, margin);
 }
 
@@ -288,7 +306,7 @@ hipError_t launch_gate_logits_fast(const void* x, const void* Wg, const float* b
     if (rem <= 16) { if (wide) MOE_FAST_R(1, 2, 8, 1, 1); else MOE_FAST_R(1, 1, 16, 1, 1); }
     else if (rem <= 32) { if (wide) MOE_FAST_R(2, 2, 4, 1, 1); else MOE_FAST_R(2, 1, 8, 1, 1); }
     else if (rem <= 64) { if (wide) MOE_FAST_R(4, 2, 4, 2, 1); else MOE_FAST_R(4, 1, 8, 2, 1); }
-    else MOE_FAST_R(8, 1, 8, 2, 1);
+    else MOE_FAST_R(8, 1, 8, 1, 1);                                 // single chains: the tighter bound halves the near-tie repairs of wide top-k
 #undef MOE_FAST_R
 #undef MOE_FAST
   }
