@@ -6,12 +6,15 @@
 
 namespace moe {
 
-template <typename ET>
+// TS x TS outputs per thread, 16 x 16 threads: 64 x 64 tiles, or 32 x 32 tiles for launches that would otherwise leave
+// most compute units without a block (the arithmetic of an output element is the same chain either way).
+template <typename ET, int TS>
 __global__ __launch_bounds__(256) void gemm_generic_kernel(const ET* __restrict__ A, const ET* __restrict__ B,
                                                            const ET* __restrict__ bias, int act,
                                                            const int32_t* __restrict__ counts, int64_t C, int K, int N,
                                                            ET* __restrict__ out) {
-  constexpr int BM = 64, BN = 64, BK = 16;
+  constexpr int BM = 16 * TS, BN = 16 * TS, BK = 64;              // long K-steps: few round trips to memory per tile
+  constexpr int PF = BM * BK / 256;                               // elements of each operand tile per thread
   __shared__ float As[BK][BM + 4];
   __shared__ float Bs[BK][BN];
   const int e = blockIdx.z;
@@ -23,29 +26,29 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(const ET* __restrict_
   const ET* Ae = A + (int64_t)e * C * K;
   const ET* Be = B + (int64_t)e * K * N;
   const int tid = threadIdx.x, ty = tid / 16, tx = tid % 16;
-  float acc[4][4];
+  float acc[TS][TS];
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < TS; ++i)
 #pragma unroll
-    for (int j = 0; j < 4; ++j) acc[i][j] = 0.f;
+    for (int j = 0; j < TS; ++j) acc[i][j] = 0.f;
 
   // the next K-step's operands are fetched into registers while this one is computed from LDS
-  float pa[4], pb[4];
+  float pa[PF], pb[PF];
   auto fetch = [&](int k0) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < PF; ++i) {
       const int id = tid + i * 256;
-      const int r = id / BK, kk = id % BK;                 // A tile: 64 rows x 16 k
+      const int r = id / BK, kk = id % BK;                 // A tile: BM rows x BK k
       const int64_t row = m0 + r;
       pa[i] = (row < rows && k0 + kk < K) ? load_as_f32<ET>(Ae + row * K + k0 + kk) : 0.f;
-      const int kb = id / BN, c = id % BN;                 // B tile: 16 k x 64 cols
+      const int kb = id / BN, c = id % BN;                 // B tile: BK k x BN cols
       pb[i] = (k0 + kb < K && n0 + c < N) ? load_as_f32<ET>(Be + (int64_t)(k0 + kb) * N + n0 + c) : 0.f;
     }
   };
   fetch(0);
   for (int k0 = 0; k0 < K; k0 += BK) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < PF; ++i) {
       const int id = tid + i * 256;
       As[id % BK][id / BK] = pa[i];
       Bs[id / BN][id % BN] = pb[i];
@@ -54,25 +57,25 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(const ET* __restrict_
     if (k0 + BK < K) fetch(k0 + BK);
 #pragma unroll
     for (int kk = 0; kk < BK; ++kk) {
-      float a[4], b[4];
+      float a[TS], b[TS];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) a[i] = As[kk][ty * 4 + i];
+      for (int i = 0; i < TS; ++i) a[i] = As[kk][ty * TS + i];
 #pragma unroll
-      for (int j = 0; j < 4; ++j) b[j] = Bs[kk][tx * 4 + j];
+      for (int j = 0; j < TS; ++j) b[j] = Bs[kk][tx * TS + j];
 #pragma unroll
-      for (int i = 0; i < 4; ++i)
+      for (int i = 0; i < TS; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], b[j], acc[i][j]);
+        for (int j = 0; j < TS; ++j) acc[i][j] = fmaf(a[i], b[j], acc[i][j]);
     }
     __syncthreads();
   }
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int64_t row = m0 + ty * 4 + i;
+  for (int i = 0; i < TS; ++i) {
+    const int64_t row = m0 + ty * TS + i;
     if (row >= rows) continue;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int col = n0 + tx * 4 + j;
+    for (int j = 0; j < TS; ++j) {
+      const int col = n0 + tx * TS + j;
       if (col >= N) continue;
       float v = acc[i][j];
       if (bias) v += load_as_f32<ET>(bias + (int64_t)e * N + col);
@@ -85,11 +88,14 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(const ET* __restrict_
 hipError_t launch_grouped_gemm_generic(const void* A, const void* B, const void* bias, int act, int dtype,
                                        const int32_t* counts, int64_t E, int64_t C, int64_t K, int64_t N, void* out,
                                        hipStream_t s) {
-  const dim3 grid((unsigned)ceil_div(N, 64), (unsigned)ceil_div(C, 64), (unsigned)E), block(256);
-  if (dtype == MOE_F32)
-    gemm_generic_kernel<float><<<grid, block, 0, s>>>((const float*)A, (const float*)B, (const float*)bias, act, counts, C, (int)K, (int)N, (float*)out);
-  else
-    gemm_generic_kernel<uint16_t><<<grid, block, 0, s>>>((const uint16_t*)A, (const uint16_t*)B, (const uint16_t*)bias, act, counts, C, (int)K, (int)N, (uint16_t*)out);
+  const dim3 block(256);
+  const bool small = ceil_div(N, 64) * ceil_div(C, 64) * E < 512;   // fewer than two 64 x 64 tiles per compute unit
+  const int ts = small ? 32 : 64;
+  const dim3 grid((unsigned)ceil_div(N, ts), (unsigned)ceil_div(C, ts), (unsigned)E);
+#define MOE_LAUNCH_GENERIC(ET, TS) gemm_generic_kernel<ET, TS><<<grid, block, 0, s>>>((const ET*)A, (const ET*)B, (const ET*)bias, act, counts, C, (int)K, (int)N, (ET*)out)
+  if (dtype == MOE_F32) { if (small) MOE_LAUNCH_GENERIC(float, 2); else MOE_LAUNCH_GENERIC(float, 4); }
+  else { if (small) MOE_LAUNCH_GENERIC(uint16_t, 2); else MOE_LAUNCH_GENERIC(uint16_t, 4); }
+#undef MOE_LAUNCH_GENERIC
   return hipGetLastError();
 }
 
