@@ -329,6 +329,34 @@ def test_expert_ffn(moe, dtype, E, C, M, H, act, bias, use_counts):
         assert np.isnan(got[~mask]).all(), "rows past counts[e] must be left untouched"
 
 
+# The grouped GEMM deals its live tiles to the XCDs in groups of 32, 16 or 8, chosen on the device from the number of
+# live tiles (below 512: 8; below 1024: 16): fills that put the first product exactly at, just below and between the
+# thresholds, with ragged last row tiles and an empty expert.  H = 1024 gives the first product
+# four column tiles per row tile and the second one.
+@pytest.mark.parametrize("row_tiles", [127, 128, 200, 255, 256])
+def test_expert_ffn_tile_group_sizes(moe, row_tiles):
+    dtype, E, M, H, act = synth.DT_BF16, 6, 256, 1024, O.ACT_SILU
+    tiles = np.array([row_tiles - 3 * (row_tiles // 4) - 1, row_tiles // 4, 0, row_tiles // 4, 1, row_tiles // 4])   # per expert
+    assert tiles.sum() == row_tiles and (tiles >= 0).all()
+    ragged = np.array([-37, 0, 0, -255, -200, 0])                    # rows short of a whole last tile
+    counts = (tiles * 256 + np.where(tiles > 0, ragged, 0)).astype(np.int32)
+    C = int(counts.max())
+    live = int(((counts + 255) // 256).sum())
+    assert live == row_tiles
+    cfg = synth.CONFIGS[1].scaled(T=E * C, M=M, H=H, E=E, dtype=dtype, cfg_id=45)
+    inp = synth.make_inputs(cfg, seed=row_tiles, bias_std=0.5)
+    Z = inp["x"].reshape(E, C, M)
+    ref = O.expert_ffn(Z, inp["W1"], inp["b1"], inp["W2"], inp["b2"], act, rows=counts)
+    Yd = torch.full((E, C, M), float("nan"), device="cuda").to(torch.bfloat16)
+    moe.expert_ffn(dev(Z, dtype), dev(inp["W1"], dtype), dev(inp["b1"], dtype), dev(inp["W2"], dtype), dev(inp["b2"], dtype), act,
+                   torch.from_numpy(counts).cuda(), Y=Yd)
+    got = host(Yd)
+    rows = np.minimum(counts, C)
+    mask = np.arange(C)[None, :] < rows[:, None]
+    assert_close(got[mask], ref[mask], dtype, "ffn (filled rows)")
+    assert np.isnan(got[~mask]).all(), "rows past counts[e] must be left untouched"
+
+
 def test_expert_ffn_gelu_epilogue_range(moe):
     """The matrix-core GEMM's GeLU epilogue through the kernel itself: one expert whose first layer is 6 x identity on
     inputs spanning [-1, 1] (so the pre-activations span [-6, 6], each an exact bf16 product) and whose second layer
